@@ -1,0 +1,299 @@
+"""CPU oracle for the NSNQuant coded-KV hot path (arXiv 2505.18231).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the HIP path is
+checked against.  Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline
+leg may import it; the product package never does, and nothing here imports the
+product package.  Everything is numpy float64 unless a storage rounding point is
+named.  No blocking, fusion, lookup tables (except `lut_scores`, which exists to
+prove the table form equals the definition) or online softmax.
+
+Parity pins (tests/test_oracle_*.py, all CPU):
+  hadamard            H H^T = I, H = H^T, |entries| = 1/sqrt(d), Sylvester doubling
+  nsn                 token norms sqrt(d) after both Normalize steps, zero channel
+                      mean after Shift, restore identity v = s1 (s2 v_nsn + o),
+                      NSN and the rotation commute (Sec. 3.2)
+  nearest_codeword    the paper's 2-d worked example (App. C.3), exhaustive search
+                      written as an independent python loop on tiny inputs
+  scale adjustment    worked example factor 1.25; (alpha v_Q - v) . v = 0 (Sec. 3.3)
+  encode / dequantize round trip error orthogonal to the rotated token; bit budget
+                      2.5 bits of Table 11's baseline row
+  decode_attention    equals lut_scores + softmax form; L = 1 gives the dequantised
+                      value token; equal scores give the mean value token
+  build_codebook      Lloyd inertia never increases; final per-dimension distortion
+                      lies between the Gaussian rate-distortion bound and the
+                      product scalar Lloyd-Max quantiser.  The centroid values
+                      themselves are "parity unpinned" against the paper (its tuned
+                      codebook is not printed); GPU and oracle are compared with
+                      one and the same codebook array.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+# ----------------------------------------------------------------------------
+# storage rounding
+# ----------------------------------------------------------------------------
+def fp16_rne(x) -> np.ndarray:
+    """Round float64 to the nearest fp16 (ties to even) in ONE rounding, return as fp16."""
+    return np.asarray(x, dtype=F64).astype(np.float16)
+
+
+# ----------------------------------------------------------------------------
+# Hadamard transform (Sec. 2 "Hadamard transform"; App. A.1 step 3: rows h = s / sqrt(d))
+# ----------------------------------------------------------------------------
+def hadamard(d: int) -> np.ndarray:
+    """Orthonormal Sylvester Hadamard matrix, natural order, no random signs."""
+    assert d >= 1 and (d & (d - 1)) == 0
+    h = np.ones((1, 1), dtype=F64)
+    while h.shape[0] < d:
+        h = np.block([[h, h], [h, -h]])
+    return h / np.sqrt(F64(d))
+
+
+# ----------------------------------------------------------------------------
+# Normalize - Shift - Normalize, exactly as the three numbered steps of Sec. 3.2
+# (no storage rounding; used by the pins and by `encode` below)
+# ----------------------------------------------------------------------------
+def _safe_div(num: np.ndarray, den: np.ndarray) -> np.ndarray:
+    """num / den with the reading 'a zero scale gives a zero vector'."""
+    den = np.asarray(den, dtype=F64)
+    out = np.zeros_like(num, dtype=F64)
+    np.divide(num, den, out=out, where=(den != 0))
+    return out
+
+
+def token_scale(v: np.ndarray) -> np.ndarray:
+    """norm(v, per token) / sqrt(d)  (steps 1 and 3 of Sec. 3.2)."""
+    d = v.shape[-1]
+    return np.sqrt(np.sum(v * v, axis=-1)) / np.sqrt(F64(d))
+
+
+def group_index(n_tokens: int, group_size: int, start: int = 0) -> np.ndarray:
+    """Shift group of each token: absolute position // G, or 0 when G == 0 (one group)."""
+    t = np.arange(start, start + n_tokens)
+    return (t // group_size) if group_size > 0 else np.zeros(n_tokens, dtype=np.int64)
+
+
+def nsn(v: np.ndarray, group_size: int = 0):
+    """Sec. 3.2 steps 1-3 on v [l][d]; returns (s1 [l], o [n_groups][d], s2 [l], v_nsn [l][d]).
+
+    The Shift mean is taken per channel over the tokens of one group (the residual-size
+    chunks of Sec. 3.2 'Residual'); group_size 0 means a single group.
+    """
+    v = np.asarray(v, dtype=F64)
+    s1 = token_scale(v)
+    vn = _safe_div(v, s1[:, None])
+    g = group_index(v.shape[0], group_size)
+    ng = int(g.max()) + 1 if v.shape[0] else 0
+    o = np.zeros((ng, v.shape[1]), dtype=F64)
+    for gi in range(ng):
+        o[gi] = vn[g == gi].mean(axis=0)
+    vns = vn - o[g]
+    s2 = token_scale(vns)
+    vnsn = _safe_div(vns, s2[:, None])
+    return s1, o, s2, vnsn
+
+
+def nsn_restore(s1, o, s2, vnsn, group_size: int = 0):
+    """v = s1 (s2 v_nsn + o)  (Sec. 3.2, sentence after the enumerated steps)."""
+    g = group_index(vnsn.shape[0], group_size)
+    return s1[:, None] * (s2[:, None] * vnsn + o[g])
+
+
+# ----------------------------------------------------------------------------
+# Vector quantisation, Eq. (1): VQ(v) = argmin_i D(v, C[i]),  D = squared Euclidean
+# ----------------------------------------------------------------------------
+def nearest_codeword(x: np.ndarray, codebook: np.ndarray, chunk: int = 32768):
+    """For each row of x [n][sub]: index of the nearest codeword (lowest index on ties),
+    plus the best and second-best squared distances (for the tests' tie window)."""
+    x = np.asarray(x, dtype=F64)
+    c = np.asarray(codebook, dtype=F64)
+    n, sub = x.shape
+    idx = np.empty(n, dtype=np.int64)
+    best = np.empty(n, dtype=F64)
+    second = np.empty(n, dtype=F64)
+    for s in range(0, n, chunk):
+        xs = x[s:s + chunk]
+        dist = np.zeros((xs.shape[0], c.shape[0]), dtype=F64)
+        for i in range(sub):
+            diff = xs[:, i:i + 1] - c[None, :, i]
+            dist += diff * diff
+        k = np.argmin(dist, axis=1)  # first occurrence = lowest index on ties
+        idx[s:s + chunk] = k
+        rows = np.arange(xs.shape[0])
+        best[s:s + chunk] = dist[rows, k]
+        if c.shape[0] > 1:
+            dist[rows, k] = np.inf
+            second[s:s + chunk] = dist.min(axis=1)
+        else:
+            second[s:s + chunk] = np.inf
+    return idx, best, second
+
+
+def scale_adjust(v: np.ndarray, vq: np.ndarray) -> np.ndarray:
+    """Sec. 3.3: factor ||v||^2 / (v . v_Q) per row; 1 where v . v_Q is not positive."""
+    d = v.shape[-1]
+    dot = np.sum(v * vq, axis=-1)
+    nrm2 = np.sum(v * v, axis=-1)
+    alpha = np.ones_like(dot)
+    ok = dot > 1e-12 * d
+    alpha[ok] = nrm2[ok] / dot[ok]
+    return alpha
+
+
+# ----------------------------------------------------------------------------
+# Encoder: NSN -> Hadamard -> VQ -> scale adjustment, with the three fp16 storage
+# rounding points (b = s1, o, a = s1 s2 alpha); rounded b and o are the values used
+# downstream, so that dequantisation is self-consistent.
+# ----------------------------------------------------------------------------
+def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: int = 0,
+           frozen_o: np.ndarray | None = None, given_b: np.ndarray | None = None,
+           given_o: np.ndarray | None = None, return_debug: bool = False):
+    """Encode tokens [start, start+l) of one (sequence, kv-head, tensor) unit.
+
+    x16       fp16 [l][d]
+    codebook  [n_codes][sub]
+    frozen_o  fp16 [n_groups][d]: append mode - use these stored means instead of
+              computing new ones (a new token never forms a one-token group)
+    given_b / given_o: override the stage-A results (two-stage parity protocol: the
+              second stage is checked conditioned on the first stage's stored values)
+    returns dict(codes u8 [l][d/sub], a fp16 [l], b fp16 [l], o fp16 [n_groups][d])
+    """
+    x = np.asarray(x16, dtype=F64)
+    l, d = x.shape
+    c = np.asarray(codebook, dtype=F64)
+    sub = c.shape[1]
+    assert d % sub == 0
+    H = hadamard(d)
+
+    # step 1 (Normalize): s1, stored as fp16 b
+    b16 = fp16_rne(token_scale(x)) if given_b is None else np.asarray(given_b, dtype=np.float16)
+    b = b16.astype(F64)
+    n = _safe_div(x, b[:, None])
+
+    # step 2 (Shift): per-group channel mean, stored as fp16 o
+    g = group_index(l, group_size, start)
+    if frozen_o is not None:
+        o16 = np.asarray(frozen_o, dtype=np.float16)
+    elif given_o is not None:
+        o16 = np.asarray(given_o, dtype=np.float16)
+    else:
+        assert group_size == 0 or start % group_size == 0, "a new group starts on a boundary"
+        assert group_size != 0 or start == 0
+        ng_total = (int(g.max()) + 1) if l else 0
+        o16 = np.zeros((ng_total, d), dtype=np.float16)
+        for gi in np.unique(g):
+            o16[gi] = fp16_rne(n[g == gi].mean(axis=0))
+    o = o16.astype(F64)
+    ns = n - o[g]
+
+    # step 3 (Normalize)
+    s2 = token_scale(ns)
+    vnsn = _safe_div(ns, s2[:, None])
+
+    # Hadamard rotation (dense mat-vec), then Eq. (1) on contiguous sub-vectors
+    y = vnsn @ H.T
+    codes, best, second = nearest_codeword(y.reshape(-1, sub), c)
+    yq = c[codes].reshape(l, d)
+
+    # scale adjustment folded into the stored scale: a = s1 s2 alpha
+    alpha = scale_adjust(y, yq)
+    a16 = fp16_rne(b * s2 * alpha)
+
+    out = dict(codes=codes.reshape(l, d // sub).astype(np.uint8), a=a16, b=b16, o=o16)
+    if return_debug:
+        out.update(y=y, s2=s2, alpha=alpha, best=best.reshape(l, -1), second=second.reshape(l, -1))
+    return out
+
+
+def dequantize(codes, a16, b16, o16, codebook, group_size: int = 0, start: int = 0) -> np.ndarray:
+    """x_hat_t = b_t o_g + a_t H^T y_Q,t  (restore identity of Sec. 3.2 with s2 alpha in a)."""
+    c = np.asarray(codebook, dtype=F64)
+    l, J = codes.shape
+    d = J * c.shape[1]
+    H = hadamard(d)
+    yq = c[codes.astype(np.int64)].reshape(l, d)
+    g = group_index(l, group_size, start)
+    a = np.asarray(a16, dtype=F64)
+    b = np.asarray(b16, dtype=F64)
+    o = np.asarray(o16, dtype=F64)
+    return b[:, None] * o[g] + a[:, None] * (yq @ H)  # H^T = H^-1; row form: yq @ H
+
+
+# ----------------------------------------------------------------------------
+# Decode attention over a coded cache (App. B, with RoPE dropped: keys are taken as given)
+# ----------------------------------------------------------------------------
+def decode_attention(q, kc: dict, vc: dict, codebook, softmax_scale: float,
+                     group_size: int = 0) -> np.ndarray:
+    """out = softmax(scale * q K_hat^T) V_hat for q [r][d] (r query heads on one kv head)."""
+    q = np.atleast_2d(np.asarray(q, dtype=F64))
+    k_hat = dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], codebook, group_size)
+    v_hat = dequantize(vc["codes"], vc["a"], vc["b"], vc["o"], codebook, group_size)
+    s = softmax_scale * (q @ k_hat.T)
+    s = s - s.max(axis=1, keepdims=True)
+    p = np.exp(s)
+    p = p / p.sum(axis=1, keepdims=True)
+    return p @ v_hat
+
+
+def lut_scores(q, kc: dict, codebook, softmax_scale: float, group_size: int = 0) -> np.ndarray:
+    """App. B last line: s1 s2 q_Had . v_Q + s1 q . o, evaluated through a per-sub-vector
+    query x codebook table.  Independent of `dequantize`; must agree with q . K_hat."""
+    q = np.atleast_2d(np.asarray(q, dtype=F64))
+    c = np.asarray(codebook, dtype=F64)
+    codes = kc["codes"].astype(np.int64)
+    l, J = codes.shape
+    sub = c.shape[1]
+    H = hadamard(J * sub)
+    q_had = q @ H.T
+    g = group_index(l, group_size)
+    out = np.zeros((q.shape[0], l), dtype=F64)
+    a = np.asarray(kc["a"], dtype=F64)
+    b = np.asarray(kc["b"], dtype=F64)
+    o = np.asarray(kc["o"], dtype=F64)
+    for r in range(q.shape[0]):
+        lut = q_had[r].reshape(J, sub) @ c.T            # [J][n_codes]
+        gathered = lut[np.arange(J)[None, :], codes].sum(axis=1)
+        q_o = o @ q[r]                                   # [n_groups]
+        out[r] = softmax_scale * (a * gathered + b * q_o[g])
+    return out
+
+
+# ----------------------------------------------------------------------------
+# Codebook: K-Means on standard normal data (Sec. 3.4, the K-Means baseline)
+# ----------------------------------------------------------------------------
+def build_codebook(samples: np.ndarray, n_codes: int = 256, iters: int = 50):
+    """Lloyd iterations; init = first n_codes samples; empty cluster keeps its centroid.
+
+    Returns (codebook float64 [n_codes][sub] rounded to fp16-representable values,
+             inertia per-dimension MSE measured at the assignment of every iteration,
+             final per-dimension MSE of the rounded codebook).
+    """
+    x = np.asarray(samples, dtype=F64)
+    n, sub = x.shape
+    c = x[:n_codes].copy()
+    history = []
+    for _ in range(iters):
+        idx, best, _ = nearest_codeword(x, c)
+        history.append(best.sum() / (n * sub))
+        for k in range(n_codes):
+            m = idx == k
+            if m.any():
+                c[k] = x[m].mean(axis=0)
+    c = fp16_rne(c).astype(F64)
+    _, best, _ = nearest_codeword(x, c)
+    return c, np.asarray(history), best.sum() / (n * sub)
+
+
+# ----------------------------------------------------------------------------
+# Storage accounting (Table 11, "Baseline" row: fp16 side information, no double quantisation)
+# ----------------------------------------------------------------------------
+def avg_bits(code_bits_per_dim: float, head_dim: int, group_size: int) -> float:
+    """Bits per cached element: codes + two fp16 scales per token + one fp16 mean vector
+    per group of `group_size` tokens."""
+    scales = 2 * 16 / head_dim
+    means = 16 * head_dim / (group_size * head_dim)
+    return code_bits_per_dim + scales + means

@@ -1,0 +1,286 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (CPU only).
+
+Every check here uses something other than the oracle's own formula: printed values,
+closed forms, invariants, brute force in plain python loops, textbook bounds.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import nsn_oracle as O
+from paper_2505_18231_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+D = 128
+
+
+def _rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [[float(t) for t in ln.split()] for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+def _rand_codebook(seed, sub, n=256):
+    g = np.random.default_rng(seed)
+    return g.standard_normal((n, sub)).astype(np.float16).astype(np.float64)
+
+
+# ---------------------------------------------------------------- storage rounding
+def test_fp16_rounding_is_single_rounding():
+    # Just above the midpoint of [1, 1+2^-10]: going through fp32 first would land on the
+    # midpoint and tie to even (1.0); one rounding gives 1+2^-10.
+    x = 1.0 + 2.0 ** -11 + 2.0 ** -40
+    assert float(O.fp16_rne(x)) == 1.0 + 2.0 ** -10
+    assert float(O.fp16_rne(1.0 + 2.0 ** -11)) == 1.0            # exact tie -> even
+    assert float(O.fp16_rne(1.0 + 3 * 2.0 ** -11)) == 1.0 + 2 * 2.0 ** -10
+    assert float(O.fp16_rne(-(1.0 + 2.0 ** -11 + 2.0 ** -40))) == -(1.0 + 2.0 ** -10)
+
+
+# ---------------------------------------------------------------- Hadamard
+@pytest.mark.parametrize("d", [2, 8, 128])
+def test_hadamard_properties(d):
+    H = O.hadamard(d)
+    assert np.allclose(H @ H.T, np.eye(d), atol=1e-14)
+    assert np.array_equal(H, H.T)
+    assert np.allclose(np.abs(H), 1.0 / math.sqrt(d), atol=1e-16)
+    if d > 1:
+        h = O.hadamard(d // 2) / math.sqrt(2.0)
+        assert np.allclose(H, np.block([[h, h], [h, -h]]), atol=1e-16)
+
+
+def test_hadamard_natural_order_entries():
+    # natural (Sylvester) order has the closed form H[k][n] = (-1)^popcount(k & n) / sqrt(d)
+    H = O.hadamard(D)
+    for k in (0, 1, 5, 64, 127):
+        for n in (0, 3, 64, 77, 127):
+            assert H[k, n] == (-1.0) ** bin(k & n).count("1") / math.sqrt(D)
+
+
+# ---------------------------------------------------------------- NSN invariants
+@pytest.mark.parametrize("G", [0, 64])
+def test_nsn_invariants_and_restore(G):
+    x = synth.make_k(11, 0, 0, 320).astype(np.float64)
+    s1, o, s2, vnsn = O.nsn(x, G)
+    vn = x / s1[:, None]
+    assert np.allclose(np.linalg.norm(vn, axis=1), math.sqrt(D), rtol=1e-13)
+    assert np.allclose(np.linalg.norm(vnsn, axis=1), math.sqrt(D), rtol=1e-13)
+    g = O.group_index(320, G)
+    for gi in range(o.shape[0]):
+        assert np.abs((vn - o[g])[g == gi].mean(axis=0)).max() < 1e-13
+    assert np.allclose(O.nsn_restore(s1, o, s2, vnsn, G), x, rtol=1e-12, atol=1e-12)
+    assert o.shape[0] == (5 if G else 1)
+
+
+def test_nsn_commutes_with_rotation():
+    x = synth.make_k(12, 0, 1, 192).astype(np.float64)
+    H = O.hadamard(D)
+    s1a, oa, s2a, na = O.nsn(x, 64)
+    s1b, ob, s2b, nb = O.nsn(x @ H.T, 64)
+    assert np.allclose(s1a, s1b, rtol=1e-13) and np.allclose(s2a, s2b, rtol=1e-12)
+    assert np.allclose(na @ H.T, nb, atol=1e-11)
+    assert np.allclose(oa @ H.T, ob, atol=1e-12)
+
+
+def test_nsn_then_rotation_is_roughly_standard_normal():
+    # Sec. 3.2: with the rotation, NSN brings channels close to N(0,1); mean square is 1 exactly
+    x = synth.make_k(13, 0, 2, 4096).astype(np.float64)
+    _, _, _, vnsn = O.nsn(x, 64)
+    y = vnsn @ O.hadamard(D).T
+    assert abs((y * y).mean() - 1.0) < 1e-12
+    assert np.abs(y.mean(axis=0)).max() < 0.1
+    v = y.var(axis=0)
+    assert 0.3 < v.min() and v.max() < 3.0
+
+
+def test_zero_token_and_single_token_group():
+    x = np.zeros((3, D), dtype=np.float16)
+    x[1] = synth.make_v(3, 0, 0, 1)[0]
+    cb = _rand_codebook(0, 8)
+    e = O.encode(x, cb, group_size=0)
+    assert float(e["b"][0]) == 0.0 and float(e["a"][0]) == 0.0
+    xh = O.dequantize(e["codes"], e["a"], e["b"], e["o"], cb, 0)
+    assert np.all(xh[0] == 0.0) and np.all(xh[2] == 0.0)
+    one = O.encode(x[1:2], cb, group_size=0)          # a one-token group: v_ns = 0
+    xh1 = O.dequantize(one["codes"], one["a"], one["b"], one["o"], cb, 0)
+    # v_ns is only the fp16 rounding residual of the stored mean: a tiny scale
+    assert float(one["a"][0]) < 1e-3 * float(one["b"][0])
+    assert np.allclose(xh1[0], x[1].astype(np.float64), rtol=2e-3, atol=2e-3)
+
+
+# ---------------------------------------------------------------- VQ + scale adjustment
+def test_worked_example_from_paper():
+    for v0, v1, a0, a1, b0, b1, idx, scale in _rows("scale_adjust_example.txt"):
+        v = np.array([[v0, v1]])
+        cb = np.array([[a0, a1], [b0, b1]])
+        k, best, second = O.nearest_codeword(v, cb)
+        assert int(k[0]) == int(idx)
+        assert best[0] < second[0]
+        alpha = O.scale_adjust(v, cb[k])
+        assert abs(alpha[0] - scale) < 1e-12
+        assert abs(np.dot(alpha[0] * cb[k[0]] - v[0], v[0])) < 1e-12   # error orthogonal to v
+
+
+@pytest.mark.parametrize("sub", [4, 8])
+def test_nearest_codeword_matches_python_brute_force(sub):
+    g = np.random.default_rng(5)
+    cb = g.standard_normal((37, sub))
+    x = g.standard_normal((50, sub))
+    k, best, second = O.nearest_codeword(x, cb, chunk=16)
+    for r in range(x.shape[0]):
+        dists = [sum((float(x[r, i]) - float(cb[c, i])) ** 2 for i in range(sub)) for c in range(37)]
+        order = sorted(range(37), key=lambda c: (dists[c], c))
+        assert int(k[r]) == order[0]
+        assert abs(best[r] - dists[order[0]]) < 1e-12
+        assert abs(second[r] - dists[order[1]]) < 1e-12
+
+
+def test_nearest_codeword_tie_takes_lowest_index():
+    cb = np.array([[1.0, 0.0], [-1.0, 0.0], [1.0, 0.0]])
+    k, best, second = O.nearest_codeword(np.array([[0.0, 0.0], [0.9, 0.0]]), cb)
+    assert list(k) == [0, 0]
+    assert best[0] == second[0] == 1.0
+
+
+@pytest.mark.parametrize("sub,G", [(8, 0), (4, 64)])
+def test_encode_scale_adjust_orthogonality_and_roundtrip(sub, G):
+    cb = _rand_codebook(1, sub)
+    x16 = synth.make_k(21, 0, 0, 256)
+    e = O.encode(x16, cb, group_size=G, return_debug=True)
+    y, alpha = e["y"], e["alpha"]
+    yq = cb[e["codes"].astype(int)].reshape(256, D)
+    assert np.abs(np.sum((alpha[:, None] * yq - y) * y, axis=1)).max() < 1e-9 * D
+    # codes are the brute-force nearest entries of contiguous sub-vectors of y
+    for t in (0, 100, 255):
+        for j in (0, D // sub - 1):
+            dists = ((y[t, j * sub:(j + 1) * sub][None, :] - cb) ** 2).sum(axis=1)
+            assert int(e["codes"][t, j]) == int(np.argmin(dists))
+    # the dequantisation error is orthogonal to the un-shifted token part, up to the
+    # fp16 rounding of the stored scale a (relative 2^-11)
+    x = x16.astype(np.float64)
+    xh = O.dequantize(e["codes"], e["a"], e["b"], e["o"], cb, G)
+    g = O.group_index(256, G)
+    centred = x - e["b"].astype(np.float64)[:, None] * e["o"].astype(np.float64)[g]
+    rel = np.abs(np.sum((xh - x) * centred, axis=1)) / np.sum(centred * centred, axis=1)
+    assert rel.max() < 1.5e-3
+
+
+def test_dequantize_is_close_with_a_real_codebook():
+    # A dropped mean term, a wrong group index or a wrong scale would blow this up:
+    # keys carry per-channel offsets of up to +20.
+    samples = synth.codebook_samples(7, 1 << 14, 4)
+    cb, _, mse = O.build_codebook(samples, 256, 8)
+    x16 = synth.make_k(22, 0, 3, 200)
+    x = x16.astype(np.float64)
+    for G in (0, 64):
+        e = O.encode(x16, cb, group_size=G)
+        xh = O.dequantize(e["codes"], e["a"], e["b"], e["o"], cb, G)
+        rel = np.linalg.norm(xh - x) / np.linalg.norm(x)
+        assert rel < 0.25, rel
+        assert e["o"].shape[0] == (4 if G else 1)
+
+
+def test_append_with_frozen_mean_uses_stored_group_mean():
+    cb = _rand_codebook(2, 8)
+    x16 = synth.make_k(23, 0, 0, 130)
+    pre = O.encode(x16[:128], cb, group_size=0)
+    app = O.encode(x16[128:], cb, group_size=0, start=128, frozen_o=pre["o"])
+    assert np.array_equal(app["o"], pre["o"])
+    xh = O.dequantize(app["codes"], app["a"], app["b"], app["o"], cb, 0, start=128)
+    x = x16[128:].astype(np.float64)
+    assert np.linalg.norm(xh - x) / np.linalg.norm(x) < 0.6
+
+
+def test_bit_budget_matches_paper_table():
+    for bits, d, G, expect in _rows("bit_budget.txt"):
+        assert abs(O.avg_bits(bits, int(d), int(G)) - expect) < 1e-12
+    # our 2-bit record: one byte per 4-dim sub-vector = 2 bits per element
+    assert 8 / 4 == 2 and 8 / 8 == 1
+
+
+# ---------------------------------------------------------------- decode attention
+def _coded_unit(seed, L, sub, G, cb):
+    k = O.encode(synth.make_k(seed, 0, 0, L), cb, group_size=G)
+    v = O.encode(synth.make_v(seed, 0, 0, L), cb, group_size=G)
+    return k, v
+
+
+@pytest.mark.parametrize("sub,G", [(8, 0), (4, 64)])
+def test_lut_form_equals_dequantise_then_dot(sub, G):
+    cb = _rand_codebook(3, sub)
+    kc, vc = _coded_unit(31, 192, sub, G, cb)
+    q = synth.make_q(31, 1, 4)[0].astype(np.float64)
+    k_hat = O.dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], cb, G)
+    s_dense = 0.1 * q @ k_hat.T
+    s_lut = O.lut_scores(q, kc, cb, 0.1, G)
+    assert np.allclose(s_dense, s_lut, rtol=1e-11, atol=1e-11)
+
+
+def test_decode_attention_against_python_loops():
+    cb = _rand_codebook(4, 8)
+    L, G = 24, 0
+    kc, vc = _coded_unit(32, L, 8, G, cb)
+    q = synth.make_q(32, 1, 2)[0].astype(np.float64)
+    out = O.decode_attention(q, kc, vc, cb, 0.2, G)
+    H = O.hadamard(D)
+    for r in range(2):
+        scores, vals = [], []
+        for t in range(L):
+            kq = np.concatenate([cb[c] for c in kc["codes"][t]])
+            vq = np.concatenate([cb[c] for c in vc["codes"][t]])
+            k_t = float(kc["b"][t]) * kc["o"][0].astype(float) + float(kc["a"][t]) * (H.T @ kq)
+            v_t = float(vc["b"][t]) * vc["o"][0].astype(float) + float(vc["a"][t]) * (H.T @ vq)
+            scores.append(0.2 * float(np.dot(q[r], k_t)))
+            vals.append(v_t)
+        m = max(scores)
+        w = [math.exp(s - m) for s in scores]
+        z = sum(w)
+        ref = sum(wi / z * vi for wi, vi in zip(w, vals))
+        assert np.allclose(out[r], ref, rtol=1e-11, atol=1e-12)
+
+
+def test_decode_special_cases():
+    cb = _rand_codebook(5, 4)
+    kc, vc = _coded_unit(33, 64, 4, 0, cb)
+    v_hat = O.dequantize(vc["codes"], vc["a"], vc["b"], vc["o"], cb, 0)
+    q = synth.make_q(33, 1, 1)[0].astype(np.float64)
+    # zero query: all scores equal -> plain mean of the value tokens
+    out = O.decode_attention(np.zeros((1, D)), kc, vc, cb, 1.0, 0)
+    assert np.allclose(out[0], v_hat.mean(axis=0), atol=1e-13)
+    # a single cached token: the output is that token's dequantised value
+    k1 = {k: (v[:1] if k != "o" else v) for k, v in kc.items()}
+    v1 = {k: (v[:1] if k != "o" else v) for k, v in vc.items()}
+    out1 = O.decode_attention(q, k1, v1, cb, 1.0, 0)
+    assert np.allclose(out1[0], v_hat[0], atol=1e-13)
+
+
+# ---------------------------------------------------------------- codebook (K-Means on N(0,1))
+@pytest.mark.parametrize("sub,lo,hi", [
+    (8, 0.25, 1.0 - 2.0 / math.pi),   # 1 bit/dim: rate-distortion bound .. sign quantiser
+    (4, 0.0625, 0.1175),              # 2 bit/dim: rate-distortion bound .. 4-level Lloyd-Max
+])
+def test_codebook_distortion_bracket_and_monotone_inertia(sub, lo, hi):
+    samples = synth.codebook_samples(9, 1 << 16, sub)
+    cb, hist, mse = O.build_codebook(samples, 256, 12)
+    assert np.all(np.diff(hist) <= 1e-12), "Lloyd inertia must not increase"
+    assert lo < mse < hi, mse
+    # centroids are cluster means, so their occupancy-weighted mean is the sample mean
+    idx, _, _ = O.nearest_codeword(samples, cb)
+    w = np.bincount(idx, minlength=256) / idx.size
+    assert np.abs(w @ cb - samples.mean(axis=0)).max() < 5e-3
+    assert np.array_equal(cb, cb.astype(np.float16).astype(np.float64))  # fp16-representable
+    cb2, _, _ = O.build_codebook(samples, 256, 12)
+    assert np.array_equal(cb, cb2)
+    # held-out distortion also sits inside the bracket (the codebook is not over-fitted)
+    fresh = synth.codebook_samples(10, 1 << 15, sub)
+    _, best, _ = O.nearest_codeword(fresh, cb)
+    assert lo < best.sum() / fresh.size < hi
+
+
+def test_kmeans_on_separated_clusters_recovers_centres():
+    g = np.random.default_rng(0)
+    centres = np.array([[-10.0, 0.0], [10.0, 0.0], [0.0, 10.0]])
+    pts = np.concatenate([c + 0.01 * g.standard_normal((50, 2)) for c in centres])
+    order = np.concatenate([[0, 50, 100], np.setdiff1d(np.arange(150), [0, 50, 100])])
+    cb, hist, _ = O.build_codebook(pts[order], 3, 5)
+    assert np.allclose(cb, centres, atol=0.02)
