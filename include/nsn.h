@@ -1,0 +1,172 @@
+/*
+ * nsn.h - C ABI of the MI355X (gfx950) coded-KV hot path of NSNQuant (arXiv 2505.18231).
+ *
+ * Three operations, all executed by hand-written HIP kernels on ONE GPU:
+ *   nsn_build_codebook    K-Means codebook on standard-normal samples      (Sec. 3.4)
+ *   nsn_encode            Normalize-Shift-Normalize, Hadamard rotation,
+ *                         nearest-codeword search, scale adjustment          (Sec. 3.2, 3.3, Eq. 1)
+ *   nsn_decode_attention  single-query attention straight from the coded
+ *                         cache                                              (App. B)
+ *
+ * Conventions
+ *   - Plain C, no exceptions cross this boundary.  Every call returns an int status:
+ *     NSN_OK (0) or a negative NSN_ERR_* code; nsn_last_error() gives a text for the
+ *     calling thread's last failure.
+ *   - "dev" pointers are device memory owned by the caller (never freed or retained
+ *     here); "host" pointers are ordinary host memory.  The library allocates nothing:
+ *     scratch comes from a caller workspace sized by nsn_workspace_bytes().
+ *   - Kernels are enqueued on the caller's hipStream_t (passed as void*; NULL = the
+ *     default stream) and the call returns without synchronising, except
+ *     nsn_build_codebook, which returns host results and therefore synchronises.
+ *   - No floating-point atomics are used: identical inputs give bit-identical outputs.
+ *   - head_dim is 128, n_codes is 256, sub_dim is 8 ("1-bit": one code byte per 8
+ *     rotated channels) or 4 ("2-bit": one code byte per 4 rotated channels).
+ *
+ * Coded cache record (one tensor kind, K or V), per (sequence b, kv-head h):
+ *   codes  J = head_dim/sub_dim bytes per token, stored in 1 KiB blocks of TB = 1024/J
+ *          tokens (TB = 32 at J = 32, TB = 64 at J = 16).  Inside a block the byte of
+ *          (token tt in [0,TB), sub-vector j in [0,J)) sits at
+ *            K:  W = J/4, NT = TB/16:
+ *                ((j/W * 16 + tt%16) * NT + tt/16) * W + j%W
+ *            V:  ((tt%32)/8 * 16 + j%16) * 2 + (J == 32 ? j/16 : tt/32)) * 8 + tt%8
+ *          (K keeps a token's codes together for the score contraction over channels;
+ *          V keeps eight tokens of one sub-vector together for the contraction over
+ *          tokens.)  nsn_k_code_offset / nsn_v_code_offset below return these offsets.
+ *   norms  one (a, b) fp16 pair per token: b = s1 (first Normalize scale), a = s1*s2*alpha
+ *          (second Normalize scale times the scale-adjustment factor of Sec. 3.3).
+ *   means  fp16 [n_groups][head_dim]: the Shift vector o of every group of group_size
+ *          tokens (group of token t = t / group_size; a single group when group_size = 0),
+ *          in the original, un-rotated channel order.
+ *   A token dequantises to  b * o_g + a * H^T concat_j C[code_j]   (Sec. 3.2 restore rule).
+ *
+ * Placement of the units:
+ *   contiguous (page_size = 0):
+ *       codes [B][Hkv][max_len * J] bytes, norms [B][Hkv][max_len] pairs
+ *   paged (page_size > 0, a multiple of 64):
+ *       codes [n_pages][Hkv][page_size * J], norms [n_pages][Hkv][page_size],
+ *       block_table dev int32 [B][max_len / page_size]: physical page of each logical page
+ *   means are never paged: fp16 [B][Hkv][NG][head_dim], NG = nsn_max_groups(shape).
+ */
+#ifndef NSN_H
+#define NSN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  NSN_OK = 0,
+  NSN_ERR_INVALID_ARG = -1, /* null pointer, negative size, misaligned start, ... */
+  NSN_ERR_UNSUPPORTED = -2, /* head_dim != 128, sub_dim not in {4,8}, n_codes != 256, ... */
+  NSN_ERR_WORKSPACE = -3,   /* workspace missing or smaller than nsn_workspace_bytes() */
+  NSN_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed */
+};
+
+enum { NSN_OP_ENCODE = 0, NSN_OP_DECODE = 1, NSN_OP_CODEBOOK = 2 };
+
+typedef struct nsn_shape {
+  int32_t head_dim;   /* 128 */
+  int32_t sub_dim;    /* 8 (1-bit) or 4 (2-bit) */
+  int32_t n_codes;    /* 256 */
+  int32_t n_q_heads;  /* multiple of n_kv_heads; n_q_heads / n_kv_heads <= 8 */
+  int32_t n_kv_heads;
+  int32_t group_size; /* G: tokens sharing one Shift mean; multiple of 64 (the paper uses 64),
+                         or 0 = one group per sequence */
+  int32_t page_size;  /* 0 = contiguous; else tokens per page, multiple of 64 */
+  int32_t max_len;    /* token capacity per sequence, multiple of 64 (and of page_size) */
+} nsn_shape;
+
+typedef struct nsn_cache {
+  uint8_t* codes;             /* dev */
+  void* norms;                /* dev, fp16 pairs (a, b) */
+  void* means;                /* dev, fp16 */
+  const int32_t* block_table; /* dev, paged layout only (else NULL) */
+} nsn_cache;
+
+/* Byte offset of (token-in-block tt, sub-vector j) inside a 1 KiB code block; J = codes per token. */
+int nsn_k_code_offset(int J, int tt, int j);
+int nsn_v_code_offset(int J, int tt, int j);
+/* Number of mean vectors kept per (sequence, kv-head): max_len / group_size rounded up, or 1. */
+int nsn_max_groups(const nsn_shape* shape);
+/* Text of the calling thread's most recent error ("" if none). Never NULL. */
+const char* nsn_last_error(void);
+
+/*
+ * Workspace (device bytes) an operation needs.
+ *   NSN_OP_ENCODE   : n = max_new (token stride of the inputs), n_splits ignored
+ *   NSN_OP_DECODE   : n ignored, n_splits as passed to nsn_decode_attention (0 = auto)
+ *   NSN_OP_CODEBOOK : n = n_samples, batch and n_splits ignored
+ * Returns 0 for an invalid shape.
+ */
+size_t nsn_workspace_bytes(const nsn_shape* shape, int op, int batch, int64_t n, int n_splits);
+
+/*
+ * K-Means codebook on standard-normal data (Sec. 3.4, the K-Means baseline; the paper's
+ * later fine-tuning step is not part of this call).
+ *   samples_dev   dev fp32 [n_samples][sub_dim], drawn by the caller (the library holds no
+ *                 random generator); the first n_codes samples are the initial centroids
+ *   iters         Lloyd iterations: assign to the nearest centroid in squared Euclidean
+ *                 distance (lowest index on ties, decided in fp64), then replace every
+ *                 non-empty cluster's centroid by its fp64 mean
+ *   codebook_dev  out, dev fp16 [n_codes][sub_dim]: final centroids rounded to fp16 once
+ *   mse_host      out, host double[1]: mean squared error per dimension of the samples
+ *                 against the rounded codebook (may be NULL)
+ * Synchronises the stream before returning.  Errors: INVALID_ARG (null pointers,
+ * n_samples < n_codes, iters < 0), UNSUPPORTED (sub_dim, n_codes), WORKSPACE, HIP.
+ */
+int nsn_build_codebook(const float* samples_dev, int64_t n_samples, int sub_dim, int n_codes,
+                       int iters, void* codebook_dev, double* mse_host, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/*
+ * Encoder (Sec. 3.2 steps 1-3, Hadamard rotation of Sec. 2, Eq. 1 on contiguous sub-vectors
+ * of the rotated token, scale adjustment of Sec. 3.3).  For every sequence b it encodes the
+ * n_new[b] tokens found in k_fp16 / v_fp16 and writes them at cache positions
+ * [seq_start[b], seq_start[b] + n_new[b]).
+ *   codebook_dev  dev fp16 [256][sub_dim]
+ *   k_fp16,v_fp16 dev fp16 [batch][n_kv_heads][max_new][head_dim]; rows >= n_new[b] are ignored
+ *   seq_start,n_new dev int32 [batch]
+ *   freeze_means  0: the Shift mean of every group touched is computed from the new tokens
+ *                    (seq_start[b] must then be a multiple of group_size, or 0 when
+ *                    group_size = 0) and stored;
+ *                 1: append mode - the stored mean of the token's group is used unchanged,
+ *                    so a new token never forms a one-token group (the group must exist).
+ *   Storage rounding: b, o and a are rounded to fp16 (nearest even, one rounding from fp64);
+ *   the rounded b and o are the values used in the later steps.
+ *   A zero scale (s1 = 0 or s2 = 0) stores a zero vector and a zero scale; the adjustment
+ *   factor is 1 when (rotated token) . (its quantised version) <= 1e-12 * head_dim.
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP.  Out-of-range positions
+ * (seq_start + n_new > max_len) are clipped on the device: such tokens are not written.
+ */
+int nsn_encode(const nsn_shape* shape, const void* codebook_dev, const void* k_fp16,
+               const void* v_fp16, int max_new, const int32_t* seq_start_dev,
+               const int32_t* n_new_dev, int batch, int freeze_means, const nsn_cache* k_cache,
+               const nsn_cache* v_cache, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One decode step of attention over the coded cache (App. B with keys taken as given, i.e.
+ * without the in-kernel RoPE of the mean):
+ *   score_t = softmax_scale * ( a^k_t * HT(q) . C[codes^k_t] + b^k_t * q . o^k_g(t) )
+ *   out     = sum_t softmax(score)_t * ( a^v_t * H^T C[codes^v_t] + b^v_t * o^v_g(t) )
+ *   q_fp16       dev fp16 [batch][n_q_heads][head_dim]; query head hq reads kv head
+ *                hq / (n_q_heads / n_kv_heads)
+ *   seq_lens_dev dev int32 [batch], cached tokens per sequence (0 gives a zero output row)
+ *   max_seq_len  host upper bound of seq_lens (sizes the launch; <= shape->max_len)
+ *   n_splits     partitions of the token axis processed by separate workgroups and merged
+ *                with fp32 running max / sum (0 = choose from the shape)
+ *   out          dev fp32 [batch][n_q_heads][head_dim]
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP.
+ */
+int nsn_decode_attention(const nsn_shape* shape, const void* codebook_dev, const void* q_fp16,
+                         const nsn_cache* k_cache, const nsn_cache* v_cache,
+                         const int32_t* seq_lens_dev, int batch, int max_seq_len,
+                         float softmax_scale, int n_splits, float* out, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NSN_H */

@@ -1,0 +1,182 @@
+"""Thin ctypes binding of libnsn.so (same names as include/nsn.h).
+
+Argument marshalling only: every step of the path runs inside the HIP kernels.  PyTorch is
+used for device memory and the current stream.  There is no CPU fallback: a missing library
+raises at import of the first call.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnsn.so")
+
+NSN_OK = 0
+NSN_ERR_INVALID_ARG, NSN_ERR_UNSUPPORTED, NSN_ERR_WORKSPACE, NSN_ERR_HIP = -1, -2, -3, -4
+NSN_OP_ENCODE, NSN_OP_DECODE, NSN_OP_CODEBOOK = 0, 1, 2
+HEAD_DIM, N_CODES, BLOCK_BYTES = 128, 256, 1024
+
+
+class nsn_shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("head_dim", "sub_dim", "n_codes", "n_q_heads", "n_kv_heads",
+                                         "group_size", "page_size", "max_len")]
+
+
+class nsn_cache(C.Structure):
+    _fields_ = [("codes", C.c_void_p), ("norms", C.c_void_p), ("means", C.c_void_p),
+                ("block_table", C.c_void_p)]
+
+
+class NsnError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libnsn error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libnsn.so (built in-tree by paper_2505_18231_amd.build); fail loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2505_18231_amd.build` "
+                "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        L.nsn_last_error.restype = C.c_char_p
+        L.nsn_workspace_bytes.restype = C.c_size_t
+        L.nsn_workspace_bytes.argtypes = [C.POINTER(nsn_shape), C.c_int, C.c_int, C.c_int64, C.c_int]
+        L.nsn_max_groups.argtypes = [C.POINTER(nsn_shape)]
+        L.nsn_k_code_offset.argtypes = [C.c_int] * 3
+        L.nsn_v_code_offset.argtypes = [C.c_int] * 3
+        L.nsn_build_codebook.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                         C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nsn_encode.argtypes = [C.POINTER(nsn_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                 C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(nsn_cache),
+                                 C.POINTER(nsn_cache), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nsn_decode_attention.argtypes = [C.POINTER(nsn_shape), C.c_void_p, C.c_void_p,
+                                           C.POINTER(nsn_cache), C.POINTER(nsn_cache), C.c_void_p, C.c_int,
+                                           C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t,
+                                           C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != NSN_OK:
+        raise NsnError(rc, lib().nsn_last_error().decode())
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def make_shape(sub_dim: int, n_q_heads: int, n_kv_heads: int, max_len: int, group_size: int = 0,
+               page_size: int = 0) -> nsn_shape:
+    return nsn_shape(HEAD_DIM, sub_dim, N_CODES, n_q_heads, n_kv_heads, group_size, page_size, max_len)
+
+
+def nsn_max_groups(shape: nsn_shape) -> int:
+    return lib().nsn_max_groups(C.byref(shape))
+
+
+def nsn_workspace_bytes(shape: nsn_shape, op: int, batch: int, n: int = 0, n_splits: int = 0) -> int:
+    return lib().nsn_workspace_bytes(C.byref(shape), op, batch, n, n_splits)
+
+
+@dataclass
+class CodedCache:
+    """Device buffers of one tensor kind (K or V) in the layout include/nsn.h documents."""
+    codes: torch.Tensor          # uint8
+    norms: torch.Tensor          # fp16 [..., 2] = (a, b)
+    means: torch.Tensor          # fp16 [B][Hkv][NG][128]
+    block_table: torch.Tensor | None
+
+    def c_struct(self) -> nsn_cache:
+        return nsn_cache(self.codes.data_ptr(), self.norms.data_ptr(), self.means.data_ptr(),
+                         _ptr(self.block_table))
+
+
+def alloc_cache(shape: nsn_shape, batch: int, device="cuda", block_table: torch.Tensor | None = None,
+                n_pages: int | None = None) -> CodedCache:
+    """Zero-initialised cache buffers.  Paged layout: n_pages physical pages (default: enough for all)."""
+    J = HEAD_DIM // shape.sub_dim
+    hkv = shape.n_kv_heads
+    ng = nsn_max_groups(shape)
+    if shape.page_size > 0:
+        pages = n_pages if n_pages is not None else batch * (shape.max_len // shape.page_size)
+        codes = torch.zeros((pages, hkv, shape.page_size * J), dtype=torch.uint8, device=device)
+        norms = torch.zeros((pages, hkv, shape.page_size, 2), dtype=torch.float16, device=device)
+        assert block_table is not None and block_table.dtype == torch.int32
+    else:
+        codes = torch.zeros((batch, hkv, shape.max_len * J), dtype=torch.uint8, device=device)
+        norms = torch.zeros((batch, hkv, shape.max_len, 2), dtype=torch.float16, device=device)
+    means = torch.zeros((batch, hkv, ng, HEAD_DIM), dtype=torch.float16, device=device)
+    return CodedCache(codes, norms, means, block_table)
+
+
+def nsn_build_codebook(samples: torch.Tensor, n_codes: int = N_CODES, iters: int = 50,
+                       workspace: torch.Tensor | None = None):
+    """samples: cuda fp32 [n][sub_dim].  Returns (codebook cuda fp16 [n_codes][sub_dim], mse per dim)."""
+    assert samples.is_cuda and samples.dtype == torch.float32 and samples.is_contiguous()
+    n, sub = samples.shape
+    shp = make_shape(sub, 1, 1, 64)
+    need = nsn_workspace_bytes(shp, NSN_OP_CODEBOOK, 1, n)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=samples.device)
+    codebook = torch.empty((n_codes, sub), dtype=torch.float16, device=samples.device)
+    mse = C.c_double(0.0)
+    _check(lib().nsn_build_codebook(samples.data_ptr(), n, sub, n_codes, iters, codebook.data_ptr(),
+                                    C.byref(mse), workspace.data_ptr(), workspace.numel(), _stream()))
+    return codebook, mse.value
+
+
+def nsn_encode(shape: nsn_shape, codebook: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+               seq_start: torch.Tensor, n_new: torch.Tensor, k_cache: CodedCache, v_cache: CodedCache,
+               freeze_means: bool = False, workspace: torch.Tensor | None = None) -> None:
+    """k, v: cuda fp16 [B][Hkv][max_new][128]; seq_start, n_new: cuda int32 [B]."""
+    assert k.is_cuda and k.dtype == torch.float16 and k.is_contiguous() and k.shape == v.shape
+    assert v.dtype == torch.float16 and v.is_contiguous()
+    assert codebook.dtype == torch.float16 and codebook.is_contiguous()
+    assert seq_start.dtype == torch.int32 and n_new.dtype == torch.int32
+    batch, hkv, max_new, d = k.shape
+    assert hkv == shape.n_kv_heads and d == HEAD_DIM
+    need = nsn_workspace_bytes(shape, NSN_OP_ENCODE, batch, max_new)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=k.device)
+    kc, vc = k_cache.c_struct(), v_cache.c_struct()
+    _check(lib().nsn_encode(C.byref(shape), codebook.data_ptr(), k.data_ptr(), v.data_ptr(), max_new,
+                            seq_start.data_ptr(), n_new.data_ptr(), batch, int(freeze_means),
+                            C.byref(kc), C.byref(vc), workspace.data_ptr(), workspace.numel(), _stream()))
+
+
+def nsn_decode_attention(shape: nsn_shape, codebook: torch.Tensor, q: torch.Tensor, k_cache: CodedCache,
+                         v_cache: CodedCache, seq_lens: torch.Tensor, max_seq_len: int,
+                         softmax_scale: float, n_splits: int = 0, out: torch.Tensor | None = None,
+                         workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """q: cuda fp16 [B][Hq][128]; returns cuda fp32 [B][Hq][128]."""
+    assert q.is_cuda and q.dtype == torch.float16 and q.is_contiguous()
+    assert seq_lens.dtype == torch.int32 and codebook.dtype == torch.float16
+    batch, hq, d = q.shape
+    assert hq == shape.n_q_heads and d == HEAD_DIM
+    if out is None:
+        out = torch.empty((batch, hq, d), dtype=torch.float32, device=q.device)
+    need = nsn_workspace_bytes(shape, NSN_OP_DECODE, batch, 0, n_splits)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    kc, vc = k_cache.c_struct(), v_cache.c_struct()
+    _check(lib().nsn_decode_attention(C.byref(shape), codebook.data_ptr(), q.data_ptr(), C.byref(kc),
+                                      C.byref(vc), seq_lens.data_ptr(), batch, max_seq_len,
+                                      float(softmax_scale), n_splits, out.data_ptr(), workspace.data_ptr(),
+                                      workspace.numel(), _stream()))
+    return out

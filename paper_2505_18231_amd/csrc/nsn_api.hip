@@ -1,0 +1,162 @@
+// extern "C" boundary of libnsn: argument validation and dispatch only.
+#include <cstdarg>
+#include <cstdio>
+
+#include "nsn_host.h"
+
+namespace nsn {
+
+static thread_local char g_err[256] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+static int check_shape(const nsn_shape* s) {
+  if (!s) {
+    set_error("shape is NULL");
+    return NSN_ERR_INVALID_ARG;
+  }
+  if (s->head_dim != kHeadDim || s->n_codes != kCodes || (s->sub_dim != 4 && s->sub_dim != 8)) {
+    set_error("unsupported shape: head_dim=%d (128), n_codes=%d (256), sub_dim=%d (4 or 8)", s->head_dim,
+              s->n_codes, s->sub_dim);
+    return NSN_ERR_UNSUPPORTED;
+  }
+  if (s->n_kv_heads <= 0 || s->n_q_heads <= 0 || s->n_q_heads % s->n_kv_heads != 0) {
+    set_error("n_q_heads=%d must be a positive multiple of n_kv_heads=%d", s->n_q_heads, s->n_kv_heads);
+    return NSN_ERR_INVALID_ARG;
+  }
+  if (s->n_q_heads / s->n_kv_heads > 8) {
+    set_error("more than 8 query heads per kv head is not supported");
+    return NSN_ERR_UNSUPPORTED;
+  }
+  if (s->group_size < 0 || s->group_size % 64 != 0) {
+    set_error("group_size=%d must be 0 or a multiple of 64", s->group_size);
+    return NSN_ERR_INVALID_ARG;
+  }
+  if (s->max_len <= 0 || s->max_len % 64 != 0) {
+    set_error("max_len=%d must be a positive multiple of 64", s->max_len);
+    return NSN_ERR_INVALID_ARG;
+  }
+  if (s->page_size < 0 || s->page_size % 64 != 0 || (s->page_size > 0 && s->max_len % s->page_size != 0)) {
+    set_error("page_size=%d must be 0 or a multiple of 64 dividing max_len=%d", s->page_size, s->max_len);
+    return NSN_ERR_INVALID_ARG;
+  }
+  return NSN_OK;
+}
+
+static int check_cache(const nsn_shape* s, const nsn_cache* c, const char* name) {
+  if (!c || !c->codes || !c->norms || !c->means) {
+    set_error("%s cache or one of its pointers is NULL", name);
+    return NSN_ERR_INVALID_ARG;
+  }
+  if (s->page_size > 0 && !c->block_table) {
+    set_error("%s cache: paged layout needs a block_table", name);
+    return NSN_ERR_INVALID_ARG;
+  }
+  return NSN_OK;
+}
+
+}  // namespace nsn
+
+using namespace nsn;
+
+extern "C" {
+
+int nsn_k_code_offset(int J, int tt, int j) { return k_code_offset(J, tt, j); }
+int nsn_v_code_offset(int J, int tt, int j) { return v_code_offset(J, tt, j); }
+
+int nsn_max_groups(const nsn_shape* shape) {
+  if (check_shape(shape) != NSN_OK) return 0;
+  return make_geometry(*shape).n_groups_max;
+}
+
+const char* nsn_last_error(void) { return g_err; }
+
+size_t nsn_workspace_bytes(const nsn_shape* shape, int op, int batch, int64_t n, int n_splits) {
+  if (op == NSN_OP_CODEBOOK) {
+    if (!shape || (shape->sub_dim != 4 && shape->sub_dim != 8) || n <= 0) return 0;
+    return codebook_workspace_bytes(shape->sub_dim, n);
+  }
+  if (check_shape(shape) != NSN_OK || batch <= 0) return 0;
+  if (op == NSN_OP_ENCODE) return n > 0 ? encode_workspace_bytes(*shape, batch, n) : 0;
+  if (op == NSN_OP_DECODE)
+    return decode_workspace_bytes(*shape, batch, decode_pick_splits(*shape, batch, shape->max_len, n_splits));
+  return 0;
+}
+
+int nsn_build_codebook(const float* samples_dev, int64_t n_samples, int sub_dim, int n_codes, int iters,
+                       void* codebook_dev, double* mse_host, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  if (n_codes != kCodes || (sub_dim != 4 && sub_dim != 8)) {
+    set_error("unsupported codebook: n_codes=%d (256), sub_dim=%d (4 or 8)", n_codes, sub_dim);
+    return NSN_ERR_UNSUPPORTED;
+  }
+  if (!samples_dev || !codebook_dev || n_samples < n_codes || iters < 0) {
+    set_error("build_codebook: null pointer, n_samples=%lld < n_codes, or iters=%d < 0", (long long)n_samples,
+              iters);
+    return NSN_ERR_INVALID_ARG;
+  }
+  if (!workspace || workspace_bytes < codebook_workspace_bytes(sub_dim, n_samples)) {
+    set_error("build_codebook: workspace of %zu bytes needed", codebook_workspace_bytes(sub_dim, n_samples));
+    return NSN_ERR_WORKSPACE;
+  }
+  const int rc = codebook_run(samples_dev, n_samples, sub_dim, iters, codebook_dev, mse_host, workspace,
+                              static_cast<hipStream_t>(stream));
+  if (rc == NSN_ERR_HIP) set_error("build_codebook: HIP error: %s", hipGetErrorString(hipGetLastError()));
+  return rc;
+}
+
+int nsn_encode(const nsn_shape* shape, const void* codebook_dev, const void* k_fp16, const void* v_fp16,
+               int max_new, const int32_t* seq_start_dev, const int32_t* n_new_dev, int batch, int freeze_means,
+               const nsn_cache* k_cache, const nsn_cache* v_cache, void* workspace, size_t workspace_bytes,
+               void* stream) {
+  int rc = check_shape(shape);
+  if (rc != NSN_OK) return rc;
+  if ((rc = check_cache(shape, k_cache, "K")) != NSN_OK) return rc;
+  if ((rc = check_cache(shape, v_cache, "V")) != NSN_OK) return rc;
+  if (!codebook_dev || !k_fp16 || !v_fp16 || !seq_start_dev || !n_new_dev || batch < 0 || max_new < 0) {
+    set_error("encode: null pointer or negative size");
+    return NSN_ERR_INVALID_ARG;
+  }
+  if (batch == 0 || max_new == 0) return NSN_OK;
+  if (!workspace || workspace_bytes < encode_workspace_bytes(*shape, batch, max_new)) {
+    set_error("encode: workspace of %zu bytes needed", encode_workspace_bytes(*shape, batch, max_new));
+    return NSN_ERR_WORKSPACE;
+  }
+  rc = encode_launch(*shape, codebook_dev, k_fp16, v_fp16, max_new, seq_start_dev, n_new_dev, batch,
+                     freeze_means != 0, *k_cache, *v_cache, workspace, static_cast<hipStream_t>(stream));
+  if (rc == NSN_ERR_HIP) set_error("encode: launch failed: %s", hipGetErrorString(hipGetLastError()));
+  return rc;
+}
+
+int nsn_decode_attention(const nsn_shape* shape, const void* codebook_dev, const void* q_fp16,
+                         const nsn_cache* k_cache, const nsn_cache* v_cache, const int32_t* seq_lens_dev,
+                         int batch, int max_seq_len, float softmax_scale, int n_splits, float* out,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != NSN_OK) return rc;
+  if ((rc = check_cache(shape, k_cache, "K")) != NSN_OK) return rc;
+  if ((rc = check_cache(shape, v_cache, "V")) != NSN_OK) return rc;
+  if (!codebook_dev || !q_fp16 || !seq_lens_dev || !out || batch < 0 || n_splits < 0 || max_seq_len < 0 ||
+      max_seq_len > shape->max_len) {
+    set_error("decode: null pointer, negative size, or max_seq_len=%d beyond max_len=%d", max_seq_len,
+              shape->max_len);
+    return NSN_ERR_INVALID_ARG;
+  }
+  if (batch == 0) return NSN_OK;
+  const int splits = decode_pick_splits(*shape, batch, max_seq_len, n_splits);
+  if (!workspace || workspace_bytes < decode_workspace_bytes(*shape, batch, splits)) {
+    set_error("decode: workspace of %zu bytes needed", decode_workspace_bytes(*shape, batch, splits));
+    return NSN_ERR_WORKSPACE;
+  }
+  rc = decode_launch(*shape, codebook_dev, q_fp16, *k_cache, *v_cache, seq_lens_dev, batch, max_seq_len,
+                     softmax_scale, splits, out, workspace, static_cast<hipStream_t>(stream));
+  if (rc == NSN_ERR_HIP) set_error("decode: launch failed: %s", hipGetErrorString(hipGetLastError()));
+  return rc;
+}
+
+}  // extern "C"

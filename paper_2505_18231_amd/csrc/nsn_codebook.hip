@@ -1,0 +1,124 @@
+// K-Means codebook on standard-normal samples (Sec. 3.4, the K-Means baseline).
+//
+// Lloyd iterations entirely on the device, deterministic (no atomics):
+//   km_assign_kernel  nearest centroid per sample (same fp32-scan + fp64-recheck search as the
+//                     encoder), per-block fp64 error sums
+//   km_update_kernel  one workgroup per cluster: fp64 mean of its members, fixed reduction order;
+//                     an empty cluster keeps its centroid
+#include "nsn_host.h"
+#include "nsn_vq.h"
+
+namespace nsn {
+
+constexpr int kAssignBlocks = 1024;
+
+__global__ void km_init_kernel(const float* __restrict__ samples, double* __restrict__ centroids, int n_elems) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_elems) centroids[i] = (double)samples[i];
+}
+
+__global__ void km_round_kernel(double* __restrict__ centroids, __half* __restrict__ out, int n_elems) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_elems) {
+    const __half hv = f64_to_f16(centroids[i]);
+    out[i] = hv;
+    centroids[i] = (double)__half2float(hv);
+  }
+}
+
+template <int SUB>
+__global__ __launch_bounds__(256) void km_assign_kernel(const float* __restrict__ samples, int64_t n,
+                                                        const double* __restrict__ centroids,
+                                                        uint8_t* __restrict__ assign,
+                                                        double* __restrict__ block_err) {
+  __shared__ VqTables<SUB> T;
+  __shared__ double red[4];
+  vq_tables_fill<SUB>(T, [&](int c, int i) { return centroids[c * SUB + i]; });
+  double err = 0.0;
+  for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * 256) {
+    double y[SUB];
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) y[i] = (double)samples[idx * SUB + i];
+    const int code = vq_search<SUB>(T, y);
+    assign[idx] = (uint8_t)code;
+    err += exact_dist<SUB>(T, y, code);
+  }
+  err = xor_sum(err, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = err;
+  __syncthreads();
+  if (threadIdx.x == 0) block_err[blockIdx.x] = ((red[0] + red[1]) + red[2]) + red[3];
+}
+
+template <int SUB>
+__global__ __launch_bounds__(256) void km_update_kernel(const float* __restrict__ samples, int64_t n,
+                                                        const uint8_t* __restrict__ assign,
+                                                        double* __restrict__ centroids) {
+  __shared__ double red[4][SUB + 1];
+  const int k = blockIdx.x;
+  double sum[SUB];
+#pragma unroll
+  for (int i = 0; i < SUB; ++i) sum[i] = 0.0;
+  double cnt = 0.0;
+  for (int64_t idx = threadIdx.x; idx < n; idx += 256) {
+    if (assign[idx] == k) {
+#pragma unroll
+      for (int i = 0; i < SUB; ++i) sum[i] += (double)samples[idx * SUB + i];
+      cnt += 1.0;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < SUB; ++i) sum[i] = xor_sum(sum[i], 64);
+  cnt = xor_sum(cnt, 64);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) red[wave][i] = sum[i];
+    red[wave][SUB] = cnt;
+  }
+  __syncthreads();
+  if (threadIdx.x <= SUB) {
+    const int i = threadIdx.x;
+    const double tot_cnt = ((red[0][SUB] + red[1][SUB]) + red[2][SUB]) + red[3][SUB];
+    if (i < SUB && tot_cnt > 0.0) centroids[k * SUB + i] = (((red[0][i] + red[1][i]) + red[2][i]) + red[3][i]) / tot_cnt;
+  }
+}
+
+size_t codebook_workspace_bytes(int sub_dim, int64_t n_samples) {
+  return (size_t)kCodes * sub_dim * sizeof(double) + kAssignBlocks * sizeof(double) +
+         (size_t)((n_samples + 255) / 256) * 256;
+}
+
+template <int SUB>
+static int codebook_run_t(const float* samples, int64_t n, int iters, void* codebook_out, double* mse_host,
+                          void* workspace, hipStream_t stream) {
+  double* centroids = static_cast<double*>(workspace);
+  double* block_err = centroids + kCodes * SUB;
+  uint8_t* assign = reinterpret_cast<uint8_t*>(block_err + kAssignBlocks);
+  const int n_elems = kCodes * SUB;
+  km_init_kernel<<<(n_elems + 255) / 256, 256, 0, stream>>>(samples, centroids, n_elems);
+  for (int it = 0; it < iters; ++it) {
+    km_assign_kernel<SUB><<<kAssignBlocks, 256, 0, stream>>>(samples, n, centroids, assign, block_err);
+    km_update_kernel<SUB><<<kCodes, 256, 0, stream>>>(samples, n, assign, centroids);
+  }
+  km_round_kernel<<<(n_elems + 255) / 256, 256, 0, stream>>>(centroids, static_cast<__half*>(codebook_out), n_elems);
+  km_assign_kernel<SUB><<<kAssignBlocks, 256, 0, stream>>>(samples, n, centroids, assign, block_err);
+  if (hipGetLastError() != hipSuccess) return NSN_ERR_HIP;
+  double host_err[kAssignBlocks];
+  if (hipMemcpyAsync(host_err, block_err, sizeof(host_err), hipMemcpyDeviceToHost, stream) != hipSuccess)
+    return NSN_ERR_HIP;
+  if (hipStreamSynchronize(stream) != hipSuccess) return NSN_ERR_HIP;
+  if (mse_host) {
+    double tot = 0.0;
+    for (int i = 0; i < kAssignBlocks; ++i) tot += host_err[i];
+    *mse_host = tot / ((double)n * SUB);
+  }
+  return NSN_OK;
+}
+
+int codebook_run(const float* samples, int64_t n_samples, int sub_dim, int iters, void* codebook_out,
+                 double* mse_host, void* workspace, hipStream_t stream) {
+  return sub_dim == 8 ? codebook_run_t<8>(samples, n_samples, iters, codebook_out, mse_host, workspace, stream)
+                      : codebook_run_t<4>(samples, n_samples, iters, codebook_out, mse_host, workspace, stream);
+}
+
+}  // namespace nsn

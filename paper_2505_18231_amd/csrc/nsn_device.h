@@ -1,0 +1,83 @@
+// Device-side helpers shared by the encode / decode / codebook kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/nsn.h"
+
+namespace nsn {
+
+constexpr int kHeadDim = 128;
+constexpr int kCodes = 256;
+constexpr int kBlockBytes = 1024;  // one code block: TB tokens x J bytes
+constexpr double kInvSqrtD = 0.08838834764831844055;  // 1/sqrt(128)
+constexpr double kSqrtD = 11.31370849898476039041;     // sqrt(128)
+
+// ---- cache addressing -----------------------------------------------------------------
+struct CacheView {
+  uint8_t* codes;
+  __half2* norms;
+  __half* means;
+  const int32_t* block_table;
+};
+
+struct Geometry {
+  int J;            // code bytes per token
+  int TB;           // tokens per 1 KiB code block
+  int n_q_heads, n_kv_heads;
+  int group_size;   // 0 = one group
+  int n_groups_max; // mean vectors per (sequence, kv-head)
+  int page_tokens;  // tokens per placement unit: page_size if paged, else max_len
+  int pages_per_seq;  // max_len / page_size if paged, else 1
+  int paged;
+};
+
+__host__ __device__ inline int k_code_offset(int J, int tt, int j) {
+  const int W = J >> 2, NT = (kBlockBytes / J) >> 4;
+  return (((j / W) * 16 + (tt & 15)) * NT + (tt >> 4)) * W + (j % W);
+}
+__host__ __device__ inline int v_code_offset(int J, int tt, int j) {
+  const int hsel = (J == 32) ? (j >> 4) : (tt >> 5);
+  return (((((tt & 31) >> 3) * 16 + (j & 15)) * 2 + hsel) << 3) + (tt & 7);
+}
+
+// Index (in tokens) of the first token of the placement unit holding token t of sequence b.
+__device__ inline int64_t unit_token_base(const Geometry& g, const int32_t* block_table, int b, int h,
+                                          int t) {
+  int64_t page = b;
+  if (g.paged) page = block_table[(int64_t)b * g.pages_per_seq + t / g.page_tokens];
+  return (page * g.n_kv_heads + h) * (int64_t)g.page_tokens;
+}
+__device__ inline int token_in_unit(const Geometry& g, int t) { return g.paged ? t % g.page_tokens : t; }
+__device__ inline int group_of(const Geometry& g, int t) { return g.group_size > 0 ? t / g.group_size : 0; }
+
+// ---- numeric helpers ------------------------------------------------------------------
+// fp64 -> fp16, round to nearest even in a single rounding: go through fp32 with
+// round-to-odd (sticky bit in the last place), then the hardware fp32 -> fp16 rounding.
+__device__ inline __half f64_to_f16(double x) {
+  float f = (float)x;
+  const double r = x - (double)f;
+  if (r != 0.0 && f != 0.0f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 1u) == 0u) {
+      const bool grow = (r > 0.0) == (f > 0.0f);
+      u = grow ? u + 1u : u - 1u;
+      f = __uint_as_float(u);
+    }
+  }
+  return __float2half_rn(f);
+}
+
+template <typename T>
+__device__ inline T xor_sum(T v, int width) {  // butterfly sum over groups of `width` lanes
+  for (int m = 1; m < width; m <<= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+  for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+  return v;
+}
+
+}  // namespace nsn

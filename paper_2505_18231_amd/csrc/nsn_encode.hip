@@ -1,0 +1,245 @@
+// KV encoder kernels: Normalize - Shift - Normalize (Sec. 3.2), Hadamard rotation (Sec. 2),
+// nearest-codeword search (Eq. 1), scale adjustment (Sec. 3.3).
+//
+// Three launches per call:
+//   enc_stats_kernel  per token: b = fp16(||x|| / sqrt(d)); per chunk: fp64 partial sums of x / b
+//   enc_means_kernel  per group: o = fp16(sum of partials / count)           (skipped in append mode)
+//   enc_quant_kernel  per token: (x / b - o) -> s2 -> rotate -> codes, a = fp16(b * s2 * alpha)
+// Normalisation, rotation and the dot products that feed fp16 roundings run in fp64 (same rate
+// as fp32 on this chip's vector units); only the 256-way distance scan runs in fp32.
+#include "nsn_host.h"
+#include "nsn_vq.h"
+
+namespace nsn {
+
+// ---------------------------------------------------------------------------------------
+// Stage A: first Normalize scale per token, partial channel sums of the normalised tokens.
+// grid (chunk, kv_head * 2 + tensor, sequence), block 256 = 4 waves; a wave owns one token
+// at a time, a lane owns two channels.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void enc_stats_kernel(Geometry g, const __half* __restrict__ k_in,
+                                                        const __half* __restrict__ v_in, int max_new,
+                                                        int max_len, const int32_t* __restrict__ seq_start,
+                                                        const int32_t* __restrict__ n_new, CacheView kc,
+                                                        CacheView vc, double* __restrict__ partial,
+                                                        int chunk_tokens, int n_chunks) {
+  const int chunk = blockIdx.x, h = blockIdx.y >> 1, tensor = blockIdx.y & 1, b = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const CacheView& cv = tensor ? vc : kc;
+  const __half* in = (tensor ? v_in : k_in) + ((int64_t)(b * g.n_kv_heads + h) * max_new) * kHeadDim;
+  const int start = seq_start[b];
+  const int count = min(n_new[b], max_new);
+  const int t_end = min((chunk + 1) * chunk_tokens, count);
+
+  double acc0 = 0.0, acc1 = 0.0;
+  for (int t = chunk * chunk_tokens + wave; t < t_end; t += 4) {
+    const int pos = start + t;
+    if (pos >= max_len) break;
+    const __half2 xv = *reinterpret_cast<const __half2*>(in + (int64_t)t * kHeadDim + 2 * lane);
+    const double x0 = (double)__low2float(xv), x1 = (double)__high2float(xv);
+    const double ss = xor_sum(x0 * x0 + x1 * x1, 64);
+    const double s1 = sqrt(ss) / kSqrtD;
+    const __half b16 = f64_to_f16(s1);
+    const double bb = (double)__half2float(b16);
+    if (bb != 0.0) {
+      acc0 += x0 / bb;
+      acc1 += x1 / bb;
+    }
+    if (lane == 0) {
+      const int64_t base = unit_token_base(g, cv.block_table, b, h, pos);
+      reinterpret_cast<__half*>(cv.norms)[2 * (base + token_in_unit(g, pos)) + 1] = b16;
+    }
+  }
+  __shared__ double red[4][kHeadDim];
+  red[wave][2 * lane] = acc0;
+  red[wave][2 * lane + 1] = acc1;
+  __syncthreads();
+  if (threadIdx.x < kHeadDim) {
+    const int c = threadIdx.x;
+    const double s = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
+    partial[((((int64_t)(b * g.n_kv_heads + h) * 2 + tensor) * n_chunks) + chunk) * kHeadDim + c] = s;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Stage A2: Shift vector of every new group.  grid (group-in-call, kv_head * 2 + tensor, sequence),
+// block 128 (one thread per channel); partial sums are added in chunk order.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(128) void enc_means_kernel(Geometry g, int max_new, int max_len,
+                                                        const int32_t* __restrict__ seq_start,
+                                                        const int32_t* __restrict__ n_new, CacheView kc,
+                                                        CacheView vc, const double* __restrict__ partial,
+                                                        int chunk_tokens, int n_chunks) {
+  const int gl = blockIdx.x, h = blockIdx.y >> 1, tensor = blockIdx.y & 1, b = blockIdx.z;
+  const int c = threadIdx.x;
+  const CacheView& cv = tensor ? vc : kc;
+  const int start = seq_start[b];
+  const int count = min(min(n_new[b], max_new), max_len - start);
+  int first_chunk, last_chunk, tokens, g_abs;
+  if (g.group_size > 0) {  // chunk_tokens == group_size
+    first_chunk = gl;
+    last_chunk = gl + 1;
+    tokens = min(g.group_size, count - gl * g.group_size);
+    g_abs = start / g.group_size + gl;
+  } else {
+    first_chunk = 0;
+    last_chunk = (count + chunk_tokens - 1) / chunk_tokens;
+    tokens = count;
+    g_abs = 0;
+  }
+  if (tokens <= 0 || g_abs >= g.n_groups_max) return;
+  const double* p = partial + (((int64_t)(b * g.n_kv_heads + h) * 2 + tensor) * n_chunks) * kHeadDim + c;
+  double s = 0.0;
+  for (int k = first_chunk; k < last_chunk; ++k) s += p[(int64_t)k * kHeadDim];
+  cv.means[((int64_t)(b * g.n_kv_heads + h) * g.n_groups_max + g_abs) * kHeadDim + c] =
+      f64_to_f16(s / (double)tokens);
+}
+
+// ---------------------------------------------------------------------------------------
+// Stage B: shift, second Normalize, rotation, search, scale adjustment, stores.
+// grid (64-token chunk, kv_head * 2 + tensor, sequence), block 256.  A lane owns one
+// sub-vector (SUB channels) of one token; a wave covers 64 / J tokens at a time.
+// ---------------------------------------------------------------------------------------
+template <int SUB>
+__global__ __launch_bounds__(256) void enc_quant_kernel(Geometry g, const __half* __restrict__ codebook,
+                                                        const __half* __restrict__ k_in,
+                                                        const __half* __restrict__ v_in, int max_new,
+                                                        int max_len, const int32_t* __restrict__ seq_start,
+                                                        const int32_t* __restrict__ n_new, CacheView kc,
+                                                        CacheView vc) {
+  constexpr int J = kHeadDim / SUB;  // lanes per token
+  constexpr int TPW = 64 / J;        // tokens per wave step
+  __shared__ VqTables<SUB> T;
+  vq_tables_fill<SUB>(T, [&](int c, int i) { return (double)__half2float(codebook[c * SUB + i]); });
+
+  const int h = blockIdx.y >> 1, tensor = blockIdx.y & 1, b = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int jj = lane % J, tk = lane / J;
+  const CacheView& cv = tensor ? vc : kc;
+  const __half* in = (tensor ? v_in : k_in) + ((int64_t)(b * g.n_kv_heads + h) * max_new) * kHeadDim;
+  const int start = seq_start[b];
+  const int count = min(n_new[b], max_new);
+  const int t_begin = blockIdx.x * 64 + wave * 16;
+  if (blockIdx.x * 64 >= count) return;
+
+  for (int it = 0; it < 16 / TPW; ++it) {
+    const int t = t_begin + it * TPW + tk;
+    const int pos = start + t;
+    const bool valid = (t < count) && (pos < max_len);
+    double v[SUB];
+    double bb = 0.0;
+    int64_t base = 0;
+    int tin = 0;
+    if (valid) {
+      base = unit_token_base(g, cv.block_table, b, h, pos);
+      tin = token_in_unit(g, pos);
+      bb = (double)__half2float(reinterpret_cast<const __half*>(cv.norms)[2 * (base + tin) + 1]);
+      const __half* xp = in + (int64_t)t * kHeadDim + jj * SUB;
+      const __half* op =
+          cv.means + ((int64_t)(b * g.n_kv_heads + h) * g.n_groups_max + min(group_of(g, pos), g.n_groups_max - 1)) *
+                         kHeadDim + jj * SUB;
+#pragma unroll
+      for (int i = 0; i < SUB; ++i) {
+        const double x = (double)__half2float(xp[i]);
+        const double o = (double)__half2float(op[i]);
+        v[i] = (bb != 0.0 ? x / bb : 0.0) - o;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < SUB; ++i) v[i] = 0.0;
+    }
+    // second Normalize
+    double ss = 0.0;
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) ss += v[i] * v[i];
+    ss = xor_sum(ss, J);
+    const double s2 = sqrt(ss) / kSqrtD;
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) v[i] = (s2 != 0.0) ? v[i] / s2 : 0.0;
+    // Walsh-Hadamard butterflies: channel bits 0..log2(SUB)-1 in registers, the rest across lanes
+#pragma unroll
+    for (int s = 1; s < SUB; s <<= 1) {
+#pragma unroll
+      for (int i = 0; i < SUB; ++i) {
+        if ((i & s) == 0) {
+          const double a0 = v[i], a1 = v[i | s];
+          v[i] = a0 + a1;
+          v[i | s] = a0 - a1;
+        }
+      }
+    }
+#pragma unroll
+    for (int m = 1; m < J; m <<= 1) {
+      const bool upper = (jj & m) != 0;
+#pragma unroll
+      for (int i = 0; i < SUB; ++i) {
+        const double other = __shfl_xor(v[i], m, 64);
+        v[i] = upper ? other - v[i] : v[i] + other;
+      }
+    }
+    double y[SUB];
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) y[i] = v[i] * kInvSqrtD;
+
+    const int code = vq_search<SUB>(T, y);
+
+    // scale adjustment: alpha = ||y||^2 / (y . y_Q)
+    double dot = 0.0, nrm2 = 0.0;
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) {
+      dot += y[i] * T.cx[code][i];
+      nrm2 += y[i] * y[i];
+    }
+    dot = xor_sum(dot, J);
+    nrm2 = xor_sum(nrm2, J);
+    const double alpha = (dot > 1e-12 * kHeadDim) ? nrm2 / dot : 1.0;
+    if (valid) {
+      const int blk = tin / g.TB, tt = tin % g.TB;
+      const int off = tensor ? v_code_offset(J, tt, jj) : k_code_offset(J, tt, jj);
+      cv.codes[base * J + (int64_t)blk * kBlockBytes + off] = (uint8_t)code;
+      if (jj == 0) reinterpret_cast<__half*>(cv.norms)[2 * (base + tin)] = f64_to_f16(bb * s2 * alpha);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+static int encode_chunk_tokens(const nsn_shape& s) { return s.group_size > 0 ? s.group_size : 256; }
+
+size_t encode_workspace_bytes(const nsn_shape& s, int batch, int64_t max_new) {
+  const int ct = encode_chunk_tokens(s);
+  const int64_t n_chunks = (max_new + ct - 1) / ct;
+  return (size_t)batch * s.n_kv_heads * 2 * n_chunks * kHeadDim * sizeof(double);
+}
+
+int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, const void* v_in, int max_new,
+                  const int32_t* seq_start, const int32_t* n_new, int batch, int freeze_means,
+                  const nsn_cache& kc, const nsn_cache& vc, void* workspace, hipStream_t stream) {
+  const Geometry g = make_geometry(s);
+  const CacheView kv = make_view(kc), vv = make_view(vc);
+  const int ct = encode_chunk_tokens(s);
+  const int n_chunks = (max_new + ct - 1) / ct;
+  double* partial = static_cast<double*>(workspace);
+  const dim3 grid_a(n_chunks, s.n_kv_heads * 2, batch);
+  enc_stats_kernel<<<grid_a, 256, 0, stream>>>(g, (const __half*)k_in, (const __half*)v_in, max_new, s.max_len,
+                                               seq_start, n_new, kv, vv, partial, ct, n_chunks);
+  if (!freeze_means) {
+    const int n_groups_new = s.group_size > 0 ? n_chunks : 1;
+    const dim3 grid_m(n_groups_new, s.n_kv_heads * 2, batch);
+    enc_means_kernel<<<grid_m, 128, 0, stream>>>(g, max_new, s.max_len, seq_start, n_new, kv, vv, partial, ct,
+                                                 n_chunks);
+  }
+  const dim3 grid_b((max_new + 63) / 64, s.n_kv_heads * 2, batch);
+  if (s.sub_dim == 8)
+    enc_quant_kernel<8><<<grid_b, 256, 0, stream>>>(g, (const __half*)codebook, (const __half*)k_in,
+                                                    (const __half*)v_in, max_new, s.max_len, seq_start, n_new, kv,
+                                                    vv);
+  else
+    enc_quant_kernel<4><<<grid_b, 256, 0, stream>>>(g, (const __half*)codebook, (const __half*)k_in,
+                                                    (const __half*)v_in, max_new, s.max_len, seq_start, n_new, kv,
+                                                    vv);
+  return hipGetLastError() == hipSuccess ? NSN_OK : NSN_ERR_HIP;
+}
+
+}  // namespace nsn

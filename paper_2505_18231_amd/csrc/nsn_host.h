@@ -1,0 +1,49 @@
+// Host-side glue shared by the translation units of libnsn.
+#pragma once
+
+#include "nsn_device.h"
+
+namespace nsn {
+
+inline Geometry make_geometry(const nsn_shape& s) {
+  Geometry g;
+  g.J = s.head_dim / s.sub_dim;
+  g.TB = kBlockBytes / g.J;
+  g.n_q_heads = s.n_q_heads;
+  g.n_kv_heads = s.n_kv_heads;
+  g.group_size = s.group_size;
+  g.n_groups_max = s.group_size > 0 ? (s.max_len + s.group_size - 1) / s.group_size : 1;
+  g.paged = s.page_size > 0;
+  g.page_tokens = g.paged ? s.page_size : s.max_len;
+  g.pages_per_seq = g.paged ? s.max_len / s.page_size : 1;
+  return g;
+}
+
+inline CacheView make_view(const nsn_cache& c) {
+  CacheView v;
+  v.codes = c.codes;
+  v.norms = static_cast<__half2*>(c.norms);
+  v.means = static_cast<__half*>(c.means);
+  v.block_table = c.block_table;
+  return v;
+}
+
+void set_error(const char* fmt, ...);
+
+// per-operation entry points implemented in the .hip files
+size_t encode_workspace_bytes(const nsn_shape& s, int batch, int64_t max_new);
+int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, const void* v_in, int max_new,
+                  const int32_t* seq_start, const int32_t* n_new, int batch, int freeze_means,
+                  const nsn_cache& kc, const nsn_cache& vc, void* workspace, hipStream_t stream);
+
+int decode_pick_splits(const nsn_shape& s, int batch, int max_seq_len, int requested);
+size_t decode_workspace_bytes(const nsn_shape& s, int batch, int n_splits);
+int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
+                  const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
+                  int n_splits, float* out, void* workspace, hipStream_t stream);
+
+size_t codebook_workspace_bytes(int sub_dim, int64_t n_samples);
+int codebook_run(const float* samples, int64_t n_samples, int sub_dim, int iters, void* codebook_out,
+                 double* mse_host, void* workspace, hipStream_t stream);
+
+}  // namespace nsn

@@ -11,3 +11,24 @@ if ROOT not in sys.path:
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
     config.addinivalue_line("markers", "slow: CPU test that takes more than ~20 s")
+
+
+@pytest.fixture(scope="session")
+def codebooks():
+    """Small K-Means codebooks from the oracle (fp16-representable), keyed by sub_dim."""
+    from oracle import nsn_oracle as O
+    from paper_2505_18231_amd import synth
+    out = {}
+    for sub in (4, 8):
+        cb, _, _ = O.build_codebook(synth.codebook_samples(77, 1 << 14, sub), 256, 6)
+        out[sub] = cb
+    return out
+
+
+@pytest.fixture(scope="session")
+def gpu_api():
+    import torch
+    from paper_2505_18231_amd import api
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    api.lib()  # fails loudly if libnsn.so is not built
+    return api

@@ -1,0 +1,129 @@
+"""Test-side helpers: the cache layout written out in numpy from the formulas in include/nsn.h
+(independent of the library's own index code), and glue between oracle dictionaries and device
+cache buffers."""
+from __future__ import annotations
+
+import numpy as np
+
+D = 128
+BLOCK = 1024
+
+
+def code_offsets(J: int, kind: str) -> np.ndarray:
+    """[TB][J] byte offset inside a 1 KiB block of (token-in-block, sub-vector)."""
+    TB = BLOCK // J
+    tt, j = np.meshgrid(np.arange(TB), np.arange(J), indexing="ij")
+    if kind == "k":
+        W, NT = J // 4, TB // 16
+        return ((j // W * 16 + tt % 16) * NT + tt // 16) * W + j % W
+    hsel = (j // 16) if J == 32 else (tt // 32)
+    return (((tt % 32) // 8 * 16 + j % 16) * 2 + hsel) * 8 + tt % 8
+
+
+def pack_codes(codes: np.ndarray, kind: str, capacity: int) -> np.ndarray:
+    """codes u8 [L][J] -> layout bytes u8 [capacity * J] (capacity a multiple of the block tokens)."""
+    L, J = codes.shape
+    TB = BLOCK // J
+    assert capacity % TB == 0 and capacity >= L
+    full = np.zeros((capacity, J), dtype=np.uint8)
+    full[:L] = codes
+    off = code_offsets(J, kind).ravel()
+    out = np.zeros((capacity // TB, BLOCK), dtype=np.uint8)
+    out[:, off] = full.reshape(capacity // TB, TB * J)
+    return out.ravel()
+
+
+def unpack_codes(raw: np.ndarray, kind: str, J: int) -> np.ndarray:
+    """layout bytes u8 [capacity * J] -> codes u8 [capacity][J]."""
+    TB = BLOCK // J
+    off = code_offsets(J, kind).ravel()
+    blocks = raw.reshape(-1, BLOCK)
+    return blocks[:, off].reshape(blocks.shape[0] * TB, J)
+
+
+def n_groups(length: int, G: int) -> int:
+    return (length + G - 1) // G if G > 0 else 1
+
+
+class HostCache:
+    """Numpy mirror of one tensor kind's cache buffers (contiguous or paged)."""
+
+    def __init__(self, kind, batch, hkv, J, max_len, G, page_size=0, block_table=None, n_pages=None):
+        self.kind, self.batch, self.hkv, self.J, self.max_len, self.G = kind, batch, hkv, J, max_len, G
+        self.page = page_size
+        self.bt = block_table
+        self.ng = n_groups(max_len, G)
+        if page_size:
+            pages = n_pages if n_pages is not None else batch * (max_len // page_size)
+            self.codes = np.zeros((pages, hkv, page_size * J), dtype=np.uint8)
+            self.norms = np.zeros((pages, hkv, page_size, 2), dtype=np.float16)
+        else:
+            self.codes = np.zeros((batch, hkv, max_len * J), dtype=np.uint8)
+            self.norms = np.zeros((batch, hkv, max_len, 2), dtype=np.float16)
+        self.means = np.zeros((batch, hkv, self.ng, D), dtype=np.float16)
+
+    def put_unit(self, b, h, enc: dict, start: int = 0, write_means: bool = True):
+        """Store an oracle-encoded run of tokens [start, start+L) of unit (b, h)."""
+        L = enc["codes"].shape[0]
+        if write_means:
+            o = enc["o"]
+            first = start // self.G if self.G else 0
+            if self.G == 0:
+                self.means[b, h, 0] = o[0]
+            else:
+                ng_new = n_groups(L, self.G)
+                self.means[b, h, first:first + ng_new] = o[first:first + ng_new]
+        logical_codes = self.get_codes(b, h)
+        logical_norms = self.get_norms(b, h)
+        logical_codes[start:start + L] = enc["codes"]
+        logical_norms[start:start + L, 0] = enc["a"]
+        logical_norms[start:start + L, 1] = enc["b"]
+        self._set_logical(b, h, logical_codes, logical_norms)
+
+    # logical views -------------------------------------------------------------------------
+    def get_codes(self, b, h) -> np.ndarray:
+        if not self.page:
+            return unpack_codes(self.codes[b, h], self.kind, self.J)
+        parts = [unpack_codes(self.codes[self.bt[b, p], h], self.kind, self.J)
+                 for p in range(self.max_len // self.page)]
+        return np.concatenate(parts, axis=0)
+
+    def get_norms(self, b, h) -> np.ndarray:
+        if not self.page:
+            return self.norms[b, h].copy()
+        return np.concatenate([self.norms[self.bt[b, p], h] for p in range(self.max_len // self.page)], axis=0)
+
+    def _set_logical(self, b, h, codes, norms):
+        if not self.page:
+            self.codes[b, h] = pack_codes(codes, self.kind, self.max_len)
+            self.norms[b, h] = norms
+            return
+        for p in range(self.max_len // self.page):
+            sl = slice(p * self.page, (p + 1) * self.page)
+            self.codes[self.bt[b, p], h] = pack_codes(codes[sl], self.kind, self.page)
+            self.norms[self.bt[b, p], h] = norms[sl]
+
+    def unit_dict(self, b, h, length) -> dict:
+        """Oracle-style dictionary of the first `length` tokens of unit (b, h)."""
+        nm = self.get_norms(b, h)
+        return dict(codes=self.get_codes(b, h)[:length], a=nm[:length, 0], b=nm[:length, 1],
+                    o=self.means[b, h, :n_groups(length, self.G)])
+
+    # device transfer -----------------------------------------------------------------------
+    def to_device(self, api, shape, device="cuda"):
+        import torch
+        bt = None if self.bt is None else torch.from_numpy(self.bt.astype(np.int32)).to(device)
+        return api.CodedCache(torch.from_numpy(self.codes).to(device), torch.from_numpy(self.norms).to(device),
+                              torch.from_numpy(self.means).to(device), bt)
+
+    def from_device(self, dc):
+        self.codes = dc.codes.cpu().numpy()
+        self.norms = dc.norms.cpu().numpy()
+        self.means = dc.means.cpu().numpy()
+
+
+def max_rel_err(out: np.ndarray, ref: np.ndarray) -> float:
+    """max_i |out_i - ref_i| / max_i |ref_i| per row, worst row."""
+    num = np.abs(out - ref).max(axis=-1)
+    den = np.abs(ref).max(axis=-1)
+    return float((num / np.maximum(den, 1e-30)).max())

@@ -1,0 +1,97 @@
+"""GPU parity of nsn_decode_attention against the oracle, on oracle-encoded caches (so the decode
+check does not depend on the GPU encoder).  Tolerance: 2e-3 max relative error per output row
+(max_i |out_i - ref_i| / max_i |ref_i|), fp32 accumulation on the device, fp64 in the oracle."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import nsn_oracle as O
+from paper_2505_18231_amd import synth
+from tests import helpers
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+def build_case(seed, batch, hq, hkv, lens, sub, G, cb, page=0, max_len=None, per_seq=False):
+    J = 128 // sub
+    max_len = max_len or ((max(max(lens), 1) + 255) // 256) * 256
+    bt = synth.shuffled_page_table(seed, batch, max_len // page) if page else None
+    kc = helpers.HostCache("k", batch, hkv, J, max_len, G, page, bt)
+    vc = helpers.HostCache("v", batch, hkv, J, max_len, G, page, bt)
+    for b in range(batch):
+        for h in range(hkv):
+            if lens[b] == 0:
+                continue
+            kc.put_unit(b, h, O.encode(synth.make_k(seed, b, h, lens[b], per_seq=per_seq), cb, G))
+            vc.put_unit(b, h, O.encode(synth.make_v(seed, b, h, lens[b]), cb, G))
+    q = synth.make_q(seed, batch, hq)
+    return kc, vc, q, max_len
+
+
+def oracle_out(kc, vc, q, lens, hq, hkv, cb, G, scale):
+    batch = q.shape[0]
+    r = hq // hkv
+    ref = np.zeros((batch, hq, 128))
+    for b in range(batch):
+        if lens[b] == 0:
+            continue
+        for h in range(hkv):
+            ref[b, h * r:(h + 1) * r] = O.decode_attention(
+                q[b, h * r:(h + 1) * r].astype(np.float64), kc.unit_dict(b, h, lens[b]),
+                vc.unit_dict(b, h, lens[b]), cb, scale, G)
+    return ref
+
+
+def gpu_out(api, kc, vc, q, lens, hq, hkv, sub, G, cb, max_len, scale, page=0, n_splits=0):
+    import torch
+    shape = api.make_shape(sub, hq, hkv, max_len, G, page)
+    dk, dv = kc.to_device(api, shape), vc.to_device(api, shape)
+    cbd = torch.from_numpy(cb.astype(np.float16)).cuda()
+    out = api.nsn_decode_attention(shape, cbd, torch.from_numpy(q).cuda(), dk, dv,
+                                   torch.tensor(lens, dtype=torch.int32).cuda(), max(max(lens), 0), scale,
+                                   n_splits)
+    torch.cuda.synchronize()
+    return out.cpu().numpy().astype(np.float64)
+
+
+CASES = [
+    # name, batch, hq, hkv, lens, sub, G, page, splits
+    ("tiny-1bit", 1, 1, 1, [1024], 8, 0, 0, 0),
+    ("tiny-1bit-1split", 1, 1, 1, [1024], 8, 0, 0, 1),
+    ("tiny-1bit-3splits", 1, 1, 1, [1000], 8, 64, 0, 3),
+    ("gqa-2bit-ragged", 2, 8, 2, [777, 130], 4, 64, 0, 4),
+    ("gqa-2bit-onegroup", 2, 8, 2, [515, 1], 4, 0, 0, 0),
+    ("mha-2bit", 2, 4, 4, [333, 700], 4, 64, 0, 2),
+    ("paged-1bit", 3, 4, 2, [1000, 256, 37], 8, 0, 256, 0),
+    ("paged-2bit-groups", 2, 8, 2, [900, 511], 4, 128, 256, 5),
+    ("empty-and-short", 3, 2, 1, [0, 1, 65], 8, 64, 0, 2),
+]
+
+
+@pytest.mark.parametrize("name,batch,hq,hkv,lens,sub,G,page,splits", CASES, ids=[c[0] for c in CASES])
+def test_decode_matches_oracle(gpu_api, codebooks, name, batch, hq, hkv, lens, sub, G, page, splits):
+    print(f"case {name} lens={lens} sub={sub} G={G} page={page} splits={splits}", flush=True)
+    cb = codebooks[sub]
+    scale = 1.0 / math.sqrt(128)
+    kc, vc, q, max_len = build_case(100 + len(name), batch, hq, hkv, lens, sub, G, cb, page)
+    ref = oracle_out(kc, vc, q, lens, hq, hkv, cb, G, scale)
+    out = gpu_out(gpu_api, kc, vc, q, lens, hq, hkv, sub, G, cb, max_len, scale, page, splits)
+    for b in range(batch):
+        if lens[b] == 0:
+            assert np.all(out[b] == 0.0)
+    live = [b for b in range(batch) if lens[b] > 0]
+    err = helpers.max_rel_err(out[live], ref[live])
+    print(f"  max rel err {err:.3e}", flush=True)
+    assert err < TOL, err
+
+
+def test_split_count_does_not_change_the_result(gpu_api, codebooks):
+    cb = codebooks[4]
+    scale = 1.0 / math.sqrt(128)
+    lens = [1500, 640]
+    kc, vc, q, max_len = build_case(7, 2, 8, 2, lens, 4, 64, cb)
+    outs = [gpu_out(gpu_api, kc, vc, q, lens, 8, 2, 4, 64, cb, max_len, scale, 0, s) for s in (1, 2, 7)]
+    for o in outs[1:]:
+        assert helpers.max_rel_err(o, outs[0]) < 2e-5

@@ -1,0 +1,80 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, its layout
+index functions agree with the formulas of include/nsn.h, and argument errors are reported
+before anything touches a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2505_18231_amd import api
+from tests import helpers
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(api.LIB_PATH):
+        from paper_2505_18231_amd.build import build_library
+        build_library(verbose=False)
+    return api.lib()
+
+
+def test_exports_every_declared_symbol(L):
+    header = open(os.path.join(ROOT, "include", "nsn.h")).read()
+    names = set(re.findall(r"\b(nsn_[a-z_]+)\s*\(", header))
+    names -= {"nsn_shape", "nsn_cache"}
+    assert {"nsn_build_codebook", "nsn_encode", "nsn_decode_attention", "nsn_workspace_bytes"} <= names
+    for n in names:
+        assert hasattr(L, n), n
+
+
+@pytest.mark.parametrize("J", [16, 32])
+def test_layout_offsets_match_header_formulas_and_are_bijections(L, J):
+    TB = 1024 // J
+    for kind, fn in (("k", L.nsn_k_code_offset), ("v", L.nsn_v_code_offset)):
+        ref = helpers.code_offsets(J, kind)
+        got = np.array([[fn(J, tt, j) for j in range(J)] for tt in range(TB)])
+        assert np.array_equal(ref, got)
+        assert sorted(got.ravel().tolist()) == list(range(1024))
+
+
+def test_pack_unpack_roundtrip():
+    g = np.random.default_rng(0)
+    for J in (16, 32):
+        codes = g.integers(0, 256, size=(200, J), dtype=np.uint8)
+        for kind in "kv":
+            raw = helpers.pack_codes(codes, kind, 256)
+            assert np.array_equal(helpers.unpack_codes(raw, kind, J)[:200], codes)
+
+
+def test_shape_validation_and_error_text(L):
+    good = api.make_shape(4, 32, 8, 8192, 64)
+    assert api.nsn_workspace_bytes(good, api.NSN_OP_DECODE, 8, 0, 4) == 8 * 32 * 4 * 258 * 4
+    assert api.nsn_workspace_bytes(good, api.NSN_OP_ENCODE, 8, 8192) == 8 * 8 * 2 * 128 * 128 * 8
+    assert api.nsn_max_groups(good) == 128
+    assert api.nsn_max_groups(api.make_shape(8, 1, 1, 1024, 0)) == 1
+    bad = api.make_shape(5, 32, 8, 8192, 64)
+    assert api.nsn_workspace_bytes(bad, api.NSN_OP_DECODE, 8) == 0
+    kc = api.nsn_cache(None, None, None, None)
+    rc = L.nsn_encode(C.byref(bad), None, None, None, 1, None, None, 1, 0, C.byref(kc), C.byref(kc), None, 0, None)
+    assert rc == api.NSN_ERR_UNSUPPORTED and b"sub_dim" in L.nsn_last_error()
+    rc = L.nsn_encode(C.byref(good), None, None, None, 1, None, None, 1, 0, C.byref(kc), C.byref(kc), None, 0, None)
+    assert rc == api.NSN_ERR_INVALID_ARG
+    odd = api.make_shape(4, 32, 8, 8192, 48)
+    rc = L.nsn_decode_attention(C.byref(odd), None, None, C.byref(kc), C.byref(kc), None, 1, 1, 1.0, 0, None,
+                                None, 0, None)
+    assert rc == api.NSN_ERR_INVALID_ARG and b"group_size" in L.nsn_last_error()
+    rc = L.nsn_build_codebook(None, 1000, 8, 128, 1, None, None, None, 0, None)
+    assert rc == api.NSN_ERR_UNSUPPORTED
+
+
+def test_product_package_does_not_import_oracle():
+    pkg = os.path.join(ROOT, "paper_2505_18231_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("oracle's tests", ""), f
