@@ -23,15 +23,13 @@
  *     rotated channels) or 4 ("2-bit": one code byte per 4 rotated channels).
  *
  * Coded cache record (one tensor kind, K or V), per (sequence b, kv-head h):
- *   codes  J = head_dim/sub_dim bytes per token, stored in 1 KiB blocks of TB = 1024/J
- *          tokens (TB = 32 at J = 32, TB = 64 at J = 16).  Inside a block the byte of
- *          (token tt in [0,TB), sub-vector j in [0,J)) sits at
- *            K:  W = J/4, NT = TB/16:
- *                ((j/W * 16 + tt%16) * NT + tt/16) * W + j%W
- *            V:  ((tt%32)/8 * 16 + j%16) * 2 + (J == 32 ? j/16 : tt/32)) * 8 + tt%8
- *          (K keeps a token's codes together for the score contraction over channels;
- *          V keeps eight tokens of one sub-vector together for the contraction over
- *          tokens.)  nsn_k_code_offset / nsn_v_code_offset below return these offsets.
+ *   codes  J = head_dim/sub_dim bytes per token.  Inside one placement unit (see below) the
+ *          byte of (token t of the unit, sub-vector j in [0,J)) sits at
+ *            K:  t * J + j                                  (token-major)
+ *            V:  (t / J) * J*J + j * J + t % J              (blocks of J tokens, sub-vector-major)
+ *          K keeps a token's codes together for the score contraction over channels; V keeps
+ *          J consecutive tokens of one sub-vector together for the contraction over tokens.
+ *          nsn_k_code_offset / nsn_v_code_offset below return these offsets.
  *   norms  one (a, b) fp16 pair per token: b = s1 (first Normalize scale), a = s1*s2*alpha
  *          (second Normalize scale times the scale-adjustment factor of Sec. 3.3).
  *   means  fp16 [n_groups][head_dim]: the Shift vector o of every group of group_size
@@ -71,7 +69,8 @@ typedef struct nsn_shape {
   int32_t head_dim;   /* 128 */
   int32_t sub_dim;    /* 8 (1-bit) or 4 (2-bit) */
   int32_t n_codes;    /* 256 */
-  int32_t n_q_heads;  /* multiple of n_kv_heads; n_q_heads / n_kv_heads <= 8 */
+  int32_t n_q_heads;  /* multiple of n_kv_heads; n_q_heads / n_kv_heads <= 8 (<= 4 takes the
+                         matrix-core decode kernel, above that the lookup-table kernel) */
   int32_t n_kv_heads;
   int32_t group_size; /* G: tokens sharing one Shift mean; multiple of 64 (the paper uses 64),
                          or 0 = one group per sequence */
@@ -86,9 +85,9 @@ typedef struct nsn_cache {
   const int32_t* block_table; /* dev, paged layout only (else NULL) */
 } nsn_cache;
 
-/* Byte offset of (token-in-block tt, sub-vector j) inside a 1 KiB code block; J = codes per token. */
-int nsn_k_code_offset(int J, int tt, int j);
-int nsn_v_code_offset(int J, int tt, int j);
+/* Byte offset of the code of (token t, sub-vector j) inside a placement unit; J = codes per token. */
+int64_t nsn_k_code_offset(int J, int64_t t, int j);
+int64_t nsn_v_code_offset(int J, int64_t t, int j);
 /* Number of mean vectors kept per (sequence, kv-head): max_len / group_size rounded up, or 1. */
 int nsn_max_groups(const nsn_shape* shape);
 /* Text of the calling thread's most recent error ("" if none). Never NULL. */

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libnsn.so")
 NSN_OK = 0
 NSN_ERR_INVALID_ARG, NSN_ERR_UNSUPPORTED, NSN_ERR_WORKSPACE, NSN_ERR_HIP = -1, -2, -3, -4
 NSN_OP_ENCODE, NSN_OP_DECODE, NSN_OP_CODEBOOK = 0, 1, 2
-HEAD_DIM, N_CODES, BLOCK_BYTES = 128, 256, 1024
+HEAD_DIM, N_CODES = 128, 256
 
 
 class nsn_shape(C.Structure):
@@ -53,8 +53,9 @@ def lib() -> C.CDLL:
         L.nsn_workspace_bytes.restype = C.c_size_t
         L.nsn_workspace_bytes.argtypes = [C.POINTER(nsn_shape), C.c_int, C.c_int, C.c_int64, C.c_int]
         L.nsn_max_groups.argtypes = [C.POINTER(nsn_shape)]
-        L.nsn_k_code_offset.argtypes = [C.c_int] * 3
-        L.nsn_v_code_offset.argtypes = [C.c_int] * 3
+        for fn in (L.nsn_k_code_offset, L.nsn_v_code_offset):
+            fn.restype = C.c_int64
+            fn.argtypes = [C.c_int, C.c_int64, C.c_int]
         L.nsn_build_codebook.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                          C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
         L.nsn_encode.argtypes = [C.POINTER(nsn_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,

@@ -66,8 +66,8 @@ using namespace nsn;
 
 extern "C" {
 
-int nsn_k_code_offset(int J, int tt, int j) { return k_code_offset(J, tt, j); }
-int nsn_v_code_offset(int J, int tt, int j) { return v_code_offset(J, tt, j); }
+int64_t nsn_k_code_offset(int J, int64_t t, int j) { return k_code_offset(J, t, j); }
+int64_t nsn_v_code_offset(int J, int64_t t, int j) { return v_code_offset(J, t, j); }
 
 int nsn_max_groups(const nsn_shape* shape) {
   if (check_shape(shape) != NSN_OK) return 0;

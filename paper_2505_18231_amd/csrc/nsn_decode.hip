@@ -6,6 +6,8 @@
 //                     q . mean term, online softmax, value accumulation in the rotated /
 //                     codeword domain plus the mean-vector term) and emit an fp32 partial
 //   dec_merge_kernel  merge the splits (running max / sum), one inverse Hadamard per head
+#include <cstdlib>
+
 #include "nsn_host.h"
 
 namespace nsn {
@@ -50,8 +52,6 @@ __global__ __launch_bounds__(256) void dec_lut_kernel(Geometry g, const __half* 
                                                       const int32_t* __restrict__ seq_lens, float scale,
                                                       int n_splits, float* __restrict__ partial) {
   constexpr int J = kHeadDim / SUB;
-  constexpr int TB = kBlockBytes / J;
-  constexpr int W = J / 4, NT = TB / 16;
   constexpr int TS = 256 / J;  // token sub-groups of the value phase
   __shared__ float lut[J][kCodes];
   __shared__ float cb[kCodes][SUB];
@@ -128,14 +128,14 @@ __global__ __launch_bounds__(256) void dec_lut_kernel(Geometry g, const __half* 
     if (valid) {
       const int64_t base = unit_token_base(g, kc.block_table, b, h, t);
       const int tin = token_in_unit(g, t);
-      const int tt = tin % TB;
-      const uint8_t* kp = kc.codes + base * J + (int64_t)(tin / TB) * kBlockBytes;
+      const uint4* kp = reinterpret_cast<const uint4*>(kc.codes + (base + tin) * J);
       float sum = 0.f;
 #pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        const uint8_t* p8 = kp + ((gq * 16 + (tt & 15)) * NT + (tt >> 4)) * W;
+      for (int w4 = 0; w4 < J / 16; ++w4) {
+        const uint4 cw = kp[w4];
+        const uint32_t wds[4] = {cw.x, cw.y, cw.z, cw.w};
 #pragma unroll
-        for (int e = 0; e < W; ++e) sum += lut[gq * W + e][p8[e]];
+        for (int e = 0; e < 16; ++e) sum += lut[w4 * 16 + e][(wds[e >> 2] >> ((e & 3) * 8)) & 0xff];
       }
       const __half2 nk = kc.norms[base + tin];
       score = scale * (__low2float(nk) * sum + __high2float(nk) * qo_s[group_of(g, t) - g_first]);
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(256) void dec_lut_kernel(Geometry g, const __half* 
       if (tv >= t1) break;
       const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tv);
       const int tin = token_in_unit(g, tv);
-      const int code = vc.codes[vbase * J + (int64_t)(tin / TB) * kBlockBytes + v_code_offset(J, tin % TB, jv)];
+      const int code = vc.codes[vbase * J + v_code_offset(J, tin, jv)];
       const float w = pa[tt];
 #pragma unroll
       for (int i = 0; i < SUB; ++i) acc[i] = fmaf(w, cb[code][i], acc[i]);
@@ -237,7 +237,14 @@ __global__ __launch_bounds__(128) void dec_merge_kernel(int n_q_heads, int n_spl
 }
 
 // ---------------------------------------------------------------------------------------
+bool decode_use_mfma(const nsn_shape& s) {
+  const char* e = getenv("NSN_DECODE_IMPL");  // "lut" forces the lookup-table kernel
+  if (e && e[0] == 'l') return false;
+  return s.n_q_heads / s.n_kv_heads <= 4;
+}
+
 int decode_pick_splits(const nsn_shape& s, int batch, int max_seq_len, int requested) {
+  if (decode_use_mfma(s)) return decode_mfma_splits(s, batch, max_seq_len, requested);
   const int cap = max(1, min(64, (max_seq_len + 255) / 256));
   if (requested > 0) return min(requested, 64);
   const int rows = max(1, batch * s.n_q_heads);
@@ -256,7 +263,10 @@ int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const
   const CacheView kv = make_view(kc), vv = make_view(vc);
   float* partial = static_cast<float*>(workspace);
   const dim3 grid(n_splits, s.n_q_heads, batch);
-  if (s.sub_dim == 8)
+  if (decode_use_mfma(s)) {
+    if (decode_mfma_launch(s, codebook, q, kc, vc, seq_lens, batch, scale, n_splits, partial, stream) != NSN_OK)
+      return NSN_ERR_HIP;
+  } else if (s.sub_dim == 8)
     dec_lut_kernel<8><<<grid, 256, 0, stream>>>(g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens,
                                                 scale, n_splits, partial);
   else

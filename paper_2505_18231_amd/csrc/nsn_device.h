@@ -11,7 +11,6 @@ namespace nsn {
 
 constexpr int kHeadDim = 128;
 constexpr int kCodes = 256;
-constexpr int kBlockBytes = 1024;  // one code block: TB tokens x J bytes
 constexpr double kInvSqrtD = 0.08838834764831844055;  // 1/sqrt(128)
 constexpr double kSqrtD = 11.31370849898476039041;     // sqrt(128)
 
@@ -25,7 +24,6 @@ struct CacheView {
 
 struct Geometry {
   int J;            // code bytes per token
-  int TB;           // tokens per 1 KiB code block
   int n_q_heads, n_kv_heads;
   int group_size;   // 0 = one group
   int n_groups_max; // mean vectors per (sequence, kv-head)
@@ -34,13 +32,13 @@ struct Geometry {
   int paged;
 };
 
-__host__ __device__ inline int k_code_offset(int J, int tt, int j) {
-  const int W = J >> 2, NT = (kBlockBytes / J) >> 4;
-  return (((j / W) * 16 + (tt & 15)) * NT + (tt >> 4)) * W + (j % W);
-}
-__host__ __device__ inline int v_code_offset(int J, int tt, int j) {
-  const int hsel = (J == 32) ? (j >> 4) : (tt >> 5);
-  return (((((tt & 31) >> 3) * 16 + (j & 15)) * 2 + hsel) << 3) + (tt & 7);
+// Byte offset, inside one placement unit, of the code of (token t of the unit, sub-vector j).
+// K: token-major (a lane that owns a token reads its J bytes in one go).
+// V: blocks of J tokens, sub-vector-major inside a block (a lane that owns a sub-vector reads
+//    the codes of J consecutive tokens in one go).
+__host__ __device__ inline int64_t k_code_offset(int J, int64_t t, int j) { return t * J + j; }
+__host__ __device__ inline int64_t v_code_offset(int J, int64_t t, int j) {
+  return (t / J) * (int64_t)(J * J) + (int64_t)j * J + (t % J);
 }
 
 // Index (in tokens) of the first token of the placement unit holding token t of sequence b.

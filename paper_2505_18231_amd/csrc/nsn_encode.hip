@@ -123,6 +123,7 @@ __global__ __launch_bounds__(256) void enc_quant_kernel(Geometry g, const __half
   if (blockIdx.x * 64 >= count) return;
 
   for (int it = 0; it < 16 / TPW; ++it) {
+    if (t_begin + it * TPW >= count) break;  // wave-uniform: nothing left for this wave
     const int t = t_begin + it * TPW + tk;
     const int pos = start + t;
     const bool valid = (t < count) && (pos < max_len);
@@ -194,9 +195,8 @@ __global__ __launch_bounds__(256) void enc_quant_kernel(Geometry g, const __half
     nrm2 = xor_sum(nrm2, J);
     const double alpha = (dot > 1e-12 * kHeadDim) ? nrm2 / dot : 1.0;
     if (valid) {
-      const int blk = tin / g.TB, tt = tin % g.TB;
-      const int off = tensor ? v_code_offset(J, tt, jj) : k_code_offset(J, tt, jj);
-      cv.codes[base * J + (int64_t)blk * kBlockBytes + off] = (uint8_t)code;
+      const int64_t off = tensor ? v_code_offset(J, tin, jj) : k_code_offset(J, tin, jj);
+      cv.codes[base * J + off] = (uint8_t)code;
       if (jj == 0) reinterpret_cast<__half*>(cv.norms)[2 * (base + tin)] = f64_to_f16(bb * s2 * alpha);
     }
   }

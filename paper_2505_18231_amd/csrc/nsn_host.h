@@ -8,7 +8,6 @@ namespace nsn {
 inline Geometry make_geometry(const nsn_shape& s) {
   Geometry g;
   g.J = s.head_dim / s.sub_dim;
-  g.TB = kBlockBytes / g.J;
   g.n_q_heads = s.n_q_heads;
   g.n_kv_heads = s.n_kv_heads;
   g.group_size = s.group_size;
@@ -37,6 +36,11 @@ int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, co
                   const nsn_cache& kc, const nsn_cache& vc, void* workspace, hipStream_t stream);
 
 int decode_pick_splits(const nsn_shape& s, int batch, int max_seq_len, int requested);
+bool decode_use_mfma(const nsn_shape& s);
+int decode_mfma_splits(const nsn_shape& s, int batch, int max_seq_len, int requested);
+int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
+                       const nsn_cache& vc, const int32_t* seq_lens, int batch, float scale, int n_splits,
+                       float* partial, hipStream_t stream);
 size_t decode_workspace_bytes(const nsn_shape& s, int batch, int n_splits);
 int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
                   const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,

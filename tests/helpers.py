@@ -6,39 +6,31 @@ from __future__ import annotations
 import numpy as np
 
 D = 128
-BLOCK = 1024
 
 
-def code_offsets(J: int, kind: str) -> np.ndarray:
-    """[TB][J] byte offset inside a 1 KiB block of (token-in-block, sub-vector)."""
-    TB = BLOCK // J
-    tt, j = np.meshgrid(np.arange(TB), np.arange(J), indexing="ij")
+def code_offsets(J: int, kind: str, n_tokens: int) -> np.ndarray:
+    """[n_tokens][J] byte offset inside a placement unit of (token, sub-vector)."""
+    t, j = np.meshgrid(np.arange(n_tokens), np.arange(J), indexing="ij")
     if kind == "k":
-        W, NT = J // 4, TB // 16
-        return ((j // W * 16 + tt % 16) * NT + tt // 16) * W + j % W
-    hsel = (j // 16) if J == 32 else (tt // 32)
-    return (((tt % 32) // 8 * 16 + j % 16) * 2 + hsel) * 8 + tt % 8
+        return t * J + j
+    return (t // J) * (J * J) + j * J + t % J
 
 
 def pack_codes(codes: np.ndarray, kind: str, capacity: int) -> np.ndarray:
-    """codes u8 [L][J] -> layout bytes u8 [capacity * J] (capacity a multiple of the block tokens)."""
+    """codes u8 [L][J] -> layout bytes u8 [capacity * J] (capacity a multiple of 64 tokens)."""
     L, J = codes.shape
-    TB = BLOCK // J
-    assert capacity % TB == 0 and capacity >= L
+    assert capacity % 64 == 0 and capacity >= L
     full = np.zeros((capacity, J), dtype=np.uint8)
     full[:L] = codes
-    off = code_offsets(J, kind).ravel()
-    out = np.zeros((capacity // TB, BLOCK), dtype=np.uint8)
-    out[:, off] = full.reshape(capacity // TB, TB * J)
-    return out.ravel()
+    out = np.zeros(capacity * J, dtype=np.uint8)
+    out[code_offsets(J, kind, capacity).ravel()] = full.ravel()
+    return out
 
 
 def unpack_codes(raw: np.ndarray, kind: str, J: int) -> np.ndarray:
     """layout bytes u8 [capacity * J] -> codes u8 [capacity][J]."""
-    TB = BLOCK // J
-    off = code_offsets(J, kind).ravel()
-    blocks = raw.reshape(-1, BLOCK)
-    return blocks[:, off].reshape(blocks.shape[0] * TB, J)
+    cap = raw.size // J
+    return raw[code_offsets(J, kind, cap).ravel()].reshape(cap, J)
 
 
 def n_groups(length: int, G: int) -> int:

@@ -67,12 +67,19 @@ CASES = [
     ("paged-1bit", 3, 4, 2, [1000, 256, 37], 8, 0, 256, 0),
     ("paged-2bit-groups", 2, 8, 2, [900, 511], 4, 128, 256, 5),
     ("empty-and-short", 3, 2, 1, [0, 1, 65], 8, 64, 0, 2),
+    ("gqa8-2bit", 1, 8, 1, [300], 4, 64, 0, 2),          # 8 query heads per kv head
+    ("long-2bit-many-splits", 1, 4, 1, [5000], 4, 0, 0, 16),
+    ("long-1bit-groups", 1, 4, 2, [3000], 8, 64, 0, 3),
 ]
 
 
+@pytest.mark.parametrize("impl", ["mfma", "lut"])
 @pytest.mark.parametrize("name,batch,hq,hkv,lens,sub,G,page,splits", CASES, ids=[c[0] for c in CASES])
-def test_decode_matches_oracle(gpu_api, codebooks, name, batch, hq, hkv, lens, sub, G, page, splits):
-    print(f"case {name} lens={lens} sub={sub} G={G} page={page} splits={splits}", flush=True)
+def test_decode_matches_oracle(gpu_api, codebooks, monkeypatch, impl, name, batch, hq, hkv, lens, sub, G, page,
+                               splits):
+    # "mfma": matrix-core kernel (default for <= 4 query heads per kv head); "lut": lookup-table kernel
+    monkeypatch.setenv("NSN_DECODE_IMPL", impl)
+    print(f"case {name} impl={impl} lens={lens} sub={sub} G={G} page={page} splits={splits}", flush=True)
     cb = codebooks[sub]
     scale = 1.0 / math.sqrt(128)
     kc, vc, q, max_len = build_case(100 + len(name), batch, hq, hkv, lens, sub, G, cb, page)
@@ -87,11 +94,18 @@ def test_decode_matches_oracle(gpu_api, codebooks, name, batch, hq, hkv, lens, s
     assert err < TOL, err
 
 
-def test_split_count_does_not_change_the_result(gpu_api, codebooks):
+@pytest.mark.parametrize("impl", ["mfma", "lut"])
+def test_split_count_does_not_change_the_result(gpu_api, codebooks, monkeypatch, impl):
+    monkeypatch.setenv("NSN_DECODE_IMPL", impl)
     cb = codebooks[4]
     scale = 1.0 / math.sqrt(128)
     lens = [1500, 640]
     kc, vc, q, max_len = build_case(7, 2, 8, 2, lens, 4, 64, cb)
     outs = [gpu_out(gpu_api, kc, vc, q, lens, 8, 2, 4, 64, cb, max_len, scale, 0, s) for s in (1, 2, 7)]
+    # lut: fp32 everywhere, only the summation order changes.  mfma: the softmax weights enter the
+    # value contraction as fp16 (relative 2^-11 each), and their rounding depends on the running max.
+    tol = 2e-5 if impl == "lut" else 1e-3
     for o in outs[1:]:
-        assert helpers.max_rel_err(o, outs[0]) < 2e-5
+        err = helpers.max_rel_err(o, outs[0])
+        print(f"  split-count difference {err:.3e}", flush=True)
+        assert err < tol

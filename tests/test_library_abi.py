@@ -33,12 +33,18 @@ def test_exports_every_declared_symbol(L):
 
 @pytest.mark.parametrize("J", [16, 32])
 def test_layout_offsets_match_header_formulas_and_are_bijections(L, J):
-    TB = 1024 // J
+    import ctypes as C
+    n = 128
     for kind, fn in (("k", L.nsn_k_code_offset), ("v", L.nsn_v_code_offset)):
-        ref = helpers.code_offsets(J, kind)
-        got = np.array([[fn(J, tt, j) for j in range(J)] for tt in range(TB)])
+        fn.restype = C.c_int64
+        fn.argtypes = [C.c_int, C.c_int64, C.c_int]
+        ref = helpers.code_offsets(J, kind, n)
+        got = np.array([[fn(J, t, j) for j in range(J)] for t in range(n)])
         assert np.array_equal(ref, got)
-        assert sorted(got.ravel().tolist()) == list(range(1024))
+        assert sorted(got.ravel().tolist()) == list(range(n * J))
+        # a V block holds J consecutive tokens of one sub-vector contiguously
+        if kind == "v":
+            assert np.array_equal(ref[:J, 3], 3 * J + np.arange(J))
 
 
 def test_pack_unpack_roundtrip():
