@@ -114,7 +114,7 @@ def main() -> int:
     v_new = v_dev[:, :, L - 1:L, :].contiguous()
     last = torch.full((B,), L - 1, dtype=torch.int32, device=dev)
     ones = torch.ones(B, dtype=torch.int32, device=dev)
-    dec_ws = torch.empty(max(1, api.nsn_workspace_bytes(shape, api.NSN_OP_DECODE, B, 0, args.n_splits)),
+    dec_ws = torch.zeros(max(1, api.nsn_workspace_bytes(shape, api.NSN_OP_DECODE, B, 0, args.n_splits)),
                          dtype=torch.uint8, device=dev)
     out = torch.empty((B, Hq, 128), dtype=torch.float32, device=dev)
 

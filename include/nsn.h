@@ -96,7 +96,10 @@ const char* nsn_last_error(void);
 /*
  * Workspace (device bytes) an operation needs.
  *   NSN_OP_ENCODE   : n = max_new (token stride of the inputs), n_splits ignored
- *   NSN_OP_DECODE   : n ignored, n_splits as passed to nsn_decode_attention (0 = auto)
+ *   NSN_OP_DECODE   : n ignored, n_splits as passed to nsn_decode_attention (0 = auto).
+ *                     The decode workspace starts with arrival counters: fill it with zeros
+ *                     ONCE after allocating it; every call leaves it ready for the next one.
+ *                     Calls that share one workspace must not overlap in time.
  *   NSN_OP_CODEBOOK : n = n_samples, batch and n_splits ignored
  * Returns 0 for an invalid shape.
  */

@@ -173,8 +173,8 @@ def nsn_decode_attention(shape: nsn_shape, codebook: torch.Tensor, q: torch.Tens
     if out is None:
         out = torch.empty((batch, hq, d), dtype=torch.float32, device=q.device)
     need = nsn_workspace_bytes(shape, NSN_OP_DECODE, batch, 0, n_splits)
-    if workspace is None:
-        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    if workspace is None:  # must start zero-filled (arrival counters); reusable afterwards
+        workspace = torch.zeros(max(need, 1), dtype=torch.uint8, device=q.device)
     kc, vc = k_cache.c_struct(), v_cache.c_struct()
     _check(lib().nsn_decode_attention(C.byref(shape), codebook.data_ptr(), q.data_ptr(), C.byref(kc),
                                       C.byref(vc), seq_lens.data_ptr(), batch, max_seq_len,

@@ -252,21 +252,23 @@ int decode_pick_splits(const nsn_shape& s, int batch, int max_seq_len, int reque
 }
 
 size_t decode_workspace_bytes(const nsn_shape& s, int batch, int n_splits) {
+  if (decode_use_mfma(s)) return decode_mfma_workspace_bytes(s, batch, n_splits);
   return (size_t)batch * s.n_q_heads * n_splits * kPartialStride * sizeof(float);
 }
 
 int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
                   const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                   int n_splits, float* out, void* workspace, hipStream_t stream) {
-  (void)max_seq_len;
+  if (decode_use_mfma(s))
+    return decode_mfma_launch(s, codebook, q, kc, vc, seq_lens, batch, max_seq_len, scale, n_splits, workspace, out,
+                              stream) == NSN_OK && hipGetLastError() == hipSuccess
+               ? NSN_OK
+               : NSN_ERR_HIP;
   const Geometry g = make_geometry(s);
   const CacheView kv = make_view(kc), vv = make_view(vc);
   float* partial = static_cast<float*>(workspace);
   const dim3 grid(n_splits, s.n_q_heads, batch);
-  if (decode_use_mfma(s)) {
-    if (decode_mfma_launch(s, codebook, q, kc, vc, seq_lens, batch, scale, n_splits, partial, stream) != NSN_OK)
-      return NSN_ERR_HIP;
-  } else if (s.sub_dim == 8)
+  if (s.sub_dim == 8)
     dec_lut_kernel<8><<<grid, 256, 0, stream>>>(g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens,
                                                 scale, n_splits, partial);
   else

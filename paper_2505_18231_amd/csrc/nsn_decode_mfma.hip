@@ -13,8 +13,10 @@
 //   * for the value side a lane owns one sub-vector of 32 (or 16) tokens; four gathered
 //     codewords are transposed in registers (v_perm_b32) into "four tokens of one channel"
 //     B operands, the fp16 weights of those four tokens are the broadcast A operand, and the
-//     fp32 accumulator is out_rot[head][channel] in the rotated domain.
-// Partial results per (split, query head) go to the same fp32 layout the merge kernel reads.
+//     fp32 accumulator is out_rot[head][channel] in the rotated domain;
+//   * one workgroup per (split, kv head, sequence); the last workgroup of a (kv head, sequence)
+//     to finish merges the splits (running max / sum), applies the single inverse Hadamard per
+//     head, adds the mean-vector term and writes the output - no second launch.
 #include <type_traits>
 
 #include "nsn_host.h"
@@ -24,9 +26,8 @@ namespace nsn {
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 
-constexpr int kPartialStrideM = 2 * kHeadDim + 2;
-constexpr float kLn2 = 0.69314718055994530942f;
-constexpr float kLazyMaxLog2 = 5.0f;  // rescale only when a score beats the running max by 2^5
+constexpr int kPartialStrideM = 2 * kHeadDim + 2;  // rotated acc, mean-term acc, m (log2 units), l
+constexpr float kLazyMaxLog2 = 5.0f;               // rescale only when a score beats the running max by 2^5
 constexpr int kTableBytes = 65536;
 
 template <int N, typename F>
@@ -54,6 +55,54 @@ template <int CTRL>
 __device__ __forceinline__ float dpp_quad(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
 }
+template <int CTRL>
+__device__ __forceinline__ float dpp_row(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float read_lane(float v, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+// Wave-wide reductions on the vector ALU (no LDS traffic); the result is uniform.
+// quad xor 1, quad xor 2, mirror within 8 lanes, mirror within 16 lanes, then the four rows.
+__device__ __forceinline__ float wave_sum_u(float v) {
+  v += dpp_row<0xB1>(v);
+  v += dpp_row<0x4E>(v);
+  v += dpp_row<0x141>(v);
+  v += dpp_row<0x140>(v);
+  return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
+}
+__device__ __forceinline__ float wave_max_u(float v) {
+  v = fmaxf(v, dpp_row<0xB1>(v));
+  v = fmaxf(v, dpp_row<0x4E>(v));
+  v = fmaxf(v, dpp_row<0x141>(v));
+  v = fmaxf(v, dpp_row<0x140>(v));
+  return fmaxf(fmaxf(read_lane(v, 0), read_lane(v, 16)), fmaxf(read_lane(v, 32), read_lane(v, 48)));
+}
+
+// Device-scope stores / loads: coherent across the chip's L2 slices without cache maintenance.
+__device__ __forceinline__ void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// LDS reads by absolute LDS byte address (the codebook table starts at LDS address 0).
+#if defined(__HIP_DEVICE_COMPILE__)
+__device__ __forceinline__ uint2 lds_read64(uint32_t addr) {
+  typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+  const u2 v = *(const u2 __attribute__((address_space(3)))*)(addr);
+  return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ uint4 lds_read128(uint32_t addr) {
+  typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+  const u4 v = *(const u4 __attribute__((address_space(3)))*)(addr);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+#else
+__device__ __forceinline__ uint2 lds_read64(uint32_t) { return make_uint2(0, 0); }
+__device__ __forceinline__ uint4 lds_read128(uint32_t) { return make_uint4(0, 0, 0, 0); }
+#endif
 
 // Transpose a 4x4 fp32 tile held as x[0..3] across the four lanes of every quad:
 // afterwards lane i of a quad holds x[k] = (old x[i] of lane k).
@@ -83,99 +132,176 @@ __device__ __forceinline__ void quad_transpose(float (&x)[4], int lane) {
   }
 }
 
+#ifdef NSN_DECODE_TIMING
+__device__ long long g_dec_timing[48];
+#define NSN_TSTAMP(slot)                                                                        \
+  do {                                                                                          \
+    if (blockIdx.x == 1 && blockIdx.y == 3 && blockIdx.z == 2 && (threadIdx.x & 63) == 0)       \
+      g_dec_timing[(threadIdx.x >> 6) == 0 ? (slot) : (threadIdx.x >> 6) == 7 ? 16 + (slot) : 47] = clock64(); \
+  } while (0)
+#else
+#define NSN_TSTAMP(slot) \
+  do {                   \
+  } while (0)
+#endif
+
+// LDS plan (dynamic, starts at LDS address 0):
+//   [0, 64 KiB)        codebook table: entry (code c, copy p) at c * 256 + p * (2 * SUB) bytes,
+//                      32 copies of 8 B (SUB = 4) or 16 copies of 16 B (SUB = 8);
+//                      after the main loop the same bytes hold the per-wave accumulators
+//   [64 KiB, +NW*2KiB) prologue: staged codewords, q, rotated q;
+//                      main loop: mean-vector term of every wave, accm[NW][4][128]
+//   tail               per-wave (m, l), the "last workgroup" flag, inverse-Hadamard scratch
+// One workgroup of 8 waves per compute unit shares a single table (64 + 16 KiB of the 160 KiB).
 template <int SUB, int NW>
 struct DecSmem {
-  // codebook table: entry (code c, copy p) at c * 256 + p * (2 * SUB) bytes;
-  // 32 copies of 8 B (SUB = 4) or 16 copies of 16 B (SUB = 8).  Reused by the epilogue.
-  __attribute__((aligned(16))) unsigned char table[kTableBytes];
-  float q_orig[4][kHeadDim];
-  float q_had[4][kHeadDim];
-  float accm[NW][4][kHeadDim];  // mean-vector term of every wave, original channel order
-  float wave_m[NW][4], wave_l[NW][4];
+  static constexpr int kUnionBytes = NW * 4 * kHeadDim * 4;
+  static constexpr int kRaccBytes = NW * 4 * kHeadDim * 4;
+  static constexpr int kTailBytes = (2 * NW * 4 + 4 + 4 * kHeadDim) * 4;
+  static constexpr bool kTailInTable = kRaccBytes + kTailBytes <= kTableBytes;
+  static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kTableBytes + kUnionBytes;
+  static constexpr int kBytes = kTableBytes + kUnionBytes + (kTailInTable ? 0 : kTailBytes);
+  static_assert(kUnionBytes >= kCodes * 2 * SUB + 2 * 4 * kHeadDim * 4, "prologue scratch must fit");
+  static_assert(kRaccBytes <= kTableBytes, "per-wave accumulators must fit in the table region");
 };
 
-template <int SUB, int NW>
+template <int SUB, int NW, bool HILO>
 __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __half* __restrict__ codebook,
                                                            const __half* __restrict__ q, CacheView kc,
                                                            CacheView vc, const int32_t* __restrict__ seq_lens,
-                                                           float scale_log2e, int n_splits,
-                                                           float* __restrict__ partial) {
-  constexpr int J = kHeadDim / SUB;       // code bytes per token
-  constexpr int KW = J / 4;               // code dwords per lane (K: one token; V: one sub-vector of J tokens)
-  constexpr int LV = J;                   // lanes per value-side token part (one lane per sub-vector)
+                                                           float scale_log2e, int n_splits, int per,
+                                                           float* partial, int* counters,
+                                                           float* __restrict__ out) {
+  constexpr int J = kHeadDim / SUB;  // code bytes per token
+  constexpr int KW = J / 4;          // code dwords per lane (K: one token; V: one sub-vector of J tokens)
+  constexpr int LV = J;              // lanes per value-side token part (one lane per sub-vector)
   constexpr int CBSZ_V = (SUB == 4) ? 3 : 2;
   constexpr int NT = NW * 64;
+  using SM = DecSmem<SUB, NW>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  auto& sm = *reinterpret_cast<DecSmem<SUB, NW>*>(smem_raw);
+  unsigned char* const sm_table = smem_raw;
+  unsigned char* const sm_stage = smem_raw + kTableBytes;                          // prologue only
+  float(*const sm_q_orig)[kHeadDim] = reinterpret_cast<float(*)[kHeadDim]>(sm_stage + kCodes * 2 * SUB);
+  float(*const sm_q_had)[kHeadDim] = sm_q_orig + 4;
+  float(*const sm_accm)[4][kHeadDim] = reinterpret_cast<float(*)[4][kHeadDim]>(smem_raw + kTableBytes);
+  float(*const sm_wave_m)[4] = reinterpret_cast<float(*)[4]>(smem_raw + SM::kTailOffset);  // after the loop
+  float(*const sm_wave_l)[4] = sm_wave_m + NW;
+  int* const sm_is_last = reinterpret_cast<int*>(sm_wave_l + NW);
+  float* const sm_rot = reinterpret_cast<float*>(sm_is_last + 4);
 
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int r = g.n_q_heads / g.n_kv_heads;  // <= 4
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int len = seq_lens[b];
-  const int per = (((len + n_splits - 1) / n_splits) + 63) & ~63;
-  const int t0 = split * per, t1 = min(len, t0 + per);
-  float* P = partial + ((int64_t)(b * g.n_q_heads + h * r) * n_splits + split) * kPartialStrideM;
-  if (t0 >= t1) {  // empty split
-    for (int i = tid; i < r * 2 * kHeadDim; i += NT)
-      P[(int64_t)(i / (2 * kHeadDim)) * n_splits * kPartialStrideM + (i % (2 * kHeadDim))] = 0.f;
-    if (tid < r) {
-      P[(int64_t)tid * n_splits * kPartialStrideM + 2 * kHeadDim] = -INFINITY;
-      P[(int64_t)tid * n_splits * kPartialStrideM + 2 * kHeadDim + 1] = 0.f;
-    }
-    return;
-  }
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // per-wave bookkeeping on the scalar unit
+  const int t0 = split * per;
+  const int64_t mean_base = (int64_t)(b * g.n_kv_heads + h) * g.n_groups_max;
 
-  // ---- prologue: replicated codebook table, rotated query ----------------------------------
-  if constexpr (SUB == 4) {
-    const uint2* cb2 = reinterpret_cast<const uint2*>(codebook);
-    for (int i = tid; i < kCodes * 32; i += NT)
-      *reinterpret_cast<uint2*>(sm.table + (i >> 5) * 256 + (i & 31) * 8) = cb2[i >> 5];
-  } else {
-    const uint4* cb4 = reinterpret_cast<const uint4*>(codebook);
-    for (int i = tid; i < kCodes * 16; i += NT)
-      *reinterpret_cast<uint4*>(sm.table + (i >> 4) * 256 + (i & 15) * 16) = cb4[i >> 4];
-  }
+  // One 64-token group's cache bytes as this lane needs them: the J code bytes of its K token,
+  // the J code bytes (J consecutive tokens) of its V sub-vector, the two norm pairs, and this
+  // lane's two channels of the group's Shift vectors.
+  struct Grp {
+    uint32_t kcode[KW], vcode[KW];
+    __half2 nk, nv, ok2, ov2;
+  };
+  auto load_group = [&](int gi, Grp& G) {
+    const int tg = t0 + (gi << 6);
+    const int64_t kbase = unit_token_base(g, kc.block_table, b, h, tg);
+    const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tg);
+    const int tin = token_in_unit(g, tg);
+    const uint4* kp = reinterpret_cast<const uint4*>(kc.codes + (kbase + tin + lane) * J);
+    const uint4* vp =
+        reinterpret_cast<const uint4*>(vc.codes + (vbase + tin) * J + (lane / LV) * (J * J) + (lane % LV) * J);
+#pragma unroll
+    for (int w4 = 0; w4 < KW / 4; ++w4) {
+      const uint4 kv4 = kp[w4], vv4 = vp[w4];
+      G.kcode[4 * w4] = kv4.x, G.kcode[4 * w4 + 1] = kv4.y, G.kcode[4 * w4 + 2] = kv4.z, G.kcode[4 * w4 + 3] = kv4.w;
+      G.vcode[4 * w4] = vv4.x, G.vcode[4 * w4 + 1] = vv4.y, G.vcode[4 * w4 + 2] = vv4.z, G.vcode[4 * w4 + 3] = vv4.w;
+    }
+    G.nk = kc.norms[kbase + tin + lane];
+    G.nv = vc.norms[vbase + tin + lane];
+    const int64_t mo = (mean_base + group_of(g, tg)) * kHeadDim + 2 * lane;
+    G.ok2 = *reinterpret_cast<const __half2*>(kc.means + mo);
+    G.ov2 = *reinterpret_cast<const __half2*>(vc.means + mo);
+  };
+
+  NSN_TSTAMP(0);
+  // ---- loads that do not depend on the sequence length go out first ------------------------
+  typedef typename std::conditional<SUB == 4, uint2, uint4>::type cw_t;
+  cw_t cw_reg = {};
+  if (tid < kCodes) cw_reg = reinterpret_cast<const cw_t*>(codebook)[tid];
+  float qv = 0.f;  // NT == 512 covers 4 heads x 128 channels; smaller blocks loop below
+  Grp cur;
+  const bool spec = !g.paged && (t0 + (wave << 6) + 64 <= g.page_tokens);  // in bounds whatever the length
+  if (spec) load_group(wave, cur);
+  const int len = seq_lens[b];  // scalar load in flight; first used after the prologue
+
+  // ---- prologue: codebook table, rotated query (independent of the sequence length) ----------
+  if (tid < kCodes) reinterpret_cast<cw_t*>(sm_stage)[tid] = cw_reg;
   for (int i = tid; i < 4 * kHeadDim; i += NT) {
     const int hh = i >> 7, c = i & 127;
-    const float v = hh < r ? __half2float(q[(int64_t)(b * g.n_q_heads + h * r + hh) * kHeadDim + c]) : 0.f;
-    sm.q_orig[hh][c] = v;
-    sm.q_had[hh][c] = v;
+    qv = hh < r ? __half2float(q[(int64_t)(b * g.n_q_heads + h * r + hh) * kHeadDim + c]) : 0.f;
+    sm_q_orig[hh][c] = qv;
   }
-  for (int s = 1; s < kHeadDim; s <<= 1) {  // d1: four 128-point Walsh-Hadamard transforms
-    __syncthreads();
-    for (int i = tid; i < 4 * 64; i += NT) {
-      const int hh = i >> 6, k = i & 63;
-      const int lo = ((k & ~(s - 1)) << 1) | (k & (s - 1));
-      const float a0 = sm.q_had[hh][lo], a1 = sm.q_had[hh][lo + s];
-      sm.q_had[hh][lo] = a0 + a1;
-      sm.q_had[hh][lo + s] = a0 - a1;
+  __syncthreads();
+  NSN_TSTAMP(12);
+  const float qscale = (float)kInvSqrtD * scale_log2e;
+  for (int hh = wave; hh < 4; hh += NW) {  // d1: one wave rotates one head, butterflies across lanes
+    float x0 = sm_q_orig[hh][2 * lane], x1 = sm_q_orig[hh][2 * lane + 1];
+    {
+      const float a0 = x0 + x1, a1 = x0 - x1;
+      x0 = a0, x1 = a1;
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+      const float p0 = __shfl_xor(x0, m, 64), p1 = __shfl_xor(x1, m, 64);
+      const bool upper = (lane & m) != 0;
+      x0 = upper ? p0 - x0 : x0 + p0;
+      x1 = upper ? p1 - x1 : x1 + p1;
+    }
+    sm_q_had[hh][2 * lane] = x0 * qscale;
+    sm_q_had[hh][2 * lane + 1] = x1 * qscale;
+  }
+  {  // replicate the staged codewords: batches of 8 reads, then 8 writes
+    constexpr int NCOPY = 256 / (2 * SUB), LOGC = (SUB == 4) ? 5 : 4;
+    for (int i0 = tid; i0 < kCodes * NCOPY; i0 += 8 * NT) {
+      cw_t tmp[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) tmp[u] = reinterpret_cast<const cw_t*>(sm_stage)[min(i0 + u * NT, kCodes * NCOPY - 1) >> LOGC];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 + u * NT;
+        if (i < kCodes * NCOPY)
+          *reinterpret_cast<cw_t*>(sm_table + (i >> LOGC) * 256 + (i & (NCOPY - 1)) * (2 * SUB)) = tmp[u];
+      }
     }
   }
-  for (int i = tid; i < NW * 4 * kHeadDim; i += NT) (&sm.accm[0][0][0])[i] = 0.f;
   __syncthreads();
+  NSN_TSTAMP(1);
+  const int t1 = min(len, t0 + per);
+  const int n_grp = t1 > t0 ? (t1 - t0 + 63) >> 6 : 0;
+  if (!spec && wave < n_grp) load_group(wave, cur);
 
   // A operands of the score contraction: slot s = channels [4s, 4s+4); block (lane / 4) of
   // register pair p holds slot 16 p + block for head (lane % 4); fp16 hi and lo parts.
-  const float qscale = (float)kInvSqrtD * scale_log2e;
   h4 QH[2], QL[2];
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
-    const float* src = &sm.q_had[lane & 3][4 * (16 * p + (lane >> 2))];
+    const float* src = &sm_q_had[lane & 3][4 * (16 * p + (lane >> 2))];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      const float x = src[k] * qscale;
+      const float x = src[k];
       const _Float16 hi = (_Float16)x;
       QH[p][k] = hi;
       QL[p][k] = (_Float16)(x - (float)hi);
     }
   }
-  const float qo0[4] = {sm.q_orig[0][2 * lane], sm.q_orig[1][2 * lane], sm.q_orig[2][2 * lane],
-                        sm.q_orig[3][2 * lane]};
-  const float qo1[4] = {sm.q_orig[0][2 * lane + 1], sm.q_orig[1][2 * lane + 1], sm.q_orig[2][2 * lane + 1],
-                        sm.q_orig[3][2 * lane + 1]};
-
+  const float qo0[4] = {sm_q_orig[0][2 * lane], sm_q_orig[1][2 * lane], sm_q_orig[2][2 * lane],
+                        sm_q_orig[3][2 * lane]};
+  const float qo1[4] = {sm_q_orig[0][2 * lane + 1], sm_q_orig[1][2 * lane + 1], sm_q_orig[2][2 * lane + 1],
+                        sm_q_orig[3][2 * lane + 1]};
   const uint32_t laneoff = (SUB == 4) ? (lane & 31) * 8 : (lane & 15) * 16;
-  const int64_t mean_base = (int64_t)(b * g.n_kv_heads + h) * g.n_groups_max;
+  __syncthreads();  // the prologue scratch is dead: its bytes become the per-wave mean-term accumulators
+  for (int i = lane; i < 4 * kHeadDim; i += 64) (&sm_accm[wave][0][0])[i] = 0.f;  // wave-private
 
   float m_run[4], l_run[4], beta[4], cf[4], qo[4];
   f4 acc[SUB];
@@ -190,82 +316,130 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
 #pragma unroll
   for (int c = 0; c < SUB; ++c) acc[c] = f4{0.f, 0.f, 0.f, 0.f};
   int cur_group = -1;
+  float ov0 = 0.f, ov1 = 0.f;  // this lane's two channels of the current group's o^v
 
-  // flush the mean-vector term of the Shift group that just ended: accm = accm * cf + beta * o^v
-  auto flush_group = [&](int grp) {
-    const __half2 o2 = *reinterpret_cast<const __half2*>(vc.means + (mean_base + grp) * kHeadDim + 2 * lane);
-    const float o0 = __low2float(o2), o1 = __high2float(o2);
+  // mean-vector term of the Shift group that just ended: accm = accm * cf + (sum of beta) * o^v
+  auto flush_group = [&]() {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float bsum = xor_sum(beta[i], 64);
-      float* dst = &sm.accm[wave][i][2 * lane];
-      dst[0] = dst[0] * cf[i] + bsum * o0;
-      dst[1] = dst[1] * cf[i] + bsum * o1;
+      const float bsum = wave_sum_u(beta[i]);
+      float* dst = &sm_accm[wave][i][2 * lane];
+      dst[0] = dst[0] * cf[i] + bsum * ov0;
+      dst[1] = dst[1] * cf[i] + bsum * ov1;
       beta[i] = 0.f;
       cf[i] = 1.f;
     }
   };
 
-  // ---- main loop: this wave's 64-token groups ---------------------------------------------
-  const int n_grp = (t1 - t0 + 63) >> 6;
-  for (int gi = wave; gi < n_grp; gi += NW) {
-    const int tg = t0 + (gi << 6);  // first token of the group (multiple of 64)
-    const int64_t kbase = unit_token_base(g, kc.block_table, b, h, tg);
-    const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tg);
-    const int tin = token_in_unit(g, tg);
-    const bool valid = (tg + lane) < t1;
-
-    uint32_t kcode[KW], vcode[KW];
-    {
-      const uint4* kp = reinterpret_cast<const uint4*>(kc.codes + (kbase + tin + lane) * J);
-      const uint4* vp = reinterpret_cast<const uint4*>(vc.codes + (vbase + tin) * J + (lane / LV) * (J * J) +
-                                                       (lane % LV) * J);
+  auto k_gather = [&](const uint32_t (&kcode)[KW], auto cc, cw_t (&buf)[8]) {
+    constexpr int ch = decltype(cc)::value;
 #pragma unroll
-      for (int w4 = 0; w4 < KW / 4; ++w4) {
-        const uint4 kv4 = kp[w4], vv4 = vp[w4];
-        kcode[4 * w4] = kv4.x, kcode[4 * w4 + 1] = kv4.y, kcode[4 * w4 + 2] = kv4.z, kcode[4 * w4 + 3] = kv4.w;
-        vcode[4 * w4] = vv4.x, vcode[4 * w4 + 1] = vv4.y, vcode[4 * w4 + 2] = vv4.z, vcode[4 * w4 + 3] = vv4.w;
-      }
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t addr = perm_b32(kcode[(8 * ch + e) / 4], laneoff, 0x0c0c0400u + ((e % 4) << 8));
+      if constexpr (SUB == 4)
+        buf[e] = lds_read64(addr);
+      else
+        buf[e] = lds_read128(addr);
     }
-    const __half2 nk = kc.norms[kbase + tin + lane];
-    const __half2 nv = vc.norms[vbase + tin + lane];
-    const float a_k = valid ? __low2float(nk) : 0.f, b_k = valid ? __high2float(nk) : 0.f;
-    const float a_v = valid ? __low2float(nv) : 0.f, b_v = valid ? __high2float(nv) : 0.f;
+  };
+  auto k_contract = [&](auto cc, const cw_t (&buf)[8], f4& d0, f4& d1) {
+    constexpr int ch = decltype(cc)::value;
+    static_for<8>([&](auto ec) {
+      constexpr int e = decltype(ec)::value;
+      constexpr int s = 8 * ch + e;
+      if constexpr (SUB == 4) {
+        const h4 bop = as_h4(buf[e].x, buf[e].y);
+        d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[s / 16], bop, d0, 4, s % 16, 0);
+        if constexpr (HILO) d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QL[s / 16], bop, d1, 4, s % 16, 0);
+      } else {
+        const h4 b0 = as_h4(buf[e].x, buf[e].y), b1 = as_h4(buf[e].z, buf[e].w);
+        d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[(2 * s) / 16], b0, d0, 4, (2 * s) % 16, 0);
+        d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[(2 * s + 1) / 16], b1, d1, 4, (2 * s + 1) % 16, 0);
+        if constexpr (HILO) {
+          d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QL[(2 * s) / 16], b0, d0, 4, (2 * s) % 16, 0);
+          d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QL[(2 * s + 1) / 16], b1, d1, 4, (2 * s + 1) % 16, 0);
+        }
+      }
+    });
+  };
+  auto v_gather = [&](uint32_t vw, cw_t (&buf)[4]) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t addr = perm_b32(vw, laneoff, 0x0c0c0400u + (k << 8));
+      if constexpr (SUB == 4)
+        buf[k] = lds_read64(addr);
+      else
+        buf[k] = lds_read128(addr);
+    }
+  };
+  auto v_contract = [&](auto ac, const cw_t (&cw)[4], const h4& wop) {
+    constexpr int a = decltype(ac)::value;
+    if constexpr (SUB == 4) {
+      const h4 b0 = as_h4(perm_b32(cw[1].x, cw[0].x, 0x05040100u), perm_b32(cw[3].x, cw[2].x, 0x05040100u));
+      const h4 b1 = as_h4(perm_b32(cw[1].x, cw[0].x, 0x07060302u), perm_b32(cw[3].x, cw[2].x, 0x07060302u));
+      const h4 b2 = as_h4(perm_b32(cw[1].y, cw[0].y, 0x05040100u), perm_b32(cw[3].y, cw[2].y, 0x05040100u));
+      const h4 b3 = as_h4(perm_b32(cw[1].y, cw[0].y, 0x07060302u), perm_b32(cw[3].y, cw[2].y, 0x07060302u));
+      acc[0] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, b0, acc[0], CBSZ_V, a, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, b1, acc[1], CBSZ_V, a, 0);
+      acc[2] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, b2, acc[2], CBSZ_V, a, 0);
+      acc[3] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, b3, acc[3], CBSZ_V, a, 0);
+    } else {
+      const uint32_t c0[4] = {cw[0].x, cw[0].y, cw[0].z, cw[0].w};
+      const uint32_t c1[4] = {cw[1].x, cw[1].y, cw[1].z, cw[1].w};
+      const uint32_t c2[4] = {cw[2].x, cw[2].y, cw[2].z, cw[2].w};
+      const uint32_t c3[4] = {cw[3].x, cw[3].y, cw[3].z, cw[3].w};
+      static_for<4>([&](auto mc) {
+        constexpr int mth = decltype(mc)::value;
+        const h4 be = as_h4(perm_b32(c1[mth], c0[mth], 0x05040100u), perm_b32(c3[mth], c2[mth], 0x05040100u));
+        const h4 bo = as_h4(perm_b32(c1[mth], c0[mth], 0x07060302u), perm_b32(c3[mth], c2[mth], 0x07060302u));
+        acc[2 * mth] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, be, acc[2 * mth], CBSZ_V, a, 0);
+        acc[2 * mth + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, bo, acc[2 * mth + 1], CBSZ_V, a, 0);
+      });
+    }
+  };
 
-    // Shift group bookkeeping (wave-uniform): q . o^k of the new group, mean term of the old one
+  NSN_TSTAMP(2);
+  // ---- main loop: this wave's 64-token groups, next group's loads in flight ------------------
+  for (int gi = wave; gi < n_grp; gi += NW) {
+    NSN_TSTAMP(3 + (gi / NW < 6 ? gi / NW : 6));
+    const int tg = t0 + (gi << 6);  // first token of the group (multiple of 64)
+    const bool valid = (tg + lane) < t1;
+    Grp nxt = cur;
+    if (gi + NW < n_grp) load_group(gi + NW, nxt);  // wave-uniform
+    const float a_k = valid ? __low2float(cur.nk) : 0.f, b_k = valid ? __high2float(cur.nk) : 0.f;
+    const float a_v = valid ? __low2float(cur.nv) : 0.f, b_v = valid ? __high2float(cur.nv) : 0.f;
+
+    // Shift group bookkeeping (wave-uniform): mean term of the old group, q . o^k of the new one
     const int grp = group_of(g, tg);
     if (grp != cur_group) {
-      if (cur_group >= 0) flush_group(cur_group);
-      const __half2 o2 = *reinterpret_cast<const __half2*>(kc.means + (mean_base + grp) * kHeadDim + 2 * lane);
-      const float o0 = __low2float(o2), o1 = __high2float(o2);
+      if (cur_group >= 0) flush_group();
+      const float o0 = __low2float(cur.ok2), o1 = __high2float(cur.ok2);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) qo[i] = xor_sum(qo0[i] * o0 + qo1[i] * o1, 64) * scale_log2e;
+      for (int i = 0; i < 4; ++i) qo[i] = wave_sum_u(qo0[i] * o0 + qo1[i] * o1) * scale_log2e;
+      ov0 = __low2float(cur.ov2);
+      ov1 = __high2float(cur.ov2);
       cur_group = grp;
     }
 
-    // d2/d3: HT(q) . C[codes] for four heads, fp32 accumulate over the sub-vectors
+    // d2/d3: HT(q) . C[codes] for four heads; gathers of chunk c+1 are issued before the
+    // contractions of chunk c
     f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
-    if constexpr (SUB == 4) {
-      static_for<32>([&](auto ic) {
-        constexpr int s = decltype(ic)::value;
-        const uint32_t addr = perm_b32(kcode[s / 4], laneoff, 0x0c0c0400u + ((s % 4) << 8));
-        const uint2 cw = *reinterpret_cast<const uint2*>(sm.table + addr);
-        const h4 bop = as_h4(cw.x, cw.y);
-        d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[s / 16], bop, d0, 4, s % 16, 0);
-        d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QL[s / 16], bop, d1, 4, s % 16, 0);
-      });
-    } else {
-      static_for<16>([&](auto ic) {
-        constexpr int s = decltype(ic)::value;
-        const uint32_t addr = perm_b32(kcode[s / 4], laneoff, 0x0c0c0400u + ((s % 4) << 8));
-        const uint4 cw = *reinterpret_cast<const uint4*>(sm.table + addr);
-        const h4 b0 = as_h4(cw.x, cw.y), b1 = as_h4(cw.z, cw.w);
-        d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[(2 * s) / 16], b0, d0, 4, (2 * s) % 16, 0);
-        d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QL[(2 * s) / 16], b0, d1, 4, (2 * s) % 16, 0);
-        d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[(2 * s + 1) / 16], b1, d0, 4, (2 * s + 1) % 16, 0);
-        d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QL[(2 * s + 1) / 16], b1, d1, 4, (2 * s + 1) % 16, 0);
+    {
+      cw_t bufA[8], bufB[8];
+      k_gather(cur.kcode, std::integral_constant<int, 0>{}, bufA);
+      static_for<J / 8>([&](auto cc) {
+        constexpr int ch = decltype(cc)::value;
+        if constexpr (ch % 2 == 0) {
+          if constexpr (ch + 1 < J / 8) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufB);
+          k_contract(cc, bufA, d0, d1);
+        } else {
+          if constexpr (ch + 1 < J / 8) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufA);
+          k_contract(cc, bufB, d0, d1);
+        }
       });
     }
+    cw_t vbufA[4], vbufB[4];
+    v_gather(cur.vcode[0], vbufA);  // first value-side gathers fly during the softmax arithmetic
 
     // d3/d4: scores in log2 units, lazy running max, weights
     float s[4], w[4];
@@ -278,7 +452,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     if (__any(need)) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float m_new = fmaxf(m_run[i], wave_max(s[i]));
+        const float m_new = fmaxf(m_run[i], wave_max_u(s[i]));
         const float corr = (m_run[i] == -INFINITY) ? 0.f : fast_exp2(m_run[i] - m_new);
         l_run[i] *= corr;
         beta[i] *= corr;
@@ -301,125 +475,191 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     for (int k = 0; k < 4; ++k) wop[k] = (_Float16)w[k];
 
     // d5: out_rot[head][channel] += sum over tokens of weight * codeword channel
-    static_for<KW>([&](auto ic) {
-      constexpr int a = decltype(ic)::value;
-      const uint32_t vw = vcode[a];
-      if constexpr (SUB == 4) {
-        uint2 cw[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-          cw[k] = *reinterpret_cast<const uint2*>(sm.table + perm_b32(vw, laneoff, 0x0c0c0400u + (k << 8)));
-        const h4 b0 = as_h4(perm_b32(cw[1].x, cw[0].x, 0x05040100u), perm_b32(cw[3].x, cw[2].x, 0x05040100u));
-        const h4 b1 = as_h4(perm_b32(cw[1].x, cw[0].x, 0x07060302u), perm_b32(cw[3].x, cw[2].x, 0x07060302u));
-        const h4 b2 = as_h4(perm_b32(cw[1].y, cw[0].y, 0x05040100u), perm_b32(cw[3].y, cw[2].y, 0x05040100u));
-        const h4 b3 = as_h4(perm_b32(cw[1].y, cw[0].y, 0x07060302u), perm_b32(cw[3].y, cw[2].y, 0x07060302u));
-        acc[0] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, b0, acc[0], CBSZ_V, a, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, b1, acc[1], CBSZ_V, a, 0);
-        acc[2] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, b2, acc[2], CBSZ_V, a, 0);
-        acc[3] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, b3, acc[3], CBSZ_V, a, 0);
+    static_for<KW>([&](auto ac) {
+      constexpr int a = decltype(ac)::value;
+      if constexpr (a % 2 == 0) {
+        if constexpr (a + 1 < KW) v_gather(cur.vcode[a + 1], vbufB);
+        v_contract(ac, vbufA, wop);
       } else {
-        uint4 cw[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-          cw[k] = *reinterpret_cast<const uint4*>(sm.table + perm_b32(vw, laneoff, 0x0c0c0400u + (k << 8)));
-        const uint32_t c0[4] = {cw[0].x, cw[0].y, cw[0].z, cw[0].w};
-        const uint32_t c1[4] = {cw[1].x, cw[1].y, cw[1].z, cw[1].w};
-        const uint32_t c2[4] = {cw[2].x, cw[2].y, cw[2].z, cw[2].w};
-        const uint32_t c3[4] = {cw[3].x, cw[3].y, cw[3].z, cw[3].w};
-#pragma unroll
-        for (int mth = 0; mth < 4; ++mth) {
-          const h4 be = as_h4(perm_b32(c1[mth], c0[mth], 0x05040100u), perm_b32(c3[mth], c2[mth], 0x05040100u));
-          const h4 bo = as_h4(perm_b32(c1[mth], c0[mth], 0x07060302u), perm_b32(c3[mth], c2[mth], 0x07060302u));
-          acc[2 * mth] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, be, acc[2 * mth], CBSZ_V, a, 0);
-          acc[2 * mth + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, bo, acc[2 * mth + 1], CBSZ_V, a, 0);
-        }
+        if constexpr (a + 1 < KW) v_gather(cur.vcode[a + 1], vbufA);
+        v_contract(ac, vbufB, wop);
       }
     });
+    cur = nxt;
   }
-  if (cur_group >= 0) flush_group(cur_group);
+  NSN_TSTAMP(10);
+  if (cur_group >= 0) flush_group();
 
-  // ---- epilogue: wave results -> LDS (reusing the table), merge the waves, write partials ---
+  // ---- epilogue: wave results -> LDS (reusing the table), merge the waves -------------------
 #pragma unroll
-  for (int i = 0; i < 4; ++i) l_run[i] = xor_sum(l_run[i], 64);
+  for (int i = 0; i < 4; ++i) l_run[i] = wave_sum_u(l_run[i]);
+  __syncthreads();  // every wave is done gathering from the table
+  float* racc = reinterpret_cast<float*>(sm_table);  // [NW][4][128]; the tail follows it
 #pragma unroll
   for (int c = 0; c < SUB; ++c)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float v = acc[c][i];
-      for (int msk = LV; msk < 64; msk <<= 1) v += __shfl_xor(v, msk, 64);
-      acc[c][i] = v;
+#pragma unroll
+      for (int msk = LV; msk < 64; msk <<= 1) v += __shfl_xor(v, msk, 64);  // add the token parts
+      if (lane < LV) racc[(wave * 4 + i) * kHeadDim + lane * SUB + c] = v;
     }
-  __syncthreads();  // every wave is done gathering from the table
-  float* racc = reinterpret_cast<float*>(sm.table);  // [NW][4][128]
-  if (lane < LV) {
-#pragma unroll
-    for (int c = 0; c < SUB; ++c)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) racc[(wave * 4 + i) * kHeadDim + lane * SUB + c] = acc[c][i];
-  }
 #pragma unroll
   for (int i = 0; i < 4; ++i)
     if (lane == i) {
-      sm.wave_m[wave][i] = m_run[i];
-      sm.wave_l[wave][i] = l_run[i];
+      sm_wave_m[wave][i] = m_run[i];
+      sm_wave_l[wave][i] = l_run[i];
     }
   __syncthreads();
+  float* P = partial + ((int64_t)(b * g.n_q_heads + h * r) * n_splits + split) * kPartialStrideM;
   for (int i = tid; i < r * kHeadDim; i += NT) {
     const int hh = i >> 7, c = i & 127;
     float M = -INFINITY;
-    for (int wv = 0; wv < NW; ++wv) M = fmaxf(M, sm.wave_m[wv][hh]);
+    for (int wv = 0; wv < NW; ++wv) M = fmaxf(M, sm_wave_m[wv][hh]);
     float L = 0.f, orot = 0.f, omean = 0.f;
     for (int wv = 0; wv < NW; ++wv) {
-      const float mw = sm.wave_m[wv][hh];
+      const float mw = sm_wave_m[wv][hh];
       const float e = (mw == -INFINITY) ? 0.f : fast_exp2(mw - M);
-      L = fmaf(e, sm.wave_l[wv][hh], L);
+      L = fmaf(e, sm_wave_l[wv][hh], L);
       orot = fmaf(e, racc[(wv * 4 + hh) * kHeadDim + c], orot);
-      omean = fmaf(e, sm.accm[wv][hh][c], omean);
+      omean = fmaf(e, sm_accm[wv][hh][c], omean);
     }
     float* Ph = P + (int64_t)hh * n_splits * kPartialStrideM;
-    Ph[c] = orot;
-    Ph[kHeadDim + c] = omean;
+    st_agent(Ph + c, orot);
+    st_agent(Ph + kHeadDim + c, omean);
     if (c == 0) {
-      Ph[2 * kHeadDim] = M * kLn2;
-      Ph[2 * kHeadDim + 1] = L;
+      st_agent(Ph + 2 * kHeadDim, M);
+      st_agent(Ph + 2 * kHeadDim + 1, L);
+    }
+  }
+  NSN_TSTAMP(11);
+
+  // ---- d6: the last workgroup of this (sequence, kv head) merges the splits -----------------
+  // The partials are published with device-scope (write-through) stores and read back with
+  // device-scope loads, ordered by the arrival counter; no bulk cache write-back is needed.
+  __builtin_amdgcn_s_waitcnt(0);  // this wave's partial stores have completed
+  __syncthreads();
+  if (tid == 0) {
+    int* cnt = counters + (b * g.n_kv_heads + h);
+    const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = (old == n_splits - 1);
+    if (last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
+    *sm_is_last = last;
+  }
+  __syncthreads();
+  if (!*sm_is_last) return;
+  float* rot = sm_rot;  // [4][128]
+  const float* P0 = partial + (int64_t)(b * g.n_q_heads + h * r) * n_splits * kPartialStrideM;
+  float mm_keep[(4 * kHeadDim + NT - 1) / NT], L_keep[(4 * kHeadDim + NT - 1) / NT];
+  {
+    int slot = 0;
+    for (int i = tid; i < 4 * kHeadDim; i += NT, ++slot) {
+      const int hh = i >> 7, c = i & 127;
+      float L = 0.f, rsum = 0.f, mm = 0.f;
+      if (hh < r) {
+        const float* Ph = P0 + (int64_t)hh * n_splits * kPartialStrideM;
+        float M = -INFINITY;
+        for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ld_agent(Ph + s * kPartialStrideM + 2 * kHeadDim));
+        if (M > -INFINITY) {
+          for (int s = 0; s < n_splits; ++s) {
+            const float* ps = Ph + s * kPartialStrideM;
+            const float e = fast_exp2(ld_agent(ps + 2 * kHeadDim) - M);
+            L = fmaf(e, ld_agent(ps + 2 * kHeadDim + 1), L);
+            rsum = fmaf(e, ld_agent(ps + c), rsum);
+            mm = fmaf(e, ld_agent(ps + kHeadDim + c), mm);
+          }
+        }
+      }
+      rot[i] = rsum;
+      mm_keep[slot] = mm;
+      L_keep[slot] = L;
+    }
+  }
+  for (int s = 1; s < kHeadDim; s <<= 1) {  // one inverse Hadamard per head (H is its own inverse)
+    __syncthreads();
+    for (int i = tid; i < 4 * 64; i += NT) {
+      const int hh = i >> 6, k = i & 63;
+      const int lo = ((k & ~(s - 1)) << 1) | (k & (s - 1));
+      const float a0 = rot[hh * kHeadDim + lo], a1 = rot[hh * kHeadDim + lo + s];
+      rot[hh * kHeadDim + lo] = a0 + a1;
+      rot[hh * kHeadDim + lo + s] = a0 - a1;
+    }
+  }
+  __syncthreads();
+  {
+    int slot = 0;
+    for (int i = tid; i < 4 * kHeadDim; i += NT, ++slot) {
+      const int hh = i >> 7, c = i & 127;
+      if (hh < r) {
+        const float L = L_keep[slot];
+        out[(int64_t)(b * g.n_q_heads + h * r + hh) * kHeadDim + c] =
+            L > 0.f ? (rot[i] * (float)kInvSqrtD + mm_keep[slot]) / L : 0.f;
+      }
     }
   }
 }
 
+#ifdef NSN_DECODE_TIMING
+extern "C" int nsn_debug_decode_timing(long long* host48) {
+  return hipMemcpyFromSymbol(host48, HIP_SYMBOL(g_dec_timing), sizeof(long long) * 48) == hipSuccess ? 0 : -1;
+}
+#endif
+
 // ---------------------------------------------------------------------------------------
-template <int SUB, int NW>
+template <int SUB, int NW, bool HILO>
 static int launch_one(const Geometry& g, const void* codebook, const void* q, const CacheView& kv,
-                      const CacheView& vv, const int32_t* seq_lens, int batch, float scale, int n_splits,
-                      float* partial, hipStream_t stream) {
-  const size_t smem = sizeof(DecSmem<SUB, NW>);
+                      const CacheView& vv, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
+                      int n_splits, void* workspace, size_t counter_bytes, float* out, hipStream_t stream) {
+  const size_t smem = DecSmem<SUB, NW>::kBytes;
   static bool attr_done = false;
   if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW>),
+    // the gathers address the codebook table by absolute LDS address: it must start at 0,
+    // i.e. the kernel may not own any static LDS in front of its dynamic block
+    hipFuncAttributes fa;
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, HILO>)) != hipSuccess ||
+        fa.sharedSizeBytes != 0)
+      return NSN_ERR_HIP;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, HILO>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return NSN_ERR_HIP;
     attr_done = true;
   }
+  const int per = (((max_seq_len + n_splits - 1) / n_splits) + 63) & ~63;
+  int* counters = static_cast<int*>(workspace);
+  float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + counter_bytes);
   const dim3 grid(n_splits, g.n_kv_heads, batch);
-  dec_mfma_kernel<SUB, NW><<<grid, NW * 64, smem, stream>>>(g, (const __half*)codebook, (const __half*)q, kv, vv,
-                                                            seq_lens, scale * 1.44269504088896340736f, n_splits,
-                                                            partial);
+  dec_mfma_kernel<SUB, NW, HILO><<<grid, NW * 64, smem, stream>>>(
+      g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens, scale * 1.44269504088896340736f, n_splits,
+      per, partial, counters, out);
   return NSN_OK;
+}
+
+// arrival counters (one int per (sequence, kv head)) sit at the head of the workspace
+static size_t counter_bytes(const nsn_shape& s, int batch) {
+  return (((size_t)batch * s.n_kv_heads * sizeof(int)) + 255) & ~(size_t)255;
 }
 
 int decode_mfma_splits(const nsn_shape& s, int batch, int max_seq_len, int requested) {
   const int cap = max(1, min(64, (max_seq_len + 255) / 256));
   if (requested > 0) return min(requested, 64);
   const int units = max(1, batch * s.n_kv_heads);
-  return max(1, min(cap, (512 + units - 1) / units));  // about two workgroups per compute unit
+  return max(1, min(cap, (256 + units - 1) / units));  // one 8-wave workgroup per compute unit
+}
+
+size_t decode_mfma_workspace_bytes(const nsn_shape& s, int batch, int n_splits) {
+  return counter_bytes(s, batch) + (size_t)batch * s.n_q_heads * n_splits * kPartialStrideM * sizeof(float);
 }
 
 int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
-                       const nsn_cache& vc, const int32_t* seq_lens, int batch, float scale, int n_splits,
-                       float* partial, hipStream_t stream) {
+                       const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
+                       int n_splits, void* workspace, float* out, hipStream_t stream) {
   const Geometry g = make_geometry(s);
   const CacheView kv = make_view(kc), vv = make_view(vc);
-  return s.sub_dim == 4 ? launch_one<4, 4>(g, codebook, q, kv, vv, seq_lens, batch, scale, n_splits, partial, stream)
-                        : launch_one<8, 4>(g, codebook, q, kv, vv, seq_lens, batch, scale, n_splits, partial, stream);
+  const size_t cb = counter_bytes(s, batch);
+  return s.sub_dim == 4 ? launch_one<4, 8, true>(g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale,
+                                                 n_splits, workspace, cb, out, stream)
+                        : launch_one<8, 8, true>(g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale,
+                                                 n_splits, workspace, cb, out, stream);
 }
 
 }  // namespace nsn

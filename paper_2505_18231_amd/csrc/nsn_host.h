@@ -38,9 +38,10 @@ int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, co
 int decode_pick_splits(const nsn_shape& s, int batch, int max_seq_len, int requested);
 bool decode_use_mfma(const nsn_shape& s);
 int decode_mfma_splits(const nsn_shape& s, int batch, int max_seq_len, int requested);
+size_t decode_mfma_workspace_bytes(const nsn_shape& s, int batch, int n_splits);
 int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
-                       const nsn_cache& vc, const int32_t* seq_lens, int batch, float scale, int n_splits,
-                       float* partial, hipStream_t stream);
+                       const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
+                       int n_splits, void* workspace, float* out, hipStream_t stream);
 size_t decode_workspace_bytes(const nsn_shape& s, int batch, int n_splits);
 int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
                   const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
