@@ -149,6 +149,24 @@ def scale_adjust(v: np.ndarray, vq: np.ndarray) -> np.ndarray:
 # rounding points (b = s1, o, a = s1 s2 alpha); rounded b and o are the values used
 # downstream, so that dequantisation is self-consistent.
 # ----------------------------------------------------------------------------
+def shift_stats(x16: np.ndarray, group_size: int = 0, start: int = 0, given_b=None, given_o=None):
+    """Stage A of the encoder: b = fp16(s1) per token (step 1 of Sec. 3.2) and o = fp16(per-group
+    channel mean of x / b) (step 2).  `given_*` replace the computed arrays."""
+    x = np.asarray(x16, dtype=F64)
+    l, d = x.shape
+    b16 = fp16_rne(token_scale(x)) if given_b is None else np.asarray(given_b, dtype=np.float16)
+    if given_o is not None:
+        return b16, np.asarray(given_o, dtype=np.float16)
+    assert group_size == 0 or start % group_size == 0, "a new group starts on a boundary"
+    assert group_size != 0 or start == 0
+    n = _safe_div(x, b16.astype(F64)[:, None])
+    g = group_index(l, group_size, start)
+    o16 = np.zeros(((int(g.max()) + 1) if l else 0, d), dtype=np.float16)
+    for gi in np.unique(g):
+        o16[gi] = fp16_rne(n[g == gi].mean(axis=0))
+    return b16, o16
+
+
 def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: int = 0,
            frozen_o: np.ndarray | None = None, given_b: np.ndarray | None = None,
            given_o: np.ndarray | None = None, return_debug: bool = False):
@@ -169,24 +187,12 @@ def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: in
     assert d % sub == 0
     H = hadamard(d)
 
-    # step 1 (Normalize): s1, stored as fp16 b
-    b16 = fp16_rne(token_scale(x)) if given_b is None else np.asarray(given_b, dtype=np.float16)
+    # steps 1 and 2 (Normalize, Shift): the two stored side-information arrays b and o
+    g = group_index(l, group_size, start)
+    b16, o16 = shift_stats(x16, group_size, start, given_b=given_b,
+                           given_o=frozen_o if frozen_o is not None else given_o)
     b = b16.astype(F64)
     n = _safe_div(x, b[:, None])
-
-    # step 2 (Shift): per-group channel mean, stored as fp16 o
-    g = group_index(l, group_size, start)
-    if frozen_o is not None:
-        o16 = np.asarray(frozen_o, dtype=np.float16)
-    elif given_o is not None:
-        o16 = np.asarray(given_o, dtype=np.float16)
-    else:
-        assert group_size == 0 or start % group_size == 0, "a new group starts on a boundary"
-        assert group_size != 0 or start == 0
-        ng_total = (int(g.max()) + 1) if l else 0
-        o16 = np.zeros((ng_total, d), dtype=np.float16)
-        for gi in np.unique(g):
-            o16[gi] = fp16_rne(n[g == gi].mean(axis=0))
     o = o16.astype(F64)
     ns = n - o[g]
 

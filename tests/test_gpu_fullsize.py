@@ -1,0 +1,91 @@
+"""Full-size GPU parity in the launch configuration bench.py times (Llama-3-8B shape, 2-bit,
+batch 8 x 8192 tokens, 32 query heads over 8 kv heads, one Shift group per sequence, automatic
+split count), plus the long-context 1-bit shape (131072 tokens, batch 1).
+
+The GPU encodes and decodes the whole batch; the oracle re-computes a sample of (sequence, kv-head)
+units: the encoder's two-stage check on those units, and decode attention on the very cache bytes
+the GPU produced (so the decode comparison is exact up to arithmetic, not up to code ties)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import nsn_oracle as O
+from paper_2505_18231_amd import synth
+from tests import helpers
+from tests.test_gpu_encode import check_unit
+
+pytestmark = pytest.mark.gpu
+
+
+def check_unit_sampled(x16, got, cb, n_tokens, seed):
+    """Long sequences (one Shift group): stage A on every token, stage B on a seeded token sample,
+    conditioned on the device's stored b and o (tokens are independent once b and o are fixed)."""
+    b_ref, o_ref = O.shift_stats(x16, 0)
+    assert np.array_equal(b_ref.view(np.uint16), got["b"].view(np.uint16)), "first-Normalize scale"
+    assert np.array_equal(o_ref.view(np.uint16), got["o"][:1].view(np.uint16)), "means"
+    idx = np.sort(np.random.default_rng(seed).choice(x16.shape[0], size=n_tokens, replace=False))
+    part = dict(codes=got["codes"][idx], a=got["a"][idx], b=got["b"][idx], o=got["o"][:1])
+    return check_unit(x16[idx], part, cb, 0, frozen=got["o"][:1])
+
+
+def _run(api, cfg_name, cb, sample_units, G=0, token_sample=None):
+    import torch
+    cfg = synth.CONFIGS[cfg_name]
+    B, Hq, Hkv, L, sub, seed = (cfg["batch"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["length"],
+                                cfg["sub_dim"], cfg["seed"])
+    J = 128 // sub
+    r = Hq // Hkv
+    scale = 1.0 / math.sqrt(128)
+    print(f"case {cfg_name} B={B} Hq={Hq} Hkv={Hkv} L={L} sub={sub}", flush=True)
+    shape = api.make_shape(sub, Hq, Hkv, L, G)
+    kc, vc = api.alloc_cache(shape, B), api.alloc_cache(shape, B)
+    cbd = torch.from_numpy(cb.astype(np.float16)).cuda()
+    zeros = torch.zeros(B, dtype=torch.int32).cuda()
+    full = torch.full((B,), L, dtype=torch.int32).cuda()
+    # encode unit by unit batches of heads to bound host memory: one sequence at a time
+    k_units, v_units = {}, {}
+    for b in range(B):
+        k = np.empty((1, Hkv, L, 128), dtype=np.float16)
+        v = np.empty_like(k)
+        for h in range(Hkv):
+            k[0, h] = synth.make_k(seed, b, h, L, per_seq=cfg.get("per_seq", False))
+            v[0, h] = synth.make_v(seed, b, h, L)
+            if (b, h) in sample_units:
+                k_units[(b, h)], v_units[(b, h)] = k[0, h].copy(), v[0, h].copy()
+        sub_k = api.CodedCache(kc.codes[b:b + 1], kc.norms[b:b + 1], kc.means[b:b + 1], None)
+        sub_v = api.CodedCache(vc.codes[b:b + 1], vc.norms[b:b + 1], vc.means[b:b + 1], None)
+        api.nsn_encode(shape, cbd, torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), zeros[:1], full[:1],
+                       sub_k, sub_v)
+    q = synth.make_q(seed, B, Hq)
+    out = api.nsn_decode_attention(shape, cbd, torch.from_numpy(q).cuda(), kc, vc, full, L, scale, 0)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy().astype(np.float64)
+    worst = 0.0
+    for (b, h) in sample_units:
+        kd = dict(codes=helpers.unpack_codes(kc.codes[b, h].cpu().numpy(), "k", J)[:L],
+                  a=kc.norms[b, h, :L, 0].cpu().numpy(), b=kc.norms[b, h, :L, 1].cpu().numpy(),
+                  o=kc.means[b, h].cpu().numpy())
+        vd = dict(codes=helpers.unpack_codes(vc.codes[b, h].cpu().numpy(), "v", J)[:L],
+                  a=vc.norms[b, h, :L, 0].cpu().numpy(), b=vc.norms[b, h, :L, 1].cpu().numpy(),
+                  o=vc.means[b, h].cpu().numpy())
+        if token_sample:
+            flips = (check_unit_sampled(k_units[(b, h)], kd, cb, token_sample, 1) +
+                     check_unit_sampled(v_units[(b, h)], vd, cb, token_sample, 2))
+        else:
+            flips = check_unit(k_units[(b, h)], kd, cb, G) + check_unit(v_units[(b, h)], vd, cb, G)
+        ref = O.decode_attention(q[b, h * r:(h + 1) * r].astype(np.float64), kd, vd, cb, scale, G)
+        err = helpers.max_rel_err(out[b, h * r:(h + 1) * r], ref)
+        print(f"  unit (b={b}, h={h}): near-tie code differences {flips}, decode max rel err {err:.3e}", flush=True)
+        worst = max(worst, err)
+    assert worst < 2e-3, worst
+    # properties that hold at any size: finite outputs, and |out| bounded by the largest value token norm
+    assert np.isfinite(out).all()
+
+
+def test_llama3_8b_2bit_full_shape(gpu_api, codebooks):
+    _run(gpu_api, "C1", codebooks[4], [(0, 0), (3, 5), (7, 7)])
+
+
+def test_long_context_1bit_full_shape(gpu_api, codebooks):
+    _run(gpu_api, "C2", codebooks[8], [(0, 2)], token_sample=4096)
