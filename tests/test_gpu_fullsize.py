@@ -29,10 +29,10 @@ def check_unit_sampled(x16, got, cb, n_tokens, seed):
     return check_unit(x16[idx], part, cb, 0, frozen=got["o"][:1])
 
 
-def _run(api, cfg_name, cb, sample_units, G=0, token_sample=None):
+def _run(api, cfg_name, cb, sample_units, G=0, token_sample=None, batch=None):
     import torch
     cfg = synth.CONFIGS[cfg_name]
-    B, Hq, Hkv, L, sub, seed = (cfg["batch"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["length"],
+    B, Hq, Hkv, L, sub, seed = (batch or cfg["batch"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["length"],
                                 cfg["sub_dim"], cfg["seed"])
     J = 128 // sub
     r = Hq // Hkv
@@ -89,3 +89,9 @@ def test_llama3_8b_2bit_full_shape(gpu_api, codebooks):
 
 def test_long_context_1bit_full_shape(gpu_api, codebooks):
     _run(gpu_api, "C2", codebooks[8], [(0, 2)], token_sample=4096)
+
+
+def test_mha_large_batch_shape_two_sequences(gpu_api, codebooks):
+    # Llama-2-7B shape (32 kv heads = 32 query heads, 32768 tokens, 2-bit, per-sequence channel
+    # biases); two of the 64 sequences, so that the host-side generation stays small
+    _run(gpu_api, "C3", codebooks[4], [(0, 0), (1, 31)], token_sample=4096, batch=2)
