@@ -229,18 +229,28 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   typedef typename std::conditional<SUB == 4, uint2, uint4>::type cw_t;
   cw_t cw_reg = {};
   if (tid < kCodes) cw_reg = reinterpret_cast<const cw_t*>(codebook)[tid];
-  float qv = 0.f;  // NT == 512 covers 4 heads x 128 channels; smaller blocks loop below
+  constexpr int QPT = (4 * kHeadDim + NT - 1) / NT;  // query elements per thread
+  float qv[QPT];
+#pragma unroll
+  for (int u = 0; u < QPT; ++u) {
+    const int i = tid + u * NT, hh = i >> 7, c = i & 127;
+    qv[u] = (i < 4 * kHeadDim && hh < r) ? __half2float(q[(int64_t)(b * g.n_q_heads + h * r + hh) * kHeadDim + c]) : 0.f;
+  }
   Grp cur;
   const bool spec = !g.paged && (t0 + (wave << 6) + 64 <= g.page_tokens);  // in bounds whatever the length
   if (spec) load_group(wave, cur);
   const int len = seq_lens[b];  // scalar load in flight; first used after the prologue
+#ifdef NSN_DECODE_TIMING
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  NSN_TSTAMP(13);
+#endif
 
   // ---- prologue: codebook table, rotated query (independent of the sequence length) ----------
   if (tid < kCodes) reinterpret_cast<cw_t*>(sm_stage)[tid] = cw_reg;
-  for (int i = tid; i < 4 * kHeadDim; i += NT) {
-    const int hh = i >> 7, c = i & 127;
-    qv = hh < r ? __half2float(q[(int64_t)(b * g.n_q_heads + h * r + hh) * kHeadDim + c]) : 0.f;
-    sm_q_orig[hh][c] = qv;
+#pragma unroll
+  for (int u = 0; u < QPT; ++u) {
+    const int i = tid + u * NT;
+    if (i < 4 * kHeadDim) sm_q_orig[i >> 7][i & 127] = qv[u];
   }
   __syncthreads();
   NSN_TSTAMP(12);
@@ -404,8 +414,9 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     NSN_TSTAMP(3 + (gi / NW < 6 ? gi / NW : 6));
     const int tg = t0 + (gi << 6);  // first token of the group (multiple of 64)
     const bool valid = (tg + lane) < t1;
-    Grp nxt = cur;
-    if (gi + NW < n_grp) load_group(gi + NW, nxt);  // wave-uniform
+    const bool has_next = gi + NW < n_grp;  // wave-uniform
+    Grp nxt;
+    if (has_next) load_group(gi + NW, nxt);
     const float a_k = valid ? __low2float(cur.nk) : 0.f, b_k = valid ? __high2float(cur.nk) : 0.f;
     const float a_v = valid ? __low2float(cur.nv) : 0.f, b_v = valid ? __high2float(cur.nv) : 0.f;
 
@@ -485,7 +496,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
         v_contract(ac, vbufB, wop);
       }
     });
-    cur = nxt;
+    if (has_next) cur = nxt;
   }
   NSN_TSTAMP(10);
   if (cur_group >= 0) flush_group();

@@ -8,7 +8,9 @@
 // Normalisation, rotation and the dot products that feed fp16 roundings run in fp64 (same rate
 // as fp32 on this chip's vector units); only the 256-way distance scan runs in fp32.
 #include "nsn_host.h"
-#include "nsn_vq.h"
+#include <cstdlib>
+
+#include "nsn_vq_mfma.h"
 
 namespace nsn {
 
@@ -100,7 +102,9 @@ __global__ __launch_bounds__(128) void enc_means_kernel(Geometry g, int max_new,
 // grid (64-token chunk, kv_head * 2 + tensor, sequence), block 256.  A lane owns one
 // sub-vector (SUB channels) of one token; a wave covers 64 / J tokens at a time.
 // ---------------------------------------------------------------------------------------
-template <int SUB>
+// MFMA:  distance contraction on the matrix cores (else the fp32 vector-ALU scan)
+// FUSED: append mode - the first-Normalize scale is computed here instead of by the stats kernel
+template <int SUB, bool MFMA, bool FUSED>
 __global__ __launch_bounds__(256) void enc_quant_kernel(Geometry g, const __half* __restrict__ codebook,
                                                         const __half* __restrict__ k_in,
                                                         const __half* __restrict__ v_in, int max_new,
@@ -114,6 +118,8 @@ __global__ __launch_bounds__(256) void enc_quant_kernel(Geometry g, const __half
 
   const int h = blockIdx.y >> 1, tensor = blockIdx.y & 1, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  MfmaCodebook<SUB> MC;
+  if constexpr (MFMA) mfma_codebook_load<SUB>(MC, T, lane);
   const int jj = lane % J, tk = lane / J;
   const CacheView& cv = tensor ? vc : kc;
   const __half* in = (tensor ? v_in : k_in) + ((int64_t)(b * g.n_kv_heads + h) * max_new) * kHeadDim;
@@ -131,10 +137,27 @@ __global__ __launch_bounds__(256) void enc_quant_kernel(Geometry g, const __half
     double bb = 0.0;
     int64_t base = 0;
     int tin = 0;
+    double xs[SUB];
+    __half b16f = __float2half(0.f);
+    if constexpr (FUSED) {  // first Normalize here: b = fp16(||x|| / sqrt(d)), stored with the token
+      double ssx = 0.0;
+#pragma unroll
+      for (int i = 0; i < SUB; ++i) {
+        xs[i] = valid ? (double)__half2float(in[(int64_t)t * kHeadDim + jj * SUB + i]) : 0.0;
+        ssx += xs[i] * xs[i];
+      }
+      ssx = xor_sum(ssx, J);
+      b16f = f64_to_f16(sqrt(ssx) / kSqrtD);
+      bb = (double)__half2float(b16f);
+    }
     if (valid) {
       base = unit_token_base(g, cv.block_table, b, h, pos);
       tin = token_in_unit(g, pos);
-      bb = (double)__half2float(reinterpret_cast<const __half*>(cv.norms)[2 * (base + tin) + 1]);
+      if constexpr (FUSED) {
+        if (jj == 0) reinterpret_cast<__half*>(cv.norms)[2 * (base + tin) + 1] = b16f;
+      } else {
+        bb = (double)__half2float(reinterpret_cast<const __half*>(cv.norms)[2 * (base + tin) + 1]);
+      }
       const __half* xp = in + (int64_t)t * kHeadDim + jj * SUB;
       const __half* op =
           cv.means + ((int64_t)(b * g.n_kv_heads + h) * g.n_groups_max + min(group_of(g, pos), g.n_groups_max - 1)) *
@@ -182,7 +205,11 @@ __global__ __launch_bounds__(256) void enc_quant_kernel(Geometry g, const __half
 #pragma unroll
     for (int i = 0; i < SUB; ++i) y[i] = v[i] * kInvSqrtD;
 
-    const int code = vq_search<SUB>(T, y);
+    int code;
+    if constexpr (MFMA)
+      code = vq_search_mfma<SUB>(T, MC, y, lane);
+    else
+      code = vq_search<SUB>(T, y);
 
     // scale adjustment: alpha = ||y||^2 / (y . y_Q)
     double dot = 0.0, nrm2 = 0.0;
@@ -221,24 +248,33 @@ int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, co
   const int ct = encode_chunk_tokens(s);
   const int n_chunks = (max_new + ct - 1) / ct;
   double* partial = static_cast<double*>(workspace);
-  const dim3 grid_a(n_chunks, s.n_kv_heads * 2, batch);
-  enc_stats_kernel<<<grid_a, 256, 0, stream>>>(g, (const __half*)k_in, (const __half*)v_in, max_new, s.max_len,
-                                               seq_start, n_new, kv, vv, partial, ct, n_chunks);
+  const char* impl = getenv("NSN_ENCODE_IMPL");  // "valu" forces the vector-ALU distance scan
+  const bool use_mfma = !(impl && impl[0] == 'v');
   if (!freeze_means) {
+    const dim3 grid_a(n_chunks, s.n_kv_heads * 2, batch);
+    enc_stats_kernel<<<grid_a, 256, 0, stream>>>(g, (const __half*)k_in, (const __half*)v_in, max_new, s.max_len,
+                                                 seq_start, n_new, kv, vv, partial, ct, n_chunks);
     const int n_groups_new = s.group_size > 0 ? n_chunks : 1;
     const dim3 grid_m(n_groups_new, s.n_kv_heads * 2, batch);
     enc_means_kernel<<<grid_m, 128, 0, stream>>>(g, max_new, s.max_len, seq_start, n_new, kv, vv, partial, ct,
                                                  n_chunks);
   }
   const dim3 grid_b((max_new + 63) / 64, s.n_kv_heads * 2, batch);
-  if (s.sub_dim == 8)
-    enc_quant_kernel<8><<<grid_b, 256, 0, stream>>>(g, (const __half*)codebook, (const __half*)k_in,
-                                                    (const __half*)v_in, max_new, s.max_len, seq_start, n_new, kv,
-                                                    vv);
-  else
-    enc_quant_kernel<4><<<grid_b, 256, 0, stream>>>(g, (const __half*)codebook, (const __half*)k_in,
-                                                    (const __half*)v_in, max_new, s.max_len, seq_start, n_new, kv,
-                                                    vv);
+  auto launch = [&](auto kernel) {
+    kernel<<<grid_b, 256, 0, stream>>>(g, (const __half*)codebook, (const __half*)k_in, (const __half*)v_in, max_new,
+                                       s.max_len, seq_start, n_new, kv, vv);
+  };
+  if (s.sub_dim == 8) {
+    if (use_mfma)
+      freeze_means ? launch(enc_quant_kernel<8, true, true>) : launch(enc_quant_kernel<8, true, false>);
+    else
+      freeze_means ? launch(enc_quant_kernel<8, false, true>) : launch(enc_quant_kernel<8, false, false>);
+  } else {
+    if (use_mfma)
+      freeze_means ? launch(enc_quant_kernel<4, true, true>) : launch(enc_quant_kernel<4, true, false>);
+    else
+      freeze_means ? launch(enc_quant_kernel<4, false, true>) : launch(enc_quant_kernel<4, false, false>);
+  }
   return hipGetLastError() == hipSuccess ? NSN_OK : NSN_ERR_HIP;
 }
 

@@ -54,6 +54,21 @@ __device__ inline double exact_dist(const VqTables<SUB>& T, const double (&y)[SU
   return d;
 }
 
+// fp64 exhaustive search, direct form, lowest index on ties (the rare path of both searches)
+template <int SUB>
+__device__ inline int vq_exact_scan(const VqTables<SUB>& T, const double (&y)[SUB]) {
+  double e1 = INFINITY;
+  int k = 0;
+  for (int c = 0; c < kCodes; ++c) {
+    const double d = exact_dist<SUB>(T, y, c);
+    if (d < e1) {
+      e1 = d;
+      k = c;
+    }
+  }
+  return k;
+}
+
 template <int SUB>
 __device__ inline int vq_search(const VqTables<SUB>& T, const double (&y)[SUB]) {
   float yf[SUB];
@@ -78,18 +93,7 @@ __device__ inline int vq_search(const VqTables<SUB>& T, const double (&y)[SUB]) 
   // Rounding-error window of the fp32 pass (inputs rounded to fp32, SUB fused steps, ||c||^2).
   const float M = T.cmax * T.cmax + 2.f * T.cmax * sqrtf(yn2);
   const float window = (8.f * (SUB + 3)) * 5.9604645e-8f * M;
-  if (!(b2 - b1 > window)) {
-    double e1 = INFINITY;
-    int k = 0;
-    for (int c = 0; c < kCodes; ++c) {
-      const double d = exact_dist<SUB>(T, y, c);
-      if (d < e1) {
-        e1 = d;
-        k = c;
-      }
-    }
-    i1 = k;
-  }
+  if (!(b2 - b1 > window)) i1 = vq_exact_scan<SUB>(T, y);
   return i1;
 }
 

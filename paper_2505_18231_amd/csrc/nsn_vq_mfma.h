@@ -1,0 +1,162 @@
+// Nearest-codeword search (Eq. 1) with the distance contraction on the matrix cores.
+//
+// One v_mfma_f32_32x32x16_f16 produces, for 32 codewords (rows) and 32 sub-vectors (columns),
+//   D = ||c||^2 - 2 c . (y_hi + y_lo) + ||y||^2 + margin      (fp32 accumulate)
+// from fp16 operands: the codeword side holds [-2c | -2c | cn_hi cn_lo 1 1 0..] (SUB = 4) or
+// [-2c | cn_hi cn_lo 1 1 0..] (SUB = 8, second pass for y_lo), the token side holds
+// [y_hi | y_lo | 1 1 yn_hi yn_lo 0..].  Codewords are fp16 values, so -2c is exact; y, ||c||^2 and
+// ||y||^2 are split into fp16 hi + lo parts (about 22 bits).  D > 0, so its bit pattern orders
+// like an integer: the low 4 bits are replaced by the row slot and the best two keys are kept
+// with one min and one med3 per value.  If the runner-up is within the error window of the best
+// (key granularity + fp32 rounding of the contraction), the decision is retaken in fp64 over all
+// codewords, exactly as in the vector-ALU search.
+#pragma once
+
+#include "nsn_vq.h"
+
+namespace nsn {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+constexpr float kVqMargin = 0.015625f;  // keeps every distance strictly positive
+
+template <int SUB>
+struct MfmaCodebook {
+  h8 A[8];  // codeword-side operands of the eight 32-codeword blocks
+};
+
+// Build the codeword-side operands (call after vq_tables_fill; every lane of the wave).
+template <int SUB>
+__device__ inline void mfma_codebook_load(MfmaCodebook<SUB>& M, const VqTables<SUB>& T, int lane) {
+#pragma unroll
+  for (int m = 0; m < 8; ++m) {
+    const int c = 32 * m + (lane & 31);
+    h8 a;
+    if (lane < 32) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] = (_Float16)T.neg2c[c][e % SUB];
+    } else {
+      const float cn = T.cn[c];
+      const _Float16 hi = (_Float16)cn;
+      a[0] = hi;
+      a[1] = (_Float16)(cn - (float)hi);
+      a[2] = (_Float16)1.0f;
+      a[3] = (_Float16)1.0f;
+      a[4] = a[5] = a[6] = a[7] = (_Float16)0.0f;
+    }
+    M.A[m] = a;
+  }
+}
+
+__device__ inline uint32_t pack_h2(_Float16 lo, _Float16 hi) {
+  union {
+    _Float16 h[2];
+    uint32_t u;
+  } cv;
+  cv.h[0] = lo;
+  cv.h[1] = hi;
+  return cv.u;
+}
+__device__ inline h8 as_h8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  union {
+    uint32_t u[4];
+    h8 h;
+  } cv;
+  cv.u[0] = a, cv.u[1] = b, cv.u[2] = c, cv.u[3] = d;
+  return cv.h;
+}
+
+// All 64 lanes call this; lane (token slot, sub-vector) layout as in the encoder: lanes [0,32) hold
+// the sub-vectors of the first token set, lanes [32,64) those of the second.
+template <int SUB>
+__device__ inline int vq_search_mfma(const VqTables<SUB>& T, const MfmaCodebook<SUB>& M, const double (&y)[SUB],
+                                     int lane) {
+  constexpr int NP = SUB / 2;  // packed dwords per hi / lo part
+  float yn = 0.f;
+  uint32_t Phi[NP], Plo[NP];
+  {
+    _Float16 yh[SUB], yl[SUB];
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) {
+      const float yf = (float)y[i];
+      yh[i] = (_Float16)yf;
+      yl[i] = (_Float16)(yf - (float)yh[i]);
+      yn = fmaf(yf, yf, yn);
+    }
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      Phi[i] = pack_h2(yh[2 * i], yh[2 * i + 1]);
+      Plo[i] = pack_h2(yl[2 * i], yl[2 * i + 1]);
+    }
+  }
+  const float ynm = yn + kVqMargin;
+  const _Float16 ynh = (_Float16)ynm;
+  const uint32_t Q = pack_h2(ynh, (_Float16)(ynm - (float)ynh));
+  uint32_t Xhi[NP], Xlo[NP];
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    Xhi[i] = __shfl_xor(Phi[i], 32, 64);
+    Xlo[i] = __shfl_xor(Plo[i], 32, 64);
+  }
+  const uint32_t Qx = __shfl_xor(Q, 32, 64);
+  const bool lo_half = lane < 32;
+  const uint32_t ONES = 0x3C003C00u;  // (1.0, 1.0)
+
+  float k1 = 0.f, k2 = 0.f;  // best two keys of the sub-vector this lane owns
+  int code = 0;
+#pragma unroll
+  for (int set = 0; set < 2; ++set) {
+    const uint32_t* ph = (set == 0) ? Phi : Xhi;
+    const uint32_t* pl = (set == 0) ? Plo : Xlo;
+    const uint32_t qq = (set == 0) ? Qx : Q;
+    h8 b1, b2;
+    if constexpr (SUB == 4) {
+      b1 = lo_half ? as_h8(ph[0], ph[1], pl[0], pl[1]) : as_h8(ONES, qq, 0u, 0u);
+      b2 = b1;
+    } else {
+      b1 = lo_half ? as_h8(ph[0], ph[1], ph[2], ph[3]) : as_h8(ONES, qq, 0u, 0u);
+      b2 = lo_half ? as_h8(pl[0], pl[1], pl[2], pl[3]) : as_h8(0u, 0u, 0u, 0u);
+    }
+    float m1 = 3.0e38f, m2 = 3.0e38f;
+    int blk = 0;
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      f16v d;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) d[r] = 0.f;
+      d = __builtin_amdgcn_mfma_f32_32x32x16_f16(M.A[m], b1, d, 0, 0, 0);
+      if constexpr (SUB == 8) d = __builtin_amdgcn_mfma_f32_32x32x16_f16(M.A[m], b2, d, 0, 0, 0);
+      const float prev = m1;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float u = __uint_as_float((__float_as_uint(d[r]) & 0xFFFFFFF0u) | (uint32_t)r);
+        m2 = __builtin_amdgcn_fmed3f(m1, m2, u);
+        m1 = fminf(m1, u);
+      }
+      blk = (m1 < prev) ? m : blk;
+    }
+    const int r = (int)(__float_as_uint(m1) & 15u);
+    const int mine = 32 * blk + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+    // the other half of the wave scanned the other 128 codewords of the same sub-vectors
+    const float o1 = __shfl_xor(m1, 32, 64), o2 = __shfl_xor(m2, 32, 64);
+    const int ocode = __shfl_xor(mine, 32, 64);
+    const float f1 = fminf(m1, o1);
+    const float f2 = fminf(fmaxf(m1, o1), fminf(m2, o2));
+    const int fcode = (o1 < m1) ? ocode : (o1 == m1 ? min(mine, ocode) : mine);
+    if ((set == 0) == lo_half) {
+      k1 = f1;
+      k2 = f2;
+      code = fcode;
+    }
+  }
+  // error window: key granularity (16 ulp, truncated) + fp32 rounding of a 16-term contraction
+  const float d1 = __uint_as_float(__float_as_uint(k1) & 0xFFFFFFF0u);
+  const float d2 = __uint_as_float(__float_as_uint(k2) & 0xFFFFFFF0u);
+  const float reach = T.cmax + sqrtf(yn);
+  const float window = 2.f * (1.9073486e-6f * d2 + 24.f * 5.9604645e-8f * (reach * reach + kVqMargin));
+  if (!(d2 - d1 > window)) code = vq_exact_scan<SUB>(T, y);
+  return code;
+}
+
+}  // namespace nsn

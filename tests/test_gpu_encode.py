@@ -76,9 +76,12 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("impl", ["mfma", "valu"])
 @pytest.mark.parametrize("name,batch,hkv,lens,sub,G,page", CASES, ids=[c[0] for c in CASES])
-def test_encode_matches_oracle(gpu_api, codebooks, name, batch, hkv, lens, sub, G, page):
-    print(f"case {name} lens={lens} sub={sub} G={G} page={page}", flush=True)
+def test_encode_matches_oracle(gpu_api, codebooks, monkeypatch, impl, name, batch, hkv, lens, sub, G, page):
+    # "mfma": distance contraction on the matrix cores (default); "valu": fp32 vector-ALU scan
+    monkeypatch.setenv("NSN_ENCODE_IMPL", impl)
+    print(f"case {name} impl={impl} lens={lens} sub={sub} G={G} page={page}", flush=True)
     cb = codebooks[sub]
     seed = 300 + len(name)
     k, v, hk, hv = run_gpu_encode(gpu_api, seed, batch, hkv, lens, sub, G, cb, page)
@@ -90,7 +93,9 @@ def test_encode_matches_oracle(gpu_api, codebooks, name, batch, hkv, lens, sub, 
     print(f"  near-tie code differences: {flips}", flush=True)
 
 
-def test_append_with_frozen_means(gpu_api, codebooks):
+@pytest.mark.parametrize("impl", ["mfma", "valu"])
+def test_append_with_frozen_means(gpu_api, codebooks, monkeypatch, impl):
+    monkeypatch.setenv("NSN_ENCODE_IMPL", impl)
     cb = codebooks[8]
     lens0 = [200, 64]
     k0, v0, hk, hv = run_gpu_encode(gpu_api, 41, 2, 2, lens0, 8, 0, cb, max_len=256)
