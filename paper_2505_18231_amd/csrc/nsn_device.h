@@ -68,6 +68,49 @@ __device__ inline __half f64_to_f16(double x) {
   return __float2half_rn(f);
 }
 
+// Value of lane (lane ^ M): DPP moves inside a 16-lane row (no LDS traffic), a bpermute across rows.
+template <int CTRL, int BANK>
+__device__ __forceinline__ int dpp_i32(int old, int v) {
+  return __builtin_amdgcn_update_dpp(old, v, CTRL, 0xf, BANK, false);
+}
+template <int M>
+__device__ __forceinline__ int xor_lane_i32(int v) {
+  if constexpr (M == 1) {
+    return dpp_i32<0xB1, 0xf>(0, v);  // quad_perm [1,0,3,2]
+  } else if constexpr (M == 2) {
+    return dpp_i32<0x4E, 0xf>(0, v);  // quad_perm [2,3,0,1]
+  } else if constexpr (M == 4) {
+    const int t = dpp_i32<0x104, 0x5>(0, v);  // row_shl:4 into lanes whose bit 2 is clear
+    return dpp_i32<0x114, 0xa>(t, v);         // row_shr:4 into lanes whose bit 2 is set
+  } else if constexpr (M == 8) {
+    return dpp_i32<0x128, 0xf>(0, v);  // row_ror:8
+  } else {
+    return __shfl_xor(v, M, 64);
+  }
+}
+template <int M>
+__device__ __forceinline__ float xor_lane(float v) {
+  return __builtin_bit_cast(float, xor_lane_i32<M>(__builtin_bit_cast(int, v)));
+}
+template <int M>
+__device__ __forceinline__ double xor_lane(double v) {
+  const long long u = __builtin_bit_cast(long long, v);
+  const unsigned lo = (unsigned)xor_lane_i32<M>((int)(u & 0xffffffffll));
+  const unsigned hi = (unsigned)xor_lane_i32<M>((int)(u >> 32));
+  return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)lo);
+}
+// Butterfly sum over groups of W lanes (W a power of two <= 64); every lane gets the total.
+template <int W, typename T>
+__device__ __forceinline__ T xor_sum_w(T v) {
+  if constexpr (W > 1) v += xor_lane<1>(v);
+  if constexpr (W > 2) v += xor_lane<2>(v);
+  if constexpr (W > 4) v += xor_lane<4>(v);
+  if constexpr (W > 8) v += xor_lane<8>(v);
+  if constexpr (W > 16) v += xor_lane<16>(v);
+  if constexpr (W > 32) v += xor_lane<32>(v);
+  return v;
+}
+
 template <typename T>
 __device__ inline T xor_sum(T v, int width) {  // butterfly sum over groups of `width` lanes
   for (int m = 1; m < width; m <<= 1) v += __shfl_xor(v, m, 64);

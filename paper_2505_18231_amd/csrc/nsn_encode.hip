@@ -9,10 +9,20 @@
 // as fp32 on this chip's vector units); only the 256-way distance scan runs in fp32.
 #include "nsn_host.h"
 #include <cstdlib>
+#include <type_traits>
 
 #include "nsn_vq_mfma.h"
 
 namespace nsn {
+
+// f(integral_constant<int, m>) for m = 1, 2, 4, ... < N
+template <int N, int M = 1, typename F>
+__device__ __forceinline__ void static_for_pow2(F&& f) {
+  if constexpr (M < N) {
+    f(std::integral_constant<int, M>{});
+    static_for_pow2<N, M * 2>(f);
+  }
+}
 
 // ---------------------------------------------------------------------------------------
 // Stage A: first Normalize scale per token, partial channel sums of the normalised tokens.
@@ -39,7 +49,7 @@ __global__ __launch_bounds__(256) void enc_stats_kernel(Geometry g, const __half
     if (pos >= max_len) break;
     const __half2 xv = *reinterpret_cast<const __half2*>(in + (int64_t)t * kHeadDim + 2 * lane);
     const double x0 = (double)__low2float(xv), x1 = (double)__high2float(xv);
-    const double ss = xor_sum(x0 * x0 + x1 * x1, 64);
+    const double ss = xor_sum_w<64>(x0 * x0 + x1 * x1);
     const double s1 = sqrt(ss) / kSqrtD;
     const __half b16 = f64_to_f16(s1);
     const double bb = (double)__half2float(b16);
@@ -102,6 +112,22 @@ __global__ __launch_bounds__(128) void enc_means_kernel(Geometry g, int max_new,
 // grid (64-token chunk, kv_head * 2 + tensor, sequence), block 256.  A lane owns one
 // sub-vector (SUB channels) of one token; a wave covers 64 / J tokens at a time.
 // ---------------------------------------------------------------------------------------
+#ifdef NSN_DECODE_TIMING
+__device__ long long g_enc_timing[16];
+#define NSN_ETSTAMP(slot)                                                             \
+  do {                                                                                \
+    if (blockIdx.x == 0 && blockIdx.y == 3 && blockIdx.z == 2 && threadIdx.x == 0)    \
+      g_enc_timing[slot] = clock64();                                                 \
+  } while (0)
+extern "C" int nsn_debug_encode_timing(long long* host16) {
+  return hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_enc_timing), sizeof(long long) * 16) == hipSuccess ? 0 : -1;
+}
+#else
+#define NSN_ETSTAMP(slot) \
+  do {                    \
+  } while (0)
+#endif
+
 // MFMA:  distance contraction on the matrix cores (else the fp32 vector-ALU scan)
 // FUSED: append mode - the first-Normalize scale is computed here instead of by the stats kernel
 template <int SUB, bool MFMA, bool FUSED>
@@ -114,69 +140,93 @@ __global__ __launch_bounds__(256) void enc_quant_kernel(Geometry g, const __half
   constexpr int J = kHeadDim / SUB;  // lanes per token
   constexpr int TPW = 64 / J;        // tokens per wave step
   __shared__ VqTables<SUB> T;
-  vq_tables_fill<SUB>(T, [&](int c, int i) { return (double)__half2float(codebook[c * SUB + i]); });
-
   const int h = blockIdx.y >> 1, tensor = blockIdx.y & 1, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  MfmaCodebook<SUB> MC;
-  if constexpr (MFMA) mfma_codebook_load<SUB>(MC, T, lane);
   const int jj = lane % J, tk = lane / J;
   const CacheView& cv = tensor ? vc : kc;
   const __half* in = (tensor ? v_in : k_in) + ((int64_t)(b * g.n_kv_heads + h) * max_new) * kHeadDim;
   const int start = seq_start[b];
   const int count = min(n_new[b], max_new);
   const int t_begin = blockIdx.x * 64 + wave * 16;
+
+  // One token's inputs as this lane needs them (vector loads of SUB fp16 values); the first
+  // token's loads are issued before the codebook tables are built, later ones one step ahead.
+  typedef typename std::conditional<SUB == 4, uint2, uint4>::type vec_t;
+  struct Tok {
+    bool valid;
+    int64_t base;
+    int tin;
+    vec_t xraw, oraw;
+    __half b16;
+  };
+  auto fetch = [&](int it) {
+    Tok k;
+    const int t = t_begin + it * TPW + tk;
+    const int pos = start + t;
+    k.valid = (t < count) && (pos < max_len);
+    k.base = 0;
+    k.tin = 0;
+    k.xraw = vec_t{};
+    k.oraw = vec_t{};
+    k.b16 = __float2half(0.f);
+    if (k.valid) {
+      k.base = unit_token_base(g, cv.block_table, b, h, pos);
+      k.tin = token_in_unit(g, pos);
+      k.xraw = *reinterpret_cast<const vec_t*>(in + (int64_t)t * kHeadDim + jj * SUB);
+      k.oraw = *reinterpret_cast<const vec_t*>(
+          cv.means + ((int64_t)(b * g.n_kv_heads + h) * g.n_groups_max + min(group_of(g, pos), g.n_groups_max - 1)) *
+                         kHeadDim + jj * SUB);
+      if constexpr (!FUSED) k.b16 = reinterpret_cast<const __half*>(cv.norms)[2 * (k.base + k.tin) + 1];
+    }
+    return k;
+  };
+  NSN_ETSTAMP(0);
+  Tok nxt = fetch(0);
+
+  vq_tables_fill<SUB>(T, [&](int c, int i) { return (double)__half2float(codebook[c * SUB + i]); });
+  MfmaCodebook<SUB> MC;
+  NSN_ETSTAMP(1);
+  if constexpr (MFMA) mfma_codebook_load<SUB>(MC, T, lane);
   if (blockIdx.x * 64 >= count) return;
+  NSN_ETSTAMP(2);
 
   for (int it = 0; it < 16 / TPW; ++it) {
     if (t_begin + it * TPW >= count) break;  // wave-uniform: nothing left for this wave
-    const int t = t_begin + it * TPW + tk;
-    const int pos = start + t;
-    const bool valid = (t < count) && (pos < max_len);
-    double v[SUB];
-    double bb = 0.0;
-    int64_t base = 0;
-    int tin = 0;
-    double xs[SUB];
-    __half b16f = __float2half(0.f);
+    const Tok cur = nxt;
+    if (it + 1 < 16 / TPW && t_begin + (it + 1) * TPW < count) nxt = fetch(it + 1);
+    const bool valid = cur.valid;
+    const int64_t base = cur.base;
+    const int tin = cur.tin;
+    const vec_t xraw = cur.xraw, oraw = cur.oraw;
+    __half b16f = cur.b16;
+    NSN_ETSTAMP(3);
+    double xs[SUB], os[SUB];
+    {
+      const __half* xh = reinterpret_cast<const __half*>(&xraw);
+      const __half* oh = reinterpret_cast<const __half*>(&oraw);
+#pragma unroll
+      for (int i = 0; i < SUB; ++i) {
+        xs[i] = (double)__half2float(xh[i]);
+        os[i] = (double)__half2float(oh[i]);
+      }
+    }
     if constexpr (FUSED) {  // first Normalize here: b = fp16(||x|| / sqrt(d)), stored with the token
       double ssx = 0.0;
 #pragma unroll
-      for (int i = 0; i < SUB; ++i) {
-        xs[i] = valid ? (double)__half2float(in[(int64_t)t * kHeadDim + jj * SUB + i]) : 0.0;
-        ssx += xs[i] * xs[i];
-      }
-      ssx = xor_sum(ssx, J);
+      for (int i = 0; i < SUB; ++i) ssx += xs[i] * xs[i];
+      ssx = xor_sum_w<J>(ssx);
       b16f = f64_to_f16(sqrt(ssx) / kSqrtD);
-      bb = (double)__half2float(b16f);
+      if (valid && jj == 0) reinterpret_cast<__half*>(cv.norms)[2 * (base + tin) + 1] = b16f;
     }
-    if (valid) {
-      base = unit_token_base(g, cv.block_table, b, h, pos);
-      tin = token_in_unit(g, pos);
-      if constexpr (FUSED) {
-        if (jj == 0) reinterpret_cast<__half*>(cv.norms)[2 * (base + tin) + 1] = b16f;
-      } else {
-        bb = (double)__half2float(reinterpret_cast<const __half*>(cv.norms)[2 * (base + tin) + 1]);
-      }
-      const __half* xp = in + (int64_t)t * kHeadDim + jj * SUB;
-      const __half* op =
-          cv.means + ((int64_t)(b * g.n_kv_heads + h) * g.n_groups_max + min(group_of(g, pos), g.n_groups_max - 1)) *
-                         kHeadDim + jj * SUB;
+    const double bb = (double)__half2float(b16f);
+    double v[SUB];
 #pragma unroll
-      for (int i = 0; i < SUB; ++i) {
-        const double x = (double)__half2float(xp[i]);
-        const double o = (double)__half2float(op[i]);
-        v[i] = (bb != 0.0 ? x / bb : 0.0) - o;
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < SUB; ++i) v[i] = 0.0;
-    }
+    for (int i = 0; i < SUB; ++i) v[i] = valid ? (bb != 0.0 ? xs[i] / bb : 0.0) - os[i] : 0.0;
     // second Normalize
     double ss = 0.0;
 #pragma unroll
     for (int i = 0; i < SUB; ++i) ss += v[i] * v[i];
-    ss = xor_sum(ss, J);
+    ss = xor_sum_w<J>(ss);
     const double s2 = sqrt(ss) / kSqrtD;
 #pragma unroll
     for (int i = 0; i < SUB; ++i) v[i] = (s2 != 0.0) ? v[i] / s2 : 0.0;
@@ -192,25 +242,27 @@ __global__ __launch_bounds__(256) void enc_quant_kernel(Geometry g, const __half
         }
       }
     }
-#pragma unroll
-    for (int m = 1; m < J; m <<= 1) {
+    static_for_pow2<J>([&](auto mc) {
+      constexpr int m = decltype(mc)::value;
       const bool upper = (jj & m) != 0;
 #pragma unroll
       for (int i = 0; i < SUB; ++i) {
-        const double other = __shfl_xor(v[i], m, 64);
+        const double other = xor_lane<m>(v[i]);
         v[i] = upper ? other - v[i] : v[i] + other;
       }
-    }
+    });
     double y[SUB];
 #pragma unroll
     for (int i = 0; i < SUB; ++i) y[i] = v[i] * kInvSqrtD;
 
+    NSN_ETSTAMP(4);
     int code;
     if constexpr (MFMA)
       code = vq_search_mfma<SUB>(T, MC, y, lane);
     else
       code = vq_search<SUB>(T, y);
 
+    NSN_ETSTAMP(5);
     // scale adjustment: alpha = ||y||^2 / (y . y_Q)
     double dot = 0.0, nrm2 = 0.0;
 #pragma unroll
@@ -218,14 +270,15 @@ __global__ __launch_bounds__(256) void enc_quant_kernel(Geometry g, const __half
       dot += y[i] * T.cx[code][i];
       nrm2 += y[i] * y[i];
     }
-    dot = xor_sum(dot, J);
-    nrm2 = xor_sum(nrm2, J);
+    dot = xor_sum_w<J>(dot);
+    nrm2 = xor_sum_w<J>(nrm2);
     const double alpha = (dot > 1e-12 * kHeadDim) ? nrm2 / dot : 1.0;
     if (valid) {
       const int64_t off = tensor ? v_code_offset(J, tin, jj) : k_code_offset(J, tin, jj);
       cv.codes[base * J + off] = (uint8_t)code;
       if (jj == 0) reinterpret_cast<__half*>(cv.norms)[2 * (base + tin)] = f64_to_f16(bb * s2 * alpha);
     }
+    NSN_ETSTAMP(6);
   }
 }
 

@@ -90,7 +90,7 @@ __device__ inline int vq_search_mfma(const VqTables<SUB>& T, const MfmaCodebook<
       Plo[i] = pack_h2(yl[2 * i], yl[2 * i + 1]);
     }
   }
-  const float ynm = yn + kVqMargin;
+  const float ynm = yn + kVqMargin;  // yn itself is needed for the window below
   const _Float16 ynh = (_Float16)ynm;
   const uint32_t Q = pack_h2(ynh, (_Float16)(ynm - (float)ynh));
   uint32_t Xhi[NP], Xlo[NP];
@@ -103,7 +103,7 @@ __device__ inline int vq_search_mfma(const VqTables<SUB>& T, const MfmaCodebook<
   const bool lo_half = lane < 32;
   const uint32_t ONES = 0x3C003C00u;  // (1.0, 1.0)
 
-  float k1 = 0.f, k2 = 0.f;  // best two keys of the sub-vector this lane owns
+  uint32_t k1 = 0u, k2 = 0u;  // best two keys of the sub-vector this lane owns
   int code = 0;
 #pragma unroll
   for (int set = 0; set < 2; ++set) {
@@ -118,8 +118,11 @@ __device__ inline int vq_search_mfma(const VqTables<SUB>& T, const MfmaCodebook<
       b1 = lo_half ? as_h8(ph[0], ph[1], ph[2], ph[3]) : as_h8(ONES, qq, 0u, 0u);
       b2 = lo_half ? as_h8(pl[0], pl[1], pl[2], pl[3]) : as_h8(0u, 0u, 0u, 0u);
     }
-    float m1 = 3.0e38f, m2 = 3.0e38f;
-    int blk = 0;
+    // keys are positive floats: unsigned-integer order equals float order (integer min avoids
+    // the NaN canonicalisation a float min would add).  Two independent best-two chains
+    // (even / odd blocks) keep a lone wave from serialising on one dependency chain.
+    uint32_t ma1 = 0x7f000000u, ma2 = 0x7f000000u, mb1 = 0x7f000000u, mb2 = 0x7f000000u;
+    int blka = 0, blkb = 1;
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
       f16v d;
@@ -127,22 +130,28 @@ __device__ inline int vq_search_mfma(const VqTables<SUB>& T, const MfmaCodebook<
       for (int r = 0; r < 16; ++r) d[r] = 0.f;
       d = __builtin_amdgcn_mfma_f32_32x32x16_f16(M.A[m], b1, d, 0, 0, 0);
       if constexpr (SUB == 8) d = __builtin_amdgcn_mfma_f32_32x32x16_f16(M.A[m], b2, d, 0, 0, 0);
-      const float prev = m1;
+      uint32_t& m1r = (m & 1) ? mb1 : ma1;
+      uint32_t& m2r = (m & 1) ? mb2 : ma2;
+      int& blkr = (m & 1) ? blkb : blka;
+      const uint32_t prev = m1r;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float u = __uint_as_float((__float_as_uint(d[r]) & 0xFFFFFFF0u) | (uint32_t)r);
-        m2 = __builtin_amdgcn_fmed3f(m1, m2, u);
-        m1 = fminf(m1, u);
+        const uint32_t u = (__float_as_uint(d[r]) & 0xFFFFFFF0u) | (uint32_t)r;
+        m2r = __float_as_uint(__builtin_amdgcn_fmed3f(__uint_as_float(m1r), __uint_as_float(m2r), __uint_as_float(u)));
+        m1r = min(m1r, u);
       }
-      blk = (m1 < prev) ? m : blk;
+      blkr = (m1r < prev) ? m : blkr;
     }
-    const int r = (int)(__float_as_uint(m1) & 15u);
+    const uint32_t m1 = min(ma1, mb1);
+    const uint32_t m2 = min(max(ma1, mb1), min(ma2, mb2));
+    const int blk = (mb1 < ma1) ? blkb : blka;
+    const int r = (int)(m1 & 15u);
     const int mine = 32 * blk + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
     // the other half of the wave scanned the other 128 codewords of the same sub-vectors
-    const float o1 = __shfl_xor(m1, 32, 64), o2 = __shfl_xor(m2, 32, 64);
+    const uint32_t o1 = __shfl_xor(m1, 32, 64), o2 = __shfl_xor(m2, 32, 64);
     const int ocode = __shfl_xor(mine, 32, 64);
-    const float f1 = fminf(m1, o1);
-    const float f2 = fminf(fmaxf(m1, o1), fminf(m2, o2));
+    const uint32_t f1 = min(m1, o1);
+    const uint32_t f2 = min(max(m1, o1), min(m2, o2));
     const int fcode = (o1 < m1) ? ocode : (o1 == m1 ? min(mine, ocode) : mine);
     if ((set == 0) == lo_half) {
       k1 = f1;
@@ -151,8 +160,8 @@ __device__ inline int vq_search_mfma(const VqTables<SUB>& T, const MfmaCodebook<
     }
   }
   // error window: key granularity (16 ulp, truncated) + fp32 rounding of a 16-term contraction
-  const float d1 = __uint_as_float(__float_as_uint(k1) & 0xFFFFFFF0u);
-  const float d2 = __uint_as_float(__float_as_uint(k2) & 0xFFFFFFF0u);
+  const float d1 = __uint_as_float(k1 & 0xFFFFFFF0u);
+  const float d2 = __uint_as_float(k2 & 0xFFFFFFF0u);
   const float reach = T.cmax + sqrtf(yn);
   const float window = 2.f * (1.9073486e-6f * d2 + 24.f * 5.9604645e-8f * (reach * reach + kVqMargin));
   if (!(d2 - d1 > window)) code = vq_exact_scan<SUB>(T, y);
