@@ -17,6 +17,7 @@
 //   * one workgroup per (split, kv head, sequence); the last workgroup of a (kv head, sequence)
 //     to finish merges the splits (running max / sum), applies the single inverse Hadamard per
 //     head, adds the mean-vector term and writes the output - no second launch.
+#include <cstdlib>
 #include <type_traits>
 
 #include "nsn_host.h"
@@ -156,7 +157,7 @@ __device__ long long g_dec_timing[48];
 template <int SUB, int NW>
 struct DecSmem {
   static constexpr int kUnionBytes = NW * 4 * kHeadDim * 4;
-  static constexpr int kRaccBytes = NW * 4 * kHeadDim * 4;
+  static constexpr int kRaccBytes = NW * (64 / (kHeadDim / SUB)) * 4 * kHeadDim * 4;
   static constexpr int kTailBytes = (2 * NW * 4 + 4 + 4 * kHeadDim) * 4;
   static constexpr bool kTailInTable = kRaccBytes + kTailBytes <= kTableBytes;
   static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kTableBytes + kUnionBytes;
@@ -175,6 +176,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   constexpr int J = kHeadDim / SUB;  // code bytes per token
   constexpr int KW = J / 4;          // code dwords per lane (K: one token; V: one sub-vector of J tokens)
   constexpr int LV = J;              // lanes per value-side token part (one lane per sub-vector)
+  constexpr int NPART = 64 / LV;     // value-side token parts of a 64-token group
   constexpr int CBSZ_V = (SUB == 4) ? 3 : 2;
   constexpr int NT = NW * 64;
   using SM = DecSmem<SUB, NW>;
@@ -261,27 +263,34 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
       const float a0 = x0 + x1, a1 = x0 - x1;
       x0 = a0, x1 = a1;
     }
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-      const float p0 = __shfl_xor(x0, m, 64), p1 = __shfl_xor(x1, m, 64);
+    static_for<6>([&](auto kc) {  // lane bit k <-> element bit k + 1
+      constexpr int m = 1 << decltype(kc)::value;
+      const float p0 = xor_lane<m>(x0), p1 = xor_lane<m>(x1);
       const bool upper = (lane & m) != 0;
       x0 = upper ? p0 - x0 : x0 + p0;
       x1 = upper ? p1 - x1 : x1 + p1;
-    }
+    });
     sm_q_had[hh][2 * lane] = x0 * qscale;
     sm_q_had[hh][2 * lane + 1] = x1 * qscale;
   }
-  {  // replicate the staged codewords: batches of 8 reads, then 8 writes
-    constexpr int NCOPY = 256 / (2 * SUB), LOGC = (SUB == 4) ? 5 : 4;
-    for (int i0 = tid; i0 < kCodes * NCOPY; i0 += 8 * NT) {
-      cw_t tmp[8];
+  {  // replicate the staged codewords with 16-byte LDS writes (8-byte codewords go out in pairs)
+    constexpr int NW16 = 16;  // 16-byte slots per 256-byte code row
+    for (int i0 = tid; i0 < kCodes * NW16; i0 += 8 * NT) {
+      uint4 tmp[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) tmp[u] = reinterpret_cast<const cw_t*>(sm_stage)[min(i0 + u * NT, kCodes * NCOPY - 1) >> LOGC];
+      for (int u = 0; u < 8; ++u) {
+        const int code = min(i0 + u * NT, kCodes * NW16 - 1) >> 4;
+        if constexpr (SUB == 4) {
+          const uint2 c2 = reinterpret_cast<const uint2*>(sm_stage)[code];
+          tmp[u] = make_uint4(c2.x, c2.y, c2.x, c2.y);
+        } else {
+          tmp[u] = reinterpret_cast<const uint4*>(sm_stage)[code];
+        }
+      }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int i = i0 + u * NT;
-        if (i < kCodes * NCOPY)
-          *reinterpret_cast<cw_t*>(sm_table + (i >> LOGC) * 256 + (i & (NCOPY - 1)) * (2 * SUB)) = tmp[u];
+        if (i < kCodes * NW16) *reinterpret_cast<uint4*>(sm_table + (i >> 4) * 256 + (i & 15) * 16) = tmp[u];
       }
     }
   }
@@ -435,6 +444,9 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     // d2/d3: HT(q) . C[codes] for four heads; gathers of chunk c+1 are issued before the
     // contractions of chunk c
     f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+#ifdef NSN_EXP_NO_K
+    d0[0] = (float)cur.kcode[0];
+#else
     {
       cw_t bufA[8], bufB[8];
       k_gather(cur.kcode, std::integral_constant<int, 0>{}, bufA);
@@ -449,6 +461,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
         }
       });
     }
+#endif
     cw_t vbufA[4], vbufB[4];
     v_gather(cur.vcode[0], vbufA);  // first value-side gathers fly during the softmax arithmetic
 
@@ -486,6 +499,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     for (int k = 0; k < 4; ++k) wop[k] = (_Float16)w[k];
 
     // d5: out_rot[head][channel] += sum over tokens of weight * codeword channel
+#ifndef NSN_EXP_NO_V
     static_for<KW>([&](auto ac) {
       constexpr int a = decltype(ac)::value;
       if constexpr (a % 2 == 0) {
@@ -496,6 +510,9 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
         v_contract(ac, vbufB, wop);
       }
     });
+#else
+    acc[0][0] += (float)wop[0] + (float)vbufA[0].x;
+#endif
     if (has_next) cur = nxt;
   }
   NSN_TSTAMP(10);
@@ -504,24 +521,25 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   // ---- epilogue: wave results -> LDS (reusing the table), merge the waves -------------------
 #pragma unroll
   for (int i = 0; i < 4; ++i) l_run[i] = wave_sum_u(l_run[i]);
+  NSN_TSTAMP(7);
   __syncthreads();  // every wave is done gathering from the table
-  float* racc = reinterpret_cast<float*>(sm_table);  // [NW][4][128]; the tail follows it
+  NSN_TSTAMP(8);
+  float* racc = reinterpret_cast<float*>(sm_table);  // [NW][NPART][4][128]; the tail follows it
 #pragma unroll
-  for (int c = 0; c < SUB; ++c)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float v = acc[c][i];
-#pragma unroll
-      for (int msk = LV; msk < 64; msk <<= 1) v += __shfl_xor(v, msk, 64);  // add the token parts
-      if (lane < LV) racc[(wave * 4 + i) * kHeadDim + lane * SUB + c] = v;
-    }
+    for (int c4 = 0; c4 < SUB / 4; ++c4)
+      *reinterpret_cast<float4*>(&racc[((wave * NPART + lane / LV) * 4 + i) * kHeadDim + (lane % LV) * SUB + 4 * c4]) =
+          make_float4(acc[4 * c4][i], acc[4 * c4 + 1][i], acc[4 * c4 + 2][i], acc[4 * c4 + 3][i]);
 #pragma unroll
   for (int i = 0; i < 4; ++i)
     if (lane == i) {
       sm_wave_m[wave][i] = m_run[i];
       sm_wave_l[wave][i] = l_run[i];
     }
+  NSN_TSTAMP(9);
   __syncthreads();
+  NSN_TSTAMP(14);
   float* P = partial + ((int64_t)(b * g.n_q_heads + h * r) * n_splits + split) * kPartialStrideM;
   for (int i = tid; i < r * kHeadDim; i += NT) {
     const int hh = i >> 7, c = i & 127;
@@ -532,7 +550,10 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
       const float mw = sm_wave_m[wv][hh];
       const float e = (mw == -INFINITY) ? 0.f : fast_exp2(mw - M);
       L = fmaf(e, sm_wave_l[wv][hh], L);
-      orot = fmaf(e, racc[(wv * 4 + hh) * kHeadDim + c], orot);
+      float part = 0.f;
+#pragma unroll
+      for (int pt = 0; pt < NPART; ++pt) part += racc[((wv * NPART + pt) * 4 + hh) * kHeadDim + c];
+      orot = fmaf(e, part, orot);
       omean = fmaf(e, sm_accm[wv][hh][c], omean);
     }
     float* Ph = P + (int64_t)hh * n_splits * kPartialStrideM;
