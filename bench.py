@@ -38,7 +38,11 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=400)
     p.add_argument("--warmup", type=int, default=40)
-    p.add_argument("--workload", default="C1", choices=["C0", "C1", "C2"])
+    p.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4"])
+    p.add_argument("--random-cache", action="store_true",
+                   help="time decode attention only, on a cache filled with random codes and norms "
+                        "(no encoder run; the only mode for the C3 / C4 shapes)")
+    p.add_argument("--bits", type=int, default=0, help="C4 only: 1 or 2 (default 2)")
     p.add_argument("--n-splits", type=int, default=0)
     p.add_argument("--rotate-bytes", type=float, default=1.2e9)
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -48,6 +52,82 @@ def parse():
     p.add_argument("--copy-calibration", action="store_true",
                    help="also run three plain 256 MiB device copies (known traffic) for counter calibration")
     return p.parse_args()
+
+
+def random_cache_decode(args, cfg) -> int:
+    """Decode attention alone on a cache with random contents (timing does not depend on values).
+    Covers the shapes whose fp16 inputs are too large to generate on the host (MHA batch 64 x 32768)
+    and the ragged paged shape."""
+    import numpy as np
+    import torch
+
+    from paper_2505_18231_amd import api, synth
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    B, Hq, Hkv, seed = cfg["batch"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["seed"]
+    page = cfg.get("page_size", 0)
+    if "length" in cfg:
+        lens = [cfg["length"]] * B
+        sub = cfg["sub_dim"]
+    else:
+        lens = (synth.ragged_lengths(seed, B, cfg["len_lo"], cfg["len_hi"]) + cfg["append_steps"]).tolist()
+        sub = 4 if args.bits in (0, 2) else 8
+    J = 128 // sub
+    max_len = ((max(lens) + 255) // 256) * 256
+    shape = api.make_shape(sub, Hq, Hkv, max_len, 0, page)
+    bt = torch.from_numpy(synth.shuffled_page_table(seed, B, max_len // page)).to(dev) if page else None
+    g = torch.Generator(device=dev).manual_seed(seed)
+    caches = []
+    for _ in range(2):
+        c = api.alloc_cache(shape, B, block_table=bt)
+        c.codes.random_(0, 256, generator=g)
+        c.norms.copy_((torch.rand(c.norms.shape, device=dev, generator=g) + 0.5).half())
+        c.means.copy_((0.1 * torch.randn(c.means.shape, device=dev, generator=g)).half())
+        caches.append(c)
+    kc, vc = caches
+    codebook = (torch.randn((256, sub), device=dev, generator=g)).half()
+    q = torch.from_numpy(synth.make_q(seed, B, Hq)).to(dev)
+    lens_d = torch.tensor(lens, dtype=torch.int32, device=dev)
+    step_bytes = sum(lens) * Hkv * (2 * J + 8) + B * Hkv * 2 * 256
+    n_copies = max(1, int(math.ceil(args.rotate_bytes / step_bytes)))
+    copies = [(kc, vc)] + [tuple(api.CodedCache(c.codes.clone(), c.norms.clone(), c.means.clone(), bt)
+                                 for c in (kc, vc)) for _ in range(n_copies - 1)]
+    ws = torch.zeros(max(1, api.nsn_workspace_bytes(shape, api.NSN_OP_DECODE, B, 0, args.n_splits)),
+                     dtype=torch.uint8, device=dev)
+    out = torch.empty((B, Hq, 128), dtype=torch.float32, device=dev)
+    scale = 1.0 / math.sqrt(128)
+
+    def step(i):
+        ck, cv = copies[i % n_copies]
+        api.nsn_decode_attention(shape, codebook, q, ck, cv, lens_d, max(lens), scale, args.n_splits, out=out,
+                                 workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    us = ev0.elapsed_time(ev1) / args.steps * 1e3
+    gbps = step_bytes / (us * 1e-6) / 1e9
+    print(json.dumps({
+        "metric": "coded-KV decode attention: achieved HBM GB/s (coded bytes read per step / step time)",
+        "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us * 1e-3, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic (random cache contents, timing only)",
+        "config": {"workload": f"{args.workload}:{cfg['name']}", "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
+                   "cached_tokens": sum(lens), "sub_dim": sub, "page_size": page,
+                   "cache_copies_in_rotation": n_copies, "step": "decode attention only"},
+        "decode_us_per_step": round(us, 3), "bytes_per_step": step_bytes,
+        "roofline": {"bound": "hbm", "kernel": "nsn::dec_mfma_kernel (one launch per decode step)",
+                     "achieved": round(gbps, 2), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": None, "algorithmic_bytes": step_bytes},
+    }), flush=True)
+    return 0
 
 
 def main() -> int:
@@ -63,6 +143,8 @@ def main() -> int:
     from paper_2505_18231_amd import api, synth
 
     cfg = synth.CONFIGS[args.workload]
+    if args.random_cache or args.workload in ("C3", "C4"):
+        return random_cache_decode(args, cfg)
     B, Hq, Hkv, L, sub, seed = (cfg["batch"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["length"],
                                 cfg["sub_dim"], cfg["seed"])
     J = 128 // sub
