@@ -166,7 +166,10 @@ struct DecSmem {
   static_assert(kRaccBytes <= kTableBytes, "per-wave accumulators must fit in the table region");
 };
 
-template <int SUB, int NW, bool HILO>
+// R = query heads per kv head handled by the kernel instance (1, 2 or 4; three heads run as 4).
+// With R <= 2 the fp16 hi and lo parts of the rotated query share the four MFMA rows
+// (rows [0,R) = hi, rows [R,2R) = lo), so one MFMA per slot suffices.
+template <int SUB, int NW, int R>
 __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __half* __restrict__ codebook,
                                                            const __half* __restrict__ q, CacheView kc,
                                                            CacheView vc, const int32_t* __restrict__ seq_lens,
@@ -179,6 +182,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   constexpr int NPART = 64 / LV;     // value-side token parts of a 64-token group
   constexpr int CBSZ_V = (SUB == 4) ? 3 : 2;
   constexpr int NT = NW * 64;
+  constexpr bool PACK = (R <= 2);  // hi and lo rows in one A operand
   using SM = DecSmem<SUB, NW>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   unsigned char* const sm_table = smem_raw;
@@ -305,13 +309,17 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   h4 QH[2], QL[2];
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
-    const float* src = &sm_q_had[lane & 3][4 * (16 * p + (lane >> 2))];
+    const int row = lane & 3;
+    const int head = PACK ? row % R : row;          // PACK: rows [0,R) hi, [R,2R) lo, rest zero
+    const bool is_lo = PACK && row >= R, dead = PACK && row >= 2 * R;
+    const float* src = &sm_q_had[head][4 * (16 * p + (lane >> 2))];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const float x = src[k];
       const _Float16 hi = (_Float16)x;
-      QH[p][k] = hi;
-      QL[p][k] = (_Float16)(x - (float)hi);
+      const _Float16 lo = (_Float16)(x - (float)hi);
+      QH[p][k] = dead ? (_Float16)0.f : (is_lo ? lo : hi);
+      QL[p][k] = lo;
     }
   }
   const float qo0[4] = {sm_q_orig[0][2 * lane], sm_q_orig[1][2 * lane], sm_q_orig[2][2 * lane],
@@ -322,7 +330,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   __syncthreads();  // the prologue scratch is dead: its bytes become the per-wave mean-term accumulators
   for (int i = lane; i < 4 * kHeadDim; i += 64) (&sm_accm[wave][0][0])[i] = 0.f;  // wave-private
 
-  float m_run[4], l_run[4], beta[4], cf[4], qo[4];
+  float m_run[4], l_run[4], beta[4], cf[4], qo[4];  // entries [0,R) are live
   f4 acc[SUB];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -340,7 +348,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   // mean-vector term of the Shift group that just ended: accm = accm * cf + (sum of beta) * o^v
   auto flush_group = [&]() {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < R; ++i) {
       const float bsum = wave_sum_u(beta[i]);
       float* dst = &sm_accm[wave][i][2 * lane];
       dst[0] = dst[0] * cf[i] + bsum * ov0;
@@ -369,12 +377,12 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
       if constexpr (SUB == 4) {
         const h4 bop = as_h4(buf[e].x, buf[e].y);
         d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[s / 16], bop, d0, 4, s % 16, 0);
-        if constexpr (HILO) d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QL[s / 16], bop, d1, 4, s % 16, 0);
+        if constexpr (!PACK) d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QL[s / 16], bop, d1, 4, s % 16, 0);
       } else {
         const h4 b0 = as_h4(buf[e].x, buf[e].y), b1 = as_h4(buf[e].z, buf[e].w);
         d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[(2 * s) / 16], b0, d0, 4, (2 * s) % 16, 0);
         d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[(2 * s + 1) / 16], b1, d1, 4, (2 * s + 1) % 16, 0);
-        if constexpr (HILO) {
+        if constexpr (!PACK) {
           d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QL[(2 * s) / 16], b0, d0, 4, (2 * s) % 16, 0);
           d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QL[(2 * s + 1) / 16], b1, d1, 4, (2 * s + 1) % 16, 0);
         }
@@ -435,7 +443,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
       if (cur_group >= 0) flush_group();
       const float o0 = __low2float(cur.ok2), o1 = __high2float(cur.ok2);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) qo[i] = wave_sum_u(qo0[i] * o0 + qo1[i] * o1) * scale_log2e;
+      for (int i = 0; i < R; ++i) qo[i] = wave_sum_u(qo0[i] * o0 + qo1[i] * o1) * scale_log2e;
       ov0 = __low2float(cur.ov2);
       ov1 = __high2float(cur.ov2);
       cur_group = grp;
@@ -469,13 +477,14 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     float s[4], w[4];
     bool need = false;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      s[i] = valid ? fmaf(a_k, d0[i] + d1[i], b_k * qo[i]) : -INFINITY;
+    for (int i = 0; i < R; ++i) {
+      const float dot = PACK ? (d0[i] + d0[R + i]) + (d1[i] + d1[R + i]) : d0[i] + d1[i];
+      s[i] = valid ? fmaf(a_k, dot, b_k * qo[i]) : -INFINITY;
       need = need || (s[i] - m_run[i] > kLazyMaxLog2);
     }
     if (__any(need)) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < R; ++i) {
         const float m_new = fmaxf(m_run[i], wave_max_u(s[i]));
         const float corr = (m_run[i] == -INFINITY) ? 0.f : fast_exp2(m_run[i] - m_new);
         l_run[i] *= corr;
@@ -487,7 +496,9 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
       }
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i) w[i] = 0.f;
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
       const float p = fast_exp2(s[i] - m_run[i]);  // 0 for masked lanes
       l_run[i] += p;
       beta[i] = fmaf(p, b_v, beta[i]);
@@ -520,19 +531,19 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
 
   // ---- epilogue: wave results -> LDS (reusing the table), merge the waves -------------------
 #pragma unroll
-  for (int i = 0; i < 4; ++i) l_run[i] = wave_sum_u(l_run[i]);
+  for (int i = 0; i < R; ++i) l_run[i] = wave_sum_u(l_run[i]);
   NSN_TSTAMP(7);
   __syncthreads();  // every wave is done gathering from the table
   NSN_TSTAMP(8);
   float* racc = reinterpret_cast<float*>(sm_table);  // [NW][NPART][4][128]; the tail follows it
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < R; ++i)
 #pragma unroll
     for (int c4 = 0; c4 < SUB / 4; ++c4)
       *reinterpret_cast<float4*>(&racc[((wave * NPART + lane / LV) * 4 + i) * kHeadDim + (lane % LV) * SUB + 4 * c4]) =
           make_float4(acc[4 * c4][i], acc[4 * c4 + 1][i], acc[4 * c4 + 2][i], acc[4 * c4 + 3][i]);
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < R; ++i)
     if (lane == i) {
       sm_wave_m[wave][i] = m_run[i];
       sm_wave_l[wave][i] = l_run[i];
@@ -638,7 +649,7 @@ extern "C" int nsn_debug_decode_timing(long long* host48) {
 #endif
 
 // ---------------------------------------------------------------------------------------
-template <int SUB, int NW, bool HILO>
+template <int SUB, int NW, int R>
 static int launch_one(const Geometry& g, const void* codebook, const void* q, const CacheView& kv,
                       const CacheView& vv, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                       int n_splits, void* workspace, size_t counter_bytes, float* out, hipStream_t stream) {
@@ -648,10 +659,10 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
     // the gathers address the codebook table by absolute LDS address: it must start at 0,
     // i.e. the kernel may not own any static LDS in front of its dynamic block
     hipFuncAttributes fa;
-    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, HILO>)) != hipSuccess ||
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R>)) != hipSuccess ||
         fa.sharedSizeBytes != 0)
       return NSN_ERR_HIP;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, HILO>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return NSN_ERR_HIP;
     attr_done = true;
@@ -660,7 +671,7 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
   int* counters = static_cast<int*>(workspace);
   float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + counter_bytes);
   const dim3 grid(n_splits, g.n_kv_heads, batch);
-  dec_mfma_kernel<SUB, NW, HILO><<<grid, NW * 64, smem, stream>>>(
+  dec_mfma_kernel<SUB, NW, R><<<grid, NW * 64, smem, stream>>>(
       g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens, scale * 1.44269504088896340736f, n_splits,
       per, partial, counters, out);
   return NSN_OK;
@@ -688,10 +699,12 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
   const Geometry g = make_geometry(s);
   const CacheView kv = make_view(kc), vv = make_view(vc);
   const size_t cb = counter_bytes(s, batch);
-  return s.sub_dim == 4 ? launch_one<4, 8, true>(g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale,
-                                                 n_splits, workspace, cb, out, stream)
-                        : launch_one<8, 8, true>(g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale,
-                                                 n_splits, workspace, cb, out, stream);
+  const int r = s.n_q_heads / s.n_kv_heads;
+#define NSN_LAUNCH(SUBV, RV) \
+  launch_one<SUBV, 8, RV>(g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, cb, out, stream)
+  if (s.sub_dim == 4) return r == 1 ? NSN_LAUNCH(4, 1) : r == 2 ? NSN_LAUNCH(4, 2) : NSN_LAUNCH(4, 4);
+  return r == 1 ? NSN_LAUNCH(8, 1) : r == 2 ? NSN_LAUNCH(8, 2) : NSN_LAUNCH(8, 4);
+#undef NSN_LAUNCH
 }
 
 }  // namespace nsn
