@@ -303,3 +303,27 @@ def avg_bits(code_bits_per_dim: float, head_dim: int, group_size: int) -> float:
     scales = 2 * 16 / head_dim
     means = 16 * head_dim / (group_size * head_dim)
     return code_bits_per_dim + scales + means
+
+
+# ----------------------------------------------------------------------------
+# Decode attention with the full-precision residual (Sec. 3.2 "Residual"): the most recent
+# tokens are still fp16 and take part in the same softmax as the coded tokens
+# ----------------------------------------------------------------------------
+def decode_attention_residual(q, kc: dict, vc: dict, k_res16, v_res16, codebook, softmax_scale: float,
+                              group_size: int = 0) -> np.ndarray:
+    """out = softmax(scale * q [K_hat ; K_res]^T) [V_hat ; V_res]; the coded part may be empty."""
+    q = np.atleast_2d(np.asarray(q, dtype=F64))
+    k_res = np.asarray(k_res16, dtype=F64).reshape(-1, q.shape[1])
+    v_res = np.asarray(v_res16, dtype=F64).reshape(-1, q.shape[1])
+    if kc["codes"].shape[0] > 0:
+        k_hat = dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], codebook, group_size)
+        v_hat = dequantize(vc["codes"], vc["a"], vc["b"], vc["o"], codebook, group_size)
+        k_all = np.concatenate([k_hat, k_res], axis=0)
+        v_all = np.concatenate([v_hat, v_res], axis=0)
+    else:
+        k_all, v_all = k_res, v_res
+    s = softmax_scale * (q @ k_all.T)
+    s = s - s.max(axis=1, keepdims=True)
+    p = np.exp(s)
+    p = p / p.sum(axis=1, keepdims=True)
+    return p @ v_all

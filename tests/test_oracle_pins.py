@@ -284,3 +284,33 @@ def test_kmeans_on_separated_clusters_recovers_centres():
     order = np.concatenate([[0, 50, 100], np.setdiff1d(np.arange(150), [0, 50, 100])])
     cb, hist, _ = O.build_codebook(pts[order], 3, 5)
     assert np.allclose(cb, centres, atol=0.02)
+
+
+# ---------------------------------------------------------------- residual (recent fp16 tokens)
+def test_residual_attention_limits():
+    cb = _rand_codebook(6, 8)
+    kc, vc = _coded_unit(41, 128, 8, 64, cb)
+    q = synth.make_q(41, 1, 2)[0].astype(np.float64)
+    k_res = synth.make_k(41, 0, 0, 5, start=128)
+    v_res = synth.make_v(41, 0, 0, 5, start=128)
+    # no residual tokens: identical to the coded-only attention
+    out0 = O.decode_attention_residual(q, kc, vc, k_res[:0], v_res[:0], cb, 0.1, 64)
+    assert np.allclose(out0, O.decode_attention(q, kc, vc, cb, 0.1, 64), rtol=1e-13, atol=1e-15)
+    # no coded tokens: plain fp16 attention, written out with python loops
+    empty = {k: v[:0] for k, v in kc.items()}
+    out1 = O.decode_attention_residual(q, empty, empty, k_res, v_res, cb, 0.1, 64)
+    for r in range(2):
+        s = [0.1 * float(np.dot(q[r], k_res[t].astype(np.float64))) for t in range(5)]
+        w = [math.exp(x - max(s)) for x in s]
+        ref = sum(wi / sum(w) * v_res[t].astype(np.float64) for t, wi in enumerate(w))
+        assert np.allclose(out1[r], ref, rtol=1e-12, atol=1e-14)
+    # both parts: equals the merge of the two partial attentions by their softmax masses
+    out = O.decode_attention_residual(q, kc, vc, k_res, v_res, cb, 0.1, 64)
+    k_hat = O.dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], cb, 64)
+    for r in range(2):
+        sc = 0.1 * (k_hat @ q[r])
+        sr = 0.1 * (k_res.astype(np.float64) @ q[r])
+        m = max(sc.max(), sr.max())
+        zc, zr = np.exp(sc - m).sum(), np.exp(sr - m).sum()
+        merged = (zc * out0[r] + zr * out1[r]) / (zc + zr)
+        assert np.allclose(out[r], merged, rtol=1e-11, atol=1e-13)
