@@ -85,6 +85,20 @@ typedef struct nsn_cache {
   const int32_t* block_table; /* dev, paged layout only (else NULL) */
 } nsn_cache;
 
+/*
+ * The residual of Sec. 3.2: the most recent tokens of every sequence, kept in fp16 until a
+ * whole group of them is encoded at once.  Rows [0, lens[b]) of a sequence are its tokens
+ * at positions seq_lens[b] .. seq_lens[b] + lens[b] - 1 (oldest first); the caller owns the
+ * buffers, appends to them and empties them (by passing them to nsn_encode and resetting
+ * lens) when they are full.
+ */
+typedef struct nsn_residual {
+  const void* k_fp16;  /* dev fp16 [batch][n_kv_heads][capacity][head_dim] */
+  const void* v_fp16;  /* dev fp16, same shape */
+  const int32_t* lens; /* dev int32 [batch], 0 .. capacity */
+  int32_t capacity;    /* rows per (sequence, kv head): 1 .. 64 (the paper uses 64) */
+} nsn_residual;
+
 /* Byte offset of the code of (token t, sub-vector j) inside a placement unit; J = codes per token. */
 int64_t nsn_k_code_offset(int J, int64_t t, int j);
 int64_t nsn_v_code_offset(int J, int64_t t, int j);
@@ -167,6 +181,23 @@ int nsn_decode_attention(const nsn_shape* shape, const void* codebook_dev, const
                          const int32_t* seq_lens_dev, int batch, int max_seq_len,
                          float softmax_scale, int n_splits, float* out, void* workspace,
                          size_t workspace_bytes, void* stream);
+
+/*
+ * The same decode step with the fp16 residual of Sec. 3.2 taking part in the softmax:
+ *   out = softmax(softmax_scale * q [K_coded ; K_residual]^T) [V_coded ; V_residual]
+ * where the coded part is exactly nsn_decode_attention's and the residual rows enter with
+ * their fp16 values (fp32 accumulation).  seq_lens_dev counts coded tokens only; a sequence
+ * with no coded and no residual token gives a zero output row.  All other arguments, the
+ * workspace and its rules are those of nsn_decode_attention.
+ * Restriction: at most 4 query heads per kv head (else UNSUPPORTED).
+ * Errors: INVALID_ARG (also capacity outside 1..64), UNSUPPORTED, WORKSPACE, HIP.
+ */
+int nsn_decode_attention_residual(const nsn_shape* shape, const void* codebook_dev,
+                                  const void* q_fp16, const nsn_cache* k_cache,
+                                  const nsn_cache* v_cache, const int32_t* seq_lens_dev,
+                                  int batch, int max_seq_len, const nsn_residual* residual,
+                                  float softmax_scale, int n_splits, float* out, void* workspace,
+                                  size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -31,6 +31,10 @@ class nsn_cache(C.Structure):
                 ("block_table", C.c_void_p)]
 
 
+class nsn_residual(C.Structure):
+    _fields_ = [("k_fp16", C.c_void_p), ("v_fp16", C.c_void_p), ("lens", C.c_void_p), ("capacity", C.c_int32)]
+
+
 class NsnError(RuntimeError):
     def __init__(self, code: int, text: str):
         super().__init__(f"libnsn error {code}: {text}")
@@ -65,6 +69,10 @@ def lib() -> C.CDLL:
                                            C.POINTER(nsn_cache), C.POINTER(nsn_cache), C.c_void_p, C.c_int,
                                            C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t,
                                            C.c_void_p]
+        L.nsn_decode_attention_residual.argtypes = [
+            C.POINTER(nsn_shape), C.c_void_p, C.c_void_p, C.POINTER(nsn_cache), C.POINTER(nsn_cache), C.c_void_p,
+            C.c_int, C.c_int, C.POINTER(nsn_residual), C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t,
+            C.c_void_p]
         _lib = L
     return _lib
 
@@ -180,4 +188,34 @@ def nsn_decode_attention(shape: nsn_shape, codebook: torch.Tensor, q: torch.Tens
                                       C.byref(vc), seq_lens.data_ptr(), batch, max_seq_len,
                                       float(softmax_scale), n_splits, out.data_ptr(), workspace.data_ptr(),
                                       workspace.numel(), _stream()))
+    return out
+
+
+def nsn_decode_attention_residual(shape: nsn_shape, codebook: torch.Tensor, q: torch.Tensor,
+                                  k_cache: CodedCache, v_cache: CodedCache, seq_lens: torch.Tensor,
+                                  max_seq_len: int, k_res: torch.Tensor, v_res: torch.Tensor,
+                                  res_lens: torch.Tensor, softmax_scale: float, n_splits: int = 0,
+                                  out: torch.Tensor | None = None,
+                                  workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """As nsn_decode_attention, plus the fp16 residual k_res, v_res: cuda fp16 [B][Hkv][capacity][128]
+    with res_lens (cuda int32 [B]) valid rows each; seq_lens counts the coded tokens only."""
+    assert q.is_cuda and q.dtype == torch.float16 and q.is_contiguous()
+    assert seq_lens.dtype == torch.int32 and res_lens.dtype == torch.int32 and codebook.dtype == torch.float16
+    batch, hq, d = q.shape
+    assert hq == shape.n_q_heads and d == HEAD_DIM
+    for t in (k_res, v_res):
+        assert t.is_cuda and t.dtype == torch.float16 and t.is_contiguous()
+        assert t.dim() == 4 and t.shape[0] == batch and t.shape[1] == shape.n_kv_heads and t.shape[3] == HEAD_DIM
+    assert k_res.shape == v_res.shape and res_lens.numel() == batch
+    if out is None:
+        out = torch.empty((batch, hq, d), dtype=torch.float32, device=q.device)
+    need = nsn_workspace_bytes(shape, NSN_OP_DECODE, batch, 0, n_splits)
+    if workspace is None:
+        workspace = torch.zeros(max(need, 1), dtype=torch.uint8, device=q.device)
+    kc, vc = k_cache.c_struct(), v_cache.c_struct()
+    res = nsn_residual(k_res.data_ptr(), v_res.data_ptr(), res_lens.data_ptr(), int(k_res.shape[2]))
+    _check(lib().nsn_decode_attention_residual(C.byref(shape), codebook.data_ptr(), q.data_ptr(), C.byref(kc),
+                                               C.byref(vc), seq_lens.data_ptr(), batch, max_seq_len,
+                                               C.byref(res), float(softmax_scale), n_splits, out.data_ptr(),
+                                               workspace.data_ptr(), workspace.numel(), _stream()))
     return out

@@ -133,10 +133,10 @@ int nsn_encode(const nsn_shape* shape, const void* codebook_dev, const void* k_f
   return rc;
 }
 
-int nsn_decode_attention(const nsn_shape* shape, const void* codebook_dev, const void* q_fp16,
+static int decode_common(const nsn_shape* shape, const void* codebook_dev, const void* q_fp16,
                          const nsn_cache* k_cache, const nsn_cache* v_cache, const int32_t* seq_lens_dev,
-                         int batch, int max_seq_len, float softmax_scale, int n_splits, float* out,
-                         void* workspace, size_t workspace_bytes, void* stream) {
+                         int batch, int max_seq_len, const nsn_residual* residual, float softmax_scale,
+                         int n_splits, float* out, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_shape(shape);
   if (rc != NSN_OK) return rc;
   if ((rc = check_cache(shape, k_cache, "K")) != NSN_OK) return rc;
@@ -147,6 +147,17 @@ int nsn_decode_attention(const nsn_shape* shape, const void* codebook_dev, const
               shape->max_len);
     return NSN_ERR_INVALID_ARG;
   }
+  if (residual) {
+    if (!residual->k_fp16 || !residual->v_fp16 || !residual->lens || residual->capacity < 1 ||
+        residual->capacity > 64) {
+      set_error("decode: residual needs k, v, lens and a capacity of 1..64 (got %d)", residual->capacity);
+      return NSN_ERR_INVALID_ARG;
+    }
+    if (!decode_use_mfma(*shape)) {
+      set_error("decode: the residual form supports at most 4 query heads per kv head");
+      return NSN_ERR_UNSUPPORTED;
+    }
+  }
   if (batch == 0) return NSN_OK;
   const int splits = decode_pick_splits(*shape, batch, max_seq_len, n_splits);
   if (!workspace || workspace_bytes < decode_workspace_bytes(*shape, batch, splits)) {
@@ -154,9 +165,30 @@ int nsn_decode_attention(const nsn_shape* shape, const void* codebook_dev, const
     return NSN_ERR_WORKSPACE;
   }
   rc = decode_launch(*shape, codebook_dev, q_fp16, *k_cache, *v_cache, seq_lens_dev, batch, max_seq_len,
-                     softmax_scale, splits, out, workspace, static_cast<hipStream_t>(stream));
+                     softmax_scale, splits, residual, out, workspace, static_cast<hipStream_t>(stream));
   if (rc == NSN_ERR_HIP) set_error("decode: launch failed: %s", hipGetErrorString(hipGetLastError()));
   return rc;
+}
+
+int nsn_decode_attention(const nsn_shape* shape, const void* codebook_dev, const void* q_fp16,
+                         const nsn_cache* k_cache, const nsn_cache* v_cache, const int32_t* seq_lens_dev,
+                         int batch, int max_seq_len, float softmax_scale, int n_splits, float* out,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_common(shape, codebook_dev, q_fp16, k_cache, v_cache, seq_lens_dev, batch, max_seq_len, nullptr,
+                       softmax_scale, n_splits, out, workspace, workspace_bytes, stream);
+}
+
+int nsn_decode_attention_residual(const nsn_shape* shape, const void* codebook_dev, const void* q_fp16,
+                                  const nsn_cache* k_cache, const nsn_cache* v_cache,
+                                  const int32_t* seq_lens_dev, int batch, int max_seq_len,
+                                  const nsn_residual* residual, float softmax_scale, int n_splits, float* out,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (!residual) {
+    set_error("decode: residual descriptor is null");
+    return NSN_ERR_INVALID_ARG;
+  }
+  return decode_common(shape, codebook_dev, q_fp16, k_cache, v_cache, seq_lens_dev, batch, max_seq_len, residual,
+                       softmax_scale, n_splits, out, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -258,12 +258,13 @@ size_t decode_workspace_bytes(const nsn_shape& s, int batch, int n_splits) {
 
 int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
                   const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
-                  int n_splits, float* out, void* workspace, hipStream_t stream) {
+                  int n_splits, const nsn_residual* residual, float* out, void* workspace, hipStream_t stream) {
   if (decode_use_mfma(s))
-    return decode_mfma_launch(s, codebook, q, kc, vc, seq_lens, batch, max_seq_len, scale, n_splits, workspace, out,
-                              stream) == NSN_OK && hipGetLastError() == hipSuccess
+    return decode_mfma_launch(s, codebook, q, kc, vc, seq_lens, batch, max_seq_len, scale, n_splits, workspace,
+                              residual, out, stream) == NSN_OK && hipGetLastError() == hipSuccess
                ? NSN_OK
                : NSN_ERR_HIP;
+  if (residual) return NSN_ERR_UNSUPPORTED;  // the lookup-table kernel reads coded tokens only
   const Geometry g = make_geometry(s);
   const CacheView kv = make_view(kc), vv = make_view(vc);
   float* partial = static_cast<float*>(workspace);

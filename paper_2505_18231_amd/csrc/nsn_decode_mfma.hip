@@ -175,7 +175,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
                                                            CacheView vc, const int32_t* __restrict__ seq_lens,
                                                            float scale_log2e, int n_splits, int per,
                                                            float* partial, int* counters,
-                                                           float* __restrict__ out) {
+                                                           ResidualView res, float* __restrict__ out) {
   constexpr int J = kHeadDim / SUB;  // code bytes per token
   constexpr int KW = J / 4;          // code dwords per lane (K: one token; V: one sub-vector of J tokens)
   constexpr int LV = J;              // lanes per value-side token part (one lane per sub-vector)
@@ -369,7 +369,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
         buf[e] = lds_read128(addr);
     }
   };
-  auto k_contract = [&](auto cc, const cw_t (&buf)[8], f4& d0, f4& d1) {
+  auto k_contract = [&](auto cc, const cw_t (&buf)[8], const h4 (&QH)[2], const h4 (&QL)[2], f4& d0, f4& d1) {
     constexpr int ch = decltype(cc)::value;
     static_for<8>([&](auto ec) {
       constexpr int e = decltype(ec)::value;
@@ -399,7 +399,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
         buf[k] = lds_read128(addr);
     }
   };
-  auto v_contract = [&](auto ac, const cw_t (&cw)[4], const h4& wop) {
+  auto v_contract = [&](auto ac, const cw_t (&cw)[4], const h4& wop, f4 (&acc)[SUB]) {
     constexpr int a = decltype(ac)::value;
     if constexpr (SUB == 4) {
       const h4 b0 = as_h4(perm_b32(cw[1].x, cw[0].x, 0x05040100u), perm_b32(cw[3].x, cw[2].x, 0x05040100u));
@@ -425,55 +425,9 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     }
   };
 
-  NSN_TSTAMP(2);
-  // ---- main loop: this wave's 64-token groups, next group's loads in flight ------------------
-  for (int gi = wave; gi < n_grp; gi += NW) {
-    NSN_TSTAMP(3 + (gi / NW < 6 ? gi / NW : 6));
-    const int tg = t0 + (gi << 6);  // first token of the group (multiple of 64)
-    const bool valid = (tg + lane) < t1;
-    const bool has_next = gi + NW < n_grp;  // wave-uniform
-    Grp nxt;
-    if (has_next) load_group(gi + NW, nxt);
-    const float a_k = valid ? __low2float(cur.nk) : 0.f, b_k = valid ? __high2float(cur.nk) : 0.f;
-    const float a_v = valid ? __low2float(cur.nv) : 0.f, b_v = valid ? __high2float(cur.nv) : 0.f;
-
-    // Shift group bookkeeping (wave-uniform): mean term of the old group, q . o^k of the new one
-    const int grp = group_of(g, tg);
-    if (grp != cur_group) {
-      if (cur_group >= 0) flush_group();
-      const float o0 = __low2float(cur.ok2), o1 = __high2float(cur.ok2);
-#pragma unroll
-      for (int i = 0; i < R; ++i) qo[i] = wave_sum_u(qo0[i] * o0 + qo1[i] * o1) * scale_log2e;
-      ov0 = __low2float(cur.ov2);
-      ov1 = __high2float(cur.ov2);
-      cur_group = grp;
-    }
-
-    // d2/d3: HT(q) . C[codes] for four heads; gathers of chunk c+1 are issued before the
-    // contractions of chunk c
-    f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
-#ifdef NSN_EXP_NO_K
-    d0[0] = (float)cur.kcode[0];
-#else
-    {
-      cw_t bufA[8], bufB[8];
-      k_gather(cur.kcode, std::integral_constant<int, 0>{}, bufA);
-      static_for<J / 8>([&](auto cc) {
-        constexpr int ch = decltype(cc)::value;
-        if constexpr (ch % 2 == 0) {
-          if constexpr (ch + 1 < J / 8) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufB);
-          k_contract(cc, bufA, d0, d1);
-        } else {
-          if constexpr (ch + 1 < J / 8) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufA);
-          k_contract(cc, bufB, d0, d1);
-        }
-      });
-    }
-#endif
-    cw_t vbufA[4], vbufB[4];
-    v_gather(cur.vcode[0], vbufA);  // first value-side gathers fly during the softmax arithmetic
-
-    // d3/d4: scores in log2 units, lazy running max, weights
+  // d3/d4: scores in log2 units, lazy running max, weights.  Returns the fp16 weights as the
+  // value-side A operand: lane i of a quad holds head i, the quad's four tokens.
+  auto softmax_step = [&](const f4& d0, const f4& d1, bool valid, float a_k, float b_k, float a_v, float b_v) -> h4 {
     float s[4], w[4];
     bool need = false;
 #pragma unroll
@@ -504,30 +458,152 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
       beta[i] = fmaf(p, b_v, beta[i]);
       w[i] = p * a_v;
     }
-    quad_transpose(w, lane);  // lane i of a quad: head i, the quad's four tokens
+    quad_transpose(w, lane);
     h4 wop;
 #pragma unroll
     for (int k = 0; k < 4; ++k) wop[k] = (_Float16)w[k];
+    return wop;
+  };
+
+  NSN_TSTAMP(2);
+  // ---- main loop: this wave's 64-token groups, next group's loads in flight ------------------
+  for (int gi = wave; gi < n_grp; gi += NW) {
+    NSN_TSTAMP(3 + (gi / NW < 6 ? gi / NW : 6));
+    const int tg = t0 + (gi << 6);  // first token of the group (multiple of 64)
+    const bool valid = (tg + lane) < t1;
+    const bool has_next = gi + NW < n_grp;  // wave-uniform
+    Grp nxt;
+    if (has_next) load_group(gi + NW, nxt);
+    const float a_k = valid ? __low2float(cur.nk) : 0.f, b_k = valid ? __high2float(cur.nk) : 0.f;
+    const float a_v = valid ? __low2float(cur.nv) : 0.f, b_v = valid ? __high2float(cur.nv) : 0.f;
+
+    // Shift group bookkeeping (wave-uniform): mean term of the old group, q . o^k of the new one
+    const int grp = group_of(g, tg);
+    if (grp != cur_group) {
+      if (cur_group >= 0) flush_group();
+      const float o0 = __low2float(cur.ok2), o1 = __high2float(cur.ok2);
+#pragma unroll
+      for (int i = 0; i < R; ++i) qo[i] = wave_sum_u(qo0[i] * o0 + qo1[i] * o1) * scale_log2e;
+      ov0 = __low2float(cur.ov2);
+      ov1 = __high2float(cur.ov2);
+      cur_group = grp;
+    }
+
+    // d2/d3: HT(q) . C[codes] for four heads; gathers of chunk c+1 are issued before the
+    // contractions of chunk c
+    f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+    {
+      cw_t bufA[8], bufB[8];
+      k_gather(cur.kcode, std::integral_constant<int, 0>{}, bufA);
+      static_for<J / 8>([&](auto cc) {
+        constexpr int ch = decltype(cc)::value;
+        if constexpr (ch % 2 == 0) {
+          if constexpr (ch + 1 < J / 8) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufB);
+          k_contract(cc, bufA, QH, QL, d0, d1);
+        } else {
+          if constexpr (ch + 1 < J / 8) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufA);
+          k_contract(cc, bufB, QH, QL, d0, d1);
+        }
+      });
+    }
+    cw_t vbufA[4], vbufB[4];
+    v_gather(cur.vcode[0], vbufA);  // first value-side gathers fly during the softmax arithmetic
+
+    const h4 wop = softmax_step(d0, d1, valid, a_k, b_k, a_v, b_v);
 
     // d5: out_rot[head][channel] += sum over tokens of weight * codeword channel
-#ifndef NSN_EXP_NO_V
     static_for<KW>([&](auto ac) {
       constexpr int a = decltype(ac)::value;
       if constexpr (a % 2 == 0) {
         if constexpr (a + 1 < KW) v_gather(cur.vcode[a + 1], vbufB);
-        v_contract(ac, vbufA, wop);
+        v_contract(ac, vbufA, wop, acc);
       } else {
         if constexpr (a + 1 < KW) v_gather(cur.vcode[a + 1], vbufA);
-        v_contract(ac, vbufB, wop);
+        v_contract(ac, vbufB, wop, acc);
       }
     });
-#else
-    acc[0][0] += (float)wop[0] + (float)vbufA[0].x;
-#endif
     if (has_next) cur = nxt;
   }
   NSN_TSTAMP(10);
+
+  // ---- residual (Sec. 3.2): the most recent tokens are still fp16 and join the same softmax ---
+  // One wave of the last split treats them as one more 64-token group: the fp16 key row of the
+  // lane's token is the B operand directly (no table), the A operand is the unrotated query,
+  // and the value rows accumulate in the original domain next to the mean-vector term.
+  f4 acc_res[SUB];
+  bool res_here = false;
+  if (res.k != nullptr && split == n_splits - 1 && wave == NW - 1) {
+    const int rl = min(res.lens[b], res.capacity);
+    if (rl > 0) {
+      res_here = true;
+      const bool valid = lane < rl;
+      h4 AH[2], AL[2];
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+        const int row = lane & 3;
+        const int head = PACK ? row % R : row;
+        const bool is_lo = PACK && row >= R, dead = (PACK && row >= 2 * R) || head >= r;
+        uint2 raw = make_uint2(0u, 0u);
+        if (!dead)
+          raw = *reinterpret_cast<const uint2*>(q + (int64_t)(b * g.n_q_heads + h * r + head) * kHeadDim +
+                                                4 * (16 * p + (lane >> 2)));
+        const h4 qh = as_h4(raw.x, raw.y);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const float x = (float)qh[k] * scale_log2e;
+          const _Float16 hi = (_Float16)x;
+          const _Float16 lo = (_Float16)(x - (float)hi);
+          AH[p][k] = is_lo ? lo : hi;
+          AL[p][k] = lo;
+        }
+      }
+      const int64_t unit_row = (int64_t)(b * g.n_kv_heads + h) * res.capacity;
+      f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+      const uint4* krow = reinterpret_cast<const uint4*>(res.k + (unit_row + lane) * kHeadDim);
+      static_for<J / 8>([&](auto cc) {
+        constexpr int ch = decltype(cc)::value;
+        cw_t buf[8];
+        if constexpr (SUB == 4) {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const uint4 x = valid ? krow[4 * ch + u] : make_uint4(0u, 0u, 0u, 0u);
+            buf[2 * u] = make_uint2(x.x, x.y);
+            buf[2 * u + 1] = make_uint2(x.z, x.w);
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) buf[u] = valid ? krow[8 * ch + u] : make_uint4(0u, 0u, 0u, 0u);
+        }
+        k_contract(cc, buf, AH, AL, d0, d1);
+      });
+      const h4 wop = softmax_step(d0, d1, valid, 1.f, 0.f, 1.f, 0.f);
+#pragma unroll
+      for (int c = 0; c < SUB; ++c) acc_res[c] = f4{0.f, 0.f, 0.f, 0.f};
+      static_for<KW>([&](auto ac) {
+        constexpr int a = decltype(ac)::value;
+        cw_t cw[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int t = (lane / LV) * J + 4 * a + k;  // the same token order as a coded group
+          cw[k] = cw_t{};
+          if (t < rl) cw[k] = *reinterpret_cast<const cw_t*>(res.v + (unit_row + t) * kHeadDim + (lane % LV) * SUB);
+        }
+        v_contract(ac, cw, wop, acc_res);
+      });
+    }
+  }
   if (cur_group >= 0) flush_group();
+  if (res_here) {  // fold the residual's value sum into this wave's original-domain accumulator
+#pragma unroll
+    for (int p = 0; p < NPART; ++p) {
+      if (lane / LV == p) {
+#pragma unroll
+        for (int i = 0; i < R; ++i)
+#pragma unroll
+          for (int c = 0; c < SUB; ++c) sm_accm[wave][i][(lane % LV) * SUB + c] += acc_res[c][i];
+      }
+    }
+  }
 
   // ---- epilogue: wave results -> LDS (reusing the table), merge the waves -------------------
 #pragma unroll
@@ -652,7 +728,8 @@ extern "C" int nsn_debug_decode_timing(long long* host48) {
 template <int SUB, int NW, int R>
 static int launch_one(const Geometry& g, const void* codebook, const void* q, const CacheView& kv,
                       const CacheView& vv, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
-                      int n_splits, void* workspace, size_t counter_bytes, float* out, hipStream_t stream) {
+                      int n_splits, void* workspace, size_t counter_bytes, const ResidualView& res, float* out,
+                      hipStream_t stream) {
   const size_t smem = DecSmem<SUB, NW>::kBytes;
   static bool attr_done = false;
   if (!attr_done) {
@@ -673,7 +750,7 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
   const dim3 grid(n_splits, g.n_kv_heads, batch);
   dec_mfma_kernel<SUB, NW, R><<<grid, NW * 64, smem, stream>>>(
       g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens, scale * 1.44269504088896340736f, n_splits,
-      per, partial, counters, out);
+      per, partial, counters, res, out);
   return NSN_OK;
 }
 
@@ -695,13 +772,18 @@ size_t decode_mfma_workspace_bytes(const nsn_shape& s, int batch, int n_splits) 
 
 int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
                        const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
-                       int n_splits, void* workspace, float* out, hipStream_t stream) {
+                       int n_splits, void* workspace, const nsn_residual* residual, float* out,
+                       hipStream_t stream) {
   const Geometry g = make_geometry(s);
+  ResidualView res = {nullptr, nullptr, nullptr, 0};
+  if (residual)
+    res = {static_cast<const __half*>(residual->k_fp16), static_cast<const __half*>(residual->v_fp16),
+           residual->lens, residual->capacity};
   const CacheView kv = make_view(kc), vv = make_view(vc);
   const size_t cb = counter_bytes(s, batch);
   const int r = s.n_q_heads / s.n_kv_heads;
 #define NSN_LAUNCH(SUBV, RV) \
-  launch_one<SUBV, 8, RV>(g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, cb, out, stream)
+  launch_one<SUBV, 8, RV>(g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, cb, res, out, stream)
   if (s.sub_dim == 4) return r == 1 ? NSN_LAUNCH(4, 1) : r == 2 ? NSN_LAUNCH(4, 2) : NSN_LAUNCH(4, 4);
   return r == 1 ? NSN_LAUNCH(8, 1) : r == 2 ? NSN_LAUNCH(8, 2) : NSN_LAUNCH(8, 4);
 #undef NSN_LAUNCH

@@ -22,6 +22,15 @@ struct CacheView {
   const int32_t* block_table;
 };
 
+// fp16 rows of the most recent tokens that are not coded yet (Sec. 3.2 "Residual"):
+// [sequence][kv head][capacity][head_dim]; k == nullptr means there is none
+struct ResidualView {
+  const __half* k;
+  const __half* v;
+  const int32_t* lens;  // valid rows per sequence
+  int capacity;         // <= 64
+};
+
 struct Geometry {
   int J;            // code bytes per token
   int n_q_heads, n_kv_heads;

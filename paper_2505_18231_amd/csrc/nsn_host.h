@@ -41,11 +41,12 @@ int decode_mfma_splits(const nsn_shape& s, int batch, int max_seq_len, int reque
 size_t decode_mfma_workspace_bytes(const nsn_shape& s, int batch, int n_splits);
 int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
                        const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
-                       int n_splits, void* workspace, float* out, hipStream_t stream);
+                       int n_splits, void* workspace, const nsn_residual* residual, float* out,
+                       hipStream_t stream);
 size_t decode_workspace_bytes(const nsn_shape& s, int batch, int n_splits);
 int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
                   const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
-                  int n_splits, float* out, void* workspace, hipStream_t stream);
+                  int n_splits, const nsn_residual* residual, float* out, void* workspace, hipStream_t stream);
 
 size_t codebook_workspace_bytes(int sub_dim, int64_t n_samples);
 int codebook_run(const float* samples, int64_t n_samples, int sub_dim, int iters, void* codebook_out,
