@@ -183,6 +183,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   constexpr int CBSZ_V = (SUB == 4) ? 3 : 2;
   constexpr int NT = NW * 64;
   constexpr bool PACK = (R <= 2);  // hi and lo rows in one A operand
+  constexpr int CH = 8;  // key-side gathers in flight per chunk
   using SM = DecSmem<SUB, NW>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   unsigned char* const sm_table = smem_raw;
@@ -209,25 +210,28 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     uint32_t kcode[KW], vcode[KW];
     __half2 nk, nv, ok2, ov2;
   };
+  // per-lane byte offsets (32-bit) that are added to wave-uniform 64-bit bases
+  const uint32_t k_lane_off = lane * J;
+  const uint32_t v_lane_off = (lane / LV) * (J * J) + (lane % LV) * J;
+  const uint32_t lane_x4 = lane * 4;
   auto load_group = [&](int gi, Grp& G) {
     const int tg = t0 + (gi << 6);
-    const int64_t kbase = unit_token_base(g, kc.block_table, b, h, tg);
-    const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tg);
     const int tin = token_in_unit(g, tg);
-    const uint4* kp = reinterpret_cast<const uint4*>(kc.codes + (kbase + tin + lane) * J);
-    const uint4* vp =
-        reinterpret_cast<const uint4*>(vc.codes + (vbase + tin) * J + (lane / LV) * (J * J) + (lane % LV) * J);
+    const int64_t kbase = unit_token_base(g, kc.block_table, b, h, tg) + tin;  // wave-uniform
+    const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tg) + tin;
+    const uint4* kp = reinterpret_cast<const uint4*>(kc.codes + kbase * J + k_lane_off);
+    const uint4* vp = reinterpret_cast<const uint4*>(vc.codes + vbase * J + v_lane_off);
 #pragma unroll
     for (int w4 = 0; w4 < KW / 4; ++w4) {
       const uint4 kv4 = kp[w4], vv4 = vp[w4];
       G.kcode[4 * w4] = kv4.x, G.kcode[4 * w4 + 1] = kv4.y, G.kcode[4 * w4 + 2] = kv4.z, G.kcode[4 * w4 + 3] = kv4.w;
       G.vcode[4 * w4] = vv4.x, G.vcode[4 * w4 + 1] = vv4.y, G.vcode[4 * w4 + 2] = vv4.z, G.vcode[4 * w4 + 3] = vv4.w;
     }
-    G.nk = kc.norms[kbase + tin + lane];
-    G.nv = vc.norms[vbase + tin + lane];
-    const int64_t mo = (mean_base + group_of(g, tg)) * kHeadDim + 2 * lane;
-    G.ok2 = *reinterpret_cast<const __half2*>(kc.means + mo);
-    G.ov2 = *reinterpret_cast<const __half2*>(vc.means + mo);
+    G.nk = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.norms + kbase) + lane_x4);
+    G.nv = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.norms + vbase) + lane_x4);
+    const int64_t mo = (mean_base + group_of(g, tg)) * kHeadDim;  // wave-uniform
+    G.ok2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.means + mo) + lane_x4);
+    G.ov2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lane_x4);
   };
 
   NSN_TSTAMP(0);
@@ -358,22 +362,22 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     }
   };
 
-  auto k_gather = [&](const uint32_t (&kcode)[KW], auto cc, cw_t (&buf)[8]) {
+  auto k_gather = [&](const uint32_t (&kcode)[KW], auto cc, cw_t (&buf)[CH]) {
     constexpr int ch = decltype(cc)::value;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const uint32_t addr = perm_b32(kcode[(8 * ch + e) / 4], laneoff, 0x0c0c0400u + ((e % 4) << 8));
+    for (int e = 0; e < CH; ++e) {
+      const uint32_t addr = perm_b32(kcode[(CH * ch + e) / 4], laneoff, 0x0c0c0400u + ((e % 4) << 8));
       if constexpr (SUB == 4)
         buf[e] = lds_read64(addr);
       else
         buf[e] = lds_read128(addr);
     }
   };
-  auto k_contract = [&](auto cc, const cw_t (&buf)[8], const h4 (&QH)[2], const h4 (&QL)[2], f4& d0, f4& d1) {
+  auto k_contract = [&](auto cc, const cw_t (&buf)[CH], const h4 (&QH)[2], const h4 (&QL)[2], f4& d0, f4& d1) {
     constexpr int ch = decltype(cc)::value;
-    static_for<8>([&](auto ec) {
+    static_for<CH>([&](auto ec) {
       constexpr int e = decltype(ec)::value;
-      constexpr int s = 8 * ch + e;
+      constexpr int s = CH * ch + e;
       if constexpr (SUB == 4) {
         const h4 bop = as_h4(buf[e].x, buf[e].y);
         d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[s / 16], bop, d0, 4, s % 16, 0);
@@ -493,15 +497,15 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     // contractions of chunk c
     f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
     {
-      cw_t bufA[8], bufB[8];
+      cw_t bufA[CH], bufB[CH];
       k_gather(cur.kcode, std::integral_constant<int, 0>{}, bufA);
-      static_for<J / 8>([&](auto cc) {
+      static_for<J / CH>([&](auto cc) {
         constexpr int ch = decltype(cc)::value;
         if constexpr (ch % 2 == 0) {
-          if constexpr (ch + 1 < J / 8) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufB);
+          if constexpr (ch + 1 < J / CH) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufB);
           k_contract(cc, bufA, QH, QL, d0, d1);
         } else {
-          if constexpr (ch + 1 < J / 8) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufA);
+          if constexpr (ch + 1 < J / CH) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufA);
           k_contract(cc, bufB, QH, QL, d0, d1);
         }
       });
@@ -560,19 +564,19 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
       const int64_t unit_row = (int64_t)(b * g.n_kv_heads + h) * res.capacity;
       f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
       const uint4* krow = reinterpret_cast<const uint4*>(res.k + (unit_row + lane) * kHeadDim);
-      static_for<J / 8>([&](auto cc) {
+      static_for<J / CH>([&](auto cc) {
         constexpr int ch = decltype(cc)::value;
-        cw_t buf[8];
+        cw_t buf[CH];
         if constexpr (SUB == 4) {
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const uint4 x = valid ? krow[4 * ch + u] : make_uint4(0u, 0u, 0u, 0u);
+          for (int u = 0; u < CH / 2; ++u) {
+            const uint4 x = valid ? krow[(CH / 2) * ch + u] : make_uint4(0u, 0u, 0u, 0u);
             buf[2 * u] = make_uint2(x.x, x.y);
             buf[2 * u + 1] = make_uint2(x.z, x.w);
           }
         } else {
 #pragma unroll
-          for (int u = 0; u < 8; ++u) buf[u] = valid ? krow[8 * ch + u] : make_uint4(0u, 0u, 0u, 0u);
+          for (int u = 0; u < CH; ++u) buf[u] = valid ? krow[CH * ch + u] : make_uint4(0u, 0u, 0u, 0u);
         }
         k_contract(cc, buf, AH, AL, d0, d1);
       });
