@@ -332,7 +332,9 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
                         sm_q_orig[3][2 * lane + 1]};
   const uint32_t laneoff = (SUB == 4) ? (lane & 31) * 8 : (lane & 15) * 16;
   __syncthreads();  // the prologue scratch is dead: its bytes become the per-wave mean-term accumulators
-  for (int i = lane; i < 4 * kHeadDim; i += 64) (&sm_accm[wave][0][0])[i] = 0.f;  // wave-private
+#pragma unroll
+  for (int i = 0; i < 4; ++i)  // wave-private; every lane owns channels 2 lane, 2 lane + 1 of each head
+    *reinterpret_cast<float2*>(&sm_accm[wave][i][2 * lane]) = make_float2(0.f, 0.f);
 
   float m_run[4], l_run[4], beta[4], cf[4], qo[4];  // entries [0,R) are live
   f4 acc[SUB];
@@ -598,15 +600,16 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   }
   if (cur_group >= 0) flush_group();
   if (res_here) {  // fold the residual's value sum into this wave's original-domain accumulator
+    // the token parts are summed across lanes first, so that every LDS word has one writer
 #pragma unroll
-    for (int p = 0; p < NPART; ++p) {
-      if (lane / LV == p) {
+    for (int i = 0; i < R; ++i)
 #pragma unroll
-        for (int i = 0; i < R; ++i)
-#pragma unroll
-          for (int c = 0; c < SUB; ++c) sm_accm[wave][i][(lane % LV) * SUB + c] += acc_res[c][i];
+      for (int c = 0; c < SUB; ++c) {
+        float v = acc_res[c][i];
+        v += xor_lane<32>(v);
+        if constexpr (NPART == 4) v += xor_lane<16>(v);
+        if (lane < LV) sm_accm[wave][i][lane * SUB + c] += v;
       }
-    }
   }
 
   // ---- epilogue: wave results -> LDS (reusing the table), merge the waves -------------------
