@@ -116,8 +116,10 @@ __global__ __launch_bounds__(128) void enc_means_kernel(Geometry g, int max_new,
 __device__ long long g_enc_timing[16];
 #define NSN_ETSTAMP(slot)                                                             \
   do {                                                                                \
-    if (blockIdx.x == 0 && blockIdx.y == 3 && blockIdx.z == 2 && threadIdx.x == 0)    \
+    if (blockIdx.x == 0 && blockIdx.y == 3 && blockIdx.z == 2 && threadIdx.x == 0) {  \
       g_enc_timing[slot] = clock64();                                                 \
+      g_enc_timing[8 + (slot)] = wall_clock64();                                      \
+    }                                                                                 \
   } while (0)
 extern "C" int nsn_debug_encode_timing(long long* host16) {
   return hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_enc_timing), sizeof(long long) * 16) == hipSuccess ? 0 : -1;
@@ -130,8 +132,11 @@ extern "C" int nsn_debug_encode_timing(long long* host16) {
 
 // MFMA:  distance contraction on the matrix cores (else the fp32 vector-ALU scan)
 // FUSED: append mode - the first-Normalize scale is computed here instead of by the stats kernel
+// The register budget is pinned to the main path's needs (4 waves per SIMD at sub-vector length 4,
+// 3 at length 8): without it the rarely taken re-listing path is scheduled for maximum
+// instruction-level parallelism and doubles the register count of the whole kernel.
 template <int SUB, bool MFMA, bool FUSED>
-__global__ __launch_bounds__(256) void enc_quant_kernel(Geometry g, const __half* __restrict__ codebook,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 4 : 3))) void enc_quant_kernel(Geometry g, const __half* __restrict__ codebook,
                                                         const __half* __restrict__ k_in,
                                                         const __half* __restrict__ v_in, int max_new,
                                                         int max_len, const int32_t* __restrict__ seq_start,

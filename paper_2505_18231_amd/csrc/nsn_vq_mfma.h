@@ -8,8 +8,9 @@
 // ||y||^2 are split into fp16 hi + lo parts (about 22 bits).  D > 0, so its bit pattern orders
 // like an integer: the low 4 bits are replaced by the row slot and the best two keys are kept
 // with one min and one med3 per value.  If the runner-up is within the error window of the best
-// (key granularity + fp32 rounding of the contraction), the decision is retaken in fp64 over all
-// codewords, exactly as in the vector-ALU search.
+// (key granularity + fp32 rounding of the contraction), the decision is retaken in fp64 among the
+// codewords inside that window, so the result equals the fp64 exhaustive search of the
+// vector-ALU form.
 #pragma once
 
 #include "nsn_vq.h"
@@ -73,33 +74,45 @@ template <int SUB>
 __device__ inline int vq_search_mfma(const VqTables<SUB>& T, const MfmaCodebook<SUB>& M, const double (&y)[SUB],
                                      int lane) {
   constexpr int NP = SUB / 2;  // packed dwords per hi / lo part
-  float yn = 0.f;
-  uint32_t Phi[NP], Plo[NP];
-  {
+  // token-side operand words of this lane's sub-vector (own: P, Q) and of lane ^ 32 (X, Qx)
+  struct Words {
+    uint32_t Phi[NP], Plo[NP], Xhi[NP], Xlo[NP], Q, Qx;
+    float yn;
+  };
+  auto make_words = [&](const double (&yy)[SUB]) {
+    Words w;
     _Float16 yh[SUB], yl[SUB];
+    w.yn = 0.f;
 #pragma unroll
     for (int i = 0; i < SUB; ++i) {
-      const float yf = (float)y[i];
+      const float yf = (float)yy[i];
       yh[i] = (_Float16)yf;
       yl[i] = (_Float16)(yf - (float)yh[i]);
-      yn = fmaf(yf, yf, yn);
+      w.yn = fmaf(yf, yf, w.yn);
     }
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
-      Phi[i] = pack_h2(yh[2 * i], yh[2 * i + 1]);
-      Plo[i] = pack_h2(yl[2 * i], yl[2 * i + 1]);
+      w.Phi[i] = pack_h2(yh[2 * i], yh[2 * i + 1]);
+      w.Plo[i] = pack_h2(yl[2 * i], yl[2 * i + 1]);
     }
-  }
-  const float ynm = yn + kVqMargin;  // yn itself is needed for the window below
-  const _Float16 ynh = (_Float16)ynm;
-  const uint32_t Q = pack_h2(ynh, (_Float16)(ynm - (float)ynh));
-  uint32_t Xhi[NP], Xlo[NP];
+    const float ynm = w.yn + kVqMargin;  // yn itself is needed for the window below
+    const _Float16 ynh = (_Float16)ynm;
+    w.Q = pack_h2(ynh, (_Float16)(ynm - (float)ynh));
 #pragma unroll
-  for (int i = 0; i < NP; ++i) {
-    Xhi[i] = __shfl_xor(Phi[i], 32, 64);
-    Xlo[i] = __shfl_xor(Plo[i], 32, 64);
-  }
-  const uint32_t Qx = __shfl_xor(Q, 32, 64);
+    for (int i = 0; i < NP; ++i) {
+      w.Xhi[i] = __shfl_xor(w.Phi[i], 32, 64);
+      w.Xlo[i] = __shfl_xor(w.Plo[i], 32, 64);
+    }
+    w.Qx = __shfl_xor(w.Q, 32, 64);
+    return w;
+  };
+  const Words W = make_words(y);
+  const float yn = W.yn;
+  const uint32_t(&Phi)[NP] = W.Phi;
+  const uint32_t(&Plo)[NP] = W.Plo;
+  const uint32_t(&Xhi)[NP] = W.Xhi;
+  const uint32_t(&Xlo)[NP] = W.Xlo;
+  const uint32_t Q = W.Q, Qx = W.Qx;
   const bool lo_half = lane < 32;
   const uint32_t ONES = 0x3C003C00u;  // (1.0, 1.0)
 
@@ -164,7 +177,81 @@ __device__ inline int vq_search_mfma(const VqTables<SUB>& T, const MfmaCodebook<
   const float d2 = __uint_as_float(k2 & 0xFFFFFFF0u);
   const float reach = T.cmax + sqrtf(yn);
   const float window = 2.f * (1.9073486e-6f * d2 + 24.f * 5.9604645e-8f * (reach * reach + kVqMargin));
-  if (!(d2 - d1 > window)) code = vq_exact_scan<SUB>(T, y);
+  const bool need = !(d2 - d1 > window);
+  if (__any(need)) {
+    // Rare path, taken by the whole wave when any of its sub-vectors is undecided: repeat the
+    // contraction and list, per undecided sub-vector, the codewords whose distance lies within
+    // the window of the best one.  Every codeword that can be the true nearest is in that list
+    // (its computed distance cannot exceed the best computed distance by more than the window).
+    // Two entries (the usual case) are settled by two fp64 distances; more fall back to the
+    // full fp64 scan.
+    const uint32_t thr = need ? (__float_as_uint(d1 + window) | 15u) : 0u;  // bit pattern bound; 0 lists nothing
+    const uint32_t thr_set[2] = {(uint32_t)__shfl((int)thr, lane & 31, 64),
+                                 (uint32_t)__shfl((int)thr, (lane & 31) + 32, 64)};
+    uint32_t listed[2];
+    // The operand words are rebuilt from an opaque copy of y, so that nothing but y has to stay
+    // in registers across the main pass for the sake of this rare path.
+    double yy[SUB];
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) {
+      yy[i] = y[i];
+      asm volatile("" : "+v"(yy[i]));
+    }
+    const Words R = make_words(yy);
+#pragma unroll
+    for (int set = 0; set < 2; ++set) {
+      const uint32_t* ph = (set == 0) ? R.Phi : R.Xhi;
+      const uint32_t* pl = (set == 0) ? R.Plo : R.Xlo;
+      const uint32_t qq = (set == 0) ? R.Qx : R.Q;
+      h8 b1, b2;
+      if constexpr (SUB == 4) {
+        b1 = lo_half ? as_h8(ph[0], ph[1], pl[0], pl[1]) : as_h8(ONES, qq, 0u, 0u);
+        b2 = b1;
+      } else {
+        b1 = lo_half ? as_h8(ph[0], ph[1], ph[2], ph[3]) : as_h8(ONES, qq, 0u, 0u);
+        b2 = lo_half ? as_h8(pl[0], pl[1], pl[2], pl[3]) : as_h8(0u, 0u, 0u, 0u);
+      }
+      // Branch- and compare-free listing with small immediates only (nothing for the compiler to
+      // park in registers across the main pass): (thr - u) >> 31 is all ones exactly when u > thr
+      // (both are bit patterns of positive floats, below 2^31); count and row offsets of the
+      // REJECTED entries are summed per block, the listed ones follow by subtraction.
+      uint32_t acc = 0u;  // count in bits 16.., sum of (index without the lane part) in bits 0..15
+      float zero = 0.f;
+#pragma unroll
+      for (int m = 0; m < 8; ++m) {
+        // one block at a time: the next contraction starts from a zero that is ordered after this
+        // block's sums, so the sixteen distances of a single block are all that is live here
+        asm volatile("" : "+v"(zero), "+v"(acc));
+        f16v d;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) d[r] = zero;
+        d = __builtin_amdgcn_mfma_f32_32x32x16_f16(M.A[m], b1, d, 0, 0, 0);
+        if constexpr (SUB == 8) d = __builtin_amdgcn_mfma_f32_32x32x16_f16(M.A[m], b2, d, 0, 0, 0);
+        int rej_cnt = 0, rej_off = 0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int out_mask = (int)(thr_set[set] - __float_as_uint(d[r])) >> 31;
+          rej_cnt -= out_mask;
+          rej_off += out_mask & (8 * (r >> 2) + (r & 3));
+        }
+        const uint32_t cnt = (uint32_t)(16 - rej_cnt);
+        const uint32_t off = (uint32_t)(216 - rej_off);  // all sixteen rows: 4 * 8 * (0+1+2+3) + 4 * (0+1+2+3)
+        acc += (cnt << 16) + off + cnt * (32u * m);
+      }
+      acc += (acc >> 16) * (4u * (lane >> 5));  // this lane's rows sit 4 * (lane / 32) further down
+      listed[set] = acc + (uint32_t)__shfl_xor((int)acc, 32, 64);
+    }
+    if (need) {
+      const uint32_t mine = lo_half ? listed[0] : listed[1];
+      const int other = (int)(mine & 0xFFFFu) - code;
+      if ((mine >> 16) == 2u && other >= 0 && other < kCodes) {
+        const double e_code = exact_dist<SUB>(T, y, code), e_other = exact_dist<SUB>(T, y, other);
+        if (e_other < e_code || (e_other == e_code && other < code)) code = other;
+      } else {
+        code = vq_exact_scan<SUB>(T, y);
+      }
+    }
+  }
   return code;
 }
 

@@ -132,3 +132,31 @@ def test_zero_tokens_and_constant_tokens(gpu_api, codebooks):
     check_unit(x[0, 0], hk.unit_dict(0, 0, 5), cb, 0)
     check_unit(x[0, 0], hv.unit_dict(0, 0, 5), cb, 0)
     assert float(hk.unit_dict(0, 0, 5)["b"][0]) == 0.0
+
+
+@pytest.mark.parametrize("impl", ["mfma", "valu"])
+@pytest.mark.parametrize("sub", [4, 8])
+def test_duplicate_codewords_take_the_lowest_index(gpu_api, codebooks, monkeypatch, impl, sub):
+    """Equal codewords give exactly equal distances: the argmin must be the lowest index (the rule
+    the oracle states), also when three or more entries coincide; all other sub-vectors keep the
+    usual bar (bit-exact outside the 1e-6 tie window)."""
+    monkeypatch.setenv("NSN_ENCODE_IMPL", impl)
+    cb = codebooks[sub].copy()
+    cb[77] = cb[5]
+    cb[200] = cb[5]          # a triple
+    cb[11] = cb[10]          # a pair
+    cb[255] = cb[128]        # a pair across the two halves of the scan
+    lens = [700]
+    k, v, hk, hv = run_gpu_encode(gpu_api, 91 + sub, 1, 1, lens, sub, 64, cb)
+    hits = 0
+    for x, hc in ((k, hk), (v, hv)):
+        got = hc.unit_dict(0, 0, lens[0])
+        ref = O.encode(x[0, 0, :lens[0]], cb, 64, given_b=got["b"], given_o=got["o"], return_debug=True)
+        same = ref["codes"] == got["codes"]
+        exact_tie = ref["second"] == ref["best"]
+        near_tie = (ref["second"] - ref["best"]) < 1e-6 * np.maximum(ref["second"], 1e-300)
+        assert np.all(same | (near_tie & ~exact_tie)), "lowest index on exact ties, bit-exact elsewhere"
+        assert not np.isin(got["codes"], [77, 200, 11, 255]).any()
+        hits += int(np.isin(got["codes"], [5, 10, 128]).sum())
+    print(f"  sub={sub} impl={impl}: {hits} sub-vectors chose a duplicated codeword", flush=True)
+    assert hits > 50
