@@ -162,7 +162,7 @@ struct DecSmem {
   static constexpr bool kTailInTable = kRaccBytes + kTailBytes <= kTableBytes;
   static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kTableBytes + kUnionBytes;
   static constexpr int kBytes = kTableBytes + kUnionBytes + (kTailInTable ? 0 : kTailBytes);
-  static_assert(kUnionBytes >= kCodes * 2 * SUB + 2 * 4 * kHeadDim * 4, "prologue scratch must fit");
+  static_assert(kUnionBytes >= kCodes * 2 * SUB + 2 * 4 * kHeadDim * 4 + 16, "prologue scratch must fit");
   static_assert(kRaccBytes <= kTableBytes, "per-wave accumulators must fit in the table region");
 };
 
@@ -190,6 +190,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   unsigned char* const sm_stage = smem_raw + kTableBytes;                          // prologue only
   float(*const sm_q_orig)[kHeadDim] = reinterpret_cast<float(*)[kHeadDim]>(sm_stage + kCodes * 2 * SUB);
   float(*const sm_q_had)[kHeadDim] = sm_q_orig + 4;
+  float* const sm_qo_first = &sm_q_had[4][0];  // q . o^k of the split's first Shift group, four heads
   float(*const sm_accm)[4][kHeadDim] = reinterpret_cast<float(*)[4][kHeadDim]>(smem_raw + kTableBytes);
   float(*const sm_wave_m)[4] = reinterpret_cast<float(*)[4]>(smem_raw + SM::kTailOffset);  // after the loop
   float(*const sm_wave_l)[4] = sm_wave_m + NW;
@@ -249,6 +250,14 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   Grp cur;
   const bool spec = !g.paged && (t0 + (wave << 6) + 64 <= g.page_tokens);  // in bounds whatever the length
   if (spec) load_group(wave, cur);
+  // The split's first Shift group is shared by all waves when there is one group per sequence:
+  // its q . o^k is formed once per workgroup (waves that do not rotate a query head), not per wave.
+  static_assert(NW == 8, "prologue work split assumes 8 waves: 4 rotate the query, 4 do the rest");
+  const int grp_pre = group_of(g, min(t0, g.page_tokens * g.pages_per_seq - 1));
+  __half2 ok_pre = __half2{};
+  if (wave >= 4 && wave - 4 < R)
+    ok_pre = *reinterpret_cast<const __half2*>(
+        reinterpret_cast<const unsigned char*>(kc.means + (mean_base + grp_pre) * kHeadDim) + lane_x4);
   const int len = seq_lens[b];  // scalar load in flight; first used after the prologue
 #ifdef NSN_DECODE_TIMING
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -281,13 +290,21 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     sm_q_had[hh][2 * lane] = x0 * qscale;
     sm_q_had[hh][2 * lane + 1] = x1 * qscale;
   }
-  {  // replicate the staged codewords with 16-byte LDS writes (8-byte codewords go out in pairs)
+  if (wave >= 4 && wave - 4 < R) {
+    const int hh = wave - 4;
+    const float dot = wave_sum_u(sm_q_orig[hh][2 * lane] * __low2float(ok_pre) +
+                                 sm_q_orig[hh][2 * lane + 1] * __high2float(ok_pre));
+    if (lane == 0) sm_qo_first[hh] = dot * scale_log2e;
+  }
+  {  // replicate the staged codewords with 16-byte LDS writes (8-byte codewords go out in pairs);
+    // the four waves that rotated a query head take 6 of the 16-byte slots per thread, the others 10
     constexpr int NW16 = 16;  // 16-byte slots per 256-byte code row
-    for (int i0 = tid; i0 < kCodes * NW16; i0 += 8 * NT) {
-      uint4 tmp[8];
+    auto fill = [&](auto nc, int first) {
+      constexpr int N = decltype(nc)::value;
+      uint4 tmp[N];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int code = min(i0 + u * NT, kCodes * NW16 - 1) >> 4;
+      for (int u = 0; u < N; ++u) {
+        const int code = (first + u * 256) >> 4;
         if constexpr (SUB == 4) {
           const uint2 c2 = reinterpret_cast<const uint2*>(sm_stage)[code];
           tmp[u] = make_uint4(c2.x, c2.y, c2.x, c2.y);
@@ -296,11 +313,16 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
         }
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int i = i0 + u * NT;
-        if (i < kCodes * NW16) *reinterpret_cast<uint4*>(sm_table + (i >> 4) * 256 + (i & 15) * 16) = tmp[u];
+      for (int u = 0; u < N; ++u) {
+        const int i = first + u * 256;
+        *reinterpret_cast<uint4*>(sm_table + (i >> 4) * 256 + (i & 15) * 16) = tmp[u];
       }
-    }
+    };
+    static_assert(256 * 6 + 256 * 10 == kCodes * NW16, "slot split must cover the table");
+    if (wave < 4)
+      fill(std::integral_constant<int, 6>{}, tid);
+    else
+      fill(std::integral_constant<int, 10>{}, 256 * 6 + (tid - 256));
   }
   __syncthreads();
   NSN_TSTAMP(1);
@@ -330,6 +352,9 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
                         sm_q_orig[3][2 * lane]};
   const float qo1[4] = {sm_q_orig[0][2 * lane + 1], sm_q_orig[1][2 * lane + 1], sm_q_orig[2][2 * lane + 1],
                         sm_q_orig[3][2 * lane + 1]};
+  float qo_pre[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) qo_pre[i] = sm_qo_first[i < R ? i : 0];
   const uint32_t laneoff = (SUB == 4) ? (lane & 31) * 8 : (lane & 15) * 16;
   __syncthreads();  // the prologue scratch is dead: its bytes become the per-wave mean-term accumulators
 #pragma unroll
@@ -487,9 +512,14 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     const int grp = group_of(g, tg);
     if (grp != cur_group) {
       if (cur_group >= 0) flush_group();
-      const float o0 = __low2float(cur.ok2), o1 = __high2float(cur.ok2);
+      if (grp == grp_pre) {
 #pragma unroll
-      for (int i = 0; i < R; ++i) qo[i] = wave_sum_u(qo0[i] * o0 + qo1[i] * o1) * scale_log2e;
+        for (int i = 0; i < R; ++i) qo[i] = qo_pre[i];
+      } else {
+        const float o0 = __low2float(cur.ok2), o1 = __high2float(cur.ok2);
+#pragma unroll
+        for (int i = 0; i < R; ++i) qo[i] = wave_sum_u(qo0[i] * o0 + qo1[i] * o1) * scale_log2e;
+      }
       ov0 = __low2float(cur.ov2);
       ov1 = __high2float(cur.ov2);
       cur_group = grp;
