@@ -44,6 +44,9 @@ def parse():
                         "(no encoder run; the only mode for the C3 / C4 shapes)")
     p.add_argument("--bits", type=int, default=0, help="C4 only: 1 or 2 (default 2)")
     p.add_argument("--n-splits", type=int, default=0)
+    p.add_argument("--group-size", type=int, default=0,
+                   help="with --random-cache: Shift group size (0 = one group per sequence as in the workload "
+                        "definitions, 64 = the paper's residual-size groups)")
     p.add_argument("--rotate-bytes", type=float, default=1.2e9)
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-units", type=int, default=4, help="(sequence, kv-head) units the oracle is timed on")
@@ -75,7 +78,8 @@ def random_cache_decode(args, cfg) -> int:
         sub = 4 if args.bits in (0, 2) else 8
     J = 128 // sub
     max_len = ((max(lens) + 255) // 256) * 256
-    shape = api.make_shape(sub, Hq, Hkv, max_len, 0, page)
+    G = args.group_size
+    shape = api.make_shape(sub, Hq, Hkv, max_len, G, page)
     bt = torch.from_numpy(synth.shuffled_page_table(seed, B, max_len // page)).to(dev) if page else None
     g = torch.Generator(device=dev).manual_seed(seed)
     caches = []
@@ -89,7 +93,8 @@ def random_cache_decode(args, cfg) -> int:
     codebook = (torch.randn((256, sub), device=dev, generator=g)).half()
     q = torch.from_numpy(synth.make_q(seed, B, Hq)).to(dev)
     lens_d = torch.tensor(lens, dtype=torch.int32, device=dev)
-    step_bytes = sum(lens) * Hkv * (2 * J + 8) + B * Hkv * 2 * 256
+    n_groups = sum((n + G - 1) // G for n in lens) if G else B
+    step_bytes = sum(lens) * Hkv * (2 * J + 8) + n_groups * Hkv * 2 * 256
     n_copies = max(1, int(math.ceil(args.rotate_bytes / step_bytes)))
     copies = [(kc, vc)] + [tuple(api.CodedCache(c.codes.clone(), c.norms.clone(), c.means.clone(), bt)
                                  for c in (kc, vc)) for _ in range(n_copies - 1)]
@@ -120,7 +125,7 @@ def random_cache_decode(args, cfg) -> int:
         "ms_per_step": round(us * 1e-3, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic (random cache contents, timing only)",
         "config": {"workload": f"{args.workload}:{cfg['name']}", "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
-                   "cached_tokens": sum(lens), "sub_dim": sub, "page_size": page,
+                   "cached_tokens": sum(lens), "sub_dim": sub, "page_size": page, "group_size": G,
                    "cache_copies_in_rotation": n_copies, "step": "decode attention only"},
         "decode_us_per_step": round(us, 3), "bytes_per_step": step_bytes,
         "roofline": {"bound": "hbm", "kernel": "nsn::dec_mfma_kernel (one launch per decode step)",

@@ -64,20 +64,31 @@ __device__ __forceinline__ float read_lane(float v, int l) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
 }
 // Wave-wide reductions on the vector ALU (no LDS traffic); the result is uniform.
-// quad xor 1, quad xor 2, mirror within 8 lanes, mirror within 16 lanes, then the four rows.
+// quad xor 1, quad xor 2, mirror within 8 lanes, mirror within 16 lanes: every lane holds its
+// row's result; then lane 15 of a row is broadcast into the next row (rows 1 and 3), lane 31 into
+// rows 2 and 3, and lane 63 holds the result of the wave.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_row_masked(float keep, float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, keep), __builtin_bit_cast(int, v),
+                                                               CTRL, ROW_MASK, 0xf, false));
+}
 __device__ __forceinline__ float wave_sum_u(float v) {
   v += dpp_row<0xB1>(v);
   v += dpp_row<0x4E>(v);
   v += dpp_row<0x141>(v);
   v += dpp_row<0x140>(v);
-  return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
+  v += dpp_row_masked<0x142, 0xA>(0.f, v);  // rows 1, 3 += row 0, 2
+  v += dpp_row_masked<0x143, 0xC>(0.f, v);  // rows 2, 3 += rows 0 + 1
+  return read_lane(v, 63);
 }
 __device__ __forceinline__ float wave_max_u(float v) {
   v = fmaxf(v, dpp_row<0xB1>(v));
   v = fmaxf(v, dpp_row<0x4E>(v));
   v = fmaxf(v, dpp_row<0x141>(v));
   v = fmaxf(v, dpp_row<0x140>(v));
-  return fmaxf(fmaxf(read_lane(v, 0), read_lane(v, 16)), fmaxf(read_lane(v, 32), read_lane(v, 48)));
+  v = fmaxf(v, dpp_row_masked<0x142, 0xA>(v, v));
+  v = fmaxf(v, dpp_row_masked<0x143, 0xC>(v, v));
+  return read_lane(v, 63);
 }
 
 // Device-scope stores / loads: coherent across the chip's L2 slices without cache maintenance.
