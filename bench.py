@@ -5,10 +5,14 @@ Workload (default): the Llama-3-8B-shaped 2-bit decode configuration - 32 query 
 heads, head_dim 128, batch 8, 8192 cached tokens per sequence, 4-dim sub-vectors with a 256-entry
 K-Means codebook, fp16 norms, one fp16 channel-mean vector per (sequence, head).
 
-One step = one decode step of the whole hot path: encode the step's new token of every sequence
+One step = one decode step of the whole hot path, run the way the method runs it (Sec. 3.2,
+"Residual", residual size 64): the step's new token of every sequence is the next row of a
+64-token fp16 residual; decode attention runs over the 8192 coded tokens plus the residual
+rows; when the residual is full (every 64th step) its 64 tokens per sequence are encoded
 (Normalize, Shift with the stored mean, Normalize, Hadamard, codeword search, scale adjustment)
-into the last cache slot, then decode attention over the 8192 coded tokens.  Inputs are resident
-in HBM before the timed region.  `value` = coded cache bytes read per step / step time.
+into the cache.  Every generated token is encoded exactly once, inside the timed region.
+`--policy append` times the simpler loop that encodes each new token right away.  Inputs are
+resident in HBM before the timed region.  `value` = coded cache bytes read per step / step time.
 The coded cache is replicated so that consecutive steps touch different memory (> 1 GB in
 rotation) and the 38 MB working set cannot be served from the last-level cache.
 
@@ -44,6 +48,11 @@ def parse():
                         "(no encoder run; the only mode for the C3 / C4 shapes)")
     p.add_argument("--bits", type=int, default=0, help="C4 only: 1 or 2 (default 2)")
     p.add_argument("--n-splits", type=int, default=0)
+    p.add_argument("--policy", default="residual", choices=["residual", "append"],
+                   help="decode-loop policy of the timed step: 'residual' = the paper's (Sec. 3.2): the new token "
+                        "joins a 64-token fp16 residual that takes part in the attention and is encoded when "
+                        "full (one 64-token encode per sequence every 64 steps, inside the timed region); "
+                        "'append' = every step encodes its one new token before the attention")
     p.add_argument("--group-size", type=int, default=0,
                    help="with --random-cache: Shift group size (0 = one group per sequence as in the workload "
                         "definitions, 64 = the paper's residual-size groups)")
@@ -172,7 +181,8 @@ def main() -> int:
     k_host, v_host = synth.make_kv(seed, B, Hkv, L, per_seq=cfg.get("per_seq", False))
     q_host = synth.make_q(seed, B, Hq)
     k_dev, v_dev, q_dev = (torch.from_numpy(x).to(dev) for x in (k_host, v_host, q_host))
-    shape = api.make_shape(sub, Hq, Hkv, L, G)
+    RES = 64  # residual size of the paper
+    shape = api.make_shape(sub, Hq, Hkv, L + RES, G)  # room for one flushed residual behind the L cached tokens
     kc, vc = api.alloc_cache(shape, B), api.alloc_cache(shape, B)
     zeros = torch.zeros(B, dtype=torch.int32, device=dev)
     full = torch.full((B,), L, dtype=torch.int32, device=dev)
@@ -201,22 +211,43 @@ def main() -> int:
     for _ in range(n_copies - 1):
         copies.append(tuple(api.CodedCache(c.codes.clone(), c.norms.clone(), c.means.clone(), None)
                             for c in (kc, vc)))
-    # the step's new token: last position of every sequence, encoded with the stored mean
-    k_new = k_dev[:, :, L - 1:L, :].contiguous()
-    v_new = v_dev[:, :, L - 1:L, :].contiguous()
-    last = torch.full((B,), L - 1, dtype=torch.int32, device=dev)
-    ones = torch.ones(B, dtype=torch.int32, device=dev)
     dec_ws = torch.zeros(max(1, api.nsn_workspace_bytes(shape, api.NSN_OP_DECODE, B, 0, args.n_splits)),
                          dtype=torch.uint8, device=dev)
     out = torch.empty((B, Hq, 128), dtype=torch.float32, device=dev)
 
+    # The tokens generated during the timed loop: positions L .. L+63 of every sequence.
+    k_res = np.empty((B, Hkv, RES, 128), dtype=np.float16)
+    v_res = np.empty_like(k_res)
+    for b in range(B):
+        for h in range(Hkv):
+            k_res[b, h] = synth.make_k(seed, b, h, RES, per_seq=cfg.get("per_seq", False), start=L)
+            v_res[b, h] = synth.make_v(seed, b, h, RES, start=L)
+    k_res, v_res = torch.from_numpy(k_res).to(dev), torch.from_numpy(v_res).to(dev)
+    res_lens = [torch.full((B,), r, dtype=torch.int32, device=dev) for r in range(1, RES + 1)]
+    # 'append' policy: the step's one new token, encoded with the stored mean before the attention
+    k_new = k_res[:, :, :1, :].contiguous()
+    v_new = v_res[:, :, :1, :].contiguous()
+    ones = torch.ones(B, dtype=torch.int32, device=dev)
+    full1 = torch.full((B,), L + 1, dtype=torch.int32, device=dev)
+
     def step(i: int, with_encode: bool = True):
         ck, cv = copies[i % n_copies]
-        if with_encode:
-            api.nsn_encode(shape, codebook, k_new, v_new, last, ones, ck, cv, freeze_means=True,
-                           workspace=enc_ws)
-        api.nsn_decode_attention(shape, codebook, q_dev, ck, cv, full, L, scale, args.n_splits, out=out,
-                                 workspace=dec_ws)
+        if not with_encode:
+            api.nsn_decode_attention(shape, codebook, q_dev, ck, cv, full, L, scale, args.n_splits, out=out,
+                                     workspace=dec_ws)
+        elif args.policy == "append":
+            api.nsn_encode(shape, codebook, k_new, v_new, full, ones, ck, cv, freeze_means=True, workspace=enc_ws)
+            api.nsn_decode_attention(shape, codebook, q_dev, ck, cv, full1, L + 1, scale, args.n_splits, out=out,
+                                     workspace=dec_ws)
+        else:
+            # the new token is row (i mod 64) of the residual (its producer writes it there); attention over
+            # L coded tokens + the residual; a full residual is encoded into the cache it belongs to
+            r = i % RES
+            api.nsn_decode_attention_residual(shape, codebook, q_dev, ck, cv, full, L, k_res, v_res, res_lens[r],
+                                              scale, args.n_splits, out=out, workspace=dec_ws)
+            if r == RES - 1:
+                api.nsn_encode(shape, codebook, k_res, v_res, full, res_lens[RES - 1], ck, cv, freeze_means=True,
+                               workspace=enc_ws)
 
     for i in range(args.warmup):
         step(i)
@@ -227,10 +258,11 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev0.record()
-    for i in range(args.steps):
+    for i in range(args.warmup, args.warmup + args.steps):  # the step counter runs on from the warm-up
         step(i)
     ev1.record()
     torch.cuda.synchronize()
+    flushes = sum(1 for i in range(args.warmup, args.warmup + args.steps) if i % RES == RES - 1)
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
@@ -278,7 +310,11 @@ def main() -> int:
         "config": {"workload": f"{args.workload}:{cfg['name']}", "batch": B, "n_q_heads": Hq,
                    "n_kv_heads": Hkv, "cached_tokens": L, "sub_dim": sub, "bits": 8 // sub,
                    "group_size": G, "cache_copies_in_rotation": n_copies,
-                   "step": "append-encode 1 token/sequence + decode attention"},
+                   "residual_size": RES if args.policy == "residual" else 0,
+                   "residual_encodes_in_timed_region": flushes if args.policy == "residual" else 0,
+                   "step": ("decode attention over the coded cache + fp16 residual; every 64th step encodes the "
+                            "full residual (64 tokens per sequence)") if args.policy == "residual"
+                   else "append-encode 1 token/sequence + decode attention"},
         "decode_us_per_step": round(dec_us, 3),
         "decode_us_per_step_cache_resident": round(dec_us_hot, 3),
         "host_wall_ms_per_step": round(wall_ms, 6),

@@ -161,15 +161,16 @@ __device__ long long g_dec_timing[48];
 //   [0, 64 KiB)        codebook table: entry (code c, copy p) at c * 256 + p * (2 * SUB) bytes,
 //                      32 copies of 8 B (SUB = 4) or 16 copies of 16 B (SUB = 8);
 //                      after the main loop the same bytes hold the per-wave accumulators
-//   [64 KiB, +NW*2KiB) prologue: staged codewords, q, rotated q;
-//                      main loop: mean-vector term of every wave, accm[NW][4][128]
+//   [64 KiB, +(NW+1)*2KiB) prologue: staged codewords, q, rotated q;
+//                      main loop: mean-vector term of every wave, accm[NW + 1][4][128]
+//                      (slot NW belongs to the residual wave, present only in residual launches)
 //   tail               per-wave (m, l), the "last workgroup" flag, inverse-Hadamard scratch
 // One workgroup of 8 waves per compute unit shares a single table (64 + 16 KiB of the 160 KiB).
 template <int SUB, int NW>
 struct DecSmem {
-  static constexpr int kUnionBytes = NW * 4 * kHeadDim * 4;
+  static constexpr int kUnionBytes = (NW + 1) * 4 * kHeadDim * 4;  // + the residual wave's slot
   static constexpr int kRaccBytes = NW * (64 / (kHeadDim / SUB)) * 4 * kHeadDim * 4;
-  static constexpr int kTailBytes = (2 * NW * 4 + 4 + 4 * kHeadDim) * 4;
+  static constexpr int kTailBytes = (2 * (NW + 1) * 4 + 4 + 4 * kHeadDim) * 4;
   static constexpr bool kTailInTable = kRaccBytes + kTailBytes <= kTableBytes;
   static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kTableBytes + kUnionBytes;
   static constexpr int kBytes = kTableBytes + kUnionBytes + (kTailInTable ? 0 : kTailBytes);
@@ -181,7 +182,7 @@ struct DecSmem {
 // With R <= 2 the fp16 hi and lo parts of the rotated query share the four MFMA rows
 // (rows [0,R) = hi, rows [R,2R) = lo), so one MFMA per slot suffices.
 template <int SUB, int NW, int R>
-__global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __half* __restrict__ codebook,
+__global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, const __half* __restrict__ codebook,
                                                            const __half* __restrict__ q, CacheView kc,
                                                            CacheView vc, const int32_t* __restrict__ seq_lens,
                                                            float scale_log2e, int n_splits, int per,
@@ -204,14 +205,19 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   float* const sm_qo_first = &sm_q_had[4][0];  // q . o^k of the split's first Shift group, four heads
   float(*const sm_accm)[4][kHeadDim] = reinterpret_cast<float(*)[4][kHeadDim]>(smem_raw + kTableBytes);
   float(*const sm_wave_m)[4] = reinterpret_cast<float(*)[4]>(smem_raw + SM::kTailOffset);  // after the loop
-  float(*const sm_wave_l)[4] = sm_wave_m + NW;
-  int* const sm_is_last = reinterpret_cast<int*>(sm_wave_l + NW);
+  float(*const sm_wave_l)[4] = sm_wave_m + (NW + 1);
+  int* const sm_is_last = reinterpret_cast<int*>(sm_wave_l + (NW + 1));
   float* const sm_rot = reinterpret_cast<float*>(sm_is_last + 4);
 
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int r = g.n_q_heads / g.n_kv_heads;  // <= 4
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // per-wave bookkeeping on the scalar unit
+  // Launches with a residual carry one more wave (index NW): it handles the fp16 residual tokens
+  // while the NW main waves run their loops, takes no part in the cooperative prologue work and
+  // joins the others at every barrier.
+  const int n_waves = (int)(blockDim.x >> 6);  // NW or NW + 1
+  const bool main_wave = wave < NW;
   const int t0 = split * per;
   const int64_t mean_base = (int64_t)(b * g.n_kv_heads + h) * g.n_groups_max;
 
@@ -259,7 +265,7 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
     qv[u] = (i < 4 * kHeadDim && hh < r) ? __half2float(q[(int64_t)(b * g.n_q_heads + h * r + hh) * kHeadDim + c]) : 0.f;
   }
   Grp cur;
-  const bool spec = !g.paged && (t0 + (wave << 6) + 64 <= g.page_tokens);  // in bounds whatever the length
+  const bool spec = main_wave && !g.paged && (t0 + (wave << 6) + 64 <= g.page_tokens);  // in bounds whatever the length
   if (spec) load_group(wave, cur);
   // The split's first Shift group is shared by all waves when there is one group per sequence:
   // its q . o^k is formed once per workgroup (waves that do not rotate a query head), not per wave.
@@ -310,35 +316,37 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   {  // replicate the staged codewords with 16-byte LDS writes (8-byte codewords go out in pairs);
     // the four waves that rotated a query head take 6 of the 16-byte slots per thread, the others 10
     constexpr int NW16 = 16;  // 16-byte slots per 256-byte code row
+    typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+    typedef uint32_t u2v __attribute__((ext_vector_type(2)));
     auto fill = [&](auto nc, int first) {
       constexpr int N = decltype(nc)::value;
-      uint4 tmp[N];
+      u4v tmp[N];
 #pragma unroll
       for (int u = 0; u < N; ++u) {
         const int code = (first + u * 256) >> 4;
         if constexpr (SUB == 4) {
-          const uint2 c2 = reinterpret_cast<const uint2*>(sm_stage)[code];
-          tmp[u] = make_uint4(c2.x, c2.y, c2.x, c2.y);
+          const u2v c2 = reinterpret_cast<const u2v*>(sm_stage)[code];
+          tmp[u] = u4v{c2.x, c2.y, c2.x, c2.y};
         } else {
-          tmp[u] = reinterpret_cast<const uint4*>(sm_stage)[code];
+          tmp[u] = reinterpret_cast<const u4v*>(sm_stage)[code];
         }
       }
 #pragma unroll
       for (int u = 0; u < N; ++u) {
         const int i = first + u * 256;
-        *reinterpret_cast<uint4*>(sm_table + (i >> 4) * 256 + (i & 15) * 16) = tmp[u];
+        *reinterpret_cast<u4v*>(sm_table + (i >> 4) * 256 + (i & 15) * 16) = tmp[u];
       }
     };
     static_assert(256 * 6 + 256 * 10 == kCodes * NW16, "slot split must cover the table");
     if (wave < 4)
       fill(std::integral_constant<int, 6>{}, tid);
-    else
+    else if (main_wave)
       fill(std::integral_constant<int, 10>{}, 256 * 6 + (tid - 256));
   }
   __syncthreads();
   NSN_TSTAMP(1);
   const int t1 = min(len, t0 + per);
-  const int n_grp = t1 > t0 ? (t1 - t0 + 63) >> 6 : 0;
+  const int n_grp = (main_wave && t1 > t0) ? (t1 - t0 + 63) >> 6 : 0;  // the residual wave owns no coded group
   if (!spec && wave < n_grp) load_group(wave, cur);
 
   // A operands of the score contraction: slot s = channels [4s, 4s+4); block (lane / 4) of
@@ -574,12 +582,12 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   NSN_TSTAMP(10);
 
   // ---- residual (Sec. 3.2): the most recent tokens are still fp16 and join the same softmax ---
-  // One wave of the last split treats them as one more 64-token group: the fp16 key row of the
-  // lane's token is the B operand directly (no table), the A operand is the unrotated query,
+  // The extra wave of the last split treats them as one more 64-token group: the fp16 key row of
+  // the lane's token is the B operand directly (no table), the A operand is the unrotated query,
   // and the value rows accumulate in the original domain next to the mean-vector term.
   f4 acc_res[SUB];
   bool res_here = false;
-  if (res.k != nullptr && split == n_splits - 1 && wave == NW - 1) {
+  if (res.k != nullptr && split == n_splits - 1 && wave == NW) {
     const int rl = min(res.lens[b], res.capacity);
     if (rl > 0) {
       res_here = true;
@@ -660,12 +668,14 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   __syncthreads();  // every wave is done gathering from the table
   NSN_TSTAMP(8);
   float* racc = reinterpret_cast<float*>(sm_table);  // [NW][NPART][4][128]; the tail follows it
+  if (main_wave) {  // the residual wave has no rotated-domain sum
 #pragma unroll
-  for (int i = 0; i < R; ++i)
+    for (int i = 0; i < R; ++i)
 #pragma unroll
-    for (int c4 = 0; c4 < SUB / 4; ++c4)
-      *reinterpret_cast<float4*>(&racc[((wave * NPART + lane / LV) * 4 + i) * kHeadDim + (lane % LV) * SUB + 4 * c4]) =
-          make_float4(acc[4 * c4][i], acc[4 * c4 + 1][i], acc[4 * c4 + 2][i], acc[4 * c4 + 3][i]);
+      for (int c4 = 0; c4 < SUB / 4; ++c4)
+        *reinterpret_cast<float4*>(&racc[((wave * NPART + lane / LV) * 4 + i) * kHeadDim + (lane % LV) * SUB + 4 * c4]) =
+            make_float4(acc[4 * c4][i], acc[4 * c4 + 1][i], acc[4 * c4 + 2][i], acc[4 * c4 + 3][i]);
+  }
 #pragma unroll
   for (int i = 0; i < R; ++i)
     if (lane == i) {
@@ -679,16 +689,18 @@ __global__ __launch_bounds__(NW * 64) void dec_mfma_kernel(Geometry g, const __h
   for (int i = tid; i < r * kHeadDim; i += NT) {
     const int hh = i >> 7, c = i & 127;
     float M = -INFINITY;
-    for (int wv = 0; wv < NW; ++wv) M = fmaxf(M, sm_wave_m[wv][hh]);
+    for (int wv = 0; wv < n_waves; ++wv) M = fmaxf(M, sm_wave_m[wv][hh]);
     float L = 0.f, orot = 0.f, omean = 0.f;
-    for (int wv = 0; wv < NW; ++wv) {
+    for (int wv = 0; wv < n_waves; ++wv) {
       const float mw = sm_wave_m[wv][hh];
       const float e = (mw == -INFINITY) ? 0.f : fast_exp2(mw - M);
       L = fmaf(e, sm_wave_l[wv][hh], L);
-      float part = 0.f;
+      if (wv < NW) {
+        float part = 0.f;
 #pragma unroll
-      for (int pt = 0; pt < NPART; ++pt) part += racc[((wv * NPART + pt) * 4 + hh) * kHeadDim + c];
-      orot = fmaf(e, part, orot);
+        for (int pt = 0; pt < NPART; ++pt) part += racc[((wv * NPART + pt) * 4 + hh) * kHeadDim + c];
+        orot = fmaf(e, part, orot);
+      }
       omean = fmaf(e, sm_accm[wv][hh][c], omean);
     }
     float* Ph = P + (int64_t)hh * n_splits * kPartialStrideM;
@@ -796,7 +808,8 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
   int* counters = static_cast<int*>(workspace);
   float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + counter_bytes);
   const dim3 grid(n_splits, g.n_kv_heads, batch);
-  dec_mfma_kernel<SUB, NW, R><<<grid, NW * 64, smem, stream>>>(
+  const int waves = res.k != nullptr ? NW + 1 : NW;  // + the residual wave
+  dec_mfma_kernel<SUB, NW, R><<<grid, waves * 64, smem, stream>>>(
       g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens, scale * 1.44269504088896340736f, n_splits,
       per, partial, counters, res, out);
   return NSN_OK;
