@@ -25,6 +25,13 @@ Parity pins (tests/test_oracle_*.py, all CPU):
                       themselves are "parity unpinned" against the paper (its tuned
                       codebook is not printed); GPU and oracle are compared with
                       one and the same codebook array.
+  decode_attention_residual   no residual = coded-only attention; no coded tokens = plain
+                      softmax attention written with loops; both = merge of the two by
+                      their softmax masses (Sec. 3.2 "Residual")
+  finetune_codebook   gradient equals central finite differences of the cosine loss at a
+                      fixed assignment and is orthogonal to its codeword; the cosine
+                      similarity rises.  Optimiser, rate and step count are this build's
+                      reading: "parity unpinned" against the paper's tuned codebook (Sec. 3.4)
 """
 from __future__ import annotations
 
@@ -292,6 +299,60 @@ def build_codebook(samples: np.ndarray, n_codes: int = 256, iters: int = 50):
     c = fp16_rne(c).astype(F64)
     _, best, _ = nearest_codeword(x, c)
     return c, np.asarray(history), best.sum() / (n * sub)
+
+
+# ----------------------------------------------------------------------------
+# Codebook fine-tuning (Sec. 3.4): lower the cosine distance between a standard-normal vector and
+# its quantised version; the lookup is not differentiated, so a sample's gradient reaches only the
+# centroid it was assigned to.  The paper gives no optimiser, rate or step count: plain full-batch
+# gradient steps with a caller-chosen rate are this build's reading (parity with the paper's tuned
+# codebook is unpinned; the gradient itself is pinned by finite differences in the tests).
+# ----------------------------------------------------------------------------
+def cosine_loss(samples, codebook, assignment=None) -> float:
+    """mean over samples of 1 - cos(x, C[k(x)]); k = Eq. 1's nearest codeword unless given.
+    Zero samples and zero codewords count as cosine 0."""
+    x = np.asarray(samples, dtype=F64)
+    c = np.asarray(codebook, dtype=F64)
+    if assignment is None:
+        assignment, _, _ = nearest_codeword(x, c)
+    cq = c[assignment]
+    den = np.linalg.norm(x, axis=1) * np.linalg.norm(cq, axis=1)
+    cos = np.divide(np.sum(x * cq, axis=1), den, out=np.zeros_like(den), where=den > 0)
+    return float(1.0 - cos.mean())
+
+
+def cosine_loss_gradient(samples, codebook, assignment) -> np.ndarray:
+    """d cosine_loss / d codebook for a fixed assignment:
+    row k = -(1 / (N |c_k|)) * (S_k - (S_k . c_k^) c_k^),  S_k = sum of x / |x| over the samples of k."""
+    x = np.asarray(samples, dtype=F64)
+    c = np.asarray(codebook, dtype=F64)
+    n = x.shape[0]
+    nx = np.linalg.norm(x, axis=1, keepdims=True)
+    xh = np.divide(x, nx, out=np.zeros_like(x), where=nx > 0)
+    g = np.zeros_like(c)
+    for k in range(c.shape[0]):
+        m = assignment == k
+        cn = float(np.linalg.norm(c[k]))
+        if not m.any() or cn == 0.0:
+            continue
+        s_k = xh[m].sum(axis=0)
+        ch = c[k] / cn
+        g[k] = -(s_k - float(s_k @ ch) * ch) / (n * cn)
+    return g
+
+
+def finetune_codebook(samples, codebook, iters: int, lr: float):
+    """`iters` steps of: assign by Eq. 1, C <- C - lr * gradient.  The result is rounded to fp16 once.
+    Returns (codebook, mean cosine similarity before every step, mean cosine similarity of the result)."""
+    x = np.asarray(samples, dtype=F64)
+    c = np.asarray(codebook, dtype=F64).copy()
+    history = []
+    for _ in range(iters):
+        idx, _, _ = nearest_codeword(x, c)
+        history.append(1.0 - cosine_loss(x, c, idx))
+        c = c - lr * cosine_loss_gradient(x, c, idx)
+    c = fp16_rne(c).astype(F64)
+    return c, np.asarray(history), 1.0 - cosine_loss(x, c)
 
 
 # ----------------------------------------------------------------------------

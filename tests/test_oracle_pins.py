@@ -314,3 +314,48 @@ def test_residual_attention_limits():
         zc, zr = np.exp(sc - m).sum(), np.exp(sr - m).sum()
         merged = (zc * out0[r] + zr * out1[r]) / (zc + zr)
         assert np.allclose(out[r], merged, rtol=1e-11, atol=1e-13)
+
+
+# ---------------------------------------------------------------- codebook fine-tuning (Sec. 3.4)
+def test_cosine_gradient_matches_finite_differences_and_is_tangential():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((400, 4))
+    c = rng.standard_normal((8, 4)) * 1.3
+    idx, _, _ = O.nearest_codeword(x, c)
+    g = O.cosine_loss_gradient(x, c, idx)
+    num = np.zeros_like(c)
+    h = 1e-6
+    for k in range(c.shape[0]):
+        for i in range(c.shape[1]):
+            cp, cm = c.copy(), c.copy()
+            cp[k, i] += h
+            cm[k, i] -= h
+            num[k, i] = (O.cosine_loss(x, cp, idx) - O.cosine_loss(x, cm, idx)) / (2 * h)
+    assert np.allclose(g, num, rtol=1e-6, atol=1e-9)
+    assert np.abs(g).max() > 1e-4                       # not trivially zero
+    assert np.allclose(np.sum(g * c, axis=1), 0.0, atol=1e-15)   # cosine ignores the codeword's length
+    # a codeword that already points along the mean direction of its samples is stationary
+    c2 = c.copy()
+    xh = x / np.linalg.norm(x, axis=1, keepdims=True)
+    for k in range(c.shape[0]):
+        c2[k] = 2.5 * xh[idx == k].sum(axis=0)
+    assert np.allclose(O.cosine_loss_gradient(x, c2, idx), 0.0, atol=1e-15)
+
+
+def test_finetune_raises_the_cosine_similarity():
+    x = synth.codebook_samples(77, 1 << 12, 4).astype(np.float64)
+    cb, _, _ = O.build_codebook(x, 256, 6)
+    # one step at a fixed assignment is a descent step of the cosine loss (first-order guarantee) ...
+    idx, _, _ = O.nearest_codeword(x, cb)
+    g = O.cosine_loss_gradient(x, cb, idx)
+    l0 = O.cosine_loss(x, cb, idx)
+    l1 = O.cosine_loss(x, cb - 64.0 * g, idx)
+    assert l1 < l0 and abs((l0 - l1) - 64.0 * np.sum(g * g)) < 0.2 * (l0 - l1)
+    # ... and the full loop (assignments retaken by Eq. 1 every step) ends above where it started
+    tuned, hist, final = O.finetune_codebook(x, cb, 12, 64.0)
+    assert abs(hist[0] - (1.0 - l0)) < 1e-15
+    assert final > hist[0] + 2e-4
+    assert np.array_equal(tuned, O.fp16_rne(tuned).astype(np.float64))   # stored as fp16
+    # zero steps only round
+    same, h0, f0 = O.finetune_codebook(x, cb, 0, 64.0)
+    assert np.array_equal(same, cb) and h0.size == 0 and abs(f0 - hist[0]) < 1e-15
