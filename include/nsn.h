@@ -120,8 +120,8 @@ const char* nsn_last_error(void);
 size_t nsn_workspace_bytes(const nsn_shape* shape, int op, int batch, int64_t n, int n_splits);
 
 /*
- * K-Means codebook on standard-normal data (Sec. 3.4, the K-Means baseline; the paper's
- * later fine-tuning step is not part of this call).
+ * K-Means codebook on standard-normal data (Sec. 3.4, the K-Means baseline; the fine-tuning
+ * step is nsn_finetune_codebook).
  *   samples_dev   dev fp32 [n_samples][sub_dim], drawn by the caller (the library holds no
  *                 random generator); the first n_codes samples are the initial centroids
  *   iters         Lloyd iterations: assign to the nearest centroid in squared Euclidean
@@ -136,6 +136,27 @@ size_t nsn_workspace_bytes(const nsn_shape* shape, int op, int batch, int64_t n,
 int nsn_build_codebook(const float* samples_dev, int64_t n_samples, int sub_dim, int n_codes,
                        int iters, void* codebook_dev, double* mse_host, void* workspace,
                        size_t workspace_bytes, void* stream);
+
+/*
+ * Fine-tune a codebook for cosine distance on standard-normal data (Sec. 3.4): `iters` times,
+ * assign every sample to its nearest codeword (Eq. 1, as nsn_build_codebook does) and take one
+ * full-batch gradient step of  mean_x (1 - cos(x, C[k(x)]))  with the assignment held fixed
+ * (the lookup is not differentiated):
+ *     C[k] += lr / (N |C[k]|) * (S_k - (S_k . c^) c^),   S_k = sum of x / |x| over the samples of k,
+ *     c^ = C[k] / |C[k]|.   Zero samples and zero codewords are left out.
+ * The paper names neither optimiser nor rate nor step count; plain gradient steps with the
+ * caller's `lr` are this library's reading.
+ *   samples_dev   dev fp32 [n_samples][sub_dim]
+ *   codebook_dev  in/out, dev fp16 [n_codes][sub_dim]: the start (e.g. from nsn_build_codebook);
+ *                 steps run in fp64, the result is rounded to fp16 once
+ *   cos_host      out, host double[2]: mean cosine similarity between the samples and their
+ *                 quantised versions before and after (may be NULL)
+ *   workspace     nsn_workspace_bytes(shape, NSN_OP_CODEBOOK, 0, n_samples, 0) bytes
+ * Synchronises the stream before returning.  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP.
+ */
+int nsn_finetune_codebook(const float* samples_dev, int64_t n_samples, int sub_dim, int n_codes,
+                          int iters, double lr, void* codebook_dev, double* cos_host,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Encoder (Sec. 3.2 steps 1-3, Hadamard rotation of Sec. 2, Eq. 1 on contiguous sub-vectors

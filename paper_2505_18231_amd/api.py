@@ -62,6 +62,8 @@ def lib() -> C.CDLL:
             fn.argtypes = [C.c_int, C.c_int64, C.c_int]
         L.nsn_build_codebook.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                          C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nsn_finetune_codebook.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_double,
+                                            C.c_void_p, C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
         L.nsn_encode.argtypes = [C.POINTER(nsn_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                  C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(nsn_cache),
                                  C.POINTER(nsn_cache), C.c_void_p, C.c_size_t, C.c_void_p]
@@ -148,6 +150,23 @@ def nsn_build_codebook(samples: torch.Tensor, n_codes: int = N_CODES, iters: int
     _check(lib().nsn_build_codebook(samples.data_ptr(), n, sub, n_codes, iters, codebook.data_ptr(),
                                     C.byref(mse), workspace.data_ptr(), workspace.numel(), _stream()))
     return codebook, mse.value
+
+
+def nsn_finetune_codebook(samples: torch.Tensor, codebook: torch.Tensor, iters: int, lr: float,
+                          workspace: torch.Tensor | None = None):
+    """samples: cuda fp32 [n][sub_dim]; codebook: cuda fp16 [256][sub_dim], updated in place.
+    Returns (codebook, mean cosine similarity before, after)."""
+    assert samples.is_cuda and samples.dtype == torch.float32 and samples.is_contiguous()
+    assert codebook.is_cuda and codebook.dtype == torch.float16 and codebook.is_contiguous()
+    n, sub = samples.shape
+    assert codebook.shape == (N_CODES, sub)
+    need = nsn_workspace_bytes(make_shape(sub, 1, 1, 64), NSN_OP_CODEBOOK, 1, n)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=samples.device)
+    cos = (C.c_double * 2)(0.0, 0.0)
+    _check(lib().nsn_finetune_codebook(samples.data_ptr(), n, sub, N_CODES, iters, float(lr), codebook.data_ptr(),
+                                       cos, workspace.data_ptr(), workspace.numel(), _stream()))
+    return codebook, cos[0], cos[1]
 
 
 def nsn_encode(shape: nsn_shape, codebook: torch.Tensor, k: torch.Tensor, v: torch.Tensor,

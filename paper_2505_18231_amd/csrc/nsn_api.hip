@@ -110,6 +110,28 @@ int nsn_build_codebook(const float* samples_dev, int64_t n_samples, int sub_dim,
   return rc;
 }
 
+int nsn_finetune_codebook(const float* samples_dev, int64_t n_samples, int sub_dim, int n_codes, int iters,
+                          double lr, void* codebook_dev, double* cos_host, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (n_codes != 256 || (sub_dim != 4 && sub_dim != 8)) {
+    set_error("finetune_codebook: unsupported n_codes=%d sub_dim=%d (256 codes of 4 or 8 dims)", n_codes, sub_dim);
+    return NSN_ERR_UNSUPPORTED;
+  }
+  if (!samples_dev || !codebook_dev || n_samples < 1 || iters < 0 || !(lr >= 0.0)) {
+    set_error("finetune_codebook: null pointer, n_samples=%lld < 1, iters=%d < 0 or a negative rate",
+              (long long)n_samples, iters);
+    return NSN_ERR_INVALID_ARG;
+  }
+  if (!workspace || workspace_bytes < codebook_workspace_bytes(sub_dim, n_samples)) {
+    set_error("finetune_codebook: workspace of %zu bytes needed", codebook_workspace_bytes(sub_dim, n_samples));
+    return NSN_ERR_WORKSPACE;
+  }
+  const int rc = finetune_run(samples_dev, n_samples, sub_dim, iters, lr, codebook_dev, cos_host, workspace,
+                              static_cast<hipStream_t>(stream));
+  if (rc == NSN_ERR_HIP) set_error("finetune_codebook: HIP error: %s", hipGetErrorString(hipGetLastError()));
+  return rc;
+}
+
 int nsn_encode(const nsn_shape* shape, const void* codebook_dev, const void* k_fp16, const void* v_fp16,
                int max_new, const int32_t* seq_start_dev, const int32_t* n_new_dev, int batch, int freeze_means,
                const nsn_cache* k_cache, const nsn_cache* v_cache, void* workspace, size_t workspace_bytes,

@@ -1,4 +1,5 @@
-// K-Means codebook on standard-normal samples (Sec. 3.4, the K-Means baseline).
+// K-Means codebook on standard-normal samples (Sec. 3.4, the K-Means baseline) and its
+// fine-tuning for cosine distance.
 //
 // Lloyd iterations entirely on the device, deterministic (no atomics):
 //   km_assign_kernel  nearest centroid per sample (same fp32-scan + fp64-recheck search as the
@@ -83,8 +84,71 @@ __global__ __launch_bounds__(256) void km_update_kernel(const float* __restrict_
   }
 }
 
+// Fine-tuning for cosine distance (Sec. 3.4): one workgroup per codeword sums x / |x| over its
+// samples in a fixed order (fp64), then moves the codeword along the part of that sum that is
+// orthogonal to it:  c += lr / (N |c|) * (S - (S . c^) c^).   cos_sum[k] = S . c^ is the cluster's
+// share of the summed cosine similarity BEFORE the move.
+template <int SUB>
+__global__ __launch_bounds__(256) void ft_update_kernel(const float* __restrict__ samples, int64_t n,
+                                                        const uint8_t* __restrict__ assign,
+                                                        double* __restrict__ centroids, double lr,
+                                                        double* __restrict__ cos_sum) {
+  __shared__ double red[4][SUB];
+  const int k = blockIdx.x;
+  double sum[SUB];
+#pragma unroll
+  for (int i = 0; i < SUB; ++i) sum[i] = 0.0;
+  for (int64_t idx = threadIdx.x; idx < n; idx += 256) {
+    if (assign[idx] == k) {
+      double x[SUB], n2 = 0.0;
+#pragma unroll
+      for (int i = 0; i < SUB; ++i) {
+        x[i] = (double)samples[idx * SUB + i];
+        n2 += x[i] * x[i];
+      }
+      if (n2 > 0.0) {
+        const double nx = sqrt(n2);
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) sum[i] += x[i] / nx;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < SUB; ++i) sum[i] = xor_sum(sum[i], 64);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) red[wave][i] = sum[i];
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double S[SUB], c[SUB], cn2 = 0.0;
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) {
+      S[i] = ((red[0][i] + red[1][i]) + red[2][i]) + red[3][i];
+      c[i] = centroids[k * SUB + i];
+      cn2 += c[i] * c[i];
+    }
+    double along = 0.0;
+    if (cn2 > 0.0) {
+      const double cn = sqrt(cn2);
+#pragma unroll
+      for (int i = 0; i < SUB; ++i) along += S[i] * (c[i] / cn);
+#pragma unroll
+      for (int i = 0; i < SUB; ++i)
+        centroids[k * SUB + i] = c[i] + lr * ((S[i] - along * (c[i] / cn)) / ((double)n * cn));
+    }
+    cos_sum[k] = along;
+  }
+}
+
+__global__ void ft_load_kernel(const __half* __restrict__ in, double* __restrict__ centroids, int n_elems) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_elems) centroids[i] = (double)__half2float(in[i]);
+}
+
 size_t codebook_workspace_bytes(int sub_dim, int64_t n_samples) {
-  return (size_t)kCodes * sub_dim * sizeof(double) + kAssignBlocks * sizeof(double) +
+  return (size_t)kCodes * sub_dim * sizeof(double) + kAssignBlocks * sizeof(double) + kCodes * sizeof(double) +
          (size_t)((n_samples + 255) / 256) * 256;
 }
 
@@ -93,7 +157,7 @@ static int codebook_run_t(const float* samples, int64_t n, int iters, void* code
                           void* workspace, hipStream_t stream) {
   double* centroids = static_cast<double*>(workspace);
   double* block_err = centroids + kCodes * SUB;
-  uint8_t* assign = reinterpret_cast<uint8_t*>(block_err + kAssignBlocks);
+  uint8_t* assign = reinterpret_cast<uint8_t*>(block_err + kAssignBlocks + kCodes);
   const int n_elems = kCodes * SUB;
   km_init_kernel<<<(n_elems + 255) / 256, 256, 0, stream>>>(samples, centroids, n_elems);
   for (int it = 0; it < iters; ++it) {
@@ -113,6 +177,53 @@ static int codebook_run_t(const float* samples, int64_t n, int iters, void* code
     *mse_host = tot / ((double)n * SUB);
   }
   return NSN_OK;
+}
+
+template <int SUB>
+static int finetune_run_t(const float* samples, int64_t n, int iters, double lr, void* codebook_io, double* cos_host,
+                          void* workspace, hipStream_t stream) {
+  double* centroids = static_cast<double*>(workspace);
+  double* block_err = centroids + kCodes * SUB;
+  double* cos_sum = block_err + kAssignBlocks;
+  uint8_t* assign = reinterpret_cast<uint8_t*>(cos_sum + kCodes);
+  const int n_elems = kCodes * SUB;
+  double host_cos[kCodes];
+  auto mean_cos = [&](double* out) -> int {  // assignment + cosine sums of the current centroids (no move: lr = 0)
+    km_assign_kernel<SUB><<<kAssignBlocks, 256, 0, stream>>>(samples, n, centroids, assign, block_err);
+    ft_update_kernel<SUB><<<kCodes, 256, 0, stream>>>(samples, n, assign, centroids, 0.0, cos_sum);
+    if (hipGetLastError() != hipSuccess) return NSN_ERR_HIP;
+    if (hipMemcpyAsync(host_cos, cos_sum, sizeof(host_cos), hipMemcpyDeviceToHost, stream) != hipSuccess)
+      return NSN_ERR_HIP;
+    if (hipStreamSynchronize(stream) != hipSuccess) return NSN_ERR_HIP;
+    double tot = 0.0;
+    for (int k = 0; k < kCodes; ++k) tot += host_cos[k];
+    *out = tot / (double)n;
+    return NSN_OK;
+  };
+  ft_load_kernel<<<(n_elems + 255) / 256, 256, 0, stream>>>(static_cast<const __half*>(codebook_io), centroids, n_elems);
+  int rc = NSN_OK;
+  double before = 0.0, after = 0.0;
+  if (cos_host && (rc = mean_cos(&before)) != NSN_OK) return rc;
+  for (int it = 0; it < iters; ++it) {
+    km_assign_kernel<SUB><<<kAssignBlocks, 256, 0, stream>>>(samples, n, centroids, assign, block_err);
+    ft_update_kernel<SUB><<<kCodes, 256, 0, stream>>>(samples, n, assign, centroids, lr, cos_sum);
+  }
+  km_round_kernel<<<(n_elems + 255) / 256, 256, 0, stream>>>(centroids, static_cast<__half*>(codebook_io), n_elems);
+  if (hipGetLastError() != hipSuccess) return NSN_ERR_HIP;
+  if (cos_host) {
+    if ((rc = mean_cos(&after)) != NSN_OK) return rc;
+    cos_host[0] = before;
+    cos_host[1] = after;
+  } else if (hipStreamSynchronize(stream) != hipSuccess) {
+    return NSN_ERR_HIP;
+  }
+  return NSN_OK;
+}
+
+int finetune_run(const float* samples, int64_t n_samples, int sub_dim, int iters, double lr, void* codebook_io,
+                 double* cos_host, void* workspace, hipStream_t stream) {
+  return sub_dim == 8 ? finetune_run_t<8>(samples, n_samples, iters, lr, codebook_io, cos_host, workspace, stream)
+                      : finetune_run_t<4>(samples, n_samples, iters, lr, codebook_io, cos_host, workspace, stream);
 }
 
 int codebook_run(const float* samples, int64_t n_samples, int sub_dim, int iters, void* codebook_out,

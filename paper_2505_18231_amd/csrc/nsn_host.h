@@ -51,5 +51,7 @@ int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const
 size_t codebook_workspace_bytes(int sub_dim, int64_t n_samples);
 int codebook_run(const float* samples, int64_t n_samples, int sub_dim, int iters, void* codebook_out,
                  double* mse_host, void* workspace, hipStream_t stream);
+int finetune_run(const float* samples, int64_t n_samples, int sub_dim, int iters, double lr, void* codebook_io,
+                 double* cos_host, void* workspace, hipStream_t stream);
 
 }  // namespace nsn

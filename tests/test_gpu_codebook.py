@@ -21,3 +21,26 @@ def test_codebook_matches_oracle(gpu_api, sub, n, iters):
     assert diff.max() <= 1
     assert (diff == 0).mean() > 0.999
     assert abs(mse - ref_mse) < 1e-9 * max(ref_mse, 1.0) + 1e-6 * (diff.max() > 0)
+
+
+@pytest.mark.parametrize("sub,n,iters,lr", [(4, 1 << 14, 6, 128.0), (8, 1 << 13, 4, 256.0)])
+def test_finetune_matches_oracle_and_raises_cosine(gpu_api, sub, n, iters, lr):
+    """nsn_finetune_codebook (Sec. 3.4) against the oracle's gradient steps from the same start."""
+    import torch
+    print(f"case sub={sub} n={n} iters={iters} lr={lr}", flush=True)
+    samples = synth.codebook_samples(56, n, sub)
+    start, _, _ = O.build_codebook(samples, 256, 3)
+    ref, hist, ref_final = O.finetune_codebook(samples, start, iters, lr)
+    cbd = torch.from_numpy(start.astype(np.float16)).cuda()
+    cb, cos0, cos1 = gpu_api.nsn_finetune_codebook(torch.from_numpy(samples).cuda(), cbd, iters, lr)
+    got = cb.cpu().numpy()
+    diff = np.abs(got.view(np.int16).astype(np.int32) - ref.astype(np.float16).view(np.int16).astype(np.int32))
+    print(f"  cosine {cos0:.6f} -> {cos1:.6f} (oracle {hist[0]:.6f} -> {ref_final:.6f}), "
+          f"{(diff != 0).sum()} of {diff.size} fp16 entries differ, max {diff.max()} ulp", flush=True)
+    assert diff.max() <= 1 and (diff == 0).mean() > 0.995
+    assert abs(cos0 - hist[0]) < 1e-12
+    assert abs(cos1 - ref_final) < 1e-9 + 1e-5 * (diff.max() > 0)
+    assert cos1 > cos0 + 1e-4
+    # zero steps: the codebook is returned unchanged
+    same, c0, c1 = gpu_api.nsn_finetune_codebook(torch.from_numpy(samples).cuda(), cbd.clone(), 0, lr)
+    assert torch.equal(same, cbd) and c0 == c1

@@ -26,8 +26,8 @@ def test_exports_every_declared_symbol(L):
     header = open(os.path.join(ROOT, "include", "nsn.h")).read()
     names = set(re.findall(r"\b(nsn_[a-z_]+)\s*\(", header))
     names -= {"nsn_shape", "nsn_cache"}
-    assert {"nsn_build_codebook", "nsn_encode", "nsn_decode_attention", "nsn_decode_attention_residual",
-            "nsn_workspace_bytes"} <= names
+    assert {"nsn_build_codebook", "nsn_finetune_codebook", "nsn_encode", "nsn_decode_attention",
+            "nsn_decode_attention_residual", "nsn_workspace_bytes"} <= names
     for n in names:
         assert hasattr(L, n), n
 
