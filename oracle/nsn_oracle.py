@@ -28,6 +28,11 @@ Parity pins (tests/test_oracle_*.py, all CPU):
   decode_attention_residual   no residual = coded-only attention; no coded tokens = plain
                       softmax attention written with loops; both = merge of the two by
                       their softmax masses (Sec. 3.2 "Residual")
+  sign + index format the (signs, nearest magnitude codeword) pair equals the exhaustive Eq. 1
+                      search over all 256 x 2^8 signed codewords on small inputs; 16 bits per
+                      8 dims; round trip keeps the scale-adjustment orthogonality.  How the
+                      paper builds its magnitude codebook is not described: K-Means on |N(0,1)|
+                      samples is this build's reading ("parity unpinned" for the codebook)
   finetune_codebook   gradient equals central finite differences of the cosine loss at a
                       fixed assignment and is orthogonal to its codeword; the cosine
                       similarity rises.  Optimiser, rate and step count are this build's
@@ -174,9 +179,27 @@ def shift_stats(x16: np.ndarray, group_size: int = 0, start: int = 0, given_b=No
     return b16, o16
 
 
+# The paper's own 2-bit format (Sec. 3.4): an 8-dim sub-vector is stored as 8 sign bits plus the
+# 8-bit index of a codeword with non-negative entries (a codebook of magnitudes); the implied
+# codebook holds the 256 x 2^8 signed versions, and because the magnitudes are non-negative the
+# nearest of those (Eq. 1) takes the signs of the sub-vector itself and the magnitude codeword
+# nearest to its absolute values.  Bit i of the sign byte is set when entry i is negative.
+def sign_bytes(y_sub: np.ndarray) -> np.ndarray:
+    """y_sub [n][8] -> uint8 [n]"""
+    neg = (np.asarray(y_sub) < 0).astype(np.uint8)
+    return (neg << np.arange(8, dtype=np.uint8)).sum(axis=1).astype(np.uint8)
+
+
+def signed_codewords(idx: np.ndarray, sgn: np.ndarray, codebook: np.ndarray) -> np.ndarray:
+    """C[idx] with the sign bits applied: [n][8]"""
+    c = np.asarray(codebook, dtype=F64)
+    neg = (sgn.astype(np.int64)[:, None] >> np.arange(8)) & 1
+    return np.where(neg == 1, -c[idx.astype(np.int64)], c[idx.astype(np.int64)])
+
+
 def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: int = 0,
            frozen_o: np.ndarray | None = None, given_b: np.ndarray | None = None,
-           given_o: np.ndarray | None = None, return_debug: bool = False):
+           given_o: np.ndarray | None = None, return_debug: bool = False, sign_format: bool = False):
     """Encode tokens [start, start+l) of one (sequence, kv-head, tensor) unit.
 
     x16       fp16 [l][d]
@@ -185,6 +208,8 @@ def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: in
               computing new ones (a new token never forms a one-token group)
     given_b / given_o: override the stage-A results (two-stage parity protocol: the
               second stage is checked conditioned on the first stage's stored values)
+    sign_format: codebook = 256 non-negative 8-dim magnitude codewords; codes are then
+              u8 [l][2 d/8]: the d/8 indices followed by the d/8 sign bytes
     returns dict(codes u8 [l][d/sub], a fp16 [l], b fp16 [l], o fp16 [n_groups][d])
     """
     x = np.asarray(x16, dtype=F64)
@@ -209,26 +234,41 @@ def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: in
 
     # Hadamard rotation (dense mat-vec), then Eq. (1) on contiguous sub-vectors
     y = vnsn @ H.T
-    codes, best, second = nearest_codeword(y.reshape(-1, sub), c)
-    yq = c[codes].reshape(l, d)
+    if sign_format:
+        assert sub == 8 and np.all(c >= 0)
+        ys = y.reshape(-1, sub)
+        idx, best, second = nearest_codeword(np.abs(ys), c)
+        sgn = sign_bytes(ys)
+        yq = signed_codewords(idx, sgn, c).reshape(l, d)
+        codes = np.concatenate([idx.reshape(l, d // sub), sgn.reshape(l, d // sub)], axis=1)
+    else:
+        codes, best, second = nearest_codeword(y.reshape(-1, sub), c)
+        yq = c[codes].reshape(l, d)
+        codes = codes.reshape(l, d // sub)
 
     # scale adjustment folded into the stored scale: a = s1 s2 alpha
     alpha = scale_adjust(y, yq)
     a16 = fp16_rne(b * s2 * alpha)
 
-    out = dict(codes=codes.reshape(l, d // sub).astype(np.uint8), a=a16, b=b16, o=o16)
+    out = dict(codes=codes.astype(np.uint8), a=a16, b=b16, o=o16)
     if return_debug:
         out.update(y=y, s2=s2, alpha=alpha, best=best.reshape(l, -1), second=second.reshape(l, -1))
     return out
 
 
-def dequantize(codes, a16, b16, o16, codebook, group_size: int = 0, start: int = 0) -> np.ndarray:
+def dequantize(codes, a16, b16, o16, codebook, group_size: int = 0, start: int = 0,
+               sign_format: bool = False) -> np.ndarray:
     """x_hat_t = b_t o_g + a_t H^T y_Q,t  (restore identity of Sec. 3.2 with s2 alpha in a)."""
     c = np.asarray(codebook, dtype=F64)
     l, J = codes.shape
-    d = J * c.shape[1]
+    if sign_format:
+        J //= 2
+        d = J * c.shape[1]
+        yq = signed_codewords(codes[:, :J].reshape(-1), codes[:, J:].reshape(-1), c).reshape(l, d)
+    else:
+        d = J * c.shape[1]
+        yq = c[codes.astype(np.int64)].reshape(l, d)
     H = hadamard(d)
-    yq = c[codes.astype(np.int64)].reshape(l, d)
     g = group_index(l, group_size, start)
     a = np.asarray(a16, dtype=F64)
     b = np.asarray(b16, dtype=F64)
@@ -240,11 +280,11 @@ def dequantize(codes, a16, b16, o16, codebook, group_size: int = 0, start: int =
 # Decode attention over a coded cache (App. B, with RoPE dropped: keys are taken as given)
 # ----------------------------------------------------------------------------
 def decode_attention(q, kc: dict, vc: dict, codebook, softmax_scale: float,
-                     group_size: int = 0) -> np.ndarray:
+                     group_size: int = 0, sign_format: bool = False) -> np.ndarray:
     """out = softmax(scale * q K_hat^T) V_hat for q [r][d] (r query heads on one kv head)."""
     q = np.atleast_2d(np.asarray(q, dtype=F64))
-    k_hat = dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], codebook, group_size)
-    v_hat = dequantize(vc["codes"], vc["a"], vc["b"], vc["o"], codebook, group_size)
+    k_hat = dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], codebook, group_size, sign_format=sign_format)
+    v_hat = dequantize(vc["codes"], vc["a"], vc["b"], vc["o"], codebook, group_size, sign_format=sign_format)
     s = softmax_scale * (q @ k_hat.T)
     s = s - s.max(axis=1, keepdims=True)
     p = np.exp(s)
@@ -371,14 +411,14 @@ def avg_bits(code_bits_per_dim: float, head_dim: int, group_size: int) -> float:
 # tokens are still fp16 and take part in the same softmax as the coded tokens
 # ----------------------------------------------------------------------------
 def decode_attention_residual(q, kc: dict, vc: dict, k_res16, v_res16, codebook, softmax_scale: float,
-                              group_size: int = 0) -> np.ndarray:
+                              group_size: int = 0, sign_format: bool = False) -> np.ndarray:
     """out = softmax(scale * q [K_hat ; K_res]^T) [V_hat ; V_res]; the coded part may be empty."""
     q = np.atleast_2d(np.asarray(q, dtype=F64))
     k_res = np.asarray(k_res16, dtype=F64).reshape(-1, q.shape[1])
     v_res = np.asarray(v_res16, dtype=F64).reshape(-1, q.shape[1])
     if kc["codes"].shape[0] > 0:
-        k_hat = dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], codebook, group_size)
-        v_hat = dequantize(vc["codes"], vc["a"], vc["b"], vc["o"], codebook, group_size)
+        k_hat = dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], codebook, group_size, sign_format=sign_format)
+        v_hat = dequantize(vc["codes"], vc["a"], vc["b"], vc["o"], codebook, group_size, sign_format=sign_format)
         k_all = np.concatenate([k_hat, k_res], axis=0)
         v_all = np.concatenate([v_hat, v_res], axis=0)
     else:

@@ -360,3 +360,61 @@ def test_finetune_raises_the_cosine_similarity():
     # zero steps only round
     same, h0, f0 = O.finetune_codebook(x, cb, 0, 64.0)
     assert np.array_equal(same, cb) and h0.size == 0 and abs(f0 - hist[0]) < 1e-15
+
+
+# ---------------------------------------------------------------- the paper's 2-bit format: 8 sign bits + 8-bit index
+def _magnitude_codebook(seed, n=4096, iters=4):
+    x = np.abs(synth.codebook_samples(seed, n, 8).astype(np.float64))
+    cb, _, _ = O.build_codebook(x, 256, iters)
+    assert np.all(cb >= 0)
+    return cb
+
+
+def test_sign_index_pair_equals_exhaustive_search_over_signed_codewords():
+    cb = _magnitude_codebook(5)
+    rng = np.random.default_rng(9)
+    y = rng.standard_normal((6, 8))
+    idx, _, _ = O.nearest_codeword(np.abs(y), cb)
+    sgn = O.sign_bytes(y)
+    picked = O.signed_codewords(idx, sgn, cb)
+    # brute force: all 256 x 256 signed codewords, python-level loops over the sign patterns
+    for t in range(y.shape[0]):
+        best, best_vec = np.inf, None
+        for pattern in range(256):
+            flip = np.array([-1.0 if (pattern >> i) & 1 else 1.0 for i in range(8)])
+            d = ((y[t][None, :] - cb * flip[None, :]) ** 2).sum(axis=1)
+            k = int(np.argmin(d))
+            if d[k] < best:
+                best, best_vec = d[k], cb[k] * flip
+        assert np.allclose(((y[t] - picked[t]) ** 2).sum(), best, rtol=1e-12)
+        assert np.allclose(picked[t], best_vec)
+    # sign byte convention: bit i set <=> entry i negative
+    assert O.sign_bytes(np.array([[-1, 2, -3, 4, 5, 6, 7, -8.0]]))[0] == 0b10000101
+
+
+def test_sign_format_round_trip_and_bit_count():
+    cb = _magnitude_codebook(6)
+    x16 = synth.make_k(31, 0, 0, 130)
+    enc = O.encode(x16, cb, 64, return_debug=True, sign_format=True)
+    assert enc["codes"].shape == (130, 32) and enc["codes"].dtype == np.uint8
+    assert enc["codes"].shape[1] * 8 / 128 == 2.0     # 16 bits per 8 dims
+    J = 16
+    yq = O.signed_codewords(enc["codes"][:, :J].reshape(-1), enc["codes"][:, J:].reshape(-1), cb).reshape(130, 128)
+    # signs of the rotated token are kept, the adjusted quantised token errs orthogonally to it (Sec. 3.3)
+    assert np.all((yq < 0) <= (enc["y"] < 0)) and np.all((enc["y"] < 0) <= ((yq < 0) | (yq == 0)))
+    err = enc["alpha"][:, None] * yq - enc["y"]
+    assert np.abs(np.sum(err * enc["y"], axis=1)).max() < 1e-9
+    xh = O.dequantize(enc["codes"], enc["a"], enc["b"], enc["o"], cb, 64, sign_format=True)
+    rel = np.linalg.norm(xh - x16.astype(np.float64)) / np.linalg.norm(x16.astype(np.float64))
+    xh1 = O.dequantize(*(lambda e: (e["codes"], e["a"], e["b"], e["o"]))(O.encode(x16, cb, 64)), cb, 64)
+    rel1 = np.linalg.norm(xh1 - x16.astype(np.float64)) / np.linalg.norm(x16.astype(np.float64))
+    assert rel < rel1        # two bits with signs beat one bit with the same (unsigned) table
+    # attention through the sign format equals dequantise-then-attend
+    q = synth.make_q(31, 1, 2)[0].astype(np.float64)
+    vc = O.encode(synth.make_v(31, 0, 0, 130), cb, 64, sign_format=True)
+    out = O.decode_attention(q, enc, vc, cb, 0.1, 64, sign_format=True)
+    kh = O.dequantize(enc["codes"], enc["a"], enc["b"], enc["o"], cb, 64, sign_format=True)
+    vh = O.dequantize(vc["codes"], vc["a"], vc["b"], vc["o"], cb, 64, sign_format=True)
+    s = 0.1 * q @ kh.T
+    p = np.exp(s - s.max(axis=1, keepdims=True))
+    assert np.allclose(out, (p / p.sum(axis=1, keepdims=True)) @ vh, rtol=1e-12, atol=1e-14)
