@@ -92,9 +92,19 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
+SIGN_CODES = 65536  # n_codes of the sign + index format: 256 magnitude codewords x 2^8 sign patterns
+
+
 def make_shape(sub_dim: int, n_q_heads: int, n_kv_heads: int, max_len: int, group_size: int = 0,
-               page_size: int = 0) -> nsn_shape:
-    return nsn_shape(HEAD_DIM, sub_dim, N_CODES, n_q_heads, n_kv_heads, group_size, page_size, max_len)
+               page_size: int = 0, sign_format: bool = False) -> nsn_shape:
+    """sign_format: the paper's 2-bit format (8 sign bits + 8-bit index per 8-dim sub-vector)."""
+    assert not sign_format or sub_dim == 8
+    return nsn_shape(HEAD_DIM, sub_dim, SIGN_CODES if sign_format else N_CODES, n_q_heads, n_kv_heads, group_size,
+                     page_size, max_len)
+
+
+def code_bytes_per_token(shape: nsn_shape) -> int:
+    return (2 if shape.n_codes == SIGN_CODES else 1) * (HEAD_DIM // shape.sub_dim)
 
 
 def nsn_max_groups(shape: nsn_shape) -> int:
@@ -121,7 +131,7 @@ class CodedCache:
 def alloc_cache(shape: nsn_shape, batch: int, device="cuda", block_table: torch.Tensor | None = None,
                 n_pages: int | None = None) -> CodedCache:
     """Zero-initialised cache buffers.  Paged layout: n_pages physical pages (default: enough for all)."""
-    J = HEAD_DIM // shape.sub_dim
+    J = code_bytes_per_token(shape)
     hkv = shape.n_kv_heads
     ng = nsn_max_groups(shape)
     if shape.page_size > 0:

@@ -20,9 +20,11 @@ static int check_shape(const nsn_shape* s) {
     set_error("shape is NULL");
     return NSN_ERR_INVALID_ARG;
   }
-  if (s->head_dim != kHeadDim || s->n_codes != kCodes || (s->sub_dim != 4 && s->sub_dim != 8)) {
-    set_error("unsupported shape: head_dim=%d (128), n_codes=%d (256), sub_dim=%d (4 or 8)", s->head_dim,
-              s->n_codes, s->sub_dim);
+  const bool plain = s->n_codes == kCodes && (s->sub_dim == 4 || s->sub_dim == 8);
+  const bool sign = s->n_codes == kSignCodes && s->sub_dim == 8;
+  if (s->head_dim != kHeadDim || !(plain || sign)) {
+    set_error("unsupported shape: head_dim=%d (128), n_codes=%d (256, or 65536 = sign + index with sub_dim 8), "
+              "sub_dim=%d (4 or 8)", s->head_dim, s->n_codes, s->sub_dim);
     return NSN_ERR_UNSUPPORTED;
   }
   if (s->n_kv_heads <= 0 || s->n_q_heads <= 0 || s->n_q_heads % s->n_kv_heads != 0) {

@@ -31,7 +31,10 @@ struct ResidualView {
   int capacity;         // <= 64
 };
 
+constexpr int kSignCodes = 65536;  // n_codes value that selects the sign + index format
+
 struct Geometry {
+  int sign;         // 1: an 8-dim sub-vector is an index byte plus a sign byte (byte rows 0..15 / 16..31)
   int J;            // code bytes per token
   int n_q_heads, n_kv_heads;
   int group_size;   // 0 = one group

@@ -135,7 +135,9 @@ extern "C" int nsn_debug_encode_timing(long long* host16) {
 // The register budget is pinned to the main path's needs (4 waves per SIMD at sub-vector length 4,
 // 3 at length 8): without it the rarely taken re-listing path is scheduled for maximum
 // instruction-level parallelism and doubles the register count of the whole kernel.
-template <int SUB, bool MFMA, bool FUSED>
+// SIGN:  the paper's 2-bit format (Sec. 3.4): the search runs on the absolute values against a
+//        codebook of magnitudes; byte row jj holds the index, byte row 16 + jj the eight sign bits
+template <int SUB, bool MFMA, bool FUSED, bool SIGN = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 4 : 3))) void enc_quant_kernel(Geometry g, const __half* __restrict__ codebook,
                                                         const __half* __restrict__ k_in,
                                                         const __half* __restrict__ v_in, int max_new,
@@ -144,6 +146,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
                                                         CacheView vc) {
   constexpr int J = kHeadDim / SUB;  // lanes per token
   constexpr int TPW = 64 / J;        // tokens per wave step
+  constexpr int JB = SIGN ? 2 * J : J;  // code bytes per token
+  static_assert(!SIGN || SUB == 8, "the sign + index format is defined on 8-dim sub-vectors");
   __shared__ VqTables<SUB> T;
   const int h = blockIdx.y >> 1, tensor = blockIdx.y & 1, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -261,26 +265,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
     for (int i = 0; i < SUB; ++i) y[i] = v[i] * kInvSqrtD;
 
     NSN_ETSTAMP(4);
+    // sign + index format: the nearest signed codeword has the signs of y and the magnitude
+    // codeword nearest to |y| (the magnitudes are non-negative), and y . y_Q = |y| . C[code]
+    double ys[SUB];
+    uint32_t sign_byte = 0u;
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) {
+      ys[i] = SIGN ? fabs(y[i]) : y[i];
+      if (SIGN && y[i] < 0.0) sign_byte |= 1u << i;
+    }
     int code;
     if constexpr (MFMA)
-      code = vq_search_mfma<SUB>(T, MC, y, lane);
+      code = vq_search_mfma<SUB>(T, MC, ys, lane);
     else
-      code = vq_search<SUB>(T, y);
+      code = vq_search<SUB>(T, ys);
 
     NSN_ETSTAMP(5);
     // scale adjustment: alpha = ||y||^2 / (y . y_Q)
     double dot = 0.0, nrm2 = 0.0;
 #pragma unroll
     for (int i = 0; i < SUB; ++i) {
-      dot += y[i] * T.cx[code][i];
+      dot += ys[i] * T.cx[code][i];
       nrm2 += y[i] * y[i];
     }
     dot = xor_sum_w<J>(dot);
     nrm2 = xor_sum_w<J>(nrm2);
     const double alpha = (dot > 1e-12 * kHeadDim) ? nrm2 / dot : 1.0;
     if (valid) {
-      const int64_t off = tensor ? v_code_offset(J, tin, jj) : k_code_offset(J, tin, jj);
-      cv.codes[base * J + off] = (uint8_t)code;
+      const int64_t off = tensor ? v_code_offset(JB, tin, jj) : k_code_offset(JB, tin, jj);
+      cv.codes[base * JB + off] = (uint8_t)code;
+      if constexpr (SIGN) {
+        const int64_t soff = tensor ? v_code_offset(JB, tin, J + jj) : k_code_offset(JB, tin, J + jj);
+        cv.codes[base * JB + soff] = (uint8_t)sign_byte;
+      }
       if (jj == 0) reinterpret_cast<__half*>(cv.norms)[2 * (base + tin)] = f64_to_f16(bb * s2 * alpha);
     }
     NSN_ETSTAMP(6);
@@ -322,7 +339,12 @@ int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, co
     kernel<<<grid_b, 256, 0, stream>>>(g, (const __half*)codebook, (const __half*)k_in, (const __half*)v_in, max_new,
                                        s.max_len, seq_start, n_new, kv, vv);
   };
-  if (s.sub_dim == 8) {
+  if (g.sign) {
+    if (use_mfma)
+      freeze_means ? launch(enc_quant_kernel<8, true, true, true>) : launch(enc_quant_kernel<8, true, false, true>);
+    else
+      freeze_means ? launch(enc_quant_kernel<8, false, true, true>) : launch(enc_quant_kernel<8, false, false, true>);
+  } else if (s.sub_dim == 8) {
     if (use_mfma)
       freeze_means ? launch(enc_quant_kernel<8, true, true>) : launch(enc_quant_kernel<8, true, false>);
     else

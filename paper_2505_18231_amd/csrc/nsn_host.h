@@ -7,7 +7,8 @@ namespace nsn {
 
 inline Geometry make_geometry(const nsn_shape& s) {
   Geometry g;
-  g.J = s.head_dim / s.sub_dim;
+  g.sign = s.n_codes == kSignCodes;
+  g.J = g.sign ? 2 * (s.head_dim / s.sub_dim) : s.head_dim / s.sub_dim;
   g.n_q_heads = s.n_q_heads;
   g.n_kv_heads = s.n_kv_heads;
   g.group_size = s.group_size;

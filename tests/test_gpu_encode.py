@@ -17,9 +17,9 @@ pytestmark = pytest.mark.gpu
 
 
 def run_gpu_encode(api, seed, batch, hkv, lens, sub, G, cb, page=0, per_seq=False, starts=None,
-                   freeze=False, caches=None, max_len=None):
+                   freeze=False, caches=None, max_len=None, sign=False):
     import torch
-    J = 128 // sub
+    J = 2 * (128 // sub) if sign else 128 // sub
     max_new = max(lens)
     starts = starts or [0] * batch
     max_len = max_len or ((max(s + l for s, l in zip(starts, lens)) + 255) // 256) * 256
@@ -29,7 +29,7 @@ def run_gpu_encode(api, seed, batch, hkv, lens, sub, G, cb, page=0, per_seq=Fals
         for h in range(hkv):
             k[b, h, :lens[b]] = synth.make_k(seed, b, h, lens[b], per_seq=per_seq, start=starts[b])
             v[b, h, :lens[b]] = synth.make_v(seed, b, h, lens[b], start=starts[b])
-    shape = api.make_shape(sub, hkv, hkv, max_len, G, page)
+    shape = api.make_shape(sub, hkv, hkv, max_len, G, page, sign_format=sign)
     if caches is None:
         bt = synth.shuffled_page_table(seed, batch, max_len // page) if page else None
         hk = helpers.HostCache("k", batch, hkv, J, max_len, G, page, bt)
@@ -47,7 +47,7 @@ def run_gpu_encode(api, seed, batch, hkv, lens, sub, G, cb, page=0, per_seq=Fals
     return k, v, hk, hv
 
 
-def check_unit(x16, got, cb, G, start=0, frozen=None):
+def check_unit(x16, got, cb, G, start=0, frozen=None, sign=False):
     """got: dict(codes, a, b, o) read back from the device for tokens [start, start+L)."""
     L = x16.shape[0]
     b_ref, o_ref = O.shift_stats(x16, G, start, given_o=frozen)
@@ -55,9 +55,14 @@ def check_unit(x16, got, cb, G, start=0, frozen=None):
     if frozen is None:
         g_used = np.unique(O.group_index(L, G, start))
         assert np.array_equal(o_ref[g_used].view(np.uint16), got["o"][g_used].view(np.uint16)), "means"
-    ref = O.encode(x16, cb, G, start=start, given_b=got["b"], given_o=got["o"], return_debug=True)
+    ref = O.encode(x16, cb, G, start=start, given_b=got["b"], given_o=got["o"], return_debug=True,
+                   sign_format=sign)
     same = ref["codes"] == got["codes"]
     near_tie = (ref["second"] - ref["best"]) < 1e-6 * np.maximum(ref["second"], 1e-300)
+    if sign:  # [indices | sign bytes]: a sign byte has no tie, unless an entry of the rotated token is exactly 0
+        J = ref["codes"].shape[1] // 2
+        assert np.all(same[:, J:] | (ref["y"].reshape(L, J, 8) == 0).any(axis=2)), "sign bytes"
+        same = same[:, :J]
     assert np.all(same | near_tie), f"{(~(same | near_tie)).sum()} code mismatches outside the tie window"
     rows_ok = same.all(axis=1)
     a_ref = ref["a"].view(np.int16).astype(np.int32)
@@ -160,3 +165,34 @@ def test_duplicate_codewords_take_the_lowest_index(gpu_api, codebooks, monkeypat
         hits += int(np.isin(got["codes"], [5, 10, 128]).sum())
     print(f"  sub={sub} impl={impl}: {hits} sub-vectors chose a duplicated codeword", flush=True)
     assert hits > 50
+
+
+@pytest.fixture(scope="module")
+def magnitude_codebook():
+    x = np.abs(synth.codebook_samples(4242, 1 << 13, 8).astype(np.float64))
+    cb, _, _ = O.build_codebook(x, 256, 5)
+    return cb
+
+
+SIGN_CASES = [
+    ("sign-groups-ragged", 2, 2, [300, 77], 64, 0),
+    ("sign-onegroup", 1, 2, [515], 0, 0),
+    ("sign-paged", 2, 1, [700, 300], 128, 256),
+]
+
+
+@pytest.mark.parametrize("impl", ["mfma", "valu"])
+@pytest.mark.parametrize("name,batch,hkv,lens,G,page", SIGN_CASES, ids=[c[0] for c in SIGN_CASES])
+def test_sign_format_encode_matches_oracle(gpu_api, magnitude_codebook, monkeypatch, impl, name, batch, hkv, lens,
+                                           G, page):
+    """The paper's 2-bit format: 8 sign bits + 8-bit index of a magnitude codeword per 8-dim sub-vector."""
+    monkeypatch.setenv("NSN_ENCODE_IMPL", impl)
+    print(f"case {name} impl={impl} lens={lens} G={G} page={page}", flush=True)
+    cb = magnitude_codebook
+    k, v, hk, hv = run_gpu_encode(gpu_api, 500 + len(name), batch, hkv, lens, 8, G, cb, page, sign=True)
+    flips = 0
+    for b in range(batch):
+        for h in range(hkv):
+            flips += check_unit(k[b, h, :lens[b]], hk.unit_dict(b, h, lens[b]), cb, G, sign=True)
+            flips += check_unit(v[b, h, :lens[b]], hv.unit_dict(b, h, lens[b]), cb, G, sign=True)
+    print(f"  near-tie code differences: {flips}", flush=True)
