@@ -53,6 +53,9 @@ def parse():
                         "joins a 64-token fp16 residual that takes part in the attention and is encoded when "
                         "full (one 64-token encode per sequence every 64 steps, inside the timed region); "
                         "'append' = every step encodes its one new token before the attention")
+    p.add_argument("--sign-format", action="store_true",
+                   help="with --random-cache: the paper's own 2-bit format (8 sign bits + 8-bit magnitude index per "
+                        "8-dim sub-vector) instead of the workload's code format")
     p.add_argument("--group-size", type=int, default=0,
                    help="with --random-cache: Shift group size (0 = one group per sequence as in the workload "
                         "definitions, 64 = the paper's residual-size groups)")
@@ -85,10 +88,12 @@ def random_cache_decode(args, cfg) -> int:
     else:
         lens = (synth.ragged_lengths(seed, B, cfg["len_lo"], cfg["len_hi"]) + cfg["append_steps"]).tolist()
         sub = 4 if args.bits in (0, 2) else 8
-    J = 128 // sub
+    if args.sign_format:
+        sub = 8
+    J = 32 if args.sign_format else 128 // sub
     max_len = ((max(lens) + 255) // 256) * 256
     G = args.group_size
-    shape = api.make_shape(sub, Hq, Hkv, max_len, G, page)
+    shape = api.make_shape(sub, Hq, Hkv, max_len, G, page, sign_format=args.sign_format)
     bt = torch.from_numpy(synth.shuffled_page_table(seed, B, max_len // page)).to(dev) if page else None
     g = torch.Generator(device=dev).manual_seed(seed)
     caches = []
@@ -100,6 +105,8 @@ def random_cache_decode(args, cfg) -> int:
         caches.append(c)
     kc, vc = caches
     codebook = (torch.randn((256, sub), device=dev, generator=g)).half()
+    if args.sign_format:
+        codebook = codebook.abs()
     q = torch.from_numpy(synth.make_q(seed, B, Hq)).to(dev)
     lens_d = torch.tensor(lens, dtype=torch.int32, device=dev)
     n_groups = sum((n + G - 1) // G for n in lens) if G else B
@@ -134,7 +141,8 @@ def random_cache_decode(args, cfg) -> int:
         "ms_per_step": round(us * 1e-3, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic (random cache contents, timing only)",
         "config": {"workload": f"{args.workload}:{cfg['name']}", "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
-                   "cached_tokens": sum(lens), "sub_dim": sub, "page_size": page, "group_size": G,
+                   "cached_tokens": sum(lens), "sub_dim": sub, "sign_format": bool(args.sign_format),
+                   "page_size": page, "group_size": G,
                    "cache_copies_in_rotation": n_copies, "step": "decode attention only"},
         "decode_us_per_step": round(us, 3), "bytes_per_step": step_bytes,
         "roofline": {"bound": "hbm", "kernel": "nsn::dec_mfma_kernel (one launch per decode step)",

@@ -238,6 +238,7 @@ __global__ __launch_bounds__(128) void dec_merge_kernel(int n_q_heads, int n_spl
 
 // ---------------------------------------------------------------------------------------
 bool decode_use_mfma(const nsn_shape& s) {
+  if (s.n_codes == kSignCodes) return true;   // the sign + index format exists in the matrix-core kernel only
   const char* e = getenv("NSN_DECODE_IMPL");  // "lut" forces the lookup-table kernel
   if (e && e[0] == 'l') return false;
   return s.n_q_heads / s.n_kv_heads <= 4;

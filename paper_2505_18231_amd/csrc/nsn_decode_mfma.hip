@@ -166,44 +166,54 @@ __device__ long long g_dec_timing[48];
 //                      (slot NW belongs to the residual wave, present only in residual launches)
 //   tail               per-wave (m, l), the "last workgroup" flag, inverse-Hadamard scratch
 // One workgroup of 8 waves per compute unit shares a single table (64 + 16 KiB of the 160 KiB).
-template <int SUB, int NW>
+template <int SUB, int NW, bool SGN = false>
 struct DecSmem {
+  // sign + index format: a 4 KiB table of sign masks sits in front of the codebook table
+  static constexpr int kSignLutBytes = SGN ? 4096 : 0;
+  static constexpr int kTable = kTableBytes + kSignLutBytes;
   static constexpr int kUnionBytes = (NW + 1) * 4 * kHeadDim * 4;  // + the residual wave's slot
   static constexpr int kRaccBytes = NW * (64 / (kHeadDim / SUB)) * 4 * kHeadDim * 4;
   static constexpr int kTailBytes = (2 * (NW + 1) * 4 + 4 + 4 * kHeadDim) * 4;
-  static constexpr bool kTailInTable = kRaccBytes + kTailBytes <= kTableBytes;
-  static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kTableBytes + kUnionBytes;
-  static constexpr int kBytes = kTableBytes + kUnionBytes + (kTailInTable ? 0 : kTailBytes);
+  static constexpr bool kTailInTable = kRaccBytes + kTailBytes <= kTable;
+  static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kTable + kUnionBytes;
+  static constexpr int kBytes = kTable + kUnionBytes + (kTailInTable ? 0 : kTailBytes);
   static_assert(kUnionBytes >= kCodes * 2 * SUB + 2 * 4 * kHeadDim * 4 + 16, "prologue scratch must fit");
-  static_assert(kRaccBytes <= kTableBytes, "per-wave accumulators must fit in the table region");
+  static_assert(kRaccBytes <= kTable, "per-wave accumulators must fit in the table region");
 };
 
 // R = query heads per kv head handled by the kernel instance (1, 2 or 4; three heads run as 4).
 // With R <= 2 the fp16 hi and lo parts of the rotated query share the four MFMA rows
 // (rows [0,R) = hi, rows [R,2R) = lo), so one MFMA per slot suffices.
-template <int SUB, int NW, int R>
+// SGN = the sign + index format (Sec. 3.4): SUB = 8, code bytes [0,16) of a token are indices into a
+// codebook of magnitudes, bytes [16,32) the sign bytes; a gathered codeword gets its sign bits from
+// two 8-byte mask entries (one per sign nibble) of a small replicated table, XORed in before the MFMA.
+template <int SUB, int NW, int R, bool SGN = false>
 __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, const __half* __restrict__ codebook,
                                                            const __half* __restrict__ q, CacheView kc,
                                                            CacheView vc, const int32_t* __restrict__ seq_lens,
                                                            float scale_log2e, int n_splits, int per,
                                                            float* partial, int* counters,
                                                            ResidualView res, float* __restrict__ out) {
-  constexpr int J = kHeadDim / SUB;  // code bytes per token
-  constexpr int KW = J / 4;          // code dwords per lane (K: one token; V: one sub-vector of J tokens)
-  constexpr int LV = J;              // lanes per value-side token part (one lane per sub-vector)
-  constexpr int NPART = 64 / LV;     // value-side token parts of a 64-token group
+  static_assert(!SGN || SUB == 8, "the sign + index format is defined on 8-dim sub-vectors");
+  constexpr int NSV = kHeadDim / SUB;         // sub-vectors per token
+  constexpr int J = SGN ? 2 * NSV : NSV;      // code bytes per token
+  constexpr int IW = NSV / 4;                 // index dwords per lane (K: one token; V: one sub-vector of NSV tokens)
+  constexpr int KW = SGN ? 2 * IW : IW;       // code dwords per lane (indices, then sign bytes)
+  constexpr int LV = NSV;                     // lanes per value-side token part (one lane per sub-vector)
+  constexpr int NPART = 64 / LV;              // value-side token parts of a 64-token group
+  constexpr uint32_t TB = SGN ? 4096u : 0u;   // LDS address of the codebook table
   constexpr int CBSZ_V = (SUB == 4) ? 3 : 2;
   constexpr int NT = NW * 64;
   constexpr bool PACK = (R <= 2);  // hi and lo rows in one A operand
-  constexpr int CH = 8;  // key-side gathers in flight per chunk
-  using SM = DecSmem<SUB, NW>;
+  constexpr int CH = SGN ? 4 : 8;  // key-side gathers in flight per chunk
+  using SM = DecSmem<SUB, NW, SGN>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   unsigned char* const sm_table = smem_raw;
-  unsigned char* const sm_stage = smem_raw + kTableBytes;                          // prologue only
+  unsigned char* const sm_stage = smem_raw + SM::kTable;                           // prologue only
   float(*const sm_q_orig)[kHeadDim] = reinterpret_cast<float(*)[kHeadDim]>(sm_stage + kCodes * 2 * SUB);
   float(*const sm_q_had)[kHeadDim] = sm_q_orig + 4;
   float* const sm_qo_first = &sm_q_had[4][0];  // q . o^k of the split's first Shift group, four heads
-  float(*const sm_accm)[4][kHeadDim] = reinterpret_cast<float(*)[4][kHeadDim]>(smem_raw + kTableBytes);
+  float(*const sm_accm)[4][kHeadDim] = reinterpret_cast<float(*)[4][kHeadDim]>(smem_raw + SM::kTable);
   float(*const sm_wave_m)[4] = reinterpret_cast<float(*)[4]>(smem_raw + SM::kTailOffset);  // after the loop
   float(*const sm_wave_l)[4] = sm_wave_m + (NW + 1);
   int* const sm_is_last = reinterpret_cast<int*>(sm_wave_l + (NW + 1));
@@ -230,7 +240,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   };
   // per-lane byte offsets (32-bit) that are added to wave-uniform 64-bit bases
   const uint32_t k_lane_off = lane * J;
-  const uint32_t v_lane_off = (lane / LV) * (J * J) + (lane % LV) * J;
+  // value side: plain formats keep a sub-vector's NSV tokens contiguous (blocks of NSV tokens); the sign
+  // format has blocks of 32 tokens with 32 byte rows: 16 tokens of index row j, their signs 16 rows on
+  const uint32_t v_lane_off = SGN ? ((lane / LV) >> 1) * (J * J) + (lane % LV) * J + ((lane / LV) & 1) * 16
+                                  : (lane / LV) * (J * J) + (lane % LV) * J;
   const uint32_t lane_x4 = lane * 4;
   auto load_group = [&](int gi, Grp& G) {
     const int tg = t0 + (gi << 6);
@@ -241,7 +254,8 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     const uint4* vp = reinterpret_cast<const uint4*>(vc.codes + vbase * J + v_lane_off);
 #pragma unroll
     for (int w4 = 0; w4 < KW / 4; ++w4) {
-      const uint4 kv4 = kp[w4], vv4 = vp[w4];
+      // sign format: the value side's second 16 bytes are the sign row, NSV rows of J bytes further on
+      const uint4 kv4 = kp[w4], vv4 = (SGN && w4 == 1) ? vp[NSV * J / 16] : vp[w4];
       G.kcode[4 * w4] = kv4.x, G.kcode[4 * w4 + 1] = kv4.y, G.kcode[4 * w4 + 2] = kv4.z, G.kcode[4 * w4 + 3] = kv4.w;
       G.vcode[4 * w4] = vv4.x, G.vcode[4 * w4 + 1] = vv4.y, G.vcode[4 * w4 + 2] = vv4.z, G.vcode[4 * w4 + 3] = vv4.w;
     }
@@ -307,6 +321,16 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     sm_q_had[hh][2 * lane] = x0 * qscale;
     sm_q_had[hh][2 * lane + 1] = x1 * qscale;
   }
+  if constexpr (SGN) {
+    // sign-mask table at LDS address 0: row = sign nibble n (256 bytes), 32 copies of the 8-byte entry
+    // whose four fp16 sign bits are bits 0..3 of n
+    if (tid < 16 * 32) {
+      const uint32_t n = tid >> 5;
+      const uint32_t w0 = ((n & 1u) ? 0x8000u : 0u) | ((n & 2u) ? 0x80000000u : 0u);
+      const uint32_t w1 = ((n & 4u) ? 0x8000u : 0u) | ((n & 8u) ? 0x80000000u : 0u);
+      *reinterpret_cast<uint2*>(sm_table + n * 256 + (tid & 31) * 8) = make_uint2(w0, w1);
+    }
+  }
   if (wave >= 4 && wave - 4 < R) {
     const int hh = wave - 4;
     const float dot = wave_sum_u(sm_q_orig[hh][2 * lane] * __low2float(ok_pre) +
@@ -334,7 +358,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
 #pragma unroll
       for (int u = 0; u < N; ++u) {
         const int i = first + u * 256;
-        *reinterpret_cast<u4v*>(sm_table + (i >> 4) * 256 + (i & 15) * 16) = tmp[u];
+        *reinterpret_cast<u4v*>(sm_table + TB + (i >> 4) * 256 + (i & 15) * 16) = tmp[u];
       }
     };
     static_assert(256 * 6 + 256 * 10 == kCodes * NW16, "slot split must cover the table");
@@ -375,6 +399,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
 #pragma unroll
   for (int i = 0; i < 4; ++i) qo_pre[i] = sm_qo_first[i < R ? i : 0];
   const uint32_t laneoff = (SUB == 4) ? (lane & 31) * 8 : (lane & 15) * 16;
+  const uint32_t laneoff8 = (lane & 31) * 8;  // sign-mask table: 32 copies of 8 bytes per 256-byte row
   __syncthreads();  // the prologue scratch is dead: its bytes become the per-wave mean-term accumulators
 #pragma unroll
   for (int i = 0; i < 4; ++i)  // wave-private; every lane owns channels 2 lane, 2 lane + 1 of each head
@@ -408,7 +433,16 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     }
   };
 
-  auto k_gather = [&](const uint32_t (&kcode)[KW], auto cc, cw_t (&buf)[CH]) {
+  // sign format: the two 8-byte mask entries (low nibble -> channels 0..3, high nibble -> 4..7)
+  // of sign byte k of `sw`; each mask word carries the fp16 sign bits of two channels
+  constexpr int MB = SGN ? CH : 1;  // mask buffers exist only in the sign format
+  auto sign_masks = [&](uint32_t sw, int k) -> uint4 {
+    const uint32_t p8 = perm_b32(sw, laneoff8, 0x0c0c0400u + (k << 8));  // (sign byte << 8) | lane offset
+    const uint2 lo = lds_read64(p8 & 0x0FFFu);
+    const uint2 hi = lds_read64(((p8 >> 4) & 0x0F00u) | laneoff8);
+    return make_uint4(lo.x, lo.y, hi.x, hi.y);
+  };
+  auto k_gather = [&](const uint32_t (&kcode)[KW], auto cc, cw_t (&buf)[CH], uint4 (&mb)[MB]) {
     constexpr int ch = decltype(cc)::value;
 #pragma unroll
     for (int e = 0; e < CH; ++e) {
@@ -416,11 +450,14 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       if constexpr (SUB == 4)
         buf[e] = lds_read64(addr);
       else
-        buf[e] = lds_read128(addr);
+        buf[e] = lds_read128(addr + TB);
+      if constexpr (SGN) mb[e] = sign_masks(kcode[IW + (CH * ch + e) / 4], e % 4);
     }
   };
-  auto k_contract = [&](auto cc, const cw_t (&buf)[CH], const h4 (&QH)[2], const h4 (&QL)[2], f4& d0, f4& d1) {
+  auto k_contract = [&](auto cc, auto signed_c, const cw_t (&buf)[CH], const uint4 (&mb)[MB], const h4 (&QH)[2],
+                        const h4 (&QL)[2], f4& d0, f4& d1) {
     constexpr int ch = decltype(cc)::value;
+    constexpr bool apply_sign = decltype(signed_c)::value;
     static_for<CH>([&](auto ec) {
       constexpr int e = decltype(ec)::value;
       constexpr int s = CH * ch + e;
@@ -429,7 +466,9 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
         d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[s / 16], bop, d0, 4, s % 16, 0);
         if constexpr (!PACK) d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QL[s / 16], bop, d1, 4, s % 16, 0);
       } else {
-        const h4 b0 = as_h4(buf[e].x, buf[e].y), b1 = as_h4(buf[e].z, buf[e].w);
+        uint4 c = make_uint4(buf[e].x, buf[e].y, buf[e].z, buf[e].w);
+        if constexpr (apply_sign) c = make_uint4(c.x ^ mb[e].x, c.y ^ mb[e].y, c.z ^ mb[e].z, c.w ^ mb[e].w);
+        const h4 b0 = as_h4(c.x, c.y), b1 = as_h4(c.z, c.w);
         d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[(2 * s) / 16], b0, d0, 4, (2 * s) % 16, 0);
         d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(QH[(2 * s + 1) / 16], b1, d1, 4, (2 * s + 1) % 16, 0);
         if constexpr (!PACK) {
@@ -439,18 +478,22 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       }
     });
   };
-  auto v_gather = [&](uint32_t vw, cw_t (&buf)[4]) {
+  constexpr int VMB = SGN ? 4 : 1;
+  auto v_gather = [&](uint32_t vw, uint32_t sw, cw_t (&buf)[4], uint4 (&mb)[VMB]) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const uint32_t addr = perm_b32(vw, laneoff, 0x0c0c0400u + (k << 8));
       if constexpr (SUB == 4)
         buf[k] = lds_read64(addr);
       else
-        buf[k] = lds_read128(addr);
+        buf[k] = lds_read128(addr + TB);
+      if constexpr (SGN) mb[k] = sign_masks(sw, k);
     }
   };
-  auto v_contract = [&](auto ac, const cw_t (&cw)[4], const h4& wop, f4 (&acc)[SUB]) {
+  auto v_contract = [&](auto ac, auto signed_c, const cw_t (&cw)[4], const uint4 (&mb)[VMB], const h4& wop,
+                        f4 (&acc)[SUB]) {
     constexpr int a = decltype(ac)::value;
+    constexpr bool apply_sign = decltype(signed_c)::value;
     if constexpr (SUB == 4) {
       const h4 b0 = as_h4(perm_b32(cw[1].x, cw[0].x, 0x05040100u), perm_b32(cw[3].x, cw[2].x, 0x05040100u));
       const h4 b1 = as_h4(perm_b32(cw[1].x, cw[0].x, 0x07060302u), perm_b32(cw[3].x, cw[2].x, 0x07060302u));
@@ -461,10 +504,16 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       acc[2] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, b2, acc[2], CBSZ_V, a, 0);
       acc[3] = __builtin_amdgcn_mfma_f32_4x4x4f16(wop, b3, acc[3], CBSZ_V, a, 0);
     } else {
-      const uint32_t c0[4] = {cw[0].x, cw[0].y, cw[0].z, cw[0].w};
-      const uint32_t c1[4] = {cw[1].x, cw[1].y, cw[1].z, cw[1].w};
-      const uint32_t c2[4] = {cw[2].x, cw[2].y, cw[2].z, cw[2].w};
-      const uint32_t c3[4] = {cw[3].x, cw[3].y, cw[3].z, cw[3].w};
+      uint32_t c0[4] = {cw[0].x, cw[0].y, cw[0].z, cw[0].w};
+      uint32_t c1[4] = {cw[1].x, cw[1].y, cw[1].z, cw[1].w};
+      uint32_t c2[4] = {cw[2].x, cw[2].y, cw[2].z, cw[2].w};
+      uint32_t c3[4] = {cw[3].x, cw[3].y, cw[3].z, cw[3].w};
+      if constexpr (apply_sign) {
+        c0[0] ^= mb[0].x, c0[1] ^= mb[0].y, c0[2] ^= mb[0].z, c0[3] ^= mb[0].w;
+        c1[0] ^= mb[1].x, c1[1] ^= mb[1].y, c1[2] ^= mb[1].z, c1[3] ^= mb[1].w;
+        c2[0] ^= mb[2].x, c2[1] ^= mb[2].y, c2[2] ^= mb[2].z, c2[3] ^= mb[2].w;
+        c3[0] ^= mb[3].x, c3[1] ^= mb[3].y, c3[2] ^= mb[3].z, c3[3] ^= mb[3].w;
+      }
       static_for<4>([&](auto mc) {
         constexpr int mth = decltype(mc)::value;
         const h4 be = as_h4(perm_b32(c1[mth], c0[mth], 0x05040100u), perm_b32(c3[mth], c2[mth], 0x05040100u));
@@ -549,32 +598,38 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
     {
       cw_t bufA[CH], bufB[CH];
-      k_gather(cur.kcode, std::integral_constant<int, 0>{}, bufA);
-      static_for<J / CH>([&](auto cc) {
+      uint4 mskA[MB], mskB[MB];
+      constexpr std::integral_constant<bool, SGN> sgn{};
+      k_gather(cur.kcode, std::integral_constant<int, 0>{}, bufA, mskA);
+      static_for<NSV / CH>([&](auto cc) {
         constexpr int ch = decltype(cc)::value;
         if constexpr (ch % 2 == 0) {
-          if constexpr (ch + 1 < J / CH) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufB);
-          k_contract(cc, bufA, QH, QL, d0, d1);
+          if constexpr (ch + 1 < NSV / CH) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufB, mskB);
+          k_contract(cc, sgn, bufA, mskA, QH, QL, d0, d1);
         } else {
-          if constexpr (ch + 1 < J / CH) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufA);
-          k_contract(cc, bufB, QH, QL, d0, d1);
+          if constexpr (ch + 1 < NSV / CH) k_gather(cur.kcode, std::integral_constant<int, ch + 1>{}, bufA, mskA);
+          k_contract(cc, sgn, bufB, mskB, QH, QL, d0, d1);
         }
       });
     }
+    constexpr std::integral_constant<bool, SGN> vsgn{};
     cw_t vbufA[4], vbufB[4];
-    v_gather(cur.vcode[0], vbufA);  // first value-side gathers fly during the softmax arithmetic
+    uint4 vmskA[VMB], vmskB[VMB];
+    // first value-side gathers fly during the softmax arithmetic
+    v_gather(cur.vcode[0], cur.vcode[SGN ? IW : 0], vbufA, vmskA);
 
     const h4 wop = softmax_step(d0, d1, valid, a_k, b_k, a_v, b_v);
 
     // d5: out_rot[head][channel] += sum over tokens of weight * codeword channel
-    static_for<KW>([&](auto ac) {
+    static_for<IW>([&](auto ac) {
       constexpr int a = decltype(ac)::value;
+      constexpr int sa = SGN ? IW + a + 1 : 0;  // dword of the next round's sign bytes
       if constexpr (a % 2 == 0) {
-        if constexpr (a + 1 < KW) v_gather(cur.vcode[a + 1], vbufB);
-        v_contract(ac, vbufA, wop, acc);
+        if constexpr (a + 1 < IW) v_gather(cur.vcode[a + 1], cur.vcode[sa], vbufB, vmskB);
+        v_contract(ac, vsgn, vbufA, vmskA, wop, acc);
       } else {
-        if constexpr (a + 1 < KW) v_gather(cur.vcode[a + 1], vbufA);
-        v_contract(ac, vbufB, wop, acc);
+        if constexpr (a + 1 < IW) v_gather(cur.vcode[a + 1], cur.vcode[sa], vbufA, vmskA);
+        v_contract(ac, vsgn, vbufB, vmskB, wop, acc);
       }
     });
     if (has_next) cur = nxt;
@@ -615,7 +670,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       const int64_t unit_row = (int64_t)(b * g.n_kv_heads + h) * res.capacity;
       f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
       const uint4* krow = reinterpret_cast<const uint4*>(res.k + (unit_row + lane) * kHeadDim);
-      static_for<J / CH>([&](auto cc) {
+      const uint4 no_mask[MB] = {};
+      const uint4 no_vmask[VMB] = {};
+      constexpr std::false_type plain{};  // fp16 rows carry their own signs
+      static_for<NSV / CH>([&](auto cc) {
         constexpr int ch = decltype(cc)::value;
         cw_t buf[CH];
         if constexpr (SUB == 4) {
@@ -629,21 +687,21 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
 #pragma unroll
           for (int u = 0; u < CH; ++u) buf[u] = valid ? krow[CH * ch + u] : make_uint4(0u, 0u, 0u, 0u);
         }
-        k_contract(cc, buf, AH, AL, d0, d1);
+        k_contract(cc, plain, buf, no_mask, AH, AL, d0, d1);
       });
       const h4 wop = softmax_step(d0, d1, valid, 1.f, 0.f, 1.f, 0.f);
 #pragma unroll
       for (int c = 0; c < SUB; ++c) acc_res[c] = f4{0.f, 0.f, 0.f, 0.f};
-      static_for<KW>([&](auto ac) {
+      static_for<IW>([&](auto ac) {
         constexpr int a = decltype(ac)::value;
         cw_t cw[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          const int t = (lane / LV) * J + 4 * a + k;  // the same token order as a coded group
+          const int t = (lane / LV) * NSV + 4 * a + k;  // the same token order as a coded group
           cw[k] = cw_t{};
           if (t < rl) cw[k] = *reinterpret_cast<const cw_t*>(res.v + (unit_row + t) * kHeadDim + (lane % LV) * SUB);
         }
-        v_contract(ac, cw, wop, acc_res);
+        v_contract(ac, plain, cw, no_vmask, wop, acc_res);
       });
     }
   }
@@ -785,21 +843,21 @@ extern "C" int nsn_debug_decode_timing(long long* host48) {
 #endif
 
 // ---------------------------------------------------------------------------------------
-template <int SUB, int NW, int R>
+template <int SUB, int NW, int R, bool SGN = false>
 static int launch_one(const Geometry& g, const void* codebook, const void* q, const CacheView& kv,
                       const CacheView& vv, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                       int n_splits, void* workspace, size_t counter_bytes, const ResidualView& res, float* out,
                       hipStream_t stream) {
-  const size_t smem = DecSmem<SUB, NW>::kBytes;
+  const size_t smem = DecSmem<SUB, NW, SGN>::kBytes;
   static bool attr_done = false;
   if (!attr_done) {
     // the gathers address the codebook table by absolute LDS address: it must start at 0,
     // i.e. the kernel may not own any static LDS in front of its dynamic block
     hipFuncAttributes fa;
-    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R>)) != hipSuccess ||
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN>)) != hipSuccess ||
         fa.sharedSizeBytes != 0)
       return NSN_ERR_HIP;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return NSN_ERR_HIP;
     attr_done = true;
@@ -809,7 +867,7 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
   float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + counter_bytes);
   const dim3 grid(n_splits, g.n_kv_heads, batch);
   const int waves = res.k != nullptr ? NW + 1 : NW;  // + the residual wave
-  dec_mfma_kernel<SUB, NW, R><<<grid, waves * 64, smem, stream>>>(
+  dec_mfma_kernel<SUB, NW, R, SGN><<<grid, waves * 64, smem, stream>>>(
       g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens, scale * 1.44269504088896340736f, n_splits,
       per, partial, counters, res, out);
   return NSN_OK;
@@ -845,6 +903,12 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
   const int r = s.n_q_heads / s.n_kv_heads;
 #define NSN_LAUNCH(SUBV, RV) \
   launch_one<SUBV, 8, RV>(g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, cb, res, out, stream)
+  if (g.sign) {
+#define NSN_LAUNCH_SIGN(RV) \
+  launch_one<8, 8, RV, true>(g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, cb, res, out, stream)
+    return r == 1 ? NSN_LAUNCH_SIGN(1) : r == 2 ? NSN_LAUNCH_SIGN(2) : NSN_LAUNCH_SIGN(4);
+#undef NSN_LAUNCH_SIGN
+  }
   if (s.sub_dim == 4) return r == 1 ? NSN_LAUNCH(4, 1) : r == 2 ? NSN_LAUNCH(4, 2) : NSN_LAUNCH(4, 4);
   return r == 1 ? NSN_LAUNCH(8, 1) : r == 2 ? NSN_LAUNCH(8, 2) : NSN_LAUNCH(8, 4);
 #undef NSN_LAUNCH
