@@ -19,12 +19,20 @@
  *     default stream) and the call returns without synchronising, except
  *     nsn_build_codebook, which returns host results and therefore synchronises.
  *   - No floating-point atomics are used: identical inputs give bit-identical outputs.
- *   - head_dim is 128, n_codes is 256, sub_dim is 8 ("1-bit": one code byte per 8
- *     rotated channels) or 4 ("2-bit": one code byte per 4 rotated channels).
+ *   - head_dim is 128.  Code formats (sub_dim, n_codes):
+ *       (8, 256)    "1-bit": one index byte per 8 rotated channels
+ *       (4, 256)    "2-bit": one index byte per 4 rotated channels
+ *       (8, 65536)  the paper's own 2-bit format (Sec. 3.4): per 8 rotated channels one index
+ *                   byte into a codebook of 256 MAGNITUDE codewords (all entries >= 0; e.g.
+ *                   nsn_build_codebook on absolute values of normal samples) plus one sign
+ *                   byte (bit i set = channel i negative); 65536 = 256 codewords x 2^8 sign
+ *                   patterns.  The codebook passed to the calls still has 256 rows.
  *
  * Coded cache record (one tensor kind, K or V), per (sequence b, kv-head h):
- *   codes  J = head_dim/sub_dim bytes per token.  Inside one placement unit (see below) the
- *          byte of (token t of the unit, sub-vector j in [0,J)) sits at
+ *   codes  J bytes per token: J = head_dim/sub_dim index bytes; in the sign + index format
+ *          J = 32: byte rows j = 0..15 are the indices of sub-vectors 0..15, rows 16..31 their
+ *          sign bytes.  Inside one placement unit (see below) the
+ *          byte of (token t of the unit, byte row j in [0,J)) sits at
  *            K:  t * J + j                                  (token-major)
  *            V:  (t / J) * J*J + j * J + t % J              (blocks of J tokens, sub-vector-major)
  *          K keeps a token's codes together for the score contraction over channels; V keeps
@@ -58,7 +66,7 @@ extern "C" {
 enum {
   NSN_OK = 0,
   NSN_ERR_INVALID_ARG = -1, /* null pointer, negative size, misaligned start, ... */
-  NSN_ERR_UNSUPPORTED = -2, /* head_dim != 128, sub_dim not in {4,8}, n_codes != 256, ... */
+  NSN_ERR_UNSUPPORTED = -2, /* head_dim != 128, a (sub_dim, n_codes) pair not listed above, ... */
   NSN_ERR_WORKSPACE = -3,   /* workspace missing or smaller than nsn_workspace_bytes() */
   NSN_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed */
 };
@@ -67,10 +75,11 @@ enum { NSN_OP_ENCODE = 0, NSN_OP_DECODE = 1, NSN_OP_CODEBOOK = 2 };
 
 typedef struct nsn_shape {
   int32_t head_dim;   /* 128 */
-  int32_t sub_dim;    /* 8 (1-bit) or 4 (2-bit) */
-  int32_t n_codes;    /* 256 */
+  int32_t sub_dim;    /* 8 or 4 */
+  int32_t n_codes;    /* 256, or 65536 with sub_dim 8: the sign + index format (see above) */
   int32_t n_q_heads;  /* multiple of n_kv_heads; n_q_heads / n_kv_heads <= 8 (<= 4 takes the
-                         matrix-core decode kernel, above that the lookup-table kernel) */
+                         matrix-core decode kernel, above that the lookup-table kernel, which
+                         knows neither the residual nor the sign + index format) */
   int32_t n_kv_heads;
   int32_t group_size; /* G: tokens sharing one Shift mean; multiple of 64 (the paper uses 64),
                          or 0 = one group per sequence */
