@@ -54,11 +54,14 @@ def parse():
                         "full (one 64-token encode per sequence every 64 steps, inside the timed region); "
                         "'append' = every step encodes its one new token before the attention")
     p.add_argument("--sign-format", action="store_true",
-                   help="with --random-cache: the paper's own 2-bit format (8 sign bits + 8-bit magnitude index per "
-                        "8-dim sub-vector) instead of the workload's code format")
+                   help="the paper's own 2-bit format (8 sign bits + 8-bit magnitude index per 8-dim sub-vector, "
+                        "magnitude codebook from K-Means on |N(0,1)|) instead of the workload's code format")
     p.add_argument("--group-size", type=int, default=0,
-                   help="with --random-cache: Shift group size (0 = one group per sequence as in the workload "
-                        "definitions, 64 = the paper's residual-size groups)")
+                   help="Shift group size (0 = one group per sequence as in the workload definitions, "
+                        "64 = the paper's residual-size groups)")
+    p.add_argument("--finetune-iters", type=int, default=0,
+                   help="cosine fine-tuning steps applied to the K-Means codebook (Sec. 3.4); 0 = none")
+    p.add_argument("--finetune-lr", type=float, default=2048.0)
     p.add_argument("--rotate-bytes", type=float, default=1.2e9)
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-units", type=int, default=4, help="(sequence, kv-head) units the oracle is timed on")
@@ -159,6 +162,11 @@ def main() -> int:
               "run it with --gpus 1", file=sys.stderr)
         return 2
 
+    if args.policy == "append" and args.group_size != 0:
+        print("bench.py: --policy append encodes single tokens against a stored mean and needs --group-size 0",
+              file=sys.stderr)
+        return 2
+
     import numpy as np
     import torch
 
@@ -169,8 +177,11 @@ def main() -> int:
         return random_cache_decode(args, cfg)
     B, Hq, Hkv, L, sub, seed = (cfg["batch"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["length"],
                                 cfg["sub_dim"], cfg["seed"])
-    J = 128 // sub
-    G = 0  # one Shift mean per (sequence, head)
+    sign = bool(args.sign_format)
+    if sign:
+        sub = 8
+    J = 32 if sign else 128 // sub   # code bytes per token
+    G = args.group_size  # 0: one Shift mean per (sequence, head), as the workload definitions say
     scale = 1.0 / math.sqrt(128)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -179,9 +190,15 @@ def main() -> int:
     # ---- setup (untimed): codebook, inputs, prefill encode ------------------------------------
     t_setup = time.time()
     samples = torch.from_numpy(synth.codebook_samples(seed, args.codebook_samples, sub)).to(dev)
+    if sign:
+        samples = samples.abs()   # codebook of magnitudes
     torch.cuda.synchronize()
     t0 = time.time()
     codebook, cb_mse = api.nsn_build_codebook(samples, 256, args.codebook_iters)
+    cos_before = cos_after = None
+    if args.finetune_iters > 0:
+        codebook, cos_before, cos_after = api.nsn_finetune_codebook(samples, codebook, args.finetune_iters,
+                                                                    args.finetune_lr)
     torch.cuda.synchronize()
     codebook_s = time.time() - t0
     del samples
@@ -190,7 +207,8 @@ def main() -> int:
     q_host = synth.make_q(seed, B, Hq)
     k_dev, v_dev, q_dev = (torch.from_numpy(x).to(dev) for x in (k_host, v_host, q_host))
     RES = 64  # residual size of the paper
-    shape = api.make_shape(sub, Hq, Hkv, L + RES, G)  # room for one flushed residual behind the L cached tokens
+    # room for one flushed residual behind the L cached tokens
+    shape = api.make_shape(sub, Hq, Hkv, L + RES, G, sign_format=sign)
     kc, vc = api.alloc_cache(shape, B), api.alloc_cache(shape, B)
     zeros = torch.zeros(B, dtype=torch.int32, device=dev)
     full = torch.full((B,), L, dtype=torch.int32, device=dev)
@@ -244,7 +262,7 @@ def main() -> int:
             api.nsn_decode_attention(shape, codebook, q_dev, ck, cv, full, L, scale, args.n_splits, out=out,
                                      workspace=dec_ws)
         elif args.policy == "append":
-            api.nsn_encode(shape, codebook, k_new, v_new, full, ones, ck, cv, freeze_means=True, workspace=enc_ws)
+            api.nsn_encode(shape, codebook, k_new, v_new, full, ones, ck, cv, freeze_means=True, workspace=enc_ws)  # G = 0 only
             api.nsn_decode_attention(shape, codebook, q_dev, ck, cv, full1, L + 1, scale, args.n_splits, out=out,
                                      workspace=dec_ws)
         else:
@@ -253,8 +271,8 @@ def main() -> int:
             r = i % RES
             api.nsn_decode_attention_residual(shape, codebook, q_dev, ck, cv, full, L, k_res, v_res, res_lens[r],
                                               scale, args.n_splits, out=out, workspace=dec_ws)
-            if r == RES - 1:
-                api.nsn_encode(shape, codebook, k_res, v_res, full, res_lens[RES - 1], ck, cv, freeze_means=True,
+            if r == RES - 1:  # G = 0: the sequence's stored mean; G = 64: the residual is a Shift group of its own
+                api.nsn_encode(shape, codebook, k_res, v_res, full, res_lens[RES - 1], ck, cv, freeze_means=(G == 0),
                                workspace=enc_ws)
 
     for i in range(args.warmup):
@@ -316,7 +334,8 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{args.workload}:{cfg['name']}", "batch": B, "n_q_heads": Hq,
-                   "n_kv_heads": Hkv, "cached_tokens": L, "sub_dim": sub, "bits": 8 // sub,
+                   "n_kv_heads": Hkv, "cached_tokens": L, "sub_dim": sub, "bits": 2 if sign else 8 // sub,
+                   "sign_format": sign, "codebook_finetune_iters": args.finetune_iters,
                    "group_size": G, "cache_copies_in_rotation": n_copies,
                    "residual_size": RES if args.policy == "residual" else 0,
                    "residual_encodes_in_timed_region": flushes if args.policy == "residual" else 0,
@@ -330,6 +349,7 @@ def main() -> int:
         "encode_ms_prefill": round(enc_ms, 4),
         "codebook_build_s": round(codebook_s, 3),
         "codebook_mse_per_dim": round(cb_mse, 6),
+        "codebook_cosine_before_after_finetune": [cos_before, cos_after],
         "bytes_per_step": step_bytes,
         "setup_s": round(setup_s, 1),
         "roofline": {"bound": "hbm", "kernel": "nsn::dec_mfma_kernel (one launch per decode step)",
@@ -352,11 +372,12 @@ def main() -> int:
         worst = 0.0
         for (b, h) in units:
             t0 = time.perf_counter()
-            ek = O.encode(k_host[b, h], cb_host, G)
-            ev = O.encode(v_host[b, h], cb_host, G)
+            ek = O.encode(k_host[b, h], cb_host, G, sign_format=sign)
+            ev = O.encode(v_host[b, h], cb_host, G, sign_format=sign)
             t_enc += time.perf_counter() - t0
             t0 = time.perf_counter()
-            ref = O.decode_attention(q_host[b, h * r:(h + 1) * r].astype(np.float64), ek, ev, cb_host, scale, G)
+            ref = O.decode_attention(q_host[b, h * r:(h + 1) * r].astype(np.float64), ek, ev, cb_host, scale, G,
+                                     sign_format=sign)
             t_dec += time.perf_counter() - t0
             got = out_host[b, h * r:(h + 1) * r]
             worst = max(worst, float((np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)).max()))
