@@ -164,6 +164,7 @@ __device__ long long g_dec_timing[48];
 //   [64 KiB, +(NW+1)*2KiB) prologue: staged codewords, q, rotated q;
 //                      main loop: mean-vector term of every wave, accm[NW + 1][4][128]
 //                      (slot NW belongs to the residual wave, present only in residual launches)
+//   then 2 KiB         the unrotated query (read again when a wave enters another Shift group)
 //   tail               per-wave (m, l), the "last workgroup" flag, inverse-Hadamard scratch
 // One workgroup of 8 waves per compute unit shares a single table (64 + 16 KiB of the 160 KiB).
 template <int SUB, int NW, bool SGN = false>
@@ -174,9 +175,11 @@ struct DecSmem {
   static constexpr int kUnionBytes = (NW + 1) * 4 * kHeadDim * 4;  // + the residual wave's slot
   static constexpr int kRaccBytes = NW * (64 / (kHeadDim / SUB)) * 4 * kHeadDim * 4;
   static constexpr int kTailBytes = (2 * (NW + 1) * 4 + 4 + 4 * kHeadDim) * 4;
+  static constexpr int kQueryBytes = 4 * kHeadDim * 4;  // unrotated query, kept for the q . o^k of later Shift groups
+  static constexpr int kQueryOffset = kTable + kUnionBytes;
   static constexpr bool kTailInTable = kRaccBytes + kTailBytes <= kTable;
-  static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kTable + kUnionBytes;
-  static constexpr int kBytes = kTable + kUnionBytes + (kTailInTable ? 0 : kTailBytes);
+  static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kQueryOffset + kQueryBytes;
+  static constexpr int kBytes = kQueryOffset + kQueryBytes + (kTailInTable ? 0 : kTailBytes);
   static_assert(kUnionBytes >= kCodes * 2 * SUB + 2 * 4 * kHeadDim * 4 + 16, "prologue scratch must fit");
   static_assert(kRaccBytes <= kTable, "per-wave accumulators must fit in the table region");
 };
@@ -205,13 +208,14 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   constexpr int CBSZ_V = (SUB == 4) ? 3 : 2;
   constexpr int NT = NW * 64;
   constexpr bool PACK = (R <= 2);  // hi and lo rows in one A operand
-  constexpr int CH = SGN ? 4 : 8;  // key-side gathers in flight per chunk
+  constexpr int CH = SGN ? 2 : 8;  // key-side gathers in flight per chunk (a sign-format gather is 8 registers)
   using SM = DecSmem<SUB, NW, SGN>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   unsigned char* const sm_table = smem_raw;
   unsigned char* const sm_stage = smem_raw + SM::kTable;                           // prologue only
   float(*const sm_q_orig)[kHeadDim] = reinterpret_cast<float(*)[kHeadDim]>(sm_stage + kCodes * 2 * SUB);
   float(*const sm_q_had)[kHeadDim] = sm_q_orig + 4;
+  float(*const sm_q_keep)[kHeadDim] = reinterpret_cast<float(*)[kHeadDim]>(smem_raw + SM::kQueryOffset);
   float* const sm_qo_first = &sm_q_had[4][0];  // q . o^k of the split's first Shift group, four heads
   float(*const sm_accm)[4][kHeadDim] = reinterpret_cast<float(*)[4][kHeadDim]>(smem_raw + SM::kTable);
   float(*const sm_wave_m)[4] = reinterpret_cast<float(*)[4]>(smem_raw + SM::kTailOffset);  // after the loop
@@ -300,7 +304,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
 #pragma unroll
   for (int u = 0; u < QPT; ++u) {
     const int i = tid + u * NT;
-    if (i < 4 * kHeadDim) sm_q_orig[i >> 7][i & 127] = qv[u];
+    if (i < 4 * kHeadDim) {
+      sm_q_orig[i >> 7][i & 127] = qv[u];
+      sm_q_keep[i >> 7][i & 127] = qv[u];
+    }
   }
   __syncthreads();
   NSN_TSTAMP(12);
@@ -391,13 +398,11 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       QL[p][k] = lo;
     }
   }
-  const float qo0[4] = {sm_q_orig[0][2 * lane], sm_q_orig[1][2 * lane], sm_q_orig[2][2 * lane],
-                        sm_q_orig[3][2 * lane]};
-  const float qo1[4] = {sm_q_orig[0][2 * lane + 1], sm_q_orig[1][2 * lane + 1], sm_q_orig[2][2 * lane + 1],
-                        sm_q_orig[3][2 * lane + 1]};
-  float qo_pre[4];
+  float qo_pre[4];  // wave-uniform: lives in scalar registers
 #pragma unroll
-  for (int i = 0; i < 4; ++i) qo_pre[i] = sm_qo_first[i < R ? i : 0];
+  for (int i = 0; i < 4; ++i)
+    qo_pre[i] = __builtin_bit_cast(
+        float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sm_qo_first[i < R ? i : 0])));
   const uint32_t laneoff = (SUB == 4) ? (lane & 31) * 8 : (lane & 15) * 16;
   const uint32_t laneoff8 = (lane & 31) * 8;  // sign-mask table: 32 copies of 8 bytes per 256-byte row
   __syncthreads();  // the prologue scratch is dead: its bytes become the per-wave mean-term accumulators
@@ -446,12 +451,13 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     constexpr int ch = decltype(cc)::value;
 #pragma unroll
     for (int e = 0; e < CH; ++e) {
-      const uint32_t addr = perm_b32(kcode[(CH * ch + e) / 4], laneoff, 0x0c0c0400u + ((e % 4) << 8));
+      const int sv = CH * ch + e;  // sub-vector: byte sv % 4 of index dword sv / 4
+      const uint32_t addr = perm_b32(kcode[sv / 4], laneoff, 0x0c0c0400u + ((sv % 4) << 8));
       if constexpr (SUB == 4)
         buf[e] = lds_read64(addr);
       else
         buf[e] = lds_read128(addr + TB);
-      if constexpr (SGN) mb[e] = sign_masks(kcode[IW + (CH * ch + e) / 4], e % 4);
+      if constexpr (SGN) mb[e] = sign_masks(kcode[IW + sv / 4], sv % 4);
     }
   };
   auto k_contract = [&](auto cc, auto signed_c, const cw_t (&buf)[CH], const uint4 (&mb)[MB], const h4 (&QH)[2],
@@ -586,7 +592,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       } else {
         const float o0 = __low2float(cur.ok2), o1 = __high2float(cur.ok2);
 #pragma unroll
-        for (int i = 0; i < R; ++i) qo[i] = wave_sum_u(qo0[i] * o0 + qo1[i] * o1) * scale_log2e;
+        for (int i = 0; i < R; ++i) {
+          const float2 q2 = *reinterpret_cast<const float2*>(&sm_q_keep[i][2 * lane]);
+          qo[i] = wave_sum_u(q2.x * o0 + q2.y * o1) * scale_log2e;
+        }
       }
       ov0 = __low2float(cur.ov2);
       ov1 = __high2float(cur.ov2);
@@ -624,7 +633,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     static_for<IW>([&](auto ac) {
       constexpr int a = decltype(ac)::value;
       constexpr int sa = SGN ? IW + a + 1 : 0;  // dword of the next round's sign bytes
-      if constexpr (a % 2 == 0) {
+      if constexpr (SGN) {  // one buffer (32 registers with its masks): gather the next round after this one's MFMAs
+        v_contract(ac, vsgn, vbufA, vmskA, wop, acc);
+        if constexpr (a + 1 < IW) v_gather(cur.vcode[a + 1], cur.vcode[sa], vbufA, vmskA);
+      } else if constexpr (a % 2 == 0) {
         if constexpr (a + 1 < IW) v_gather(cur.vcode[a + 1], cur.vcode[sa], vbufB, vmskB);
         v_contract(ac, vsgn, vbufA, vmskA, wop, acc);
       } else {
