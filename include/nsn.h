@@ -77,9 +77,9 @@ typedef struct nsn_shape {
   int32_t head_dim;   /* 128 */
   int32_t sub_dim;    /* 8 or 4 */
   int32_t n_codes;    /* 256, or 65536 with sub_dim 8: the sign + index format (see above) */
-  int32_t n_q_heads;  /* multiple of n_kv_heads; n_q_heads / n_kv_heads <= 8 (<= 4 takes the
-                         matrix-core decode kernel, above that the lookup-table kernel, which
-                         knows neither the residual nor the sign + index format) */
+  int32_t n_q_heads;  /* multiple of n_kv_heads; n_q_heads / n_kv_heads <= 8 (the decode kernel
+                         takes four query heads per kv head per launch: five to eight heads run
+                         as two launches, the second reading the cache again) */
   int32_t n_kv_heads;
   int32_t group_size; /* G: tokens sharing one Shift mean; multiple of 64 (the paper uses 64),
                          or 0 = one group per sequence */
@@ -219,7 +219,6 @@ int nsn_decode_attention(const nsn_shape* shape, const void* codebook_dev, const
  * their fp16 values (fp32 accumulation).  seq_lens_dev counts coded tokens only; a sequence
  * with no coded and no residual token gives a zero output row.  All other arguments, the
  * workspace and its rules are those of nsn_decode_attention.
- * Restriction: at most 4 query heads per kv head (else UNSUPPORTED).
  * Errors: INVALID_ARG (also capacity outside 1..64), UNSUPPORTED, WORKSPACE, HIP.
  */
 int nsn_decode_attention_residual(const nsn_shape* shape, const void* codebook_dev,

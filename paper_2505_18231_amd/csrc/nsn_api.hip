@@ -171,10 +171,6 @@ static int decode_common(const nsn_shape* shape, const void* codebook_dev, const
               shape->max_len);
     return NSN_ERR_INVALID_ARG;
   }
-  if (shape->n_codes == kSignCodes && shape->n_q_heads / shape->n_kv_heads > 4) {
-    set_error("decode: the sign + index format supports at most 4 query heads per kv head");
-    return NSN_ERR_UNSUPPORTED;
-  }
   if (residual) {
     if (!residual->k_fp16 || !residual->v_fp16 || !residual->lens || residual->capacity < 1 ||
         residual->capacity > 64) {
@@ -182,7 +178,7 @@ static int decode_common(const nsn_shape* shape, const void* codebook_dev, const
       return NSN_ERR_INVALID_ARG;
     }
     if (!decode_use_mfma(*shape)) {
-      set_error("decode: the residual form supports at most 4 query heads per kv head");
+      set_error("decode: the lookup-table kernel (NSN_DECODE_IMPL=lut) has no residual form");
       return NSN_ERR_UNSUPPORTED;
     }
   }

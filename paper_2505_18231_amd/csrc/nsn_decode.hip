@@ -241,7 +241,7 @@ bool decode_use_mfma(const nsn_shape& s) {
   if (s.n_codes == kSignCodes) return true;   // the sign + index format exists in the matrix-core kernel only
   const char* e = getenv("NSN_DECODE_IMPL");  // "lut" forces the lookup-table kernel
   if (e && e[0] == 'l') return false;
-  return s.n_q_heads / s.n_kv_heads <= 4;
+  return true;  // up to 8 query heads per kv head (checked with the shape): one launch per four heads
 }
 
 int decode_pick_splits(const nsn_shape& s, int batch, int max_seq_len, int requested) {
@@ -265,7 +265,7 @@ int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const
                               residual, out, stream) == NSN_OK && hipGetLastError() == hipSuccess
                ? NSN_OK
                : NSN_ERR_HIP;
-  if (residual) return NSN_ERR_UNSUPPORTED;  // the lookup-table kernel reads coded tokens only
+  if (residual) return NSN_ERR_UNSUPPORTED;  // the lookup-table kernel (forced by NSN_DECODE_IMPL) reads coded tokens only
   const Geometry g = make_geometry(s);
   const CacheView kv = make_view(kc), vv = make_view(vc);
   float* partial = static_cast<float*>(workspace);

@@ -196,7 +196,8 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
                                                            CacheView vc, const int32_t* __restrict__ seq_lens,
                                                            float scale_log2e, int n_splits, int per,
                                                            float* partial, int* counters,
-                                                           ResidualView res, float* __restrict__ out) {
+                                                           ResidualView res, int head_off, int r_pass,
+                                                           float* __restrict__ out) {
   static_assert(!SGN || SUB == 8, "the sign + index format is defined on 8-dim sub-vectors");
   constexpr int NSV = kHeadDim / SUB;         // sub-vectors per token
   constexpr int J = SGN ? 2 * NSV : NSV;      // code bytes per token
@@ -224,7 +225,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   float* const sm_rot = reinterpret_cast<float*>(sm_is_last + 4);
 
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  const int r = g.n_q_heads / g.n_kv_heads;  // <= 4
+  // this launch handles query heads [head_off, head_off + r_pass) of every kv head (r_pass <= 4;
+  // more than four heads per kv head run as two launches)
+  const int r = r_pass;
+  const int hq0 = h * (g.n_q_heads / g.n_kv_heads) + head_off;  // first query head of this workgroup
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // per-wave bookkeeping on the scalar unit
   // Launches with a residual carry one more wave (index NW): it handles the fp16 residual tokens
@@ -280,7 +284,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
 #pragma unroll
   for (int u = 0; u < QPT; ++u) {
     const int i = tid + u * NT, hh = i >> 7, c = i & 127;
-    qv[u] = (i < 4 * kHeadDim && hh < r) ? __half2float(q[(int64_t)(b * g.n_q_heads + h * r + hh) * kHeadDim + c]) : 0.f;
+    qv[u] = (i < 4 * kHeadDim && hh < r) ? __half2float(q[(int64_t)(b * g.n_q_heads + hq0 + hh) * kHeadDim + c]) : 0.f;
   }
   Grp cur;
   const bool spec = main_wave && !g.paged && (t0 + (wave << 6) + 64 <= g.page_tokens);  // in bounds whatever the length
@@ -667,7 +671,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
         const bool is_lo = PACK && row >= R, dead = (PACK && row >= 2 * R) || head >= r;
         uint2 raw = make_uint2(0u, 0u);
         if (!dead)
-          raw = *reinterpret_cast<const uint2*>(q + (int64_t)(b * g.n_q_heads + h * r + head) * kHeadDim +
+          raw = *reinterpret_cast<const uint2*>(q + (int64_t)(b * g.n_q_heads + hq0 + head) * kHeadDim +
                                                 4 * (16 * p + (lane >> 2)));
         const h4 qh = as_h4(raw.x, raw.y);
 #pragma unroll
@@ -755,7 +759,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   NSN_TSTAMP(9);
   __syncthreads();
   NSN_TSTAMP(14);
-  float* P = partial + ((int64_t)(b * g.n_q_heads + h * r) * n_splits + split) * kPartialStrideM;
+  float* P = partial + ((int64_t)(b * g.n_q_heads + hq0) * n_splits + split) * kPartialStrideM;
   for (int i = tid; i < r * kHeadDim; i += NT) {
     const int hh = i >> 7, c = i & 127;
     float M = -INFINITY;
@@ -798,7 +802,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   __syncthreads();
   if (!*sm_is_last) return;
   float* rot = sm_rot;  // [4][128]
-  const float* P0 = partial + (int64_t)(b * g.n_q_heads + h * r) * n_splits * kPartialStrideM;
+  const float* P0 = partial + (int64_t)(b * g.n_q_heads + hq0) * n_splits * kPartialStrideM;
   float mm_keep[(4 * kHeadDim + NT - 1) / NT], L_keep[(4 * kHeadDim + NT - 1) / NT];
   {
     int slot = 0;
@@ -841,7 +845,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       const int hh = i >> 7, c = i & 127;
       if (hh < r) {
         const float L = L_keep[slot];
-        out[(int64_t)(b * g.n_q_heads + h * r + hh) * kHeadDim + c] =
+        out[(int64_t)(b * g.n_q_heads + hq0 + hh) * kHeadDim + c] =
             L > 0.f ? (rot[i] * (float)kInvSqrtD + mm_keep[slot]) / L : 0.f;
       }
     }
@@ -858,8 +862,8 @@ extern "C" int nsn_debug_decode_timing(long long* host48) {
 template <int SUB, int NW, int R, bool SGN = false>
 static int launch_one(const Geometry& g, const void* codebook, const void* q, const CacheView& kv,
                       const CacheView& vv, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
-                      int n_splits, void* workspace, size_t counter_bytes, const ResidualView& res, float* out,
-                      hipStream_t stream) {
+                      int n_splits, void* workspace, size_t counter_bytes, const ResidualView& res, int head_off,
+                      int r_pass, float* out, hipStream_t stream) {
   const size_t smem = DecSmem<SUB, NW, SGN>::kBytes;
   static bool attr_done = false;
   if (!attr_done) {
@@ -881,7 +885,7 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
   const int waves = res.k != nullptr ? NW + 1 : NW;  // + the residual wave
   dec_mfma_kernel<SUB, NW, R, SGN><<<grid, waves * 64, smem, stream>>>(
       g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens, scale * 1.44269504088896340736f, n_splits,
-      per, partial, counters, res, out);
+      per, partial, counters, res, head_off, r_pass, out);
   return NSN_OK;
 }
 
@@ -912,18 +916,25 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
            residual->lens, residual->capacity};
   const CacheView kv = make_view(kc), vv = make_view(vc);
   const size_t cb = counter_bytes(s, batch);
-  const int r = s.n_q_heads / s.n_kv_heads;
-#define NSN_LAUNCH(SUBV, RV) \
-  launch_one<SUBV, 8, RV>(g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, cb, res, out, stream)
-  if (g.sign) {
-#define NSN_LAUNCH_SIGN(RV) \
-  launch_one<8, 8, RV, true>(g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, cb, res, out, stream)
-    return r == 1 ? NSN_LAUNCH_SIGN(1) : r == 2 ? NSN_LAUNCH_SIGN(2) : NSN_LAUNCH_SIGN(4);
-#undef NSN_LAUNCH_SIGN
+  const int r_total = s.n_q_heads / s.n_kv_heads;
+  // up to four query heads per kv head in one launch; five to eight as two launches on the same
+  // stream (the second reads the cache again; partials and counters are reused in stream order)
+  for (int head_off = 0; head_off < r_total; head_off += 4) {
+    const int r = min(4, r_total - head_off);
+#define NSN_ARGS \
+  g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, cb, res, head_off, r, out, stream
+    int rc;
+    if (g.sign)
+      rc = r == 1 ? launch_one<8, 8, 1, true>(NSN_ARGS) : r == 2 ? launch_one<8, 8, 2, true>(NSN_ARGS)
+                                                                  : launch_one<8, 8, 4, true>(NSN_ARGS);
+    else if (s.sub_dim == 4)
+      rc = r == 1 ? launch_one<4, 8, 1>(NSN_ARGS) : r == 2 ? launch_one<4, 8, 2>(NSN_ARGS) : launch_one<4, 8, 4>(NSN_ARGS);
+    else
+      rc = r == 1 ? launch_one<8, 8, 1>(NSN_ARGS) : r == 2 ? launch_one<8, 8, 2>(NSN_ARGS) : launch_one<8, 8, 4>(NSN_ARGS);
+#undef NSN_ARGS
+    if (rc != NSN_OK) return rc;
   }
-  if (s.sub_dim == 4) return r == 1 ? NSN_LAUNCH(4, 1) : r == 2 ? NSN_LAUNCH(4, 2) : NSN_LAUNCH(4, 4);
-  return r == 1 ? NSN_LAUNCH(8, 1) : r == 2 ? NSN_LAUNCH(8, 2) : NSN_LAUNCH(8, 4);
-#undef NSN_LAUNCH
+  return NSN_OK;
 }
 
 }  // namespace nsn

@@ -26,6 +26,8 @@ CASES = [
     ("gqa3-2bit-onegroup", 3, 1, [500, 77], [20, 64], 4, 0, 0, 4),   # 3 heads run in the 4-head kernel
     ("residual-only", 4, 1, [0, 0], [64, 9], 4, 64, 0, 0),
     ("nothing-at-all", 4, 1, [0, 192], [0, 0], 8, 64, 0, 0),
+    ("gqa8-two-launches", 16, 2, [384, 64], [33, 64], 4, 64, 0, 0),   # 8 query heads per kv head
+    ("gqa5-two-launches", 5, 1, [130], [7], 8, 0, 0, 2),              # 4 + 1
 ]
 
 
