@@ -253,25 +253,51 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   const uint32_t v_lane_off = SGN ? ((lane / LV) >> 1) * (J * J) + (lane % LV) * J + ((lane / LV) & 1) * 16
                                   : (lane / LV) * (J * J) + (lane % LV) * J;
   const uint32_t lane_x4 = lane * 4;
-  auto load_group = [&](int gi, Grp& G) {
+  // The three parts of a group's bytes can be loaded separately: the sign-format instances, which
+  // are short of registers, refill the code registers in place as soon as their phase is over; the
+  // others fetch the whole next group one iteration ahead into a second set (longer prefetch
+  // distance: measured 0.7 us faster on the 38 MB shape).
+  auto load_k_codes = [&](int gi, Grp& G) {
     const int tg = t0 + (gi << 6);
-    const int tin = token_in_unit(g, tg);
-    const int64_t kbase = unit_token_base(g, kc.block_table, b, h, tg) + tin;  // wave-uniform
-    const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tg) + tin;
+    const int64_t kbase = unit_token_base(g, kc.block_table, b, h, tg) + token_in_unit(g, tg);  // wave-uniform
     const uint4* kp = reinterpret_cast<const uint4*>(kc.codes + kbase * J + k_lane_off);
+#pragma unroll
+    for (int w4 = 0; w4 < KW / 4; ++w4) {
+      const uint4 kv4 = kp[w4];
+      G.kcode[4 * w4] = kv4.x, G.kcode[4 * w4 + 1] = kv4.y, G.kcode[4 * w4 + 2] = kv4.z, G.kcode[4 * w4 + 3] = kv4.w;
+    }
+  };
+  auto load_v_codes = [&](int gi, Grp& G) {
+    const int tg = t0 + (gi << 6);
+    const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tg) + token_in_unit(g, tg);
     const uint4* vp = reinterpret_cast<const uint4*>(vc.codes + vbase * J + v_lane_off);
 #pragma unroll
     for (int w4 = 0; w4 < KW / 4; ++w4) {
       // sign format: the value side's second 16 bytes are the sign row, NSV rows of J bytes further on
-      const uint4 kv4 = kp[w4], vv4 = (SGN && w4 == 1) ? vp[NSV * J / 16] : vp[w4];
-      G.kcode[4 * w4] = kv4.x, G.kcode[4 * w4 + 1] = kv4.y, G.kcode[4 * w4 + 2] = kv4.z, G.kcode[4 * w4 + 3] = kv4.w;
+      const uint4 vv4 = (SGN && w4 == 1) ? vp[NSV * J / 16] : vp[w4];
       G.vcode[4 * w4] = vv4.x, G.vcode[4 * w4 + 1] = vv4.y, G.vcode[4 * w4 + 2] = vv4.z, G.vcode[4 * w4 + 3] = vv4.w;
     }
-    G.nk = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.norms + kbase) + lane_x4);
-    G.nv = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.norms + vbase) + lane_x4);
+  };
+  struct Side {  // norm pairs of the lane's token, the lane's two channels of the group's Shift vectors
+    __half2 nk, nv, ok2, ov2;
+  };
+  auto load_side = [&](int gi, Side& S) {
+    const int tg = t0 + (gi << 6);
+    const int tin = token_in_unit(g, tg);
+    const int64_t kbase = unit_token_base(g, kc.block_table, b, h, tg) + tin;
+    const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tg) + tin;
+    S.nk = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.norms + kbase) + lane_x4);
+    S.nv = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.norms + vbase) + lane_x4);
     const int64_t mo = (mean_base + group_of(g, tg)) * kHeadDim;  // wave-uniform
-    G.ok2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.means + mo) + lane_x4);
-    G.ov2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lane_x4);
+    S.ok2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.means + mo) + lane_x4);
+    S.ov2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lane_x4);
+  };
+  auto load_group = [&](int gi, Grp& G) {
+    load_k_codes(gi, G);
+    load_v_codes(gi, G);
+    Side S;
+    load_side(gi, S);
+    G.nk = S.nk, G.nv = S.nv, G.ok2 = S.ok2, G.ov2 = S.ov2;
   };
 
   NSN_TSTAMP(0);
@@ -581,8 +607,15 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     const int tg = t0 + (gi << 6);  // first token of the group (multiple of 64)
     const bool valid = (tg + lane) < t1;
     const bool has_next = gi + NW < n_grp;  // wave-uniform
-    Grp nxt;
-    if (has_next) load_group(gi + NW, nxt);
+    constexpr bool kInPlace = SGN;
+    Side nxt;
+    Grp nxt_full;
+    if (has_next) {
+      if constexpr (kInPlace)
+        load_side(gi + NW, nxt);
+      else
+        load_group(gi + NW, nxt_full);
+    }
     const float a_k = valid ? __low2float(cur.nk) : 0.f, b_k = valid ? __high2float(cur.nk) : 0.f;
     const float a_v = valid ? __low2float(cur.nv) : 0.f, b_v = valid ? __high2float(cur.nv) : 0.f;
 
@@ -625,6 +658,8 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
         }
       });
     }
+    if constexpr (kInPlace)
+      if (has_next) load_k_codes(gi + NW, cur);  // the key codes are consumed: refill them in place
     constexpr std::integral_constant<bool, SGN> vsgn{};
     cw_t vbufA[4], vbufB[4];
     uint4 vmskA[VMB], vmskB[VMB];
@@ -648,7 +683,14 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
         v_contract(ac, vsgn, vbufB, vmskB, wop, acc);
       }
     });
-    if (has_next) cur = nxt;
+    if (has_next) {
+      if constexpr (kInPlace) {
+        load_v_codes(gi + NW, cur);  // likewise the value codes
+        cur.nk = nxt.nk, cur.nv = nxt.nv, cur.ok2 = nxt.ok2, cur.ov2 = nxt.ov2;
+      } else {
+        cur = nxt_full;
+      }
+    }
   }
   NSN_TSTAMP(10);
 
