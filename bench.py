@@ -64,7 +64,7 @@ def parse():
     p.add_argument("--finetune-lr", type=float, default=2048.0)
     p.add_argument("--rotate-bytes", type=float, default=1.2e9)
     p.add_argument("--no-cpu-baseline", action="store_true")
-    p.add_argument("--cpu-units", type=int, default=4, help="(sequence, kv-head) units the oracle is timed on")
+    p.add_argument("--cpu-units", type=int, default=12, help="(sequence, kv-head) units the oracle is timed on")
     p.add_argument("--codebook-samples", type=int, default=1 << 20)
     p.add_argument("--codebook-iters", type=int, default=50)
     p.add_argument("--copy-calibration", action="store_true",
