@@ -109,7 +109,7 @@ __global__ __launch_bounds__(128) void enc_means_kernel(Geometry g, int max_new,
 
 // ---------------------------------------------------------------------------------------
 // Stage B: shift, second Normalize, rotation, search, scale adjustment, stores.
-// grid (64-token chunk, kv_head * 2 + tensor, sequence), block 256.  A lane owns one
+// grid (64- or 16-token chunk, kv_head * 2 + tensor, sequence), block 256.  A lane owns one
 // sub-vector (SUB channels) of one token; a wave covers 64 / J tokens at a time.
 // ---------------------------------------------------------------------------------------
 #ifdef NSN_DECODE_TIMING
@@ -143,7 +143,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
                                                         const __half* __restrict__ v_in, int max_new,
                                                         int max_len, const int32_t* __restrict__ seq_start,
                                                         const int32_t* __restrict__ n_new, CacheView kc,
-                                                        CacheView vc) {
+                                                        CacheView vc, int wave_tokens) {
+  // wave_tokens: tokens per wave (16, or 4 when the call is too small to fill the chip with 64-token blocks)
   constexpr int J = kHeadDim / SUB;  // lanes per token
   constexpr int TPW = 64 / J;        // tokens per wave step
   constexpr int JB = SIGN ? 2 * J : J;  // code bytes per token
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
   const __half* in = (tensor ? v_in : k_in) + ((int64_t)(b * g.n_kv_heads + h) * max_new) * kHeadDim;
   const int start = seq_start[b];
   const int count = min(n_new[b], max_new);
-  const int t_begin = blockIdx.x * 64 + wave * 16;
+  const int t_begin = blockIdx.x * (4 * wave_tokens) + wave * wave_tokens;
 
   // One token's inputs as this lane needs them (vector loads of SUB fp16 values); the first
   // token's loads are issued before the codebook tables are built, later ones one step ahead.
@@ -196,13 +197,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
   MfmaCodebook<SUB> MC;
   NSN_ETSTAMP(1);
   if constexpr (MFMA) mfma_codebook_load<SUB>(MC, T, lane);
-  if (blockIdx.x * 64 >= count) return;
+  if (blockIdx.x * (4 * wave_tokens) >= count) return;
   NSN_ETSTAMP(2);
 
-  for (int it = 0; it < 16 / TPW; ++it) {
+  const int n_it = wave_tokens / TPW;
+  for (int it = 0; it < n_it; ++it) {
     if (t_begin + it * TPW >= count) break;  // wave-uniform: nothing left for this wave
     const Tok cur = nxt;
-    if (it + 1 < 16 / TPW && t_begin + (it + 1) * TPW < count) nxt = fetch(it + 1);
+    if (it + 1 < n_it && t_begin + (it + 1) * TPW < count) nxt = fetch(it + 1);
     const bool valid = cur.valid;
     const int64_t base = cur.base;
     const int tin = cur.tin;
@@ -334,10 +336,13 @@ int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, co
     enc_means_kernel<<<grid_m, 128, 0, stream>>>(g, max_new, s.max_len, seq_start, n_new, kv, vv, partial, ct,
                                                  n_chunks);
   }
-  const dim3 grid_b((max_new + 63) / 64, s.n_kv_heads * 2, batch);
+  // 64 tokens per workgroup; calls that would leave most compute units idle use 16 (4 per wave)
+  const int64_t blocks64 = (int64_t)((max_new + 63) / 64) * s.n_kv_heads * 2 * batch;
+  const int wave_tokens = blocks64 >= 1024 ? 16 : 4;
+  const dim3 grid_b((max_new + 4 * wave_tokens - 1) / (4 * wave_tokens), s.n_kv_heads * 2, batch);
   auto launch = [&](auto kernel) {
     kernel<<<grid_b, 256, 0, stream>>>(g, (const __half*)codebook, (const __half*)k_in, (const __half*)v_in, max_new,
-                                       s.max_len, seq_start, n_new, kv, vv);
+                                       s.max_len, seq_start, n_new, kv, vv, wave_tokens);
   };
   if (g.sign) {
     if (use_mfma)
