@@ -853,15 +853,41 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       float L = 0.f, rsum = 0.f, mm = 0.f;
       if (hh < r) {
         const float* Ph = P0 + (int64_t)hh * n_splits * kPartialStrideM;
-        float M = -INFINITY;
-        for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ld_agent(Ph + s * kPartialStrideM + 2 * kHeadDim));
-        if (M > -INFINITY) {
-          for (int s = 0; s < n_splits; ++s) {
-            const float* ps = Ph + s * kPartialStrideM;
-            const float e = fast_exp2(ld_agent(ps + 2 * kHeadDim) - M);
-            L = fmaf(e, ld_agent(ps + 2 * kHeadDim + 1), L);
-            rsum = fmaf(e, ld_agent(ps + c), rsum);
-            mm = fmaf(e, ld_agent(ps + kHeadDim + c), mm);
+        constexpr int SFAST = 8;
+        if (n_splits <= SFAST) {
+          // few splits: every load is issued before the first use, one memory round trip in all
+          float pm[SFAST], pl[SFAST], pr[SFAST], pq[SFAST];
+#pragma unroll
+          for (int s = 0; s < SFAST; ++s) {
+            const float* ps = Ph + min(s, n_splits - 1) * kPartialStrideM;
+            pm[s] = ld_agent(ps + 2 * kHeadDim);
+            pl[s] = ld_agent(ps + 2 * kHeadDim + 1);
+            pr[s] = ld_agent(ps + c);
+            pq[s] = ld_agent(ps + kHeadDim + c);
+          }
+          float M = -INFINITY;
+#pragma unroll
+          for (int s = 0; s < SFAST; ++s) M = fmaxf(M, pm[s]);  // slots past n_splits repeat the last split
+          if (M > -INFINITY) {
+#pragma unroll
+            for (int s = 0; s < SFAST; ++s) {
+              const float e = s < n_splits ? fast_exp2(pm[s] - M) : 0.f;
+              L = fmaf(e, pl[s], L);
+              rsum = fmaf(e, pr[s], rsum);
+              mm = fmaf(e, pq[s], mm);
+            }
+          }
+        } else {
+          float M = -INFINITY;
+          for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ld_agent(Ph + s * kPartialStrideM + 2 * kHeadDim));
+          if (M > -INFINITY) {
+            for (int s = 0; s < n_splits; ++s) {
+              const float* ps = Ph + s * kPartialStrideM;
+              const float e = fast_exp2(ld_agent(ps + 2 * kHeadDim) - M);
+              L = fmaf(e, ld_agent(ps + 2 * kHeadDim + 1), L);
+              rsum = fmaf(e, ld_agent(ps + c), rsum);
+              mm = fmaf(e, ld_agent(ps + kHeadDim + c), mm);
+            }
           }
         }
       }
