@@ -843,81 +843,73 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   }
   __syncthreads();
   if (!*sm_is_last) return;
-  float* rot = sm_rot;  // [4][128]
-  const float* P0 = partial + (int64_t)(b * g.n_q_heads + hq0) * n_splits * kPartialStrideM;
-  float mm_keep[(4 * kHeadDim + NT - 1) / NT], L_keep[(4 * kHeadDim + NT - 1) / NT];
-  {
-    int slot = 0;
-    for (int i = tid; i < 4 * kHeadDim; i += NT, ++slot) {
-      const int hh = i >> 7, c = i & 127;
-      float L = 0.f, rsum = 0.f, mm = 0.f;
-      if (hh < r) {
-        const float* Ph = P0 + (int64_t)hh * n_splits * kPartialStrideM;
-        constexpr int SFAST = 8;
-        if (n_splits <= SFAST) {
-          // few splits: every load is issued before the first use, one memory round trip in all
-          float pm[SFAST], pl[SFAST], pr[SFAST], pq[SFAST];
+  // One wave per query head: a lane owns channels 2 lane and 2 lane + 1, merges them over the
+  // splits, and the inverse Hadamard (H is its own inverse) runs across the wave's lanes in
+  // registers - no LDS, no barriers.
+  if (wave >= r) return;
+  const int hh = wave;
+  const float* Ph = partial + ((int64_t)(b * g.n_q_heads + hq0 + hh) * n_splits) * kPartialStrideM;
+  auto ld2 = [](const float* p) -> float2 {  // 8-byte device-scope load (p is 8-byte aligned)
+    const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32)));
+  };
+  float L = 0.f, x0 = 0.f, x1 = 0.f, mm0 = 0.f, mm1 = 0.f;
+  constexpr int SFAST = 8;
+  if (n_splits <= SFAST) {
+    // few splits: every load is issued before the first use, one memory round trip in all
+    float2 pml[SFAST], pr[SFAST], pq[SFAST];
 #pragma unroll
-          for (int s = 0; s < SFAST; ++s) {
-            const float* ps = Ph + min(s, n_splits - 1) * kPartialStrideM;
-            pm[s] = ld_agent(ps + 2 * kHeadDim);
-            pl[s] = ld_agent(ps + 2 * kHeadDim + 1);
-            pr[s] = ld_agent(ps + c);
-            pq[s] = ld_agent(ps + kHeadDim + c);
-          }
-          float M = -INFINITY;
+    for (int s = 0; s < SFAST; ++s) {
+      const float* ps = Ph + min(s, n_splits - 1) * kPartialStrideM;  // slots past n_splits repeat the last split
+      pml[s] = ld2(ps + 2 * kHeadDim);
+      pr[s] = ld2(ps + 2 * lane);
+      pq[s] = ld2(ps + kHeadDim + 2 * lane);
+    }
+    float M = -INFINITY;
 #pragma unroll
-          for (int s = 0; s < SFAST; ++s) M = fmaxf(M, pm[s]);  // slots past n_splits repeat the last split
-          if (M > -INFINITY) {
+    for (int s = 0; s < SFAST; ++s) M = fmaxf(M, pml[s].x);
+    if (M > -INFINITY) {
 #pragma unroll
-            for (int s = 0; s < SFAST; ++s) {
-              const float e = s < n_splits ? fast_exp2(pm[s] - M) : 0.f;
-              L = fmaf(e, pl[s], L);
-              rsum = fmaf(e, pr[s], rsum);
-              mm = fmaf(e, pq[s], mm);
-            }
-          }
-        } else {
-          float M = -INFINITY;
-          for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ld_agent(Ph + s * kPartialStrideM + 2 * kHeadDim));
-          if (M > -INFINITY) {
-            for (int s = 0; s < n_splits; ++s) {
-              const float* ps = Ph + s * kPartialStrideM;
-              const float e = fast_exp2(ld_agent(ps + 2 * kHeadDim) - M);
-              L = fmaf(e, ld_agent(ps + 2 * kHeadDim + 1), L);
-              rsum = fmaf(e, ld_agent(ps + c), rsum);
-              mm = fmaf(e, ld_agent(ps + kHeadDim + c), mm);
-            }
-          }
-        }
+      for (int s = 0; s < SFAST; ++s) {
+        const float e = s < n_splits ? fast_exp2(pml[s].x - M) : 0.f;
+        L = fmaf(e, pml[s].y, L);
+        x0 = fmaf(e, pr[s].x, x0);
+        x1 = fmaf(e, pr[s].y, x1);
+        mm0 = fmaf(e, pq[s].x, mm0);
+        mm1 = fmaf(e, pq[s].y, mm1);
       }
-      rot[i] = rsum;
-      mm_keep[slot] = mm;
-      L_keep[slot] = L;
     }
-  }
-  for (int s = 1; s < kHeadDim; s <<= 1) {  // one inverse Hadamard per head (H is its own inverse)
-    __syncthreads();
-    for (int i = tid; i < 4 * 64; i += NT) {
-      const int hh = i >> 6, k = i & 63;
-      const int lo = ((k & ~(s - 1)) << 1) | (k & (s - 1));
-      const float a0 = rot[hh * kHeadDim + lo], a1 = rot[hh * kHeadDim + lo + s];
-      rot[hh * kHeadDim + lo] = a0 + a1;
-      rot[hh * kHeadDim + lo + s] = a0 - a1;
-    }
-  }
-  __syncthreads();
-  {
-    int slot = 0;
-    for (int i = tid; i < 4 * kHeadDim; i += NT, ++slot) {
-      const int hh = i >> 7, c = i & 127;
-      if (hh < r) {
-        const float L = L_keep[slot];
-        out[(int64_t)(b * g.n_q_heads + hq0 + hh) * kHeadDim + c] =
-            L > 0.f ? (rot[i] * (float)kInvSqrtD + mm_keep[slot]) / L : 0.f;
+  } else {
+    float M = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ld_agent(Ph + s * kPartialStrideM + 2 * kHeadDim));
+    if (M > -INFINITY) {
+      for (int s = 0; s < n_splits; ++s) {
+        const float* ps = Ph + s * kPartialStrideM;
+        const float2 ml = ld2(ps + 2 * kHeadDim), pr = ld2(ps + 2 * lane), pq = ld2(ps + kHeadDim + 2 * lane);
+        const float e = fast_exp2(ml.x - M);
+        L = fmaf(e, ml.y, L);
+        x0 = fmaf(e, pr.x, x0);
+        x1 = fmaf(e, pr.y, x1);
+        mm0 = fmaf(e, pq.x, mm0);
+        mm1 = fmaf(e, pq.y, mm1);
       }
     }
   }
+  {
+    const float a0 = x0 + x1, a1 = x0 - x1;
+    x0 = a0, x1 = a1;
+  }
+  static_for<6>([&](auto kc) {  // lane bit k <-> element bit k + 1
+    constexpr int m = 1 << decltype(kc)::value;
+    const float p0 = xor_lane<m>(x0), p1 = xor_lane<m>(x1);
+    const bool upper = (lane & m) != 0;
+    x0 = upper ? p0 - x0 : x0 + p0;
+    x1 = upper ? p1 - x1 : x1 + p1;
+  });
+  float2 o2 = make_float2(0.f, 0.f);
+  if (L > 0.f) o2 = make_float2((x0 * (float)kInvSqrtD + mm0) / L, (x1 * (float)kInvSqrtD + mm1) / L);
+  *reinterpret_cast<float2*>(out + (int64_t)(b * g.n_q_heads + hq0 + hh) * kHeadDim + 2 * lane) = o2;
 }
 
 #ifdef NSN_DECODE_TIMING
