@@ -161,26 +161,25 @@ __device__ long long g_dec_timing[48];
 //   [0, 64 KiB)        codebook table: entry (code c, copy p) at c * 256 + p * (2 * SUB) bytes,
 //                      32 copies of 8 B (SUB = 4) or 16 copies of 16 B (SUB = 8);
 //                      after the main loop the same bytes hold the per-wave accumulators
-//   [64 KiB, +(NW+1)*2KiB) prologue: staged codewords, q, rotated q;
-//                      main loop: mean-vector term of every wave, accm[NW + 1][4][128]
-//                      (slot NW belongs to the residual wave, present only in residual launches)
-//   then 2 KiB         the unrotated query (read again when a wave enters another Shift group)
-//   tail               per-wave (m, l), the "last workgroup" flag, inverse-Hadamard scratch
-// One workgroup of 8 waves per compute unit shares a single table (64 + 16 KiB of the 160 KiB).
+//   then 8.25 KiB      staged codewords, unrotated query (read again when a wave enters another
+//                      Shift group), rotated query, q . o^k of the split's first group
+//   then (NW+1)*2 KiB  mean-vector term of every wave, accm[NW + 1][4][128] (slot NW belongs to
+//                      the residual wave, present only in residual launches)
+//   tail               per-wave (m, l), the "last workgroup" flag
+// One workgroup of 8 waves per compute unit shares a single table (about 92 of the 160 KiB).
 template <int SUB, int NW, bool SGN = false>
 struct DecSmem {
   // sign + index format: a 4 KiB table of sign masks sits in front of the codebook table
   static constexpr int kSignLutBytes = SGN ? 4096 : 0;
   static constexpr int kTable = kTableBytes + kSignLutBytes;
-  static constexpr int kUnionBytes = (NW + 1) * 4 * kHeadDim * 4;  // + the residual wave's slot
+  static constexpr int kStageBytes = ((kCodes * 2 * SUB + 2 * 4 * kHeadDim * 4 + 16) + 255) & ~255;
+  static constexpr int kAccmOffset = kTable + kStageBytes;
+  static constexpr int kAccmBytes = (NW + 1) * 4 * kHeadDim * 4;  // + the residual wave's slot
   static constexpr int kRaccBytes = NW * (64 / (kHeadDim / SUB)) * 4 * kHeadDim * 4;
   static constexpr int kTailBytes = (2 * (NW + 1) * 4 + 4 + 4 * kHeadDim) * 4;
-  static constexpr int kQueryBytes = 4 * kHeadDim * 4;  // unrotated query, kept for the q . o^k of later Shift groups
-  static constexpr int kQueryOffset = kTable + kUnionBytes;
   static constexpr bool kTailInTable = kRaccBytes + kTailBytes <= kTable;
-  static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kQueryOffset + kQueryBytes;
-  static constexpr int kBytes = kQueryOffset + kQueryBytes + (kTailInTable ? 0 : kTailBytes);
-  static_assert(kUnionBytes >= kCodes * 2 * SUB + 2 * 4 * kHeadDim * 4 + 16, "prologue scratch must fit");
+  static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kAccmOffset + kAccmBytes;
+  static constexpr int kBytes = kAccmOffset + kAccmBytes + (kTailInTable ? 0 : kTailBytes);
   static_assert(kRaccBytes <= kTable, "per-wave accumulators must fit in the table region");
 };
 
@@ -213,12 +212,12 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   using SM = DecSmem<SUB, NW, SGN>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   unsigned char* const sm_table = smem_raw;
-  unsigned char* const sm_stage = smem_raw + SM::kTable;                           // prologue only
+  unsigned char* const sm_stage = smem_raw + SM::kTable;
   float(*const sm_q_orig)[kHeadDim] = reinterpret_cast<float(*)[kHeadDim]>(sm_stage + kCodes * 2 * SUB);
   float(*const sm_q_had)[kHeadDim] = sm_q_orig + 4;
-  float(*const sm_q_keep)[kHeadDim] = reinterpret_cast<float(*)[kHeadDim]>(smem_raw + SM::kQueryOffset);
+  float(*const sm_q_keep)[kHeadDim] = sm_q_orig;  // stays valid for the whole kernel
   float* const sm_qo_first = &sm_q_had[4][0];  // q . o^k of the split's first Shift group, four heads
-  float(*const sm_accm)[4][kHeadDim] = reinterpret_cast<float(*)[4][kHeadDim]>(smem_raw + SM::kTable);
+  float(*const sm_accm)[4][kHeadDim] = reinterpret_cast<float(*)[4][kHeadDim]>(smem_raw + SM::kAccmOffset);
   float(*const sm_wave_m)[4] = reinterpret_cast<float(*)[4]>(smem_raw + SM::kTailOffset);  // after the loop
   float(*const sm_wave_l)[4] = sm_wave_m + (NW + 1);
   int* const sm_is_last = reinterpret_cast<int*>(sm_wave_l + (NW + 1));
@@ -334,10 +333,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
 #pragma unroll
   for (int u = 0; u < QPT; ++u) {
     const int i = tid + u * NT;
-    if (i < 4 * kHeadDim) {
-      sm_q_orig[i >> 7][i & 127] = qv[u];
-      sm_q_keep[i >> 7][i & 127] = qv[u];
-    }
+    if (i < 4 * kHeadDim) sm_q_orig[i >> 7][i & 127] = qv[u];
   }
   __syncthreads();
   NSN_TSTAMP(12);
@@ -435,7 +431,6 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
         float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sm_qo_first[i < R ? i : 0])));
   const uint32_t laneoff = (SUB == 4) ? (lane & 31) * 8 : (lane & 15) * 16;
   const uint32_t laneoff8 = (lane & 31) * 8;  // sign-mask table: 32 copies of 8 bytes per 256-byte row
-  __syncthreads();  // the prologue scratch is dead: its bytes become the per-wave mean-term accumulators
 #pragma unroll
   for (int i = 0; i < 4; ++i)  // wave-private; every lane owns channels 2 lane, 2 lane + 1 of each head
     *reinterpret_cast<float2*>(&sm_accm[wave][i][2 * lane]) = make_float2(0.f, 0.f);
