@@ -856,10 +856,14 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     float2 pml[SFAST], pr[SFAST], pq[SFAST];
 #pragma unroll
     for (int s = 0; s < SFAST; ++s) {
-      const float* ps = Ph + min(s, n_splits - 1) * kPartialStrideM;  // slots past n_splits repeat the last split
-      pml[s] = ld2(ps + 2 * kHeadDim);
-      pr[s] = ld2(ps + 2 * lane);
-      pq[s] = ld2(ps + kHeadDim + 2 * lane);
+      pml[s] = make_float2(-INFINITY, 0.f);
+      pr[s] = pq[s] = make_float2(0.f, 0.f);
+      if (s < n_splits) {  // uniform
+        const float* ps = Ph + s * kPartialStrideM;
+        pml[s] = ld2(ps + 2 * kHeadDim);
+        pr[s] = ld2(ps + 2 * lane);
+        pq[s] = ld2(ps + kHeadDim + 2 * lane);
+      }
     }
     float M = -INFINITY;
 #pragma unroll
