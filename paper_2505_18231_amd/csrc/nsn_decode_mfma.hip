@@ -799,20 +799,31 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   float* P = partial + ((int64_t)(b * g.n_q_heads + hq0) * n_splits + split) * kPartialStrideM;
   for (int i = tid; i < r * kHeadDim; i += NT) {
     const int hh = i >> 7, c = i & 127;
-    float M = -INFINITY;
-    for (int wv = 0; wv < n_waves; ++wv) M = fmaxf(M, sm_wave_m[wv][hh]);
-    float L = 0.f, orot = 0.f, omean = 0.f;
-    for (int wv = 0; wv < n_waves; ++wv) {
-      const float mw = sm_wave_m[wv][hh];
-      const float e = (mw == -INFINITY) ? 0.f : fast_exp2(mw - M);
-      L = fmaf(e, sm_wave_l[wv][hh], L);
-      if (wv < NW) {
-        float part = 0.f;
+    // all LDS reads go out before the first use (fixed trip counts, the residual wave's slot
+    // predicated), instead of one dependent read per wave
+    float mw[NW + 1], lw[NW + 1], part[NW + 1], mean[NW + 1];
 #pragma unroll
-        for (int pt = 0; pt < NPART; ++pt) part += racc[((wv * NPART + pt) * 4 + hh) * kHeadDim + c];
-        orot = fmaf(e, part, orot);
+    for (int wv = 0; wv <= NW; ++wv) {
+      const bool present = wv < n_waves;  // uniform: slot NW exists in residual launches only
+      mw[wv] = present ? sm_wave_m[wv][hh] : -INFINITY;
+      lw[wv] = present ? sm_wave_l[wv][hh] : 0.f;
+      mean[wv] = present ? sm_accm[wv][hh][c] : 0.f;
+      part[wv] = 0.f;
+      if (wv < NW) {
+#pragma unroll
+        for (int pt = 0; pt < NPART; ++pt) part[wv] += racc[((wv * NPART + pt) * 4 + hh) * kHeadDim + c];
       }
-      omean = fmaf(e, sm_accm[wv][hh][c], omean);
+    }
+    float M = -INFINITY;
+#pragma unroll
+    for (int wv = 0; wv <= NW; ++wv) M = fmaxf(M, mw[wv]);
+    float L = 0.f, orot = 0.f, omean = 0.f;
+#pragma unroll
+    for (int wv = 0; wv <= NW; ++wv) {
+      const float e = (mw[wv] == -INFINITY) ? 0.f : fast_exp2(mw[wv] - M);
+      L = fmaf(e, lw[wv], L);
+      orot = fmaf(e, part[wv], orot);
+      omean = fmaf(e, mean[wv], omean);
     }
     float* Ph = P + (int64_t)hh * n_splits * kPartialStrideM;
     st_agent(Ph + c, orot);
