@@ -172,7 +172,8 @@ struct DecSmem {
   // sign + index format: a 4 KiB table of sign masks sits in front of the codebook table
   static constexpr int kSignLutBytes = SGN ? 4096 : 0;
   static constexpr int kTable = kTableBytes + kSignLutBytes;
-  static constexpr int kStageBytes = ((kCodes * 2 * SUB + 2 * 4 * kHeadDim * 4 + 16) + 255) & ~255;
+  static constexpr int kQoTabGroups = 64;  // q . o^k of up to 64 Shift groups of a split, four heads each
+  static constexpr int kStageBytes = ((kCodes * 2 * SUB + 2 * 4 * kHeadDim * 4 + 16 + kQoTabGroups * 16) + 255) & ~255;
   static constexpr int kAccmOffset = kTable + kStageBytes;
   static constexpr int kAccmBytes = (NW + 1) * 4 * kHeadDim * 4;  // + the residual wave's slot
   static constexpr int kRaccBytes = NW * (64 / (kHeadDim / SUB)) * 4 * kHeadDim * 4;
@@ -217,6 +218,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   float(*const sm_q_had)[kHeadDim] = sm_q_orig + 4;
   float(*const sm_q_keep)[kHeadDim] = sm_q_orig;  // stays valid for the whole kernel
   float* const sm_qo_first = &sm_q_had[4][0];  // q . o^k of the split's first Shift group, four heads
+  float4* const sm_qo_tab = reinterpret_cast<float4*>(sm_qo_first + 4);  // [kQoTabGroups], 16-byte aligned
   float(*const sm_accm)[4][kHeadDim] = reinterpret_cast<float(*)[4][kHeadDim]>(smem_raw + SM::kAccmOffset);
   float(*const sm_wave_m)[4] = reinterpret_cast<float(*)[4]>(smem_raw + SM::kTailOffset);  // after the loop
   float(*const sm_wave_l)[4] = sm_wave_m + (NW + 1);
@@ -322,6 +324,24 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   if (wave >= 4 && wave - 4 < R)
     ok_pre = *reinterpret_cast<const __half2*>(
         reinterpret_cast<const unsigned char*>(kc.means + (mean_base + grp_pre) * kHeadDim) + lane_x4);
+  // With several Shift groups per split (group_size > 0), wave 5 forms q . o^k of all of them at
+  // once: lane j owns group g_first + j, its fp16 mean row is the B operand of the same contraction
+  // that the residual tokens use (unrotated query hi + lo as the A operand), 64 MFMAs in the
+  // shadow of the table fill instead of four wave-wide sums per group and wave in the main loop.
+  const int g_first = grp_pre;
+  int n_tab = 0;
+  if (g.group_size > 0) {
+    const int g_last = group_of(g, min(t0 + per - 1, g.page_tokens * g.pages_per_seq - 1));
+    n_tab = g_last - g_first + 1;
+    if (n_tab > SM::kQoTabGroups) n_tab = 0;  // very long splits keep the in-loop form
+  }
+  uint4 orow[16];  // one 256-byte mean row
+  const bool tab_wave = (wave == 5) && n_tab > 0;
+  if (tab_wave) {
+    const uint4* rp = reinterpret_cast<const uint4*>(kc.means + (mean_base + min(g_first + lane, g.n_groups_max - 1)) * kHeadDim);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) orow[u] = (lane < n_tab) ? rp[u] : make_uint4(0u, 0u, 0u, 0u);
+  }
   const int len = seq_lens[b];  // scalar load in flight; first used after the prologue
 #ifdef NSN_DECODE_TIMING
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -369,6 +389,39 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     const float dot = wave_sum_u(sm_q_orig[hh][2 * lane] * __low2float(ok_pre) +
                                  sm_q_orig[hh][2 * lane + 1] * __high2float(ok_pre));
     if (lane == 0) sm_qo_first[hh] = dot * scale_log2e;
+  }
+  if (tab_wave) {
+    h4 AH[2], AL[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const int row = lane & 3;
+      const int head = PACK ? row % R : row;
+      const bool is_lo = PACK && row >= R, dead = (PACK && row >= 2 * R) || head >= r;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float x = dead ? 0.f : sm_q_orig[head][4 * (16 * p + (lane >> 2)) + k] * scale_log2e;
+        const _Float16 hi = (_Float16)x;
+        const _Float16 lo = (_Float16)(x - (float)hi);
+        AH[p][k] = is_lo ? lo : hi;
+        AL[p][k] = lo;
+      }
+    }
+    f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+    static_for<16>([&](auto uc) {  // 16 bytes = slots 2u, 2u + 1 (four channels each)
+      constexpr int u = decltype(uc)::value;
+      const h4 b0 = as_h4(orow[u].x, orow[u].y), b1 = as_h4(orow[u].z, orow[u].w);
+      d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(AH[(2 * u) / 16], b0, d0, 4, (2 * u) % 16, 0);
+      d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(AH[(2 * u + 1) / 16], b1, d1, 4, (2 * u + 1) % 16, 0);
+      if constexpr (!PACK) {
+        d0 = __builtin_amdgcn_mfma_f32_4x4x4f16(AL[(2 * u) / 16], b0, d0, 4, (2 * u) % 16, 0);
+        d1 = __builtin_amdgcn_mfma_f32_4x4x4f16(AL[(2 * u + 1) / 16], b1, d1, 4, (2 * u + 1) % 16, 0);
+      }
+    });
+    float4 t4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float* tv = &t4.x;
+#pragma unroll
+    for (int i = 0; i < R; ++i) tv[i] = PACK ? (d0[i] + d0[R + i]) + (d1[i] + d1[R + i]) : d0[i] + d1[i];
+    if (lane < n_tab) sm_qo_tab[lane] = t4;
   }
   {  // replicate the staged codewords with 16-byte LDS writes (8-byte codewords go out in pairs);
     // the four waves that rotated a query head take 6 of the 16-byte slots per thread, the others 10
@@ -618,7 +671,12 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     const int grp = group_of(g, tg);
     if (grp != cur_group) {
       if (cur_group >= 0) flush_group();
-      if (grp == grp_pre) {
+      if (grp - g_first < n_tab) {  // n_tab > 0 only with group_size > 0
+        const float4 t4 = sm_qo_tab[grp - g_first];
+        const float tv[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+        for (int i = 0; i < R; ++i) qo[i] = tv[i];
+      } else if (grp == grp_pre) {
 #pragma unroll
         for (int i = 0; i < R; ++i) qo[i] = qo_pre[i];
       } else {
