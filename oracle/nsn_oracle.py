@@ -37,6 +37,13 @@ Parity pins (tests/test_oracle_*.py, all CPU):
                       fixed assignment and is orthogonal to its codeword; the cosine
                       similarity rises.  Optimiser, rate and step count are this build's
                       reading: "parity unpinned" against the paper's tuned codebook (Sec. 3.4)
+  rope / pre-RoPE keys   a hand-computed 4-channel rotation (fixes pairing and sense of rotation);
+                      complex-multiplication form; scores depend on the position difference only;
+                      zero frequencies reduce encode / decode to the plain path; the restore
+                      identity RoPE(x) = s1 (s2 RoPE(v_nsn) + RoPE(o)); App. B's two-branch score
+                      with the query turned back instead of the mean turned forward.  Pairing,
+                      frequencies and positions are this build's reading (the paper names its
+                      models' RoPE without restating it)
 """
 from __future__ import annotations
 
@@ -157,6 +164,25 @@ def scale_adjust(v: np.ndarray, vq: np.ndarray) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
+# Rotary position embedding as the Llama-family models of the paper's experiments apply it:
+# channel i and channel i + d/2 form a pair that turns by the angle position * inv_freq[i].
+# Sec. 3.2 ("NSN applied to key and value") normalises keys BEFORE this rotation: the rotation
+# is applied to v_nsn on the way into the quantiser and to the stored mean o inside the score
+# computation (App. B).
+# ----------------------------------------------------------------------------
+def rope(x: np.ndarray, positions, inv_freq) -> np.ndarray:
+    """Rows of x [l][d] rotated by their positions [l]; inv_freq [d/2] (radians per position)."""
+    x = np.asarray(x, dtype=F64)
+    half = x.shape[1] // 2
+    ang = np.asarray(positions, dtype=F64)[:, None] * np.asarray(inv_freq, dtype=F64)[None, :]
+    c, s = np.cos(ang), np.sin(ang)
+    out = np.empty_like(x)
+    out[:, :half] = x[:, :half] * c - x[:, half:] * s
+    out[:, half:] = x[:, half:] * c + x[:, :half] * s
+    return out
+
+
+# ----------------------------------------------------------------------------
 # Encoder: NSN -> Hadamard -> VQ -> scale adjustment, with the three fp16 storage
 # rounding points (b = s1, o, a = s1 s2 alpha); rounded b and o are the values used
 # downstream, so that dequantisation is self-consistent.
@@ -199,7 +225,8 @@ def signed_codewords(idx: np.ndarray, sgn: np.ndarray, codebook: np.ndarray) -> 
 
 def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: int = 0,
            frozen_o: np.ndarray | None = None, given_b: np.ndarray | None = None,
-           given_o: np.ndarray | None = None, return_debug: bool = False, sign_format: bool = False):
+           given_o: np.ndarray | None = None, return_debug: bool = False, sign_format: bool = False,
+           rope_inv_freq=None):
     """Encode tokens [start, start+l) of one (sequence, kv-head, tensor) unit.
 
     x16       fp16 [l][d]
@@ -210,6 +237,9 @@ def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: in
               second stage is checked conditioned on the first stage's stored values)
     sign_format: codebook = 256 non-negative 8-dim magnitude codewords; codes are then
               u8 [l][2 d/8]: the d/8 indices followed by the d/8 sign bytes
+    rope_inv_freq: [d/2] - x16 holds keys BEFORE the rotary embedding (Sec. 3.2): NSN runs on them
+              as they are, v_nsn of token t is rotated by position start + t, then quantised;
+              the stored mean o stays un-rotated
     returns dict(codes u8 [l][d/sub], a fp16 [l], b fp16 [l], o fp16 [n_groups][d])
     """
     x = np.asarray(x16, dtype=F64)
@@ -232,6 +262,9 @@ def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: in
     s2 = token_scale(ns)
     vnsn = _safe_div(ns, s2[:, None])
 
+    if rope_inv_freq is not None:
+        vnsn = rope(vnsn, start + np.arange(l), rope_inv_freq)
+
     # Hadamard rotation (dense mat-vec), then Eq. (1) on contiguous sub-vectors
     y = vnsn @ H.T
     if sign_format:
@@ -252,13 +285,15 @@ def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: in
 
     out = dict(codes=codes.astype(np.uint8), a=a16, b=b16, o=o16)
     if return_debug:
-        out.update(y=y, s2=s2, alpha=alpha, best=best.reshape(l, -1), second=second.reshape(l, -1))
+        out.update(y=y, s2=s2, alpha=alpha, best=best.reshape(l, -1), second=second.reshape(l, -1), vnsn=vnsn)
     return out
 
 
 def dequantize(codes, a16, b16, o16, codebook, group_size: int = 0, start: int = 0,
-               sign_format: bool = False) -> np.ndarray:
-    """x_hat_t = b_t o_g + a_t H^T y_Q,t  (restore identity of Sec. 3.2 with s2 alpha in a)."""
+               sign_format: bool = False, rope_inv_freq=None) -> np.ndarray:
+    """x_hat_t = b_t o_g + a_t H^T y_Q,t  (restore identity of Sec. 3.2 with s2 alpha in a).
+    With rope_inv_freq (keys coded before the rotary embedding) the result is the key AFTER it:
+    the mean enters as RoPE_t(o_g) (App. B, second line of the derivation)."""
     c = np.asarray(codebook, dtype=F64)
     l, J = codes.shape
     if sign_format:
@@ -273,17 +308,22 @@ def dequantize(codes, a16, b16, o16, codebook, group_size: int = 0, start: int =
     a = np.asarray(a16, dtype=F64)
     b = np.asarray(b16, dtype=F64)
     o = np.asarray(o16, dtype=F64)
-    return b[:, None] * o[g] + a[:, None] * (yq @ H)  # H^T = H^-1; row form: yq @ H
+    mean_part = o[g]
+    if rope_inv_freq is not None:
+        mean_part = rope(mean_part, start + np.arange(l), rope_inv_freq)
+    return b[:, None] * mean_part + a[:, None] * (yq @ H)  # H^T = H^-1; row form: yq @ H
 
 
 # ----------------------------------------------------------------------------
-# Decode attention over a coded cache (App. B, with RoPE dropped: keys are taken as given)
+# Decode attention over a coded cache (App. B; keys are taken as given unless rope_inv_freq is passed)
 # ----------------------------------------------------------------------------
 def decode_attention(q, kc: dict, vc: dict, codebook, softmax_scale: float,
-                     group_size: int = 0, sign_format: bool = False) -> np.ndarray:
-    """out = softmax(scale * q K_hat^T) V_hat for q [r][d] (r query heads on one kv head)."""
+                     group_size: int = 0, sign_format: bool = False, rope_inv_freq=None) -> np.ndarray:
+    """out = softmax(scale * q K_hat^T) V_hat for q [r][d] (r query heads on one kv head).
+    rope_inv_freq: the key cache was coded before the rotary embedding; q is the query after it."""
     q = np.atleast_2d(np.asarray(q, dtype=F64))
-    k_hat = dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], codebook, group_size, sign_format=sign_format)
+    k_hat = dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], codebook, group_size, sign_format=sign_format,
+                       rope_inv_freq=rope_inv_freq)
     v_hat = dequantize(vc["codes"], vc["a"], vc["b"], vc["o"], codebook, group_size, sign_format=sign_format)
     s = softmax_scale * (q @ k_hat.T)
     s = s - s.max(axis=1, keepdims=True)
@@ -312,6 +352,30 @@ def lut_scores(q, kc: dict, codebook, softmax_scale: float, group_size: int = 0)
         gathered = lut[np.arange(J)[None, :], codes].sum(axis=1)
         q_o = o @ q[r]                                   # [n_groups]
         out[r] = softmax_scale * (a * gathered + b * q_o[g])
+    return out
+
+
+def two_branch_scores_rope(q, kc: dict, codebook, softmax_scale: float, inv_freq, group_size: int = 0) -> np.ndarray:
+    """App. B's last line for keys coded before the rotary embedding:
+    s1 s2 q_Had . v_Q + s1 q . RoPE_t(o), the second branch evaluated as RoPE_{-t}(q) . o (the
+    rotation is orthogonal, so it can be taken off the mean and put on the query with the
+    opposite angle).  Independent of `dequantize`; must agree with q . K_hat."""
+    q = np.atleast_2d(np.asarray(q, dtype=F64))
+    c = np.asarray(codebook, dtype=F64)
+    codes = kc["codes"].astype(np.int64)
+    l, J = codes.shape
+    H = hadamard(J * c.shape[1])
+    q_had = q @ H.T
+    g = group_index(l, group_size)
+    a = np.asarray(kc["a"], dtype=F64)
+    b = np.asarray(kc["b"], dtype=F64)
+    o = np.asarray(kc["o"], dtype=F64)
+    out = np.zeros((q.shape[0], l), dtype=F64)
+    for r in range(q.shape[0]):
+        for t in range(l):
+            first = float(q_had[r] @ c[codes[t]].reshape(-1))
+            q_back = rope(q[r][None, :], [-t], inv_freq)[0]
+            out[r, t] = softmax_scale * (a[t] * first + b[t] * float(q_back @ o[g[t]]))
     return out
 
 
@@ -411,13 +475,16 @@ def avg_bits(code_bits_per_dim: float, head_dim: int, group_size: int) -> float:
 # tokens are still fp16 and take part in the same softmax as the coded tokens
 # ----------------------------------------------------------------------------
 def decode_attention_residual(q, kc: dict, vc: dict, k_res16, v_res16, codebook, softmax_scale: float,
-                              group_size: int = 0, sign_format: bool = False) -> np.ndarray:
-    """out = softmax(scale * q [K_hat ; K_res]^T) [V_hat ; V_res]; the coded part may be empty."""
+                              group_size: int = 0, sign_format: bool = False, rope_inv_freq=None) -> np.ndarray:
+    """out = softmax(scale * q [K_hat ; K_res]^T) [V_hat ; V_res]; the coded part may be empty.
+    rope_inv_freq: the coded keys were normalised before the rotary embedding; k_res16 holds the
+    residual keys AFTER it (as attention uses them)."""
     q = np.atleast_2d(np.asarray(q, dtype=F64))
     k_res = np.asarray(k_res16, dtype=F64).reshape(-1, q.shape[1])
     v_res = np.asarray(v_res16, dtype=F64).reshape(-1, q.shape[1])
     if kc["codes"].shape[0] > 0:
-        k_hat = dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], codebook, group_size, sign_format=sign_format)
+        k_hat = dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], codebook, group_size, sign_format=sign_format,
+                           rope_inv_freq=rope_inv_freq)
         v_hat = dequantize(vc["codes"], vc["a"], vc["b"], vc["o"], codebook, group_size, sign_format=sign_format)
         k_all = np.concatenate([k_hat, k_res], axis=0)
         v_all = np.concatenate([v_hat, v_res], axis=0)

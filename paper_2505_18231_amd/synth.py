@@ -89,6 +89,11 @@ def codebook_samples(seed: int, n: int, sub_dim: int) -> np.ndarray:
     return g.standard_normal((n, sub_dim), dtype=np.float32)
 
 
+def rope_inv_freq(base: float = 10000.0, d: int = HEAD_DIM) -> np.ndarray:
+    """Rotary-embedding frequencies of a model configuration: fp32 [d/2], base ** (-2 i / d)."""
+    return (float(base) ** (-np.arange(d // 2, dtype=np.float64) * 2.0 / d)).astype(np.float32)
+
+
 def shuffled_page_table(seed: int, batch: int, pages_per_seq: int) -> np.ndarray:
     """A permutation of physical pages: int32 [batch][pages_per_seq] (for the paged layout)."""
     g = _rng(seed, "misc", 0, 0, extra=1)

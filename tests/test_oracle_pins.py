@@ -418,3 +418,97 @@ def test_sign_format_round_trip_and_bit_count():
     s = 0.1 * q @ kh.T
     p = np.exp(s - s.max(axis=1, keepdims=True))
     assert np.allclose(out, (p / p.sum(axis=1, keepdims=True)) @ vh, rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------- rotary embedding, keys normalised before it
+def test_rope_hand_computed_rotation():
+    # d = 4: pairs (0, 2) and (1, 3).  Position 1 with frequencies (pi/2, pi): the pair (1, 3) turns a
+    # quarter turn counter-clockwise to (-3, 1), the pair (2, 4) a half turn to (-2, -4).
+    got = O.rope(np.array([[1.0, 2.0, 3.0, 4.0]]), [1], [math.pi / 2, math.pi])
+    assert np.allclose(got, [[-3.0, -2.0, 1.0, -4.0]], atol=1e-14)
+    # position 0 leaves a row alone, two positions add up
+    x = np.random.default_rng(5).standard_normal((3, D))
+    f = synth.rope_inv_freq(10000.0)
+    assert np.array_equal(O.rope(x, [0, 0, 0], f), x)
+    assert np.allclose(O.rope(O.rope(x, [3, 5, 7], f), [10, 20, 30], f), O.rope(x, [13, 25, 37], f), atol=1e-12)
+
+
+def test_rope_equals_complex_multiplication_and_keeps_relative_position():
+    g = np.random.default_rng(6)
+    x = g.standard_normal((4, D))
+    f = synth.rope_inv_freq(500000.0).astype(np.float64)
+    pos = np.array([0, 17, 4096, 131071])
+    z = (x[:, :64] + 1j * x[:, 64:]) * np.exp(1j * pos[:, None] * f[None, :])
+    assert np.allclose(O.rope(x, pos, f), np.concatenate([z.real, z.imag], axis=1), atol=1e-9)
+    # norm kept; the score of a rotated query and a rotated key depends on the position difference only
+    assert np.allclose(np.linalg.norm(O.rope(x, pos, f), axis=1), np.linalg.norm(x, axis=1))
+    q, k = g.standard_normal((1, D)), g.standard_normal((1, D))
+    s0 = float((O.rope(q, [100], f) @ O.rope(k, [40], f).T)[0, 0])
+    s1 = float((O.rope(q, [5060], f) @ O.rope(k, [5000], f).T)[0, 0])
+    assert abs(s0 - s1) < 1e-9
+    assert abs(s0 - float((O.rope(q, [60], f) @ k.T)[0, 0])) < 1e-9
+
+
+@pytest.mark.parametrize("sub,G,sign", [(4, 64, False), (8, 0, False), (8, 64, True)])
+def test_pre_rope_encode_restores_the_rotated_key(sub, G, sign):
+    f = synth.rope_inv_freq(10000.0)
+    L = 192
+    x16 = synth.make_k(77, 0, 0, L)
+    cb = np.abs(_rand_codebook(3, sub)) if sign else _rand_codebook(3, sub)
+    enc = O.encode(x16, cb, G, return_debug=True, sign_format=sign, rope_inv_freq=f)
+    # zero frequencies: nothing turns, the plain encoder's result
+    plain = O.encode(x16, cb, G, sign_format=sign)
+    still = O.encode(x16, cb, G, sign_format=sign, rope_inv_freq=np.zeros(64))
+    assert np.array_equal(plain["codes"], still["codes"]) and np.array_equal(plain["a"], still["a"])
+    # side information does not see the rotation at all
+    assert np.array_equal(plain["b"], enc["b"]) and np.array_equal(plain["o"], enc["o"])
+    assert not np.array_equal(plain["codes"], enc["codes"])
+    # restore identity through the rotation (it is linear): RoPE(x) = b (s2 RoPE(v_nsn) + RoPE(o))
+    pos = np.arange(L)
+    gidx = O.group_index(L, G)
+    b, o = enc["b"].astype(np.float64), enc["o"].astype(np.float64)
+    want = O.rope(x16.astype(np.float64), pos, f)
+    got = b[:, None] * (enc["s2"][:, None] * enc["vnsn"] + O.rope(o[gidx], pos, f))
+    assert np.allclose(got, want, rtol=0, atol=1e-9 * np.abs(want).max())
+    # the coded key dequantises to the key AFTER the embedding; error orthogonal to the rotated
+    # token in the Hadamard domain (scale adjustment), up to the fp16 rounding of a
+    k_hat = O.dequantize(enc["codes"], enc["a"], enc["b"], enc["o"], cb, G, sign_format=sign, rope_inv_freq=f)
+    rel = np.linalg.norm(k_hat - want) / np.linalg.norm(want)
+    k_hat_plain = O.dequantize(plain["codes"], plain["a"], plain["b"], plain["o"], cb, G, sign_format=sign)
+    rel_plain = np.linalg.norm(k_hat_plain - x16.astype(np.float64)) / np.linalg.norm(x16.astype(np.float64))
+    assert rel < 1.5 * rel_plain + 1e-3, (rel, rel_plain)
+    H = O.hadamard(D)
+    resid = (k_hat - want) @ H.T                      # = a y_Q - b s2 y
+    y = enc["y"]
+    cosang = np.abs(np.sum(resid * y, axis=1)) / (np.linalg.norm(resid, axis=1) * np.linalg.norm(y, axis=1) + 1e-300)
+    assert cosang.max() < 2e-3
+
+
+def test_pre_rope_scores_two_branch_form_and_attention():
+    f = synth.rope_inv_freq(10000.0)
+    L, G, sub = 130, 64, 4
+    cb = _rand_codebook(9, sub)
+    kc = O.encode(synth.make_k(78, 0, 0, L), cb, G, rope_inv_freq=f)
+    vc = O.encode(synth.make_v(78, 0, 0, L), cb, G)
+    q = synth.make_q(78, 1, 2)[0].astype(np.float64)
+    scale = 1.0 / math.sqrt(D)
+    k_hat = O.dequantize(kc["codes"], kc["a"], kc["b"], kc["o"], cb, G, rope_inv_freq=f)
+    want = scale * (q @ k_hat.T)
+    got = O.two_branch_scores_rope(q, kc, cb, scale, f, G)
+    assert np.allclose(got, want, rtol=0, atol=1e-10 * np.abs(want).max())
+    # the un-rotated mean gives different scores: the rotation is not a no-op on this data
+    assert np.abs(O.lut_scores(q, kc, cb, scale, G) - want).max() > 1e-2
+    # attention = plain softmax attention over the dequantised (rotated) keys, written with loops
+    out = O.decode_attention(q, kc, vc, cb, scale, G, rope_inv_freq=f)
+    v_hat = O.dequantize(vc["codes"], vc["a"], vc["b"], vc["o"], cb, G)
+    for r in range(2):
+        w = [math.exp(want[r, t] - want[r].max()) for t in range(L)]
+        ref = sum(w[t] * v_hat[t] for t in range(L)) / sum(w)
+        assert np.allclose(out[r], ref, atol=1e-12)
+    # residual form: the fp16 rows enter as they are
+    k_res, v_res = synth.make_k(78, 0, 0, 5, start=L), synth.make_v(78, 0, 0, 5, start=L)
+    out_r = O.decode_attention_residual(q, kc, vc, k_res, v_res, cb, scale, G, rope_inv_freq=f)
+    s_all = np.concatenate([want, scale * (q @ k_res.astype(np.float64).T)], axis=1)
+    p = np.exp(s_all - s_all.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    assert np.allclose(out_r, p @ np.concatenate([v_hat, v_res.astype(np.float64)]), atol=1e-12)
