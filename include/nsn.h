@@ -7,6 +7,8 @@
  *                         nearest-codeword search, scale adjustment          (Sec. 3.2, 3.3, Eq. 1)
  *   nsn_decode_attention  single-query attention straight from the coded
  *                         cache                                              (App. B)
+ * plus nsn_finetune_codebook (Sec. 3.4), nsn_decode_attention_residual (Sec. 3.2 "Residual") and
+ * nsn_build_rope_table (keys normalised before the rotary embedding, Sec. 3.2 / App. B).
  *
  * Conventions
  *   - Plain C, no exceptions cross this boundary.  Every call returns an int status:
@@ -85,6 +87,10 @@ typedef struct nsn_shape {
                          or 0 = one group per sequence */
   int32_t page_size;  /* 0 = contiguous; else tokens per page, multiple of 64 */
   int32_t max_len;    /* token capacity per sequence, multiple of 64 (and of page_size) */
+  const void* rope_table; /* NULL: keys are coded as given.  Else dev table written by
+                             nsn_build_rope_table for a max_len >= this one: the K input of
+                             nsn_encode holds keys BEFORE the rotary embedding (Sec. 3.2 "NSN applied
+                             to key and value"); see nsn_build_rope_table for what changes */
 } nsn_shape;
 
 typedef struct nsn_cache {
@@ -107,6 +113,32 @@ typedef struct nsn_residual {
   const int32_t* lens; /* dev int32 [batch], 0 .. capacity */
   int32_t capacity;    /* rows per (sequence, kv head): 1 .. 64 (the paper uses 64) */
 } nsn_residual;
+
+/*
+ * Keys normalised before the rotary embedding (Sec. 3.2 "NSN applied to key and value", App. B).
+ * The embedding meant is the Llama-family one: channel i and channel i + 64 form a pair that
+ * turns by the angle position * inv_freq[i]; the position of a token is its index in the sequence.
+ * With shape->rope_table set,
+ *   nsn_encode  runs Normalize-Shift-Normalize on the K rows as given (before the embedding),
+ *               turns v_nsn of every token by its position, then rotates, searches and adjusts as
+ *               usual; b and the stored mean o are those of the un-embedded keys.  V is unaffected.
+ *   nsn_decode_attention[_residual]  take the query AFTER the embedding and turn the mean inside
+ *               the kernel:  score_t = softmax_scale * (a_t HT(q) . C[codes_t] + b_t q . RoPE_t(o_g(t))).
+ *               Residual K rows are the keys after the embedding (as attention uses them); the
+ *               caller keeps the un-embedded copies for the nsn_encode call that empties the residual.
+ * The table holds cosines and sines evaluated in fp64: of 64 * block * inv_freq[i] per 64-token
+ * block (fp64 and fp32 copies), of j * inv_freq[i] for j < 64 (fp64, and as fp16 hi + lo pairs for
+ * the matrix cores); angles of a token are composed from the two by the addition theorems.  A table
+ * built for a larger max_len serves every smaller one.
+ *   inv_freq_host  host fp32 [64]
+ *   max_len        positions covered, a positive multiple of 64
+ *   table_dev      out, dev, nsn_rope_table_bytes(max_len) bytes, 256-byte aligned
+ * Enqueues one kernel on `stream`; the table may be used by later calls on the same stream.
+ * Errors: INVALID_ARG (null pointer, max_len, table_bytes too small), HIP.
+ */
+size_t nsn_rope_table_bytes(int max_len);
+int nsn_build_rope_table(const float* inv_freq_host, int max_len, void* table_dev, size_t table_bytes,
+                         void* stream);
 
 /* Byte offset of the code of (token t, sub-vector j) inside a placement unit; J = codes per token. */
 int64_t nsn_k_code_offset(int J, int64_t t, int j);
@@ -193,8 +225,8 @@ int nsn_encode(const nsn_shape* shape, const void* codebook_dev, const void* k_f
                const nsn_cache* v_cache, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * One decode step of attention over the coded cache (App. B with keys taken as given, i.e.
- * without the in-kernel RoPE of the mean):
+ * One decode step of attention over the coded cache (App. B; the mean enters as stored unless
+ * shape->rope_table is set, see nsn_build_rope_table):
  *   score_t = softmax_scale * ( a^k_t * HT(q) . C[codes^k_t] + b^k_t * q . o^k_g(t) )
  *   out     = sum_t softmax(score)_t * ( a^v_t * H^T C[codes^v_t] + b^v_t * o^v_g(t) )
  *   q_fp16       dev fp16 [batch][n_q_heads][head_dim]; query head hq reads kv head

@@ -23,7 +23,7 @@ HEAD_DIM, N_CODES = 128, 256
 
 class nsn_shape(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("head_dim", "sub_dim", "n_codes", "n_q_heads", "n_kv_heads",
-                                         "group_size", "page_size", "max_len")]
+                                         "group_size", "page_size", "max_len")] + [("rope_table", C.c_void_p)]
 
 
 class nsn_cache(C.Structure):
@@ -64,6 +64,9 @@ def lib() -> C.CDLL:
                                          C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
         L.nsn_finetune_codebook.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_double,
                                             C.c_void_p, C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nsn_rope_table_bytes.restype = C.c_size_t
+        L.nsn_rope_table_bytes.argtypes = [C.c_int]
+        L.nsn_build_rope_table.argtypes = [C.POINTER(C.c_float), C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
         L.nsn_encode.argtypes = [C.POINTER(nsn_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                  C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.POINTER(nsn_cache),
                                  C.POINTER(nsn_cache), C.c_void_p, C.c_size_t, C.c_void_p]
@@ -96,11 +99,27 @@ SIGN_CODES = 65536  # n_codes of the sign + index format: 256 magnitude codeword
 
 
 def make_shape(sub_dim: int, n_q_heads: int, n_kv_heads: int, max_len: int, group_size: int = 0,
-               page_size: int = 0, sign_format: bool = False) -> nsn_shape:
-    """sign_format: the paper's 2-bit format (8 sign bits + 8-bit index per 8-dim sub-vector)."""
+               page_size: int = 0, sign_format: bool = False, rope_table: torch.Tensor | None = None) -> nsn_shape:
+    """sign_format: the paper's 2-bit format (8 sign bits + 8-bit index per 8-dim sub-vector).
+    rope_table: result of nsn_build_rope_table - keys are normalised before the rotary embedding."""
     assert not sign_format or sub_dim == 8
-    return nsn_shape(HEAD_DIM, sub_dim, SIGN_CODES if sign_format else N_CODES, n_q_heads, n_kv_heads, group_size,
-                     page_size, max_len)
+    shape = nsn_shape(HEAD_DIM, sub_dim, SIGN_CODES if sign_format else N_CODES, n_q_heads, n_kv_heads, group_size,
+                      page_size, max_len, _ptr(rope_table))
+    shape._rope_keepalive = rope_table  # the struct only holds the address
+    return shape
+
+
+def nsn_build_rope_table(inv_freq, max_len: int, device="cuda") -> torch.Tensor:
+    """inv_freq: 64 fp32 values (host).  Returns the device table (uint8) for positions < max_len."""
+    import numpy as np
+    f = np.ascontiguousarray(np.asarray(inv_freq, dtype=np.float32))
+    assert f.shape == (HEAD_DIM // 2,)
+    need = lib().nsn_rope_table_bytes(max_len)
+    assert need > 0, "max_len must be a positive multiple of 64"
+    table = torch.empty(need, dtype=torch.uint8, device=device)
+    _check(lib().nsn_build_rope_table(f.ctypes.data_as(C.POINTER(C.c_float)), max_len, table.data_ptr(), need,
+                                      _stream()))
+    return table
 
 
 def code_bytes_per_token(shape: nsn_shape) -> int:

@@ -43,6 +43,10 @@ static int check_shape(const nsn_shape* s) {
     set_error("max_len=%d must be a positive multiple of 64", s->max_len);
     return NSN_ERR_INVALID_ARG;
   }
+  if (s->rope_table && (reinterpret_cast<uintptr_t>(s->rope_table) & 255) != 0) {
+    set_error("rope_table must be 256-byte aligned");
+    return NSN_ERR_INVALID_ARG;
+  }
   if (s->page_size < 0 || s->page_size % 64 != 0 || (s->page_size > 0 && s->max_len % s->page_size != 0)) {
     set_error("page_size=%d must be 0 or a multiple of 64 dividing max_len=%d", s->page_size, s->max_len);
     return NSN_ERR_INVALID_ARG;
@@ -77,6 +81,23 @@ int nsn_max_groups(const nsn_shape* shape) {
 }
 
 const char* nsn_last_error(void) { return g_err; }
+
+size_t nsn_rope_table_bytes(int max_len) {
+  return (max_len > 0 && max_len % 64 == 0) ? rope_table_bytes(max_len) : 0;
+}
+
+int nsn_build_rope_table(const float* inv_freq_host, int max_len, void* table_dev, size_t table_bytes,
+                         void* stream) {
+  if (!inv_freq_host || !table_dev || max_len <= 0 || max_len % 64 != 0 ||
+      (reinterpret_cast<uintptr_t>(table_dev) & 255) != 0 || table_bytes < rope_table_bytes(max_len)) {
+    set_error("build_rope_table: null pointer, max_len=%d not a positive multiple of 64, table not 256-byte aligned "
+              "or smaller than %zu bytes", max_len, max_len > 0 ? rope_table_bytes(max_len) : (size_t)0);
+    return NSN_ERR_INVALID_ARG;
+  }
+  const int rc = rope_table_build(inv_freq_host, max_len, table_dev, static_cast<hipStream_t>(stream));
+  if (rc == NSN_ERR_HIP) set_error("build_rope_table: launch failed: %s", hipGetErrorString(hipGetLastError()));
+  return rc;
+}
 
 size_t nsn_workspace_bytes(const nsn_shape* shape, int op, int batch, int64_t n, int n_splits) {
   if (op == NSN_OP_CODEBOOK) {
@@ -181,6 +202,10 @@ static int decode_common(const nsn_shape* shape, const void* codebook_dev, const
       set_error("decode: the lookup-table kernel (NSN_DECODE_IMPL=lut) has no residual form");
       return NSN_ERR_UNSUPPORTED;
     }
+  }
+  if (shape->rope_table && !decode_use_mfma(*shape)) {
+    set_error("decode: the lookup-table kernel (NSN_DECODE_IMPL=lut) does not turn the mean (rope_table set)");
+    return NSN_ERR_UNSUPPORTED;
   }
   if (batch == 0) return NSN_OK;
   const int splits = decode_pick_splits(*shape, batch, max_seq_len, n_splits);

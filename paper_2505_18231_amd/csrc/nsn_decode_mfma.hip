@@ -25,6 +25,7 @@
 namespace nsn {
 
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef _Float16 h8d __attribute__((ext_vector_type(8)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int kPartialStrideM = 2 * kHeadDim + 2;  // rotated acc, mean-term acc, m (log2 units), l
@@ -166,8 +167,11 @@ __device__ long long g_dec_timing[48];
 //   then (NW+1)*2 KiB  mean-vector term of every wave, accm[NW + 1][4][128] (slot NW belongs to
 //                      the residual wave, present only in residual launches)
 //   tail               per-wave (m, l), the "last workgroup" flag
+//   ROPE only: 32 KiB  fp16 hi and lo parts of (cos, sin)(j * inv_freq[i]), rows of 256 bytes whose
+//                      16-byte chunks are XOR-swizzled by the row number (conflict-free operand reads)
+//              32 KiB  per wave, q . RoPE_t(o^k) of the 64 tokens of its next four groups, four heads each
 // One workgroup of 8 waves per compute unit shares a single table (about 92 of the 160 KiB).
-template <int SUB, int NW, bool SGN = false>
+template <int SUB, int NW, bool SGN = false, bool ROPE = false>
 struct DecSmem {
   // sign + index format: a 4 KiB table of sign masks sits in front of the codebook table
   static constexpr int kSignLutBytes = SGN ? 4096 : 0;
@@ -180,7 +184,14 @@ struct DecSmem {
   static constexpr int kTailBytes = (2 * (NW + 1) * 4 + 4 + 4 * kHeadDim) * 4;
   static constexpr bool kTailInTable = kRaccBytes + kTailBytes <= kTable;
   static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kAccmOffset + kAccmBytes;
-  static constexpr int kBytes = kAccmOffset + kAccmBytes + (kTailInTable ? 0 : kTailBytes);
+  static constexpr int kPlainBytes = kAccmOffset + kAccmBytes + (kTailInTable ? 0 : kTailBytes);
+  static constexpr int kRopeBatch = 4;  // groups per wave whose mean term is formed in one go
+  static constexpr int kRopeTabOffset = (kPlainBytes + 255) & ~255;
+  static constexpr int kRopeTabBytes = 2 * 64 * 256;
+  static constexpr int kRopeDotOffset = kRopeTabOffset + kRopeTabBytes;
+  static constexpr int kRopeDotBytes = NW * kRopeBatch * 64 * 16;
+  static constexpr int kBytes = ROPE ? kRopeDotOffset + kRopeDotBytes : kPlainBytes;
+  static_assert(kBytes <= 160 * 1024, "LDS of one compute unit");
   static_assert(kRaccBytes <= kTable, "per-wave accumulators must fit in the table region");
 };
 
@@ -190,7 +201,16 @@ struct DecSmem {
 // SGN = the sign + index format (Sec. 3.4): SUB = 8, code bytes [0,16) of a token are indices into a
 // codebook of magnitudes, bytes [16,32) the sign bytes; a gathered codeword gets its sign bits from
 // two 8-byte mask entries (one per sign nibble) of a small replicated table, XORed in before the MFMA.
-template <int SUB, int NW, int R, bool SGN = false>
+// ROPE = the keys were normalised before the rotary embedding (Sec. 3.2 "NSN applied to key and value"):
+// the mean term of the score is b_t * q . RoPE_t(o) (App. B).  With t = 64 * block + j and the pair
+// (i, i + 64) of channels,   q . RoPE_t(o) = sum_i cos(j w_i) A'_i + sin(j w_i) B'_i,   where
+//   A_i = q_i o_i + q_i' o_i',  B_i = q_i' o_i - q_i o_i'   (i' = i + 64)
+//   A'_i = A_i c_i + B_i s_i,   B'_i = B_i c_i - A_i s_i,   (c_i, s_i) = (cos, sin)(64 * block * w_i):
+// a [64 tokens x 128] x [128 x heads] contraction whose token-side operand is the same for every
+// group.  A wave forms it for its next four groups at once with v_mfma_f32_16x16x32_f16 (rows = (group,
+// head), columns = 16 tokens; fp16 hi + lo parts on both sides, three products), leaves the 64 x 4
+// results per group in LDS, and the main loop reads one 16-byte entry per lane and group.
+template <int SUB, int NW, int R, bool SGN = false, bool ROPE = false>
 __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, const __half* __restrict__ codebook,
                                                            const __half* __restrict__ q, CacheView kc,
                                                            CacheView vc, const int32_t* __restrict__ seq_lens,
@@ -210,7 +230,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   constexpr int NT = NW * 64;
   constexpr bool PACK = (R <= 2);  // hi and lo rows in one A operand
   constexpr int CH = SGN ? 2 : 8;  // key-side gathers in flight per chunk (a sign-format gather is 8 registers)
-  using SM = DecSmem<SUB, NW, SGN>;
+  using SM = DecSmem<SUB, NW, SGN, ROPE>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   unsigned char* const sm_table = smem_raw;
   unsigned char* const sm_stage = smem_raw + SM::kTable;
@@ -223,7 +243,9 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   float(*const sm_wave_m)[4] = reinterpret_cast<float(*)[4]>(smem_raw + SM::kTailOffset);  // after the loop
   float(*const sm_wave_l)[4] = sm_wave_m + (NW + 1);
   int* const sm_is_last = reinterpret_cast<int*>(sm_wave_l + (NW + 1));
-  float* const sm_rot = reinterpret_cast<float*>(sm_is_last + 4);
+  unsigned char* const sm_rope_tab = smem_raw + SM::kRopeTabOffset;  // ROPE only
+  float4(*const sm_rope_dot)[SM::kRopeBatch][64] =
+      reinterpret_cast<float4(*)[SM::kRopeBatch][64]>(smem_raw + SM::kRopeDotOffset);
 
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   // this launch handles query heads [head_off, head_off + r_pass) of every kv head (r_pass <= 4;
@@ -313,6 +335,14 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     const int i = tid + u * NT, hh = i >> 7, c = i & 127;
     qv[u] = (i < 4 * kHeadDim && hh < r) ? __half2float(q[(int64_t)(b * g.n_q_heads + hq0 + hh) * kHeadDim + c]) : 0.f;
   }
+  // ROPE: the fp16 cosine / sine rows go to LDS with the codebook (four 16-byte chunks per thread)
+  uint4 trow[4] = {};
+  if constexpr (ROPE) {
+    if (main_wave) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) trow[u] = reinterpret_cast<const uint4*>(g.rope + kRopeHiOff)[tid + u * NT];
+    }
+  }
   Grp cur;
   const bool spec = main_wave && !g.paged && (t0 + (wave << 6) + 64 <= g.page_tokens);  // in bounds whatever the length
   if (spec) load_group(wave, cur);
@@ -321,7 +351,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   static_assert(NW == 8, "prologue work split assumes 8 waves: 4 rotate the query, 4 do the rest");
   const int grp_pre = group_of(g, min(t0, g.page_tokens * g.pages_per_seq - 1));
   __half2 ok_pre = __half2{};
-  if (wave >= 4 && wave - 4 < R)
+  if (!ROPE && wave >= 4 && wave - 4 < R)
     ok_pre = *reinterpret_cast<const __half2*>(
         reinterpret_cast<const unsigned char*>(kc.means + (mean_base + grp_pre) * kHeadDim) + lane_x4);
   // With several Shift groups per split (group_size > 0), wave 5 forms q . o^k of all of them at
@@ -330,7 +360,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   // shadow of the table fill instead of four wave-wide sums per group and wave in the main loop.
   const int g_first = grp_pre;
   int n_tab = 0;
-  if (g.group_size > 0) {
+  if (!ROPE && g.group_size > 0) {
     const int g_last = group_of(g, min(t0 + per - 1, g.page_tokens * g.pages_per_seq - 1));
     n_tab = g_last - g_first + 1;
     if (n_tab > SM::kQoTabGroups) n_tab = 0;  // very long splits keep the in-loop form
@@ -354,6 +384,16 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   for (int u = 0; u < QPT; ++u) {
     const int i = tid + u * NT;
     if (i < 4 * kHeadDim) sm_q_orig[i >> 7][i & 127] = qv[u];
+  }
+  if constexpr (ROPE) {
+    if (main_wave) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int c = tid + u * NT;  // chunk c: part (hi / lo) c >> 10, row (c >> 4) & 63, 16-byte chunk c & 15
+        const int row = (c >> 4) & 63;
+        *reinterpret_cast<uint4*>(sm_rope_tab + (c >> 10) * 16384 + row * 256 + (((c & 15) ^ (row & 15)) << 4)) = trow[u];
+      }
+    }
   }
   __syncthreads();
   NSN_TSTAMP(12);
@@ -384,7 +424,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       *reinterpret_cast<uint2*>(sm_table + n * 256 + (tid & 31) * 8) = make_uint2(w0, w1);
     }
   }
-  if (wave >= 4 && wave - 4 < R) {
+  if (!ROPE && wave >= 4 && wave - 4 < R) {
     const int hh = wave - 4;
     const float dot = wave_sum_u(sm_q_orig[hh][2 * lane] * __low2float(ok_pre) +
                                  sm_q_orig[hh][2 * lane + 1] * __high2float(ok_pre));
@@ -648,9 +688,74 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     return wop;
   };
 
+  // ROPE: q . RoPE_t(o^k) (log2 units) for the 64 tokens of this wave's groups gi0, gi0 + NW, ... (four of
+  // them): lane (m = lane % 16, kq = lane / 16) supplies row (group m / 4, head m % 4) of the turned
+  // products A', B' at channels 32 ks + 8 kq + e and column m of the token-side table.
+  auto rope_batch = [&](int gi0) {
+    const int m = lane & 15, bi = m >> 2, head = m & 3, kq = lane >> 4;
+    // groups past the end repeat the last one (their results are never read)
+    const int tg = min(t0 + ((gi0 + NW * bi) << 6), (t1 - 1) & ~63);
+    const __half* orow = kc.means + (mean_base + group_of(g, tg)) * kHeadDim;
+    const unsigned char* rec = g.rope + kRopeBlkOff + (int64_t)(tg >> 6) * kRopeBlkStride;
+    h8d AH[4], AL[4];
+#pragma unroll
+    for (int ksp = 0; ksp < 2; ++ksp) {
+      const int i0 = 32 * ksp + 8 * kq;  // first of eight pairs (i, i + 64)
+      const uint4 oa4 = *reinterpret_cast<const uint4*>(orow + i0);
+      const uint4 ob4 = *reinterpret_cast<const uint4*>(orow + 64 + i0);
+      const h8d oa = __builtin_bit_cast(h8d, oa4), ob = __builtin_bit_cast(h8d, ob4);
+      float cs[16], qa[8], qb[8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float4 c4 = reinterpret_cast<const float4*>(rec)[(i0 >> 1) + u];  // (cos, sin) of two pairs
+        cs[4 * u] = c4.x, cs[4 * u + 1] = c4.y, cs[4 * u + 2] = c4.z, cs[4 * u + 3] = c4.w;
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const float4 a4 = *reinterpret_cast<const float4*>(&sm_q_keep[head][i0 + 4 * u]);
+        const float4 b4 = *reinterpret_cast<const float4*>(&sm_q_keep[head][64 + i0 + 4 * u]);
+        qa[4 * u] = a4.x, qa[4 * u + 1] = a4.y, qa[4 * u + 2] = a4.z, qa[4 * u + 3] = a4.w;
+        qb[4 * u] = b4.x, qb[4 * u + 1] = b4.y, qb[4 * u + 2] = b4.z, qb[4 * u + 3] = b4.w;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = qa[e] * scale_log2e, y = qb[e] * scale_log2e;
+        const float o0 = (float)oa[e], o1 = (float)ob[e];
+        const float A = x * o0 + y * o1, B = y * o0 - x * o1;
+        const float Ap = A * cs[2 * e] + B * cs[2 * e + 1], Bp = B * cs[2 * e] - A * cs[2 * e + 1];
+        const _Float16 ah = (_Float16)Ap, bh = (_Float16)Bp;
+        AH[ksp][e] = ah;
+        AL[ksp][e] = (_Float16)(Ap - (float)ah);
+        AH[ksp + 2][e] = bh;
+        AL[ksp + 2][e] = (_Float16)(Bp - (float)bh);
+      }
+    }
+#pragma unroll
+    for (int tile = 0; tile < 4; ++tile) {
+      f4 d = {0.f, 0.f, 0.f, 0.f};
+      const uint32_t row_addr = SM::kRopeTabOffset + (16 * tile + m) * 256;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const uint32_t a = row_addr + (((4 * ks + kq) ^ m) << 4);
+        const h8d th = __builtin_bit_cast(h8d, lds_read128(a));
+        const h8d tl = __builtin_bit_cast(h8d, lds_read128(a + 16384));
+        d = __builtin_amdgcn_mfma_f32_16x16x32_f16(AH[ks], th, d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x32_f16(AL[ks], th, d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x32_f16(AH[ks], tl, d, 0, 0, 0);
+      }
+      // this lane holds group kq, token 16 tile + m, heads 0..3
+      sm_rope_dot[wave][kq][16 * tile + m] = make_float4(d[0], d[1], d[2], d[3]);
+    }
+    // the entries are read back by other lanes of this wave
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+
   NSN_TSTAMP(2);
   // ---- main loop: this wave's 64-token groups, next group's loads in flight ------------------
-  for (int gi = wave; gi < n_grp; gi += NW) {
+  int it = 0;  // this wave's iteration count
+  for (int gi = wave; gi < n_grp; gi += NW, ++it) {
     NSN_TSTAMP(3 + (gi / NW < 6 ? gi / NW : 6));
     const int tg = t0 + (gi << 6);  // first token of the group (multiple of 64)
     const bool valid = (tg + lane) < t1;
@@ -669,9 +774,18 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
 
     // Shift group bookkeeping (wave-uniform): mean term of the old group, q . o^k of the new one
     const int grp = group_of(g, tg);
+    if constexpr (ROPE) {
+      if ((it & (SM::kRopeBatch - 1)) == 0) rope_batch(gi);
+      const float4 rd = sm_rope_dot[wave][it & (SM::kRopeBatch - 1)][lane];
+      const float rv[4] = {rd.x, rd.y, rd.z, rd.w};
+#pragma unroll
+      for (int i = 0; i < R; ++i) qo[i] = rv[i];
+    }
     if (grp != cur_group) {
       if (cur_group >= 0) flush_group();
-      if (grp - g_first < n_tab) {  // n_tab > 0 only with group_size > 0
+      if constexpr (ROPE) {
+        // the mean term is per token (above)
+      } else if (grp - g_first < n_tab) {  // n_tab > 0 only with group_size > 0
         const float4 t4 = sm_qo_tab[grp - g_first];
         const float tv[4] = {t4.x, t4.y, t4.z, t4.w};
 #pragma unroll
@@ -987,21 +1101,21 @@ extern "C" int nsn_debug_decode_timing(long long* host48) {
 #endif
 
 // ---------------------------------------------------------------------------------------
-template <int SUB, int NW, int R, bool SGN = false>
+template <int SUB, int NW, int R, bool SGN = false, bool ROPE = false>
 static int launch_one(const Geometry& g, const void* codebook, const void* q, const CacheView& kv,
                       const CacheView& vv, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                       int n_splits, void* workspace, size_t counter_bytes, const ResidualView& res, int head_off,
                       int r_pass, float* out, hipStream_t stream) {
-  const size_t smem = DecSmem<SUB, NW, SGN>::kBytes;
+  const size_t smem = DecSmem<SUB, NW, SGN, ROPE>::kBytes;
   static bool attr_done = false;
   if (!attr_done) {
     // the gathers address the codebook table by absolute LDS address: it must start at 0,
     // i.e. the kernel may not own any static LDS in front of its dynamic block
     hipFuncAttributes fa;
-    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN>)) != hipSuccess ||
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN, ROPE>)) != hipSuccess ||
         fa.sharedSizeBytes != 0)
       return NSN_ERR_HIP;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN, ROPE>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return NSN_ERR_HIP;
     attr_done = true;
@@ -1011,7 +1125,7 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
   float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + counter_bytes);
   const dim3 grid(n_splits, g.n_kv_heads, batch);
   const int waves = res.k != nullptr ? NW + 1 : NW;  // + the residual wave
-  dec_mfma_kernel<SUB, NW, R, SGN><<<grid, waves * 64, smem, stream>>>(
+  dec_mfma_kernel<SUB, NW, R, SGN, ROPE><<<grid, waves * 64, smem, stream>>>(
       g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens, scale * 1.44269504088896340736f, n_splits,
       per, partial, counters, res, head_off, r_pass, out);
   return NSN_OK;
@@ -1052,7 +1166,16 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
 #define NSN_ARGS \
   g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, cb, res, head_off, r, out, stream
     int rc;
-    if (g.sign)
+    if (g.rope && g.sign)
+      rc = r == 1 ? launch_one<8, 8, 1, true, true>(NSN_ARGS) : r == 2 ? launch_one<8, 8, 2, true, true>(NSN_ARGS)
+                                                                        : launch_one<8, 8, 4, true, true>(NSN_ARGS);
+    else if (g.rope && s.sub_dim == 4)
+      rc = r == 1 ? launch_one<4, 8, 1, false, true>(NSN_ARGS) : r == 2 ? launch_one<4, 8, 2, false, true>(NSN_ARGS)
+                                                                         : launch_one<4, 8, 4, false, true>(NSN_ARGS);
+    else if (g.rope)
+      rc = r == 1 ? launch_one<8, 8, 1, false, true>(NSN_ARGS) : r == 2 ? launch_one<8, 8, 2, false, true>(NSN_ARGS)
+                                                                         : launch_one<8, 8, 4, false, true>(NSN_ARGS);
+    else if (g.sign)
       rc = r == 1 ? launch_one<8, 8, 1, true>(NSN_ARGS) : r == 2 ? launch_one<8, 8, 2, true>(NSN_ARGS)
                                                                   : launch_one<8, 8, 4, true>(NSN_ARGS);
     else if (s.sub_dim == 4)

@@ -33,7 +33,15 @@ struct ResidualView {
 
 constexpr int kSignCodes = 65536;  // n_codes value that selects the sign + index format
 
+// Table of nsn_build_rope_table (byte offsets): fp16 hi / lo of (cos, sin)(j * inv_freq[i]) as
+// rows [j][128] (64 cosines, then 64 sines), the same angles in fp64 as (cos, sin) pairs [j][i],
+// then one 1536-byte record per 64-token block: (cos, sin)(64 * block * inv_freq[i]) as 64 fp32
+// pairs followed by 64 fp64 pairs.
+constexpr int kRopeHiOff = 0, kRopeLoOff = 16384, kRopeInOff = 32768, kRopeBlkOff = 32768 + 65536;
+constexpr int kRopeBlkStride = 1536, kRopeBlk64 = 512;
+
 struct Geometry {
+  const unsigned char* rope;  // table of nsn_build_rope_table, or nullptr (keys coded as given)
   int sign;         // 1: an 8-dim sub-vector is an index byte plus a sign byte (byte rows 0..15 / 16..31)
   int J;            // code bytes per token
   int n_q_heads, n_kv_heads;

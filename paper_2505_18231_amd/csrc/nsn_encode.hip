@@ -137,7 +137,9 @@ extern "C" int nsn_debug_encode_timing(long long* host16) {
 // instruction-level parallelism and doubles the register count of the whole kernel.
 // SIGN:  the paper's 2-bit format (Sec. 3.4): the search runs on the absolute values against a
 //        codebook of magnitudes; byte row jj holds the index, byte row 16 + jj the eight sign bits
-template <int SUB, bool MFMA, bool FUSED, bool SIGN = false>
+// ROPE:  the K rows are keys before the rotary embedding (Sec. 3.2 "NSN applied to key and value"):
+//        v_nsn is turned by the token's position between the second Normalize and the Hadamard rotation
+template <int SUB, bool MFMA, bool FUSED, bool SIGN = false, bool ROPE = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 4 : 3))) void enc_quant_kernel(Geometry g, const __half* __restrict__ codebook,
                                                         const __half* __restrict__ k_in,
                                                         const __half* __restrict__ v_in, int max_new,
@@ -165,7 +167,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
   struct Tok {
     bool valid;
     int64_t base;
-    int tin;
+    int tin, pos;
     vec_t xraw, oraw;
     __half b16;
   };
@@ -174,6 +176,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
     const int t = t_begin + it * TPW + tk;
     const int pos = start + t;
     k.valid = (t < count) && (pos < max_len);
+    k.pos = pos;
     k.base = 0;
     k.tin = 0;
     k.xraw = vec_t{};
@@ -241,6 +244,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
     const double s2 = sqrt(ss) / kSqrtD;
 #pragma unroll
     for (int i = 0; i < SUB; ++i) v[i] = (s2 != 0.0) ? v[i] / s2 : 0.0;
+    if constexpr (ROPE) {
+      if (tensor == 0) {  // keys only; the partner channel c ^ 64 lives in lane jj ^ (J / 2)
+        // cos / sin of position * inv_freq[pair] from the fp64 table: block part and in-block part
+        // combined by the addition theorems
+        const int pc = min(max(cur.pos, 0), max_len - 1);  // lanes without a token hold zeros; keep them in bounds
+        const int pair0 = (jj % (J / 2)) * SUB;
+        const double2* blk = reinterpret_cast<const double2*>(g.rope + kRopeBlkOff +
+                                                              (int64_t)(pc >> 6) * kRopeBlkStride + kRopeBlk64) + pair0;
+        const double2* inb = reinterpret_cast<const double2*>(g.rope + kRopeInOff) + (pc & 63) * 64 + pair0;
+        const bool upper = jj >= J / 2;
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) {
+          const double other = xor_lane<J / 2>(v[i]);
+          const double2 c0 = blk[i], cj = inb[i];
+          const double c = c0.x * cj.x - c0.y * cj.y, sn = c0.y * cj.x + c0.x * cj.y;
+          v[i] = upper ? v[i] * c + other * sn : v[i] * c - other * sn;
+        }
+      }
+    }
     // Walsh-Hadamard butterflies: channel bits 0..log2(SUB)-1 in registers, the rest across lanes
 #pragma unroll
     for (int s = 1; s < SUB; s <<= 1) {
@@ -344,7 +366,14 @@ int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, co
     kernel<<<grid_b, 256, 0, stream>>>(g, (const __half*)codebook, (const __half*)k_in, (const __half*)v_in, max_new,
                                        s.max_len, seq_start, n_new, kv, vv, wave_tokens);
   };
-  if (g.sign) {
+  if (g.rope) {  // keys before the rotary embedding: matrix-core search only
+    if (g.sign)
+      freeze_means ? launch(enc_quant_kernel<8, true, true, true, true>) : launch(enc_quant_kernel<8, true, false, true, true>);
+    else if (s.sub_dim == 8)
+      freeze_means ? launch(enc_quant_kernel<8, true, true, false, true>) : launch(enc_quant_kernel<8, true, false, false, true>);
+    else
+      freeze_means ? launch(enc_quant_kernel<4, true, true, false, true>) : launch(enc_quant_kernel<4, true, false, false, true>);
+  } else if (g.sign) {
     if (use_mfma)
       freeze_means ? launch(enc_quant_kernel<8, true, true, true>) : launch(enc_quant_kernel<8, true, false, true>);
     else

@@ -7,6 +7,7 @@ namespace nsn {
 
 inline Geometry make_geometry(const nsn_shape& s) {
   Geometry g;
+  g.rope = static_cast<const unsigned char*>(s.rope_table);
   g.sign = s.n_codes == kSignCodes;
   g.J = g.sign ? 2 * (s.head_dim / s.sub_dim) : s.head_dim / s.sub_dim;
   g.n_q_heads = s.n_q_heads;
@@ -48,6 +49,9 @@ size_t decode_workspace_bytes(const nsn_shape& s, int batch, int n_splits);
 int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
                   const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                   int n_splits, const nsn_residual* residual, float* out, void* workspace, hipStream_t stream);
+
+size_t rope_table_bytes(int max_len);
+int rope_table_build(const float* inv_freq_host, int max_len, void* table_dev, hipStream_t stream);
 
 size_t codebook_workspace_bytes(int sub_dim, int64_t n_samples);
 int codebook_run(const float* samples, int64_t n_samples, int sub_dim, int iters, void* codebook_out,

@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 
 
 def run_gpu_encode(api, seed, batch, hkv, lens, sub, G, cb, page=0, per_seq=False, starts=None,
-                   freeze=False, caches=None, max_len=None, sign=False):
+                   freeze=False, caches=None, max_len=None, sign=False, rope_table=None):
     import torch
     J = 2 * (128 // sub) if sign else 128 // sub
     max_new = max(lens)
@@ -29,7 +29,7 @@ def run_gpu_encode(api, seed, batch, hkv, lens, sub, G, cb, page=0, per_seq=Fals
         for h in range(hkv):
             k[b, h, :lens[b]] = synth.make_k(seed, b, h, lens[b], per_seq=per_seq, start=starts[b])
             v[b, h, :lens[b]] = synth.make_v(seed, b, h, lens[b], start=starts[b])
-    shape = api.make_shape(sub, hkv, hkv, max_len, G, page, sign_format=sign)
+    shape = api.make_shape(sub, hkv, hkv, max_len, G, page, sign_format=sign, rope_table=rope_table)
     if caches is None:
         bt = synth.shuffled_page_table(seed, batch, max_len // page) if page else None
         hk = helpers.HostCache("k", batch, hkv, J, max_len, G, page, bt)
@@ -47,7 +47,7 @@ def run_gpu_encode(api, seed, batch, hkv, lens, sub, G, cb, page=0, per_seq=Fals
     return k, v, hk, hv
 
 
-def check_unit(x16, got, cb, G, start=0, frozen=None, sign=False):
+def check_unit(x16, got, cb, G, start=0, frozen=None, sign=False, rope_inv_freq=None):
     """got: dict(codes, a, b, o) read back from the device for tokens [start, start+L)."""
     L = x16.shape[0]
     b_ref, o_ref = O.shift_stats(x16, G, start, given_o=frozen)
@@ -56,7 +56,7 @@ def check_unit(x16, got, cb, G, start=0, frozen=None, sign=False):
         g_used = np.unique(O.group_index(L, G, start))
         assert np.array_equal(o_ref[g_used].view(np.uint16), got["o"][g_used].view(np.uint16)), "means"
     ref = O.encode(x16, cb, G, start=start, given_b=got["b"], given_o=got["o"], return_debug=True,
-                   sign_format=sign)
+                   sign_format=sign, rope_inv_freq=rope_inv_freq)
     same = ref["codes"] == got["codes"]
     near_tie = (ref["second"] - ref["best"]) < 1e-6 * np.maximum(ref["second"], 1e-300)
     if sign:  # [indices | sign bytes]: a sign byte has no tie, unless an entry of the rotated token is exactly 0

@@ -27,7 +27,8 @@ def test_exports_every_declared_symbol(L):
     names = set(re.findall(r"\b(nsn_[a-z_]+)\s*\(", header))
     names -= {"nsn_shape", "nsn_cache"}
     assert {"nsn_build_codebook", "nsn_finetune_codebook", "nsn_encode", "nsn_decode_attention",
-            "nsn_decode_attention_residual", "nsn_workspace_bytes"} <= names
+            "nsn_decode_attention_residual", "nsn_workspace_bytes", "nsn_build_rope_table",
+            "nsn_rope_table_bytes"} <= names
     for n in names:
         assert hasattr(L, n), n
 
@@ -77,6 +78,11 @@ def test_shape_validation_and_error_text(L):
     assert rc == api.NSN_ERR_INVALID_ARG and b"group_size" in L.nsn_last_error()
     rc = L.nsn_build_codebook(None, 1000, 8, 128, 1, None, None, None, 0, None)
     assert rc == api.NSN_ERR_UNSUPPORTED
+    # rotary table: three fixed parts (2 x 16 KiB fp16, 64 KiB fp64) + 1536 bytes per 64-token block
+    assert L.nsn_rope_table_bytes(8192) == 98304 + 128 * 1536
+    assert L.nsn_rope_table_bytes(100) == 0 and L.nsn_rope_table_bytes(0) == 0
+    rc = L.nsn_build_rope_table(None, 8192, None, 0, None)
+    assert rc == api.NSN_ERR_INVALID_ARG and b"rope" in L.nsn_last_error()
 
 
 def test_product_package_does_not_import_oracle():
