@@ -59,6 +59,10 @@ def parse():
     p.add_argument("--group-size", type=int, default=0,
                    help="Shift group size (0 = one group per sequence as in the workload definitions, "
                         "64 = the paper's residual-size groups)")
+    p.add_argument("--pre-rope", action="store_true",
+                   help="keys are normalised before the rotary embedding (Sec. 3.2): the encoder turns v_nsn by "
+                        "the token position, the attention kernel turns the stored mean (App. B)")
+    p.add_argument("--rope-base", type=float, default=500000.0, help="rotary base of --pre-rope (Llama-3: 5e5)")
     p.add_argument("--finetune-iters", type=int, default=0,
                    help="cosine fine-tuning steps applied to the K-Means codebook (Sec. 3.4); 0 = none")
     p.add_argument("--finetune-lr", type=float, default=2048.0)
@@ -96,7 +100,8 @@ def random_cache_decode(args, cfg) -> int:
     J = 32 if args.sign_format else 128 // sub
     max_len = ((max(lens) + 255) // 256) * 256
     G = args.group_size
-    shape = api.make_shape(sub, Hq, Hkv, max_len, G, page, sign_format=args.sign_format)
+    rope_table = api.nsn_build_rope_table(synth.rope_inv_freq(args.rope_base), max_len) if args.pre_rope else None
+    shape = api.make_shape(sub, Hq, Hkv, max_len, G, page, sign_format=args.sign_format, rope_table=rope_table)
     bt = torch.from_numpy(synth.shuffled_page_table(seed, B, max_len // page)).to(dev) if page else None
     g = torch.Generator(device=dev).manual_seed(seed)
     caches = []
@@ -145,7 +150,7 @@ def random_cache_decode(args, cfg) -> int:
         "dtype": "f32", "data": "synthetic (random cache contents, timing only)",
         "config": {"workload": f"{args.workload}:{cfg['name']}", "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "cached_tokens": sum(lens), "sub_dim": sub, "sign_format": bool(args.sign_format),
-                   "page_size": page, "group_size": G,
+                   "page_size": page, "group_size": G, "pre_rope_keys": bool(args.pre_rope),
                    "cache_copies_in_rotation": n_copies, "step": "decode attention only"},
         "decode_us_per_step": round(us, 3), "bytes_per_step": step_bytes,
         "roofline": {"bound": "hbm", "kernel": "nsn::dec_mfma_kernel (one launch per decode step)",
@@ -208,7 +213,9 @@ def main() -> int:
     k_dev, v_dev, q_dev = (torch.from_numpy(x).to(dev) for x in (k_host, v_host, q_host))
     RES = 64  # residual size of the paper
     # room for one flushed residual behind the L cached tokens
-    shape = api.make_shape(sub, Hq, Hkv, L + RES, G, sign_format=sign)
+    inv_freq = synth.rope_inv_freq(args.rope_base) if args.pre_rope else None
+    rope_table = api.nsn_build_rope_table(inv_freq, L + RES) if args.pre_rope else None
+    shape = api.make_shape(sub, Hq, Hkv, L + RES, G, sign_format=sign, rope_table=rope_table)
     kc, vc = api.alloc_cache(shape, B), api.alloc_cache(shape, B)
     zeros = torch.zeros(B, dtype=torch.int32, device=dev)
     full = torch.full((B,), L, dtype=torch.int32, device=dev)
@@ -249,6 +256,9 @@ def main() -> int:
             k_res[b, h] = synth.make_k(seed, b, h, RES, per_seq=cfg.get("per_seq", False), start=L)
             v_res[b, h] = synth.make_v(seed, b, h, RES, start=L)
     k_res, v_res = torch.from_numpy(k_res).to(dev), torch.from_numpy(v_res).to(dev)
+    # --pre-rope: attention reads the residual keys after the embedding, the encoder the copies before it; a
+    # model holds both.  Timing does not depend on the values, so the second buffer is a copy of the first.
+    k_res_enc = k_res.clone() if args.pre_rope else k_res
     res_lens = [torch.full((B,), r, dtype=torch.int32, device=dev) for r in range(1, RES + 1)]
     # 'append' policy: the step's one new token, encoded with the stored mean before the attention
     k_new = k_res[:, :, :1, :].contiguous()
@@ -272,8 +282,8 @@ def main() -> int:
             api.nsn_decode_attention_residual(shape, codebook, q_dev, ck, cv, full, L, k_res, v_res, res_lens[r],
                                               scale, args.n_splits, out=out, workspace=dec_ws)
             if r == RES - 1:  # G = 0: the sequence's stored mean; G = 64: the residual is a Shift group of its own
-                api.nsn_encode(shape, codebook, k_res, v_res, full, res_lens[RES - 1], ck, cv, freeze_means=(G == 0),
-                               workspace=enc_ws)
+                api.nsn_encode(shape, codebook, k_res_enc, v_res, full, res_lens[RES - 1], ck, cv,
+                               freeze_means=(G == 0), workspace=enc_ws)
 
     for i in range(args.warmup):
         step(i)
@@ -336,6 +346,7 @@ def main() -> int:
         "config": {"workload": f"{args.workload}:{cfg['name']}", "batch": B, "n_q_heads": Hq,
                    "n_kv_heads": Hkv, "cached_tokens": L, "sub_dim": sub, "bits": 2 if sign else 8 // sub,
                    "sign_format": sign, "codebook_finetune_iters": args.finetune_iters,
+                   "pre_rope_keys": bool(args.pre_rope),
                    "group_size": G, "cache_copies_in_rotation": n_copies,
                    "residual_size": RES if args.policy == "residual" else 0,
                    "residual_encodes_in_timed_region": flushes if args.policy == "residual" else 0,
@@ -372,12 +383,12 @@ def main() -> int:
         worst = 0.0
         for (b, h) in units:
             t0 = time.perf_counter()
-            ek = O.encode(k_host[b, h], cb_host, G, sign_format=sign)
+            ek = O.encode(k_host[b, h], cb_host, G, sign_format=sign, rope_inv_freq=inv_freq)
             ev = O.encode(v_host[b, h], cb_host, G, sign_format=sign)
             t_enc += time.perf_counter() - t0
             t0 = time.perf_counter()
             ref = O.decode_attention(q_host[b, h * r:(h + 1) * r].astype(np.float64), ek, ev, cb_host, scale, G,
-                                     sign_format=sign)
+                                     sign_format=sign, rope_inv_freq=inv_freq)
             t_dec += time.perf_counter() - t0
             got = out_host[b, h * r:(h + 1) * r]
             worst = max(worst, float((np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)).max()))

@@ -336,12 +336,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     qv[u] = (i < 4 * kHeadDim && hh < r) ? __half2float(q[(int64_t)(b * g.n_q_heads + hq0 + hh) * kHeadDim + c]) : 0.f;
   }
   // ROPE: the fp16 cosine / sine rows go to LDS with the codebook (four 16-byte chunks per thread)
-  uint4 trow[4] = {};
-  if constexpr (ROPE) {
-    if (main_wave) {
+  uint4 trow[ROPE ? 4 : 1];
+  if constexpr (ROPE) {  // (the residual wave loads in-bounds chunks that it never stores)
 #pragma unroll
-      for (int u = 0; u < 4; ++u) trow[u] = reinterpret_cast<const uint4*>(g.rope + kRopeHiOff)[tid + u * NT];
-    }
+    for (int u = 0; u < 4; ++u) trow[u] = reinterpret_cast<const uint4*>(g.rope + kRopeHiOff)[min(tid, NT - 1) + u * NT];
   }
   Grp cur;
   const bool spec = main_wave && !g.paged && (t0 + (wave << 6) + 64 <= g.page_tokens);  // in bounds whatever the length
@@ -700,34 +698,30 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     h8d AH[4], AL[4];
 #pragma unroll
     for (int ksp = 0; ksp < 2; ++ksp) {
-      const int i0 = 32 * ksp + 8 * kq;  // first of eight pairs (i, i + 64)
-      const uint4 oa4 = *reinterpret_cast<const uint4*>(orow + i0);
-      const uint4 ob4 = *reinterpret_cast<const uint4*>(orow + 64 + i0);
-      const h8d oa = __builtin_bit_cast(h8d, oa4), ob = __builtin_bit_cast(h8d, ob4);
-      float cs[16], qa[8], qb[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const float4 c4 = reinterpret_cast<const float4*>(rec)[(i0 >> 1) + u];  // (cos, sin) of two pairs
-        cs[4 * u] = c4.x, cs[4 * u + 1] = c4.y, cs[4 * u + 2] = c4.z, cs[4 * u + 3] = c4.w;
-      }
+      for (int hf = 0; hf < 2; ++hf) {  // four pairs (i, i + 64) at a time keeps the live set small
+        const int i0 = 32 * ksp + 8 * kq + 4 * hf;
+        const uint2 oa2 = *reinterpret_cast<const uint2*>(orow + i0);
+        const uint2 ob2 = *reinterpret_cast<const uint2*>(orow + 64 + i0);
+        const h4 oa = as_h4(oa2.x, oa2.y), ob = as_h4(ob2.x, ob2.y);
+        const float4 c01 = reinterpret_cast<const float4*>(rec)[i0 >> 1];  // (cos, sin) of pairs i0, i0 + 1
+        const float4 c23 = reinterpret_cast<const float4*>(rec)[(i0 >> 1) + 1];
+        const float4 a4 = *reinterpret_cast<const float4*>(&sm_q_keep[head][i0]);
+        const float4 b4 = *reinterpret_cast<const float4*>(&sm_q_keep[head][64 + i0]);
+        const float cs[8] = {c01.x, c01.y, c01.z, c01.w, c23.x, c23.y, c23.z, c23.w};
+        const float qa[4] = {a4.x, a4.y, a4.z, a4.w}, qb[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const float4 a4 = *reinterpret_cast<const float4*>(&sm_q_keep[head][i0 + 4 * u]);
-        const float4 b4 = *reinterpret_cast<const float4*>(&sm_q_keep[head][64 + i0 + 4 * u]);
-        qa[4 * u] = a4.x, qa[4 * u + 1] = a4.y, qa[4 * u + 2] = a4.z, qa[4 * u + 3] = a4.w;
-        qb[4 * u] = b4.x, qb[4 * u + 1] = b4.y, qb[4 * u + 2] = b4.z, qb[4 * u + 3] = b4.w;
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float x = qa[e] * scale_log2e, y = qb[e] * scale_log2e;
-        const float o0 = (float)oa[e], o1 = (float)ob[e];
-        const float A = x * o0 + y * o1, B = y * o0 - x * o1;
-        const float Ap = A * cs[2 * e] + B * cs[2 * e + 1], Bp = B * cs[2 * e] - A * cs[2 * e + 1];
-        const _Float16 ah = (_Float16)Ap, bh = (_Float16)Bp;
-        AH[ksp][e] = ah;
-        AL[ksp][e] = (_Float16)(Ap - (float)ah);
-        AH[ksp + 2][e] = bh;
-        AL[ksp + 2][e] = (_Float16)(Bp - (float)bh);
+        for (int e = 0; e < 4; ++e) {
+          const float x = qa[e] * scale_log2e, y = qb[e] * scale_log2e;
+          const float o0 = (float)oa[e], o1 = (float)ob[e];
+          const float A = x * o0 + y * o1, B = y * o0 - x * o1;
+          const float Ap = A * cs[2 * e] + B * cs[2 * e + 1], Bp = B * cs[2 * e] - A * cs[2 * e + 1];
+          const _Float16 ah = (_Float16)Ap, bh = (_Float16)Bp;
+          AH[ksp][4 * hf + e] = ah;
+          AL[ksp][4 * hf + e] = (_Float16)(Ap - (float)ah);
+          AH[ksp + 2][4 * hf + e] = bh;
+          AL[ksp + 2][4 * hf + e] = (_Float16)(Bp - (float)bh);
+        }
       }
     }
 #pragma unroll
@@ -761,6 +755,9 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     const bool valid = (tg + lane) < t1;
     const bool has_next = gi + NW < n_grp;  // wave-uniform
     constexpr bool kInPlace = SGN;
+    if constexpr (ROPE) {  // before the next group's loads are issued: fewer live registers
+      if ((it & (SM::kRopeBatch - 1)) == 0) rope_batch(gi);
+    }
     Side nxt;
     Grp nxt_full;
     if (has_next) {
@@ -774,8 +771,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
 
     // Shift group bookkeeping (wave-uniform): mean term of the old group, q . o^k of the new one
     const int grp = group_of(g, tg);
-    if constexpr (ROPE) {
-      if ((it & (SM::kRopeBatch - 1)) == 0) rope_batch(gi);
+    if constexpr (ROPE) {  // this token's q . RoPE_t(o^k), four heads
       const float4 rd = sm_rope_dot[wave][it & (SM::kRopeBatch - 1)][lane];
       const float rv[4] = {rd.x, rd.y, rd.z, rd.w};
 #pragma unroll
