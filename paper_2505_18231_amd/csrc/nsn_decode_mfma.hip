@@ -323,6 +323,27 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     G.nk = S.nk, G.nv = S.nv, G.ok2 = S.ok2, G.ov2 = S.ov2;
   };
 
+  // ROPE: global operands of one batch of the mean term (four groups gi0, gi0 + NW, ...).  The four
+  // lanes of a quad own the four heads of one group; for the loads they split the group's 16 pairs
+  // (i, i + 64) of this lane's channel range: lane c of the quad takes four pairs of the mean row
+  // (fp16) and of the block's (cos, sin) row (fp32).
+  struct RopeIn {
+    uint2 oa, ob;
+    float4 c01, c23;
+  };
+  auto rope_load = [&](int gi0, RopeIn& in) {
+    const int m = lane & 15, bi = m >> 2, c = m & 3, kq = lane >> 4;
+    // blocks past the sequence end are clamped into the tables (their results are never read)
+    const int tg = min(t0 + ((gi0 + NW * bi) << 6), g.page_tokens * g.pages_per_seq - 64);
+    const __half* orow = kc.means + (mean_base + group_of(g, tg)) * kHeadDim;
+    const unsigned char* rec = g.rope + kRopeBlkOff + (int64_t)(tg >> 6) * kRopeBlkStride;
+    const int i0 = 32 * (c >> 1) + 8 * kq + 4 * (c & 1);
+    in.oa = *reinterpret_cast<const uint2*>(orow + i0);
+    in.ob = *reinterpret_cast<const uint2*>(orow + 64 + i0);
+    in.c01 = reinterpret_cast<const float4*>(rec)[i0 >> 1];  // (cos, sin) of pairs i0, i0 + 1
+    in.c23 = reinterpret_cast<const float4*>(rec)[(i0 >> 1) + 1];
+  };
+
   NSN_TSTAMP(0);
   // ---- loads that do not depend on the sequence length go out first ------------------------
   typedef typename std::conditional<SUB == 4, uint2, uint4>::type cw_t;
@@ -340,6 +361,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   if constexpr (ROPE) {  // (the residual wave loads in-bounds chunks that it never stores)
 #pragma unroll
     for (int u = 0; u < 4; ++u) trow[u] = reinterpret_cast<const uint4*>(g.rope + kRopeHiOff)[min(tid, NT - 1) + u * NT];
+  }
+  RopeIn rin = {};
+  if constexpr (ROPE) {
+    if (main_wave) rope_load(wave, rin);  // first batch: in bounds whatever the length
   }
   Grp cur;
   const bool spec = main_wave && !g.paged && (t0 + (wave << 6) + 64 <= g.page_tokens);  // in bounds whatever the length
@@ -689,41 +714,42 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   // ROPE: q . RoPE_t(o^k) (log2 units) for the 64 tokens of this wave's groups gi0, gi0 + NW, ... (four of
   // them): lane (m = lane % 16, kq = lane / 16) supplies row (group m / 4, head m % 4) of the turned
   // products A', B' at channels 32 ks + 8 kq + e and column m of the token-side table.
-  auto rope_batch = [&](int gi0) {
-    const int m = lane & 15, bi = m >> 2, head = m & 3, kq = lane >> 4;
-    // groups past the end repeat the last one (their results are never read)
-    const int tg = min(t0 + ((gi0 + NW * bi) << 6), (t1 - 1) & ~63);
-    const __half* orow = kc.means + (mean_base + group_of(g, tg)) * kHeadDim;
-    const unsigned char* rec = g.rope + kRopeBlkOff + (int64_t)(tg >> 6) * kRopeBlkStride;
-    h8d AH[4], AL[4];
+  auto rope_compute = [&](const RopeIn& in) {
+    const int m = lane & 15, head = m & 3, kq = lane >> 4;
+    // the block's turned mean ro = RoPE_(64 block)(o) (times the score scale) at this lane's four pairs;
+    // with it  A'_i = q_i ro_i + q_i' ro_i',  B'_i = q_i' ro_i - q_i ro_i'
+    float rl[4], rh[4];
+    {
+      const h4 oa = as_h4(in.oa.x, in.oa.y), ob = as_h4(in.ob.x, in.ob.y);
+      const float cs[8] = {in.c01.x, in.c01.y, in.c01.z, in.c01.w, in.c23.x, in.c23.y, in.c23.z, in.c23.w};
 #pragma unroll
-    for (int ksp = 0; ksp < 2; ++ksp) {
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {  // four pairs (i, i + 64) at a time keeps the live set small
-        const int i0 = 32 * ksp + 8 * kq + 4 * hf;
-        const uint2 oa2 = *reinterpret_cast<const uint2*>(orow + i0);
-        const uint2 ob2 = *reinterpret_cast<const uint2*>(orow + 64 + i0);
-        const h4 oa = as_h4(oa2.x, oa2.y), ob = as_h4(ob2.x, ob2.y);
-        const float4 c01 = reinterpret_cast<const float4*>(rec)[i0 >> 1];  // (cos, sin) of pairs i0, i0 + 1
-        const float4 c23 = reinterpret_cast<const float4*>(rec)[(i0 >> 1) + 1];
-        const float4 a4 = *reinterpret_cast<const float4*>(&sm_q_keep[head][i0]);
-        const float4 b4 = *reinterpret_cast<const float4*>(&sm_q_keep[head][64 + i0]);
-        const float cs[8] = {c01.x, c01.y, c01.z, c01.w, c23.x, c23.y, c23.z, c23.w};
-        const float qa[4] = {a4.x, a4.y, a4.z, a4.w}, qb[4] = {b4.x, b4.y, b4.z, b4.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float x = qa[e] * scale_log2e, y = qb[e] * scale_log2e;
-          const float o0 = (float)oa[e], o1 = (float)ob[e];
-          const float A = x * o0 + y * o1, B = y * o0 - x * o1;
-          const float Ap = A * cs[2 * e] + B * cs[2 * e + 1], Bp = B * cs[2 * e] - A * cs[2 * e + 1];
-          const _Float16 ah = (_Float16)Ap, bh = (_Float16)Bp;
-          AH[ksp][4 * hf + e] = ah;
-          AL[ksp][4 * hf + e] = (_Float16)(Ap - (float)ah);
-          AH[ksp + 2][4 * hf + e] = bh;
-          AL[ksp + 2][4 * hf + e] = (_Float16)(Bp - (float)bh);
-        }
+      for (int e = 0; e < 4; ++e) {
+        const float o0 = (float)oa[e], o1 = (float)ob[e];
+        const float cc = cs[2 * e] * scale_log2e, ss = cs[2 * e + 1] * scale_log2e;
+        rl[e] = o0 * cc - o1 * ss;
+        rh[e] = o1 * cc + o0 * ss;
       }
     }
+    h8d AH[4], AL[4];
+    static_for<4>([&](auto cc) {  // chunk c of the quad's lane c: four pairs from i0
+      constexpr int c = decltype(cc)::value;
+      constexpr int ksp = c >> 1, hf = c & 1;
+      constexpr int ctrl = c | (c << 2) | (c << 4) | (c << 6);  // quad_perm: every lane reads lane c of its quad
+      const int i0 = 32 * ksp + 8 * kq + 4 * hf;
+      const float4 a4 = *reinterpret_cast<const float4*>(&sm_q_keep[head][i0]);
+      const float4 b4 = *reinterpret_cast<const float4*>(&sm_q_keep[head][64 + i0]);
+      const float qa[4] = {a4.x, a4.y, a4.z, a4.w}, qb[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float xl = dpp_quad<ctrl>(rl[e]), xh = dpp_quad<ctrl>(rh[e]);
+        const float Ap = qa[e] * xl + qb[e] * xh, Bp = qb[e] * xl - qa[e] * xh;
+        const _Float16 ah = (_Float16)Ap, bh = (_Float16)Bp;
+        AH[ksp][4 * hf + e] = ah;
+        AL[ksp][4 * hf + e] = (_Float16)(Ap - (float)ah);
+        AH[ksp + 2][4 * hf + e] = bh;
+        AL[ksp + 2][4 * hf + e] = (_Float16)(Bp - (float)bh);
+      }
+    });
 #pragma unroll
     for (int tile = 0; tile < 4; ++tile) {
       f4 d = {0.f, 0.f, 0.f, 0.f};
@@ -746,6 +772,11 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   };
 
+  // the first batch (groups wave, wave + NW, ...) from the operands loaded at kernel start
+  if constexpr (ROPE) {
+    if (n_grp > wave) rope_compute(rin);
+  }
+
   NSN_TSTAMP(2);
   // ---- main loop: this wave's 64-token groups, next group's loads in flight ------------------
   int it = 0;  // this wave's iteration count
@@ -756,7 +787,11 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     const bool has_next = gi + NW < n_grp;  // wave-uniform
     constexpr bool kInPlace = SGN;
     if constexpr (ROPE) {  // before the next group's loads are issued: fewer live registers
-      if ((it & (SM::kRopeBatch - 1)) == 0) rope_batch(gi);
+      if (it > 0 && (it & (SM::kRopeBatch - 1)) == 0) {
+        RopeIn in;
+        rope_load(gi, in);
+        rope_compute(in);
+      }
     }
     Side nxt;
     Grp nxt_full;
