@@ -44,6 +44,12 @@ Parity pins (tests/test_oracle_*.py, all CPU):
                       with the query turned back instead of the mean turned forward.  Pairing,
                       frequencies and positions are this build's reading (the paper names its
                       models' RoPE without restating it)
+  double quantization rtn4 reproduces an exactly representable 16-level grid, its error is at most
+                      half a step, a constant group gives step 0; the bit budget reproduces
+                      Table 11's 2.33 and 2.23 (printed to two decimals); with 4-bit side
+                      information encode / dequantize keep the restore identity with the
+                      dequantised scale and mean.  Min/max (asymmetric) levels with fp16 minimum and
+                      step are this build's reading of "4-bit round-to-nearest"
 """
 from __future__ import annotations
 
@@ -164,6 +170,57 @@ def scale_adjust(v: np.ndarray, vq: np.ndarray) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
+# Double quantization (Sec. 3.5): the side information itself is stored in 4 bits, round-to-nearest
+# on 16 levels between a group's minimum and maximum; the minimum and the step are kept in fp16.
+# Groups: 32 channels of a mean vector o; the s1 of the 64 tokens of one residual-size chunk.
+# ----------------------------------------------------------------------------
+def rtn4_encode(x):
+    """One group of values -> (codes u8 in 0..15, minimum fp16, step fp16).  The codes are taken
+    against the ROUNDED minimum and step (what the decoder will see); a zero step gives code 0."""
+    x = np.asarray(x, dtype=F64).reshape(-1)
+    mn = fp16_rne(x.min())
+    st = fp16_rne((x.max() - x.min()) / 15.0)
+    if float(st) == 0.0:
+        return np.zeros(x.shape, dtype=np.uint8), mn, st
+    lvl = np.floor((x - float(mn)) / float(st) + 0.5)
+    return np.clip(lvl, 0, 15).astype(np.uint8), mn, st
+
+
+def rtn4_decode(codes, mn, st) -> np.ndarray:
+    return float(mn) + float(st) * np.asarray(codes, dtype=F64)
+
+
+def quantize_side_info(b16: np.ndarray, o_mean: np.ndarray, start: int = 0):
+    """b16 fp16 [l] (first-Normalize scales of tokens start.., start a multiple of 64),
+    o_mean float64 [n_groups][d] (rows that are all zero are groups without tokens).
+    Returns dict(b_code u8 [l], b_par fp16 [n_blocks][2] (min, step) indexed by absolute 64-token block,
+                 o_code u8 [n_groups][d], o_par fp16 [n_groups][d/32][2],
+                 b_hat float64 [l], o_hat float64 [n_groups][d])."""
+    assert start % 64 == 0
+    l = b16.shape[0]
+    n_blk = (start + l + 63) // 64
+    b_code = np.zeros(l, dtype=np.uint8)
+    b_par = np.zeros((n_blk, 2), dtype=np.float16)
+    b_hat = np.zeros(l, dtype=F64)
+    for blk in range(start // 64, n_blk):
+        lo, hi = blk * 64 - start, min((blk + 1) * 64 - start, l)
+        code, mn, st = rtn4_encode(b16[lo:hi].astype(F64))
+        b_code[lo:hi], b_par[blk] = code, (mn, st)
+        b_hat[lo:hi] = rtn4_decode(code, mn, st)
+    ng, d = o_mean.shape
+    o_code = np.zeros((ng, d), dtype=np.uint8)
+    o_par = np.zeros((ng, d // 32, 2), dtype=np.float16)
+    o_hat = np.zeros((ng, d), dtype=F64)
+    for gi in range(ng):
+        for c in range(d // 32):
+            sl = slice(32 * c, 32 * c + 32)
+            code, mn, st = rtn4_encode(o_mean[gi, sl])
+            o_code[gi, sl], o_par[gi, c] = code, (mn, st)
+            o_hat[gi, sl] = rtn4_decode(code, mn, st)
+    return dict(b_code=b_code, b_par=b_par, o_code=o_code, o_par=o_par, b_hat=b_hat, o_hat=o_hat)
+
+
+# ----------------------------------------------------------------------------
 # Rotary position embedding as the Llama-family models of the paper's experiments apply it:
 # channel i and channel i + d/2 form a pair that turns by the angle position * inv_freq[i].
 # Sec. 3.2 ("NSN applied to key and value") normalises keys BEFORE this rotation: the rotation
@@ -187,9 +244,11 @@ def rope(x: np.ndarray, positions, inv_freq) -> np.ndarray:
 # rounding points (b = s1, o, a = s1 s2 alpha); rounded b and o are the values used
 # downstream, so that dequantisation is self-consistent.
 # ----------------------------------------------------------------------------
-def shift_stats(x16: np.ndarray, group_size: int = 0, start: int = 0, given_b=None, given_o=None):
+def shift_stats(x16: np.ndarray, group_size: int = 0, start: int = 0, given_b=None, given_o=None,
+                raw_mean: bool = False):
     """Stage A of the encoder: b = fp16(s1) per token (step 1 of Sec. 3.2) and o = fp16(per-group
-    channel mean of x / b) (step 2).  `given_*` replace the computed arrays."""
+    channel mean of x / b) (step 2).  `given_*` replace the computed arrays.  raw_mean: return the
+    float64 means before any storage rounding (the input of the 4-bit quantiser of Sec. 3.5)."""
     x = np.asarray(x16, dtype=F64)
     l, d = x.shape
     b16 = fp16_rne(token_scale(x)) if given_b is None else np.asarray(given_b, dtype=np.float16)
@@ -199,9 +258,10 @@ def shift_stats(x16: np.ndarray, group_size: int = 0, start: int = 0, given_b=No
     assert group_size != 0 or start == 0
     n = _safe_div(x, b16.astype(F64)[:, None])
     g = group_index(l, group_size, start)
-    o16 = np.zeros(((int(g.max()) + 1) if l else 0, d), dtype=np.float16)
+    o16 = np.zeros(((int(g.max()) + 1) if l else 0, d), dtype=F64 if raw_mean else np.float16)
     for gi in np.unique(g):
-        o16[gi] = fp16_rne(n[g == gi].mean(axis=0))
+        m = n[g == gi].mean(axis=0)
+        o16[gi] = m if raw_mean else fp16_rne(m)
     return b16, o16
 
 
@@ -226,7 +286,7 @@ def signed_codewords(idx: np.ndarray, sgn: np.ndarray, codebook: np.ndarray) -> 
 def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: int = 0,
            frozen_o: np.ndarray | None = None, given_b: np.ndarray | None = None,
            given_o: np.ndarray | None = None, return_debug: bool = False, sign_format: bool = False,
-           rope_inv_freq=None):
+           rope_inv_freq=None, side_bits: int = 16):
     """Encode tokens [start, start+l) of one (sequence, kv-head, tensor) unit.
 
     x16       fp16 [l][d]
@@ -240,6 +300,14 @@ def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: in
     rope_inv_freq: [d/2] - x16 holds keys BEFORE the rotary embedding (Sec. 3.2): NSN runs on them
               as they are, v_nsn of token t is rotated by position start + t, then quantised;
               the stored mean o stays un-rotated
+    side_bits: 4 = double quantization (Sec. 3.5).  s1 is rounded to fp16 and used for the first
+              Normalize as always, but STORED as 4-bit codes per 64-token block (start must be a
+              multiple of 64); the group means are stored as 4-bit codes per 32 channels and the
+              Shift uses the dequantised mean; the stored per-token scale is a' = fp16(s2 alpha).
+              The dict then holds the effective float64 values under the usual keys
+              (a = b_hat a', b = b_hat, o = o_hat, so `dequantize` applies unchanged) and the stored
+              fields a_stored, b_code, b_par, o_code, o_par (see quantize_side_info); given_o, if
+              passed, is the dequantised mean array
     returns dict(codes u8 [l][d/sub], a fp16 [l], b fp16 [l], o fp16 [n_groups][d])
     """
     x = np.asarray(x16, dtype=F64)
@@ -251,11 +319,20 @@ def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: in
 
     # steps 1 and 2 (Normalize, Shift): the two stored side-information arrays b and o
     g = group_index(l, group_size, start)
-    b16, o16 = shift_stats(x16, group_size, start, given_b=given_b,
-                           given_o=frozen_o if frozen_o is not None else given_o)
+    side = None
+    if side_bits == 4:
+        fixed_o = frozen_o if frozen_o is not None else given_o
+        b16, o_raw = shift_stats(x16, group_size, start, given_b=given_b, raw_mean=True,
+                                 given_o=None if fixed_o is None else np.zeros((1, d), dtype=np.float16))
+        side = quantize_side_info(b16, np.zeros((1, d)) if fixed_o is not None else o_raw, start)
+        o16 = side["o_hat"] if fixed_o is None else np.asarray(fixed_o, dtype=F64)
+    else:
+        assert side_bits == 16
+        b16, o16 = shift_stats(x16, group_size, start, given_b=given_b,
+                               given_o=frozen_o if frozen_o is not None else given_o)
     b = b16.astype(F64)
     n = _safe_div(x, b[:, None])
-    o = o16.astype(F64)
+    o = np.asarray(o16, dtype=F64)
     ns = n - o[g]
 
     # step 3 (Normalize)
@@ -281,9 +358,14 @@ def encode(x16: np.ndarray, codebook: np.ndarray, group_size: int = 0, start: in
 
     # scale adjustment folded into the stored scale: a = s1 s2 alpha
     alpha = scale_adjust(y, yq)
-    a16 = fp16_rne(b * s2 * alpha)
-
-    out = dict(codes=codes.astype(np.uint8), a=a16, b=b16, o=o16)
+    if side is not None:
+        a_stored = fp16_rne(s2 * alpha)
+        out = dict(codes=codes.astype(np.uint8), a=side["b_hat"] * a_stored.astype(F64), b=side["b_hat"], o=o,
+                   a_stored=a_stored, b16=b16, b_code=side["b_code"], b_par=side["b_par"], o_code=side["o_code"],
+                   o_par=side["o_par"])
+    else:
+        a16 = fp16_rne(b * s2 * alpha)
+        out = dict(codes=codes.astype(np.uint8), a=a16, b=b16, o=o16)
     if return_debug:
         out.update(y=y, s2=s2, alpha=alpha, best=best.reshape(l, -1), second=second.reshape(l, -1), vnsn=vnsn)
     return out
@@ -467,6 +549,14 @@ def avg_bits(code_bits_per_dim: float, head_dim: int, group_size: int) -> float:
     per group of `group_size` tokens."""
     scales = 2 * 16 / head_dim
     means = 16 * head_dim / (group_size * head_dim)
+    return code_bits_per_dim + scales + means
+
+
+def avg_bits_dq(code_bits_per_dim: float, head_dim: int, group_size: int, mean_dq: bool, scale_dq: bool) -> float:
+    """Table 11's rows: means as 4-bit codes + (min, step) fp16 per 32 channels; s1 as 4-bit codes +
+    (min, step) fp16 per `group_size` tokens next to the fp16 s2."""
+    means = (4 * head_dim + (head_dim // 32) * 32) / (group_size * head_dim) if mean_dq else 16 / group_size
+    scales = (16 + 4 + 32 / group_size) / head_dim if scale_dq else 2 * 16 / head_dim
     return code_bits_per_dim + scales + means
 
 

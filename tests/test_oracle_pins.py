@@ -512,3 +512,72 @@ def test_pre_rope_scores_two_branch_form_and_attention():
     p = np.exp(s_all - s_all.max(axis=1, keepdims=True))
     p /= p.sum(axis=1, keepdims=True)
     assert np.allclose(out_r, p @ np.concatenate([v_hat, v_res.astype(np.float64)]), atol=1e-12)
+
+
+# ---------------------------------------------------------------- double quantization (Sec. 3.5)
+def test_rtn4_grid_error_bound_and_degenerate_group():
+    # sixteen equally spaced values that fp16 holds exactly come back exactly, codes 0..15 in order
+    x = 1.0 + 0.125 * np.arange(16)
+    code, mn, st = O.rtn4_encode(x[::-1])
+    assert float(mn) == 1.0 and float(st) == 0.125
+    assert np.array_equal(code, np.arange(16)[::-1])
+    assert np.array_equal(O.rtn4_decode(code, mn, st), x[::-1])
+    # random group: monotone codes, error at most half a step (+ the fp16 rounding of min and step)
+    g = np.random.default_rng(11)
+    for _ in range(20):
+        v = g.standard_normal(32) * 10 ** g.uniform(-3, 1) + g.standard_normal()
+        code, mn, st = O.rtn4_encode(v)
+        assert code.min() == 0 and code.max() == 15
+        order = np.argsort(v)
+        assert np.all(np.diff(code[order].astype(int)) >= 0)
+        err = np.abs(O.rtn4_decode(code, mn, st) - v)
+        slack = 2.0 ** -11 * (abs(v.min()) + 15 * float(st))      # rounding of the stored minimum and step
+        assert err.max() <= 0.5 * float(st) + slack, (err.max(), float(st))
+    # a constant group has step 0 and decodes to the fp16 value
+    code, mn, st = O.rtn4_encode(np.full(64, 3.69921875))
+    assert float(st) == 0.0 and not code.any() and np.all(O.rtn4_decode(code, mn, st) == 3.69921875)
+
+
+def test_double_quantization_bit_budget_matches_paper_table():
+    for mean_dq, scale_dq, printed in _rows("bit_budget_dq.txt"):
+        got = O.avg_bits_dq(2, 128, 64, bool(mean_dq), bool(scale_dq))
+        assert abs(got - printed) < 0.01, (got, printed)      # printed to two decimals
+    assert O.avg_bits_dq(2, 128, 64, False, False) == O.avg_bits(2, 128, 64)
+
+
+@pytest.mark.parametrize("sub,G", [(4, 64), (8, 0)])
+def test_double_quantized_side_information_round_trip(sub, G):
+    L = 200
+    x16 = synth.make_k(91, 0, 0, L)
+    cb = _rand_codebook(4, sub)
+    enc = O.encode(x16, cb, G, return_debug=True, side_bits=4)
+    plain = O.encode(x16, cb, G, return_debug=True)
+    # s1 itself is untouched by the storage format; its stored form is within half a step of it
+    assert np.array_equal(enc["b16"], plain["b"])
+    for blk in range((L + 63) // 64):
+        sl = slice(64 * blk, min(64 * blk + 64, L))
+        st = float(enc["b_par"][blk, 1])
+        assert np.abs(enc["b"][sl] - enc["b16"][sl].astype(np.float64)).max() <= 0.5 * st + 2.0 ** -10 * 16 * st + 1e-3
+    # means: 4-bit codes per 32 channels, within half a step of the fp64 group mean
+    _, o_raw = O.shift_stats(x16, G, raw_mean=True)
+    for gi in range(o_raw.shape[0]):
+        for c in range(4):
+            st = float(enc["o_par"][gi, c, 1])
+            e = np.abs(enc["o"][gi, 32 * c:32 * c + 32] - o_raw[gi, 32 * c:32 * c + 32]).max()
+            assert e <= 0.5 * st + 2.0 ** -10 * (np.abs(o_raw[gi]).max() + 16 * st)
+    # restore identity with the STORED side information: x = s1 (s2 v_nsn + o_hat) holds exactly for the
+    # s1 used in Normalize, and the dequantised token only swaps s1 for its 4-bit version
+    gidx = O.group_index(L, G)
+    b16 = enc["b16"].astype(np.float64)
+    H = O.hadamard(D)
+    v_nsn = enc["y"] @ H                                   # y = H v_nsn
+    back = b16[:, None] * (enc["s2"][:, None] * v_nsn + enc["o"][gidx])
+    assert np.allclose(back, x16.astype(np.float64), rtol=0, atol=1e-9 * np.abs(x16.astype(np.float64)).max())
+    k_hat = O.dequantize(enc["codes"], enc["a"], enc["b"], enc["o"], cb, G)
+    k_hat_plain = O.dequantize(plain["codes"], plain["a"], plain["b"], plain["o"], cb, G)
+    xx = x16.astype(np.float64)
+    rel, rel_plain = np.linalg.norm(k_hat - xx) / np.linalg.norm(xx), np.linalg.norm(k_hat_plain - xx) / np.linalg.norm(xx)
+    assert rel < rel_plain * 1.1 + 5e-3, (rel, rel_plain)
+    # effective per-token scale = dequantised s1 times the stored fp16 s2 alpha
+    assert np.array_equal(enc["a"], enc["b"] * enc["a_stored"].astype(np.float64))
+    assert np.allclose(enc["a_stored"].astype(np.float64), enc["s2"] * enc["alpha"], rtol=2.0 ** -10)
