@@ -47,6 +47,25 @@
  *          in the original, un-rotated channel order.
  *   A token dequantises to  b * o_g + a * H^T concat_j C[code_j]   (Sec. 3.2 restore rule).
  *
+ * Double quantization (Sec. 3.5; shape->side_bits = 4): the side information is stored in 4 bits,
+ * round-to-nearest on the 16 levels  min + step * code  between a group's minimum and maximum
+ * (min and step fp16; code = clamp(floor((x - min) / step + 1/2), 0, 15) against the rounded min
+ * and step, 0 when step = 0).  norms and means then have these byte layouts instead:
+ *   norms  one 164-byte record per 64-token block of a placement unit (record t / 64):
+ *            [0,128)   a'_t = fp16(s2 * alpha) of the block's tokens
+ *            [128,160) 4-bit codes of s1 (token t & 63 in byte (t & 63) / 2, even token = low nibble)
+ *            [160,164) (min, step) fp16 of the block's s1 codes, taken over the tokens the encode
+ *                      call wrote; b_t = min + step * code_t and a_t = b_t * a'_t
+ *          contiguous: [B][Hkv][max_len / 64] records, paged: [n_pages][Hkv][page_size / 64]
+ *   means  one 80-byte record per group, [B][Hkv][NG][80]:
+ *            [0,64)    4-bit codes of the 128 channels (channel c in byte c / 2, even = low nibble)
+ *            [64,80)   (min, step) fp16 for each of the four 32-channel groups
+ *   The first Normalize still divides by fp16(s1); only its stored form is 4-bit.  The Shift
+ *   subtracts the DEQUANTISED mean, so the mean's quantisation error is absorbed by the code.
+ *   nsn_encode then needs seq_start[b] to be a multiple of 64 (the paper encodes residual-size
+ *   chunks), and append mode (freeze_means) re-derives the s1 levels of the block it writes from
+ *   the tokens of that call alone.
+ *
  * Placement of the units:
  *   contiguous (page_size = 0):
  *       codes [B][Hkv][max_len * J] bytes, norms [B][Hkv][max_len] pairs
@@ -91,6 +110,7 @@ typedef struct nsn_shape {
                              nsn_build_rope_table for a max_len >= this one: the K input of
                              nsn_encode holds keys BEFORE the rotary embedding (Sec. 3.2 "NSN applied
                              to key and value"); see nsn_build_rope_table for what changes */
+  int32_t side_bits;      /* 0 or 16: fp16 norms and means; 4: double quantization (see above) */
 } nsn_shape;
 
 typedef struct nsn_cache {

@@ -23,7 +23,8 @@ HEAD_DIM, N_CODES = 128, 256
 
 class nsn_shape(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("head_dim", "sub_dim", "n_codes", "n_q_heads", "n_kv_heads",
-                                         "group_size", "page_size", "max_len")] + [("rope_table", C.c_void_p)]
+                                         "group_size", "page_size", "max_len")] + [("rope_table", C.c_void_p),
+                                                                                     ("side_bits", C.c_int32)]
 
 
 class nsn_cache(C.Structure):
@@ -99,12 +100,14 @@ SIGN_CODES = 65536  # n_codes of the sign + index format: 256 magnitude codeword
 
 
 def make_shape(sub_dim: int, n_q_heads: int, n_kv_heads: int, max_len: int, group_size: int = 0,
-               page_size: int = 0, sign_format: bool = False, rope_table: torch.Tensor | None = None) -> nsn_shape:
+               page_size: int = 0, sign_format: bool = False, rope_table: torch.Tensor | None = None,
+               side_bits: int = 16) -> nsn_shape:
     """sign_format: the paper's 2-bit format (8 sign bits + 8-bit index per 8-dim sub-vector).
-    rope_table: result of nsn_build_rope_table - keys are normalised before the rotary embedding."""
+    rope_table: result of nsn_build_rope_table - keys are normalised before the rotary embedding.
+    side_bits: 4 = double quantization of the first-Normalize scales and the group means."""
     assert not sign_format or sub_dim == 8
     shape = nsn_shape(HEAD_DIM, sub_dim, SIGN_CODES if sign_format else N_CODES, n_q_heads, n_kv_heads, group_size,
-                      page_size, max_len, _ptr(rope_table))
+                      page_size, max_len, _ptr(rope_table), side_bits)
     shape._rope_keepalive = rope_table  # the struct only holds the address
     return shape
 
@@ -153,15 +156,19 @@ def alloc_cache(shape: nsn_shape, batch: int, device="cuda", block_table: torch.
     J = code_bytes_per_token(shape)
     hkv = shape.n_kv_heads
     ng = nsn_max_groups(shape)
+    dq = shape.side_bits == 4   # norms: 164-byte records per 64 tokens; means: 80-byte records
     if shape.page_size > 0:
         pages = n_pages if n_pages is not None else batch * (shape.max_len // shape.page_size)
         codes = torch.zeros((pages, hkv, shape.page_size * J), dtype=torch.uint8, device=device)
-        norms = torch.zeros((pages, hkv, shape.page_size, 2), dtype=torch.float16, device=device)
+        norms = (torch.zeros((pages, hkv, shape.page_size // 64, 164), dtype=torch.uint8, device=device) if dq else
+                 torch.zeros((pages, hkv, shape.page_size, 2), dtype=torch.float16, device=device))
         assert block_table is not None and block_table.dtype == torch.int32
     else:
         codes = torch.zeros((batch, hkv, shape.max_len * J), dtype=torch.uint8, device=device)
-        norms = torch.zeros((batch, hkv, shape.max_len, 2), dtype=torch.float16, device=device)
-    means = torch.zeros((batch, hkv, ng, HEAD_DIM), dtype=torch.float16, device=device)
+        norms = (torch.zeros((batch, hkv, shape.max_len // 64, 164), dtype=torch.uint8, device=device) if dq else
+                 torch.zeros((batch, hkv, shape.max_len, 2), dtype=torch.float16, device=device))
+    means = (torch.zeros((batch, hkv, ng, 80), dtype=torch.uint8, device=device) if dq else
+             torch.zeros((batch, hkv, ng, HEAD_DIM), dtype=torch.float16, device=device))
     return CodedCache(codes, norms, means, block_table)
 
 

@@ -43,6 +43,10 @@ static int check_shape(const nsn_shape* s) {
     set_error("max_len=%d must be a positive multiple of 64", s->max_len);
     return NSN_ERR_INVALID_ARG;
   }
+  if (s->side_bits != 0 && s->side_bits != 16 && s->side_bits != 4) {
+    set_error("side_bits=%d must be 16 (or 0) or 4", s->side_bits);
+    return NSN_ERR_UNSUPPORTED;
+  }
   if (s->rope_table && (reinterpret_cast<uintptr_t>(s->rope_table) & 255) != 0) {
     set_error("rope_table must be 256-byte aligned");
     return NSN_ERR_INVALID_ARG;
@@ -203,8 +207,8 @@ static int decode_common(const nsn_shape* shape, const void* codebook_dev, const
       return NSN_ERR_UNSUPPORTED;
     }
   }
-  if (shape->rope_table && !decode_use_mfma(*shape)) {
-    set_error("decode: the lookup-table kernel (NSN_DECODE_IMPL=lut) does not turn the mean (rope_table set)");
+  if ((shape->rope_table || shape->side_bits == 4) && !decode_use_mfma(*shape)) {
+    set_error("decode: the lookup-table kernel (NSN_DECODE_IMPL=lut) handles neither rope_table nor side_bits = 4");
     return NSN_ERR_UNSUPPORTED;
   }
   if (batch == 0) return NSN_OK;

@@ -210,7 +210,9 @@ struct DecSmem {
 // group.  A wave forms it for its next four groups at once with v_mfma_f32_16x16x32_f16 (rows = (group,
 // head), columns = 16 tokens; fp16 hi + lo parts on both sides, three products), leaves the 64 x 4
 // results per group in LDS, and the main loop reads one 16-byte entry per lane and group.
-template <int SUB, int NW, int R, bool SGN = false, bool ROPE = false>
+// DQ = double quantization (Sec. 3.5): norms and means are 4-bit codes with fp16 (min, step) per group;
+// they are expanded where the fp16 forms are unpacked, everything downstream is unchanged.
+template <int SUB, int NW, int R, bool SGN = false, bool ROPE = false, bool DQ = false>
 __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, const __half* __restrict__ codebook,
                                                            const __half* __restrict__ q, CacheView kc,
                                                            CacheView vc, const int32_t* __restrict__ seq_lens,
@@ -265,9 +267,22 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   // One 64-token group's cache bytes as this lane needs them: the J code bytes of its K token,
   // the J code bytes (J consecutive tokens) of its V sub-vector, the two norm pairs, and this
   // lane's two channels of the group's Shift vectors.
+  struct Side {  // side information of the lane's token and the lane's two channels of the group's Shift vectors
+    __half2 nk, nv, ok2, ov2;  // fp16 form: (a, b) of the K / V token, channels 2 lane, 2 lane + 1 of o^k / o^v
+    // 4-bit form (DQ):
+    uint32_t ka, va;    // a' = fp16(s2 alpha) of the token (low 16 bits)
+    uint32_t kq, vq;    // byte holding the token's 4-bit s1 code (even token = low nibble)
+    __half2 kp, vp;     // (min, step) of the 64-token block's s1 codes
+    uint32_t okq, ovq;  // byte holding the lane's two 4-bit mean codes
+    __half2 okp, ovp;   // (min, step) of the lane's 32-channel group
+  };
   struct Grp {
     uint32_t kcode[KW], vcode[KW];
-    __half2 nk, nv, ok2, ov2;
+    Side s;
+  };
+  auto half_bits = [](uint32_t u) -> float { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xffffu)); };
+  auto lvl = [](__half2 par, uint32_t code) -> float {  // min + step * code
+    return fmaf(__high2float(par), (float)code, __low2float(par));
   };
   // per-lane byte offsets (32-bit) that are added to wave-uniform 64-bit bases
   const uint32_t k_lane_off = lane * J;
@@ -301,26 +316,52 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       G.vcode[4 * w4] = vv4.x, G.vcode[4 * w4 + 1] = vv4.y, G.vcode[4 * w4 + 2] = vv4.z, G.vcode[4 * w4 + 3] = vv4.w;
     }
   };
-  struct Side {  // norm pairs of the lane's token, the lane's two channels of the group's Shift vectors
-    __half2 nk, nv, ok2, ov2;
-  };
   auto load_side = [&](int gi, Side& S) {
     const int tg = t0 + (gi << 6);
     const int tin = token_in_unit(g, tg);
     const int64_t kbase = unit_token_base(g, kc.block_table, b, h, tg) + tin;
     const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tg) + tin;
-    S.nk = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.norms + kbase) + lane_x4);
-    S.nv = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.norms + vbase) + lane_x4);
-    const int64_t mo = (mean_base + group_of(g, tg)) * kHeadDim;  // wave-uniform
-    S.ok2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.means + mo) + lane_x4);
-    S.ov2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lane_x4);
+    if constexpr (DQ) {
+      const unsigned char* kr = reinterpret_cast<const unsigned char*>(kc.norms) + (kbase >> 6) * kDqNormRec;
+      const unsigned char* vr = reinterpret_cast<const unsigned char*>(vc.norms) + (vbase >> 6) * kDqNormRec;
+      S.ka = *reinterpret_cast<const uint16_t*>(kr + 2 * lane);
+      S.va = *reinterpret_cast<const uint16_t*>(vr + 2 * lane);
+      S.kq = kr[kDqNormCodes + (lane >> 1)];
+      S.vq = vr[kDqNormCodes + (lane >> 1)];
+      S.kp = *reinterpret_cast<const __half2*>(kr + kDqNormPar);
+      S.vp = *reinterpret_cast<const __half2*>(vr + kDqNormPar);
+      const int64_t mo = (mean_base + group_of(g, tg)) * kDqMeanRec;  // wave-uniform
+      const unsigned char* km = reinterpret_cast<const unsigned char*>(kc.means) + mo;
+      const unsigned char* vm = reinterpret_cast<const unsigned char*>(vc.means) + mo;
+      S.okq = km[lane];
+      S.ovq = vm[lane];
+      S.okp = *reinterpret_cast<const __half2*>(km + kDqMeanPar + 4 * (lane >> 4));
+      S.ovp = *reinterpret_cast<const __half2*>(vm + kDqMeanPar + 4 * (lane >> 4));
+    } else {
+      S.nk = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.norms + kbase) + lane_x4);
+      S.nv = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.norms + vbase) + lane_x4);
+      const int64_t mo = (mean_base + group_of(g, tg)) * kHeadDim;  // wave-uniform
+      S.ok2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.means + mo) + lane_x4);
+      S.ov2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lane_x4);
+    }
+  };
+  // the lane's two channels of a Shift vector as floats
+  auto mean_pair = [&](const Side& S, bool key, float& o0, float& o1) {
+    if constexpr (DQ) {
+      const uint32_t q8 = key ? S.okq : S.ovq;
+      const __half2 par = key ? S.okp : S.ovp;
+      o0 = lvl(par, q8 & 15u);
+      o1 = lvl(par, (q8 >> 4) & 15u);
+    } else {
+      const __half2 o2 = key ? S.ok2 : S.ov2;
+      o0 = __low2float(o2);
+      o1 = __high2float(o2);
+    }
   };
   auto load_group = [&](int gi, Grp& G) {
     load_k_codes(gi, G);
     load_v_codes(gi, G);
-    Side S;
-    load_side(gi, S);
-    G.nk = S.nk, G.nv = S.nv, G.ok2 = S.ok2, G.ov2 = S.ov2;
+    load_side(gi, G.s);
   };
 
   // ROPE: global operands of one batch of the mean term (four groups gi0, gi0 + NW, ...).  The four
@@ -328,18 +369,28 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   // (i, i + 64) of this lane's channel range: lane c of the quad takes four pairs of the mean row
   // (fp16) and of the block's (cos, sin) row (fp32).
   struct RopeIn {
-    uint2 oa, ob;
+    uint2 oa, ob;      // fp16 form: four channels from i0 and from 64 + i0
+    uint32_t oaq, obq; // 4-bit form: their codes (two bytes each) ...
+    __half2 oap, obp;  // ... and the (min, step) of their 32-channel groups
     float4 c01, c23;
   };
   auto rope_load = [&](int gi0, RopeIn& in) {
     const int m = lane & 15, bi = m >> 2, c = m & 3, kq = lane >> 4;
     // blocks past the sequence end are clamped into the tables (their results are never read)
     const int tg = min(t0 + ((gi0 + NW * bi) << 6), g.page_tokens * g.pages_per_seq - 64);
-    const __half* orow = kc.means + (mean_base + group_of(g, tg)) * kHeadDim;
     const unsigned char* rec = g.rope + kRopeBlkOff + (int64_t)(tg >> 6) * kRopeBlkStride;
     const int i0 = 32 * (c >> 1) + 8 * kq + 4 * (c & 1);
-    in.oa = *reinterpret_cast<const uint2*>(orow + i0);
-    in.ob = *reinterpret_cast<const uint2*>(orow + 64 + i0);
+    if constexpr (DQ) {
+      const unsigned char* mr = reinterpret_cast<const unsigned char*>(kc.means) + (mean_base + group_of(g, tg)) * kDqMeanRec;
+      in.oaq = *reinterpret_cast<const uint16_t*>(mr + (i0 >> 1));
+      in.obq = *reinterpret_cast<const uint16_t*>(mr + ((64 + i0) >> 1));
+      in.oap = *reinterpret_cast<const __half2*>(mr + kDqMeanPar + 4 * (i0 >> 5));
+      in.obp = *reinterpret_cast<const __half2*>(mr + kDqMeanPar + 4 * ((64 + i0) >> 5));
+    } else {
+      const __half* orow = kc.means + (mean_base + group_of(g, tg)) * kHeadDim;
+      in.oa = *reinterpret_cast<const uint2*>(orow + i0);
+      in.ob = *reinterpret_cast<const uint2*>(orow + 64 + i0);
+    }
     in.c01 = reinterpret_cast<const float4*>(rec)[i0 >> 1];  // (cos, sin) of pairs i0, i0 + 1
     in.c23 = reinterpret_cast<const float4*>(rec)[(i0 >> 1) + 1];
   };
@@ -373,17 +424,24 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   // its q . o^k is formed once per workgroup (waves that do not rotate a query head), not per wave.
   static_assert(NW == 8, "prologue work split assumes 8 waves: 4 rotate the query, 4 do the rest");
   const int grp_pre = group_of(g, min(t0, g.page_tokens * g.pages_per_seq - 1));
-  __half2 ok_pre = __half2{};
-  if (!ROPE && wave >= 4 && wave - 4 < R)
-    ok_pre = *reinterpret_cast<const __half2*>(
-        reinterpret_cast<const unsigned char*>(kc.means + (mean_base + grp_pre) * kHeadDim) + lane_x4);
+  Side pre = {};  // only the key-side mean fields are used
+  if (!ROPE && wave >= 4 && wave - 4 < R) {
+    if constexpr (DQ) {
+      const unsigned char* km = reinterpret_cast<const unsigned char*>(kc.means) + (mean_base + grp_pre) * kDqMeanRec;
+      pre.okq = km[lane];
+      pre.okp = *reinterpret_cast<const __half2*>(km + kDqMeanPar + 4 * (lane >> 4));
+    } else {
+      pre.ok2 = *reinterpret_cast<const __half2*>(
+          reinterpret_cast<const unsigned char*>(kc.means + (mean_base + grp_pre) * kHeadDim) + lane_x4);
+    }
+  }
   // With several Shift groups per split (group_size > 0), wave 5 forms q . o^k of all of them at
   // once: lane j owns group g_first + j, its fp16 mean row is the B operand of the same contraction
   // that the residual tokens use (unrotated query hi + lo as the A operand), 64 MFMAs in the
   // shadow of the table fill instead of four wave-wide sums per group and wave in the main loop.
   const int g_first = grp_pre;
   int n_tab = 0;
-  if (!ROPE && g.group_size > 0) {
+  if (!ROPE && !DQ && g.group_size > 0) {  // (4-bit means: no fp16 rows to feed the matrix cores; in-loop form)
     const int g_last = group_of(g, min(t0 + per - 1, g.page_tokens * g.pages_per_seq - 1));
     n_tab = g_last - g_first + 1;
     if (n_tab > SM::kQoTabGroups) n_tab = 0;  // very long splits keep the in-loop form
@@ -449,8 +507,9 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   }
   if (!ROPE && wave >= 4 && wave - 4 < R) {
     const int hh = wave - 4;
-    const float dot = wave_sum_u(sm_q_orig[hh][2 * lane] * __low2float(ok_pre) +
-                                 sm_q_orig[hh][2 * lane + 1] * __high2float(ok_pre));
+    float op0, op1;
+    mean_pair(pre, true, op0, op1);
+    const float dot = wave_sum_u(sm_q_orig[hh][2 * lane] * op0 + sm_q_orig[hh][2 * lane + 1] * op1);
     if (lane == 0) sm_qo_first[hh] = dot * scale_log2e;
   }
   if (tab_wave) {
@@ -724,7 +783,8 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       const float cs[8] = {in.c01.x, in.c01.y, in.c01.z, in.c01.w, in.c23.x, in.c23.y, in.c23.z, in.c23.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const float o0 = (float)oa[e], o1 = (float)ob[e];
+        const float o0 = DQ ? lvl(in.oap, (in.oaq >> (4 * e)) & 15u) : (float)oa[e];
+        const float o1 = DQ ? lvl(in.obp, (in.obq >> (4 * e)) & 15u) : (float)ob[e];
         const float cc = cs[2 * e] * scale_log2e, ss = cs[2 * e + 1] * scale_log2e;
         rl[e] = o0 * cc - o1 * ss;
         rh[e] = o1 * cc + o0 * ss;
@@ -801,8 +861,15 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       else
         load_group(gi + NW, nxt_full);
     }
-    const float a_k = valid ? __low2float(cur.nk) : 0.f, b_k = valid ? __high2float(cur.nk) : 0.f;
-    const float a_v = valid ? __low2float(cur.nv) : 0.f, b_v = valid ? __high2float(cur.nv) : 0.f;
+    float a_k = 0.f, b_k = 0.f, a_v = 0.f, b_v = 0.f;
+    if constexpr (DQ) {  // b = min + step * code, a = b * a'
+      const uint32_t sh = (lane & 1) * 4;
+      const float bk = lvl(cur.s.kp, (cur.s.kq >> sh) & 15u), bv = lvl(cur.s.vp, (cur.s.vq >> sh) & 15u);
+      if (valid) a_k = bk * half_bits(cur.s.ka), b_k = bk, a_v = bv * half_bits(cur.s.va), b_v = bv;
+    } else {
+      if (valid)
+        a_k = __low2float(cur.s.nk), b_k = __high2float(cur.s.nk), a_v = __low2float(cur.s.nv), b_v = __high2float(cur.s.nv);
+    }
 
     // Shift group bookkeeping (wave-uniform): mean term of the old group, q . o^k of the new one
     const int grp = group_of(g, tg);
@@ -825,15 +892,15 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
 #pragma unroll
         for (int i = 0; i < R; ++i) qo[i] = qo_pre[i];
       } else {
-        const float o0 = __low2float(cur.ok2), o1 = __high2float(cur.ok2);
+        float o0, o1;
+        mean_pair(cur.s, true, o0, o1);
 #pragma unroll
         for (int i = 0; i < R; ++i) {
           const float2 q2 = *reinterpret_cast<const float2*>(&sm_q_keep[i][2 * lane]);
           qo[i] = wave_sum_u(q2.x * o0 + q2.y * o1) * scale_log2e;
         }
       }
-      ov0 = __low2float(cur.ov2);
-      ov1 = __high2float(cur.ov2);
+      mean_pair(cur.s, false, ov0, ov1);
       cur_group = grp;
     }
 
@@ -884,7 +951,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     if (has_next) {
       if constexpr (kInPlace) {
         load_v_codes(gi + NW, cur);  // likewise the value codes
-        cur.nk = nxt.nk, cur.nv = nxt.nv, cur.ok2 = nxt.ok2, cur.ov2 = nxt.ov2;
+        cur.s = nxt;
       } else {
         cur = nxt_full;
       }
@@ -1132,7 +1199,7 @@ extern "C" int nsn_debug_decode_timing(long long* host48) {
 #endif
 
 // ---------------------------------------------------------------------------------------
-template <int SUB, int NW, int R, bool SGN = false, bool ROPE = false>
+template <int SUB, int NW, int R, bool SGN = false, bool ROPE = false, bool DQ = false>
 static int launch_one(const Geometry& g, const void* codebook, const void* q, const CacheView& kv,
                       const CacheView& vv, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                       int n_splits, void* workspace, size_t counter_bytes, const ResidualView& res, int head_off,
@@ -1143,10 +1210,10 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
     // the gathers address the codebook table by absolute LDS address: it must start at 0,
     // i.e. the kernel may not own any static LDS in front of its dynamic block
     hipFuncAttributes fa;
-    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN, ROPE>)) != hipSuccess ||
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN, ROPE, DQ>)) != hipSuccess ||
         fa.sharedSizeBytes != 0)
       return NSN_ERR_HIP;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN, ROPE>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN, ROPE, DQ>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return NSN_ERR_HIP;
     attr_done = true;
@@ -1156,7 +1223,7 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
   float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + counter_bytes);
   const dim3 grid(n_splits, g.n_kv_heads, batch);
   const int waves = res.k != nullptr ? NW + 1 : NW;  // + the residual wave
-  dec_mfma_kernel<SUB, NW, R, SGN, ROPE><<<grid, waves * 64, smem, stream>>>(
+  dec_mfma_kernel<SUB, NW, R, SGN, ROPE, DQ><<<grid, waves * 64, smem, stream>>>(
       g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens, scale * 1.44269504088896340736f, n_splits,
       per, partial, counters, res, head_off, r_pass, out);
   return NSN_OK;
@@ -1196,23 +1263,24 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
     const int r = min(4, r_total - head_off);
 #define NSN_ARGS \
   g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, cb, res, head_off, r, out, stream
+    // instance = (code format) x (heads of this launch: 1, 2, or 3-4) x (mean turned in the kernel) x (4-bit side information)
+    auto with_r = [&](auto sub, auto sgn, auto rope, auto dq) {
+      constexpr int kSub = decltype(sub)::value;
+      constexpr bool kSgn = decltype(sgn)::value, kRope = decltype(rope)::value, kDq = decltype(dq)::value;
+      return r == 1   ? launch_one<kSub, 8, 1, kSgn, kRope, kDq>(NSN_ARGS)
+             : r == 2 ? launch_one<kSub, 8, 2, kSgn, kRope, kDq>(NSN_ARGS)
+                      : launch_one<kSub, 8, 4, kSgn, kRope, kDq>(NSN_ARGS);
+    };
+    auto with_format = [&](auto rope, auto dq) {
+      if (g.sign) return with_r(std::integral_constant<int, 8>{}, std::true_type{}, rope, dq);
+      if (s.sub_dim == 4) return with_r(std::integral_constant<int, 4>{}, std::false_type{}, rope, dq);
+      return with_r(std::integral_constant<int, 8>{}, std::false_type{}, rope, dq);
+    };
     int rc;
-    if (g.rope && g.sign)
-      rc = r == 1 ? launch_one<8, 8, 1, true, true>(NSN_ARGS) : r == 2 ? launch_one<8, 8, 2, true, true>(NSN_ARGS)
-                                                                        : launch_one<8, 8, 4, true, true>(NSN_ARGS);
-    else if (g.rope && s.sub_dim == 4)
-      rc = r == 1 ? launch_one<4, 8, 1, false, true>(NSN_ARGS) : r == 2 ? launch_one<4, 8, 2, false, true>(NSN_ARGS)
-                                                                         : launch_one<4, 8, 4, false, true>(NSN_ARGS);
-    else if (g.rope)
-      rc = r == 1 ? launch_one<8, 8, 1, false, true>(NSN_ARGS) : r == 2 ? launch_one<8, 8, 2, false, true>(NSN_ARGS)
-                                                                         : launch_one<8, 8, 4, false, true>(NSN_ARGS);
-    else if (g.sign)
-      rc = r == 1 ? launch_one<8, 8, 1, true>(NSN_ARGS) : r == 2 ? launch_one<8, 8, 2, true>(NSN_ARGS)
-                                                                  : launch_one<8, 8, 4, true>(NSN_ARGS);
-    else if (s.sub_dim == 4)
-      rc = r == 1 ? launch_one<4, 8, 1>(NSN_ARGS) : r == 2 ? launch_one<4, 8, 2>(NSN_ARGS) : launch_one<4, 8, 4>(NSN_ARGS);
+    if (g.rope)
+      rc = g.dq ? with_format(std::true_type{}, std::true_type{}) : with_format(std::true_type{}, std::false_type{});
     else
-      rc = r == 1 ? launch_one<8, 8, 1>(NSN_ARGS) : r == 2 ? launch_one<8, 8, 2>(NSN_ARGS) : launch_one<8, 8, 4>(NSN_ARGS);
+      rc = g.dq ? with_format(std::false_type{}, std::true_type{}) : with_format(std::false_type{}, std::false_type{});
 #undef NSN_ARGS
     if (rc != NSN_OK) return rc;
   }

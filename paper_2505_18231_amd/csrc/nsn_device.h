@@ -40,7 +40,12 @@ constexpr int kSignCodes = 65536;  // n_codes value that selects the sign + inde
 constexpr int kRopeHiOff = 0, kRopeLoOff = 16384, kRopeInOff = 32768, kRopeBlkOff = 32768 + 65536;
 constexpr int kRopeBlkStride = 1536, kRopeBlk64 = 512;
 
+// Double quantization (side_bits = 4): byte sizes of a 64-token norms record and of a mean record
+constexpr int kDqNormRec = 164, kDqNormCodes = 128, kDqNormPar = 160;
+constexpr int kDqMeanRec = 80, kDqMeanPar = 64;
+
 struct Geometry {
+  int dq;                     // 1: norms and means are stored in 4 bits (records above)
   const unsigned char* rope;  // table of nsn_build_rope_table, or nullptr (keys coded as given)
   int sign;         // 1: an 8-dim sub-vector is an index byte plus a sign byte (byte rows 0..15 / 16..31)
   int J;            // code bytes per token
@@ -70,6 +75,15 @@ __device__ inline int64_t unit_token_base(const Geometry& g, const int32_t* bloc
 }
 __device__ inline int token_in_unit(const Geometry& g, int t) { return g.paged ? t % g.page_tokens : t; }
 __device__ inline int group_of(const Geometry& g, int t) { return g.group_size > 0 ? t / g.group_size : 0; }
+
+// Double quantization: record of the 64-token block holding token t of a placement unit that starts at
+// token index `base`; mean record of (unit-relative) group gidx
+__device__ inline unsigned char* dq_norm_rec(const CacheView& cv, int64_t base, int tin) {
+  return reinterpret_cast<unsigned char*>(cv.norms) + ((base + tin) >> 6) * kDqNormRec;
+}
+__device__ inline unsigned char* dq_mean_rec(const CacheView& cv, int64_t mean_index) {
+  return reinterpret_cast<unsigned char*>(cv.means) + mean_index * kDqMeanRec;
+}
 
 // ---- numeric helpers ------------------------------------------------------------------
 // fp64 -> fp16, round to nearest even in a single rounding: go through fp32 with

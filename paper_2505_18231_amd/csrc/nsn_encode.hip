@@ -5,6 +5,10 @@
 //   enc_stats_kernel  per token: b = fp16(||x|| / sqrt(d)); per chunk: fp64 partial sums of x / b
 //   enc_means_kernel  per group: o = fp16(sum of partials / count)           (skipped in append mode)
 //   enc_quant_kernel  per token: (x / b - o) -> s2 -> rotate -> codes, a = fp16(b * s2 * alpha)
+// Double quantization (Sec. 3.5, side_bits = 4): enc_stats_kernel leaves fp16(s1) in the workspace,
+// enc_brtn_kernel turns every 64-token block of them into 4-bit codes, enc_means_kernel stores the
+// means as 4-bit codes per 32 channels, and enc_quant_kernel shifts by the dequantised mean and
+// stores a' = fp16(s2 * alpha).
 // Normalisation, rotation and the dot products that feed fp16 roundings run in fp64 (same rate
 // as fp32 on this chip's vector units); only the 256-way distance scan runs in fp32.
 #include "nsn_host.h"
@@ -34,11 +38,12 @@ __global__ __launch_bounds__(256) void enc_stats_kernel(Geometry g, const __half
                                                         int max_len, const int32_t* __restrict__ seq_start,
                                                         const int32_t* __restrict__ n_new, CacheView kc,
                                                         CacheView vc, double* __restrict__ partial,
-                                                        int chunk_tokens, int n_chunks) {
+                                                        int chunk_tokens, int n_chunks, __half* __restrict__ ws_b) {
   const int chunk = blockIdx.x, h = blockIdx.y >> 1, tensor = blockIdx.y & 1, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const CacheView& cv = tensor ? vc : kc;
   const __half* in = (tensor ? v_in : k_in) + ((int64_t)(b * g.n_kv_heads + h) * max_new) * kHeadDim;
+  __half* wsb = ws_b + ((int64_t)(b * g.n_kv_heads + h) * 2 + tensor) * max_new;  // side_bits = 4 only
   const int start = seq_start[b];
   const int count = min(n_new[b], max_new);
   const int t_end = min((chunk + 1) * chunk_tokens, count);
@@ -58,8 +63,12 @@ __global__ __launch_bounds__(256) void enc_stats_kernel(Geometry g, const __half
       acc1 += x1 / bb;
     }
     if (lane == 0) {
-      const int64_t base = unit_token_base(g, cv.block_table, b, h, pos);
-      reinterpret_cast<__half*>(cv.norms)[2 * (base + token_in_unit(g, pos)) + 1] = b16;
+      if (g.dq) {
+        wsb[t] = b16;
+      } else {
+        const int64_t base = unit_token_base(g, cv.block_table, b, h, pos);
+        reinterpret_cast<__half*>(cv.norms)[2 * (base + token_in_unit(g, pos)) + 1] = b16;
+      }
     }
   }
   __shared__ double red[4][kHeadDim];
@@ -71,6 +80,47 @@ __global__ __launch_bounds__(256) void enc_stats_kernel(Geometry g, const __half
     const double s = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
     partial[((((int64_t)(b * g.n_kv_heads + h) * 2 + tensor) * n_chunks) + chunk) * kHeadDim + c] = s;
   }
+}
+
+// 4-bit round-to-nearest levels of one group (Sec. 3.5): minimum and step in fp16, the code of x taken
+// against the rounded minimum and step
+__device__ inline int rtn4_code(double x, double mn, double st) {
+  if (st == 0.0) return 0;
+  const double lvl = floor((x - mn) / st + 0.5);
+  return (int)fmin(fmax(lvl, 0.0), 15.0);
+}
+
+// ---------------------------------------------------------------------------------------
+// Stage A1 (side_bits = 4): 4-bit codes of fp16(s1) per 64-token block.  grid (64-token block of the
+// call, kv_head * 2 + tensor, sequence), block 64: a lane owns one token.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void enc_brtn_kernel(Geometry g, int max_new, int max_len,
+                                                      const int32_t* __restrict__ seq_start,
+                                                      const int32_t* __restrict__ n_new, CacheView kc, CacheView vc,
+                                                      const __half* __restrict__ ws_b) {
+  const int h = blockIdx.y >> 1, tensor = blockIdx.y & 1, b = blockIdx.z;
+  const int lane = threadIdx.x;
+  const CacheView& cv = tensor ? vc : kc;
+  const int start = seq_start[b];
+  const int count = min(n_new[b], max_new);
+  const int t = blockIdx.x * 64 + lane, pos = start + t;
+  const bool valid = t < count && pos < max_len;
+  if (blockIdx.x * 64 >= count || start + blockIdx.x * 64 >= max_len) return;  // uniform: lane 0 is valid below
+  const float x = valid ? __half2float(ws_b[((int64_t)(b * g.n_kv_heads + h) * 2 + tensor) * max_new + t]) : 0.f;
+  float lo = valid ? x : INFINITY, hi = valid ? x : -INFINITY;
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    lo = fminf(lo, __shfl_xor(lo, m, 64));
+    hi = fmaxf(hi, __shfl_xor(hi, m, 64));
+  }
+  const __half mn16 = f64_to_f16((double)lo);  // exact: the minimum is one of the fp16 inputs
+  const __half st16 = f64_to_f16(((double)hi - (double)lo) / 15.0);
+  const int code = valid ? rtn4_code((double)x, (double)__half2float(mn16), (double)__half2float(st16)) : 0;
+  const int other = __shfl_xor(code, 1, 64);
+  const int pos0 = start + blockIdx.x * 64;  // the block's first token (the record is chosen by it)
+  unsigned char* rec = dq_norm_rec(cv, unit_token_base(g, cv.block_table, b, h, pos0), token_in_unit(g, pos0));
+  if ((lane & 1) == 0 && valid) rec[kDqNormCodes + (lane >> 1)] = (unsigned char)(code | (other << 4));
+  if (lane == 0) *reinterpret_cast<__half2*>(rec + kDqNormPar) = __halves2half2(mn16, st16);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -103,8 +153,25 @@ __global__ __launch_bounds__(128) void enc_means_kernel(Geometry g, int max_new,
   const double* p = partial + (((int64_t)(b * g.n_kv_heads + h) * 2 + tensor) * n_chunks) * kHeadDim + c;
   double s = 0.0;
   for (int k = first_chunk; k < last_chunk; ++k) s += p[(int64_t)k * kHeadDim];
-  cv.means[((int64_t)(b * g.n_kv_heads + h) * g.n_groups_max + g_abs) * kHeadDim + c] =
-      f64_to_f16(s / (double)tokens);
+  const double mean = s / (double)tokens;
+  const int64_t mean_index = (int64_t)(b * g.n_kv_heads + h) * g.n_groups_max + g_abs;
+  if (!g.dq) {
+    cv.means[mean_index * kHeadDim + c] = f64_to_f16(mean);
+    return;
+  }
+  // side_bits = 4: 16 levels per 32 channels (half a wave)
+  double lo = mean, hi = mean;
+#pragma unroll
+  for (int m = 1; m < 32; m <<= 1) {
+    lo = fmin(lo, __shfl_xor(lo, m, 64));
+    hi = fmax(hi, __shfl_xor(hi, m, 64));
+  }
+  const __half mn16 = f64_to_f16(lo), st16 = f64_to_f16((hi - lo) / 15.0);
+  const int code = rtn4_code(mean, (double)__half2float(mn16), (double)__half2float(st16));
+  const int other = __shfl_xor(code, 1, 64);
+  unsigned char* rec = dq_mean_rec(cv, mean_index);
+  if ((c & 1) == 0) rec[c >> 1] = (unsigned char)(code | (other << 4));
+  if ((c & 31) == 0) *reinterpret_cast<__half2*>(rec + kDqMeanPar + 4 * (c >> 5)) = __halves2half2(mn16, st16);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -145,7 +212,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
                                                         const __half* __restrict__ v_in, int max_new,
                                                         int max_len, const int32_t* __restrict__ seq_start,
                                                         const int32_t* __restrict__ n_new, CacheView kc,
-                                                        CacheView vc, int wave_tokens) {
+                                                        CacheView vc, int wave_tokens,
+                                                        const __half* __restrict__ ws_b) {
   // wave_tokens: tokens per wave (16, or 4 when the call is too small to fill the chip with 64-token blocks)
   constexpr int J = kHeadDim / SUB;  // lanes per token
   constexpr int TPW = 64 / J;        // tokens per wave step
@@ -170,6 +238,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
     int tin, pos;
     vec_t xraw, oraw;
     __half b16;
+    uint32_t oq;  // side_bits = 4: the SUB 4-bit codes of this lane's channels of the mean
+    __half2 op;   //                (min, step) of their 32-channel group
   };
   auto fetch = [&](int it) {
     Tok k;
@@ -182,14 +252,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
     k.xraw = vec_t{};
     k.oraw = vec_t{};
     k.b16 = __float2half(0.f);
+    k.oq = 0u;
+    k.op = __half2{};
     if (k.valid) {
       k.base = unit_token_base(g, cv.block_table, b, h, pos);
       k.tin = token_in_unit(g, pos);
       k.xraw = *reinterpret_cast<const vec_t*>(in + (int64_t)t * kHeadDim + jj * SUB);
-      k.oraw = *reinterpret_cast<const vec_t*>(
-          cv.means + ((int64_t)(b * g.n_kv_heads + h) * g.n_groups_max + min(group_of(g, pos), g.n_groups_max - 1)) *
-                         kHeadDim + jj * SUB);
-      if constexpr (!FUSED) k.b16 = reinterpret_cast<const __half*>(cv.norms)[2 * (k.base + k.tin) + 1];
+      const int64_t mean_index =
+          (int64_t)(b * g.n_kv_heads + h) * g.n_groups_max + min(group_of(g, pos), g.n_groups_max - 1);
+      if (g.dq) {
+        const unsigned char* rec = dq_mean_rec(cv, mean_index);
+        if constexpr (SUB == 4)
+          k.oq = *reinterpret_cast<const uint16_t*>(rec + jj * 2);
+        else
+          k.oq = *reinterpret_cast<const uint32_t*>(rec + jj * 4);
+        k.op = *reinterpret_cast<const __half2*>(rec + kDqMeanPar + 4 * ((jj * SUB) >> 5));
+        if constexpr (!FUSED) k.b16 = ws_b[((int64_t)(b * g.n_kv_heads + h) * 2 + tensor) * max_new + t];
+      } else {
+        k.oraw = *reinterpret_cast<const vec_t*>(cv.means + mean_index * kHeadDim + jj * SUB);
+        if constexpr (!FUSED) k.b16 = reinterpret_cast<const __half*>(cv.norms)[2 * (k.base + k.tin) + 1];
+      }
     }
     return k;
   };
@@ -223,6 +305,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
         xs[i] = (double)__half2float(xh[i]);
         os[i] = (double)__half2float(oh[i]);
       }
+      if (g.dq) {  // dequantised mean: min + step * code
+        const double mn = (double)__low2float(cur.op), st = (double)__high2float(cur.op);
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) os[i] = mn + st * (double)((cur.oq >> (4 * i)) & 15u);
+      }
     }
     if constexpr (FUSED) {  // first Normalize here: b = fp16(||x|| / sqrt(d)), stored with the token
       double ssx = 0.0;
@@ -230,7 +317,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
       for (int i = 0; i < SUB; ++i) ssx += xs[i] * xs[i];
       ssx = xor_sum_w<J>(ssx);
       b16f = f64_to_f16(sqrt(ssx) / kSqrtD);
-      if (valid && jj == 0) reinterpret_cast<__half*>(cv.norms)[2 * (base + tin) + 1] = b16f;
+      if (valid && jj == 0 && !g.dq) reinterpret_cast<__half*>(cv.norms)[2 * (base + tin) + 1] = b16f;
     }
     const double bb = (double)__half2float(b16f);
     double v[SUB];
@@ -322,7 +409,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
         const int64_t soff = tensor ? v_code_offset(JB, tin, J + jj) : k_code_offset(JB, tin, J + jj);
         cv.codes[base * JB + soff] = (uint8_t)sign_byte;
       }
-      if (jj == 0) reinterpret_cast<__half*>(cv.norms)[2 * (base + tin)] = f64_to_f16(bb * s2 * alpha);
+      if (jj == 0) {
+        if (g.dq)  // a' = fp16(s2 alpha); s1 is stored separately as a 4-bit code
+          reinterpret_cast<__half*>(dq_norm_rec(cv, base, tin))[tin & 63] = f64_to_f16(s2 * alpha);
+        else
+          reinterpret_cast<__half*>(cv.norms)[2 * (base + tin)] = f64_to_f16(bb * s2 * alpha);
+      }
     }
     NSN_ETSTAMP(6);
   }
@@ -333,10 +425,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
 // ---------------------------------------------------------------------------------------
 static int encode_chunk_tokens(const nsn_shape& s) { return s.group_size > 0 ? s.group_size : 256; }
 
-size_t encode_workspace_bytes(const nsn_shape& s, int batch, int64_t max_new) {
+static size_t encode_partial_bytes(const nsn_shape& s, int batch, int64_t max_new) {
   const int ct = encode_chunk_tokens(s);
   const int64_t n_chunks = (max_new + ct - 1) / ct;
   return (size_t)batch * s.n_kv_heads * 2 * n_chunks * kHeadDim * sizeof(double);
+}
+
+size_t encode_workspace_bytes(const nsn_shape& s, int batch, int64_t max_new) {
+  // side_bits = 4: fp16(s1) of every new token passes through the workspace
+  const size_t b_bytes = s.side_bits == 4 ? (((size_t)batch * s.n_kv_heads * 2 * max_new * sizeof(__half)) + 255) & ~(size_t)255 : 0;
+  return encode_partial_bytes(s, batch, max_new) + b_bytes;
 }
 
 int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, const void* v_in, int max_new,
@@ -347,47 +445,55 @@ int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, co
   const int ct = encode_chunk_tokens(s);
   const int n_chunks = (max_new + ct - 1) / ct;
   double* partial = static_cast<double*>(workspace);
+  __half* ws_b = reinterpret_cast<__half*>(static_cast<unsigned char*>(workspace) + encode_partial_bytes(s, batch, max_new));
   const char* impl = getenv("NSN_ENCODE_IMPL");  // "valu" forces the vector-ALU distance scan
   const bool use_mfma = !(impl && impl[0] == 'v');
-  if (!freeze_means) {
+  if (!freeze_means || g.dq) {  // side_bits = 4: the s1 codes of a block need all its tokens first
     const dim3 grid_a(n_chunks, s.n_kv_heads * 2, batch);
     enc_stats_kernel<<<grid_a, 256, 0, stream>>>(g, (const __half*)k_in, (const __half*)v_in, max_new, s.max_len,
-                                                 seq_start, n_new, kv, vv, partial, ct, n_chunks);
+                                                 seq_start, n_new, kv, vv, partial, ct, n_chunks, ws_b);
+    if (g.dq) {
+      const dim3 grid_r((max_new + 63) / 64, s.n_kv_heads * 2, batch);
+      enc_brtn_kernel<<<grid_r, 64, 0, stream>>>(g, max_new, s.max_len, seq_start, n_new, kv, vv, ws_b);
+    }
+  }
+  if (!freeze_means) {
     const int n_groups_new = s.group_size > 0 ? n_chunks : 1;
     const dim3 grid_m(n_groups_new, s.n_kv_heads * 2, batch);
     enc_means_kernel<<<grid_m, 128, 0, stream>>>(g, max_new, s.max_len, seq_start, n_new, kv, vv, partial, ct,
                                                  n_chunks);
   }
+  const bool fused = freeze_means && !g.dq;  // the quantiser computes s1 itself (append mode)
   // 64 tokens per workgroup; calls that would leave most compute units idle use 16 (4 per wave)
   const int64_t blocks64 = (int64_t)((max_new + 63) / 64) * s.n_kv_heads * 2 * batch;
   const int wave_tokens = blocks64 >= 1024 ? 16 : 4;
   const dim3 grid_b((max_new + 4 * wave_tokens - 1) / (4 * wave_tokens), s.n_kv_heads * 2, batch);
   auto launch = [&](auto kernel) {
     kernel<<<grid_b, 256, 0, stream>>>(g, (const __half*)codebook, (const __half*)k_in, (const __half*)v_in, max_new,
-                                       s.max_len, seq_start, n_new, kv, vv, wave_tokens);
+                                       s.max_len, seq_start, n_new, kv, vv, wave_tokens, ws_b);
   };
   if (g.rope) {  // keys before the rotary embedding: matrix-core search only
     if (g.sign)
-      freeze_means ? launch(enc_quant_kernel<8, true, true, true, true>) : launch(enc_quant_kernel<8, true, false, true, true>);
+      fused ? launch(enc_quant_kernel<8, true, true, true, true>) : launch(enc_quant_kernel<8, true, false, true, true>);
     else if (s.sub_dim == 8)
-      freeze_means ? launch(enc_quant_kernel<8, true, true, false, true>) : launch(enc_quant_kernel<8, true, false, false, true>);
+      fused ? launch(enc_quant_kernel<8, true, true, false, true>) : launch(enc_quant_kernel<8, true, false, false, true>);
     else
-      freeze_means ? launch(enc_quant_kernel<4, true, true, false, true>) : launch(enc_quant_kernel<4, true, false, false, true>);
+      fused ? launch(enc_quant_kernel<4, true, true, false, true>) : launch(enc_quant_kernel<4, true, false, false, true>);
   } else if (g.sign) {
     if (use_mfma)
-      freeze_means ? launch(enc_quant_kernel<8, true, true, true>) : launch(enc_quant_kernel<8, true, false, true>);
+      fused ? launch(enc_quant_kernel<8, true, true, true>) : launch(enc_quant_kernel<8, true, false, true>);
     else
-      freeze_means ? launch(enc_quant_kernel<8, false, true, true>) : launch(enc_quant_kernel<8, false, false, true>);
+      fused ? launch(enc_quant_kernel<8, false, true, true>) : launch(enc_quant_kernel<8, false, false, true>);
   } else if (s.sub_dim == 8) {
     if (use_mfma)
-      freeze_means ? launch(enc_quant_kernel<8, true, true>) : launch(enc_quant_kernel<8, true, false>);
+      fused ? launch(enc_quant_kernel<8, true, true>) : launch(enc_quant_kernel<8, true, false>);
     else
-      freeze_means ? launch(enc_quant_kernel<8, false, true>) : launch(enc_quant_kernel<8, false, false>);
+      fused ? launch(enc_quant_kernel<8, false, true>) : launch(enc_quant_kernel<8, false, false>);
   } else {
     if (use_mfma)
-      freeze_means ? launch(enc_quant_kernel<4, true, true>) : launch(enc_quant_kernel<4, true, false>);
+      fused ? launch(enc_quant_kernel<4, true, true>) : launch(enc_quant_kernel<4, true, false>);
     else
-      freeze_means ? launch(enc_quant_kernel<4, false, true>) : launch(enc_quant_kernel<4, false, false>);
+      fused ? launch(enc_quant_kernel<4, false, true>) : launch(enc_quant_kernel<4, false, false>);
   }
   return hipGetLastError() == hipSuccess ? NSN_OK : NSN_ERR_HIP;
 }

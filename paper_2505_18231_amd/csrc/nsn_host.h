@@ -7,6 +7,7 @@ namespace nsn {
 
 inline Geometry make_geometry(const nsn_shape& s) {
   Geometry g;
+  g.dq = s.side_bits == 4;
   g.rope = static_cast<const unsigned char*>(s.rope_table);
   g.sign = s.n_codes == kSignCodes;
   g.J = g.sign ? 2 * (s.head_dim / s.sub_dim) : s.head_dim / s.sub_dim;

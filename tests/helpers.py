@@ -119,3 +119,87 @@ def max_rel_err(out: np.ndarray, ref: np.ndarray) -> float:
     num = np.abs(out - ref).max(axis=-1)
     den = np.abs(ref).max(axis=-1)
     return float((num / np.maximum(den, 1e-30)).max())
+
+
+# ---- double quantization (side_bits = 4): the record layouts of include/nsn.h, written out in numpy ----
+def _pack_nibbles(codes: np.ndarray) -> np.ndarray:
+    """u8 [..., 2n] values 0..15 -> u8 [..., n]; even index = low nibble."""
+    return (codes[..., 0::2] | (codes[..., 1::2] << 4)).astype(np.uint8)
+
+
+def _unpack_nibbles(raw: np.ndarray) -> np.ndarray:
+    out = np.empty(raw.shape[:-1] + (raw.shape[-1] * 2,), dtype=np.uint8)
+    out[..., 0::2] = raw & 15
+    out[..., 1::2] = raw >> 4
+    return out
+
+
+class HostCacheDQ(HostCache):
+    """HostCache with 4-bit side information: norms = 164-byte records per 64-token block
+    ([0,128) a' fp16, [128,160) s1 codes, [160,164) (min, step) fp16), means = 80-byte records per group
+    ([0,64) codes, [64,80) four (min, step) fp16 pairs)."""
+
+    def __init__(self, kind, batch, hkv, J, max_len, G, page_size=0, block_table=None, n_pages=None):
+        super().__init__(kind, batch, hkv, J, max_len, G, page_size, block_table, n_pages)
+        units = self.codes.shape[0]
+        per_unit = (page_size or max_len) // 64
+        self.norms = np.zeros((units, hkv, per_unit, 164), dtype=np.uint8)
+        self.means = np.zeros((batch, hkv, self.ng, 80), dtype=np.uint8)
+
+    # norm records of one (sequence, head) in logical block order: [max_len / 64][164]
+    def _records(self, b, h) -> np.ndarray:
+        if not self.page:
+            return self.norms[b, h].copy()
+        return np.concatenate([self.norms[self.bt[b, p], h] for p in range(self.max_len // self.page)], axis=0)
+
+    def _set_records(self, b, h, rec):
+        if not self.page:
+            self.norms[b, h] = rec
+            return
+        per = self.page // 64
+        for p in range(self.max_len // self.page):
+            self.norms[self.bt[b, p], h] = rec[p * per:(p + 1) * per]
+
+    def put_unit(self, b, h, enc: dict, start: int = 0, write_means: bool = True):
+        L = enc["codes"].shape[0]
+        assert start % 64 == 0
+        if write_means:
+            first = start // self.G if self.G else 0
+            ng_new = n_groups(L, self.G) if self.G else 1
+            for gi in range(first, first + ng_new):
+                self.means[b, h, gi, :64] = _pack_nibbles(enc["o_code"][gi])
+                self.means[b, h, gi, 64:] = enc["o_par"][gi].astype(np.float16).reshape(-1).view(np.uint8)
+        logical_codes = self.get_codes(b, h)
+        logical_codes[start:start + L] = enc["codes"]
+        rec = self._records(b, h)
+        a_all = rec[:, :128].copy().view(np.float16).reshape(-1)
+        c_all = _unpack_nibbles(rec[:, 128:160]).reshape(-1)
+        a_all[start:start + L] = enc["a_stored"]
+        c_all[start:start + L] = enc["b_code"]
+        rec[:, :128] = a_all.reshape(-1, 64).view(np.uint8)
+        rec[:, 128:160] = _pack_nibbles(c_all.reshape(-1, 64))
+        for blk in range(start // 64, (start + L + 63) // 64):
+            rec[blk, 160:164] = enc["b_par"][blk].astype(np.float16).view(np.uint8)
+        self._set_records(b, h, rec)
+        if not self.page:
+            self.codes[b, h] = pack_codes(logical_codes, self.kind, self.max_len)
+        else:
+            for p in range(self.max_len // self.page):
+                self.codes[self.bt[b, p], h] = pack_codes(logical_codes[p * self.page:(p + 1) * self.page], self.kind,
+                                                          self.page)
+
+    def unit_dict(self, b, h, length) -> dict:
+        """Effective float64 a, b, o (what the decoder reconstructs) plus the stored fields."""
+        rec = self._records(b, h)
+        a_stored = rec[:, :128].copy().view(np.float16).reshape(-1)[:length]
+        b_code = _unpack_nibbles(rec[:, 128:160]).reshape(-1)[:length]
+        b_par = rec[:, 160:164].copy().view(np.float16).reshape(-1, 2)
+        blk = np.arange(length) // 64
+        b_hat = b_par[blk, 0].astype(np.float64) + b_par[blk, 1].astype(np.float64) * b_code
+        ng = n_groups(length, self.G)
+        o_code = _unpack_nibbles(self.means[b, h, :ng, :64])
+        o_par = self.means[b, h, :ng, 64:].copy().view(np.float16).reshape(ng, 4, 2)
+        o_hat = (np.repeat(o_par[:, :, 0].astype(np.float64), 32, axis=1) +
+                 np.repeat(o_par[:, :, 1].astype(np.float64), 32, axis=1) * o_code)
+        return dict(codes=self.get_codes(b, h)[:length], a=b_hat * a_stored.astype(np.float64), b=b_hat, o=o_hat,
+                    a_stored=a_stored, b_code=b_code, b_par=b_par[:(length + 63) // 64], o_code=o_code, o_par=o_par)

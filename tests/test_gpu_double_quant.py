@@ -1,0 +1,272 @@
+"""GPU parity with double quantization (Sec. 3.5; shape.side_bits = 4): the first-Normalize scale is
+stored as 4-bit codes per 64-token block, the group means as 4-bit codes per 32 channels.
+Encoder: the stored side information (codes, fp16 minimum and step) is compared bit-exactly with
+the oracle's; codes and a' then follow the usual two-stage protocol, conditioned on the device's
+stored means.  Decode: oracle-encoded caches, 2e-3 per output row."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import nsn_oracle as O
+from paper_2505_18231_amd import synth
+from tests import helpers
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def magnitude_codebook():
+    x = np.abs(synth.codebook_samples(4242, 1 << 13, 8).astype(np.float64))
+    cb, _, _ = O.build_codebook(x, 256, 5)
+    return cb
+
+
+@pytest.fixture(scope="module")
+def rope(gpu_api):
+    f = synth.rope_inv_freq(500000.0)
+    return f, gpu_api.nsn_build_rope_table(f, 8192)
+
+
+def _encode_on_gpu(api, seed, batch, hkv, lens, sub, G, cb, page, sign, starts=None, freeze=False, caches=None,
+                   max_len=None, rope_table=None):
+    import torch
+    J = (2 if sign else 1) * (128 // sub)
+    starts = starts or [0] * batch
+    max_new = max(lens)
+    max_len = max_len or ((max(s + l for s, l in zip(starts, lens)) + 255) // 256) * 256
+    k = np.zeros((batch, hkv, max_new, 128), dtype=np.float16)
+    v = np.zeros_like(k)
+    for b in range(batch):
+        for h in range(hkv):
+            k[b, h, :lens[b]] = synth.make_k(seed, b, h, lens[b], start=starts[b])
+            v[b, h, :lens[b]] = synth.make_v(seed, b, h, lens[b], start=starts[b])
+    shape = api.make_shape(sub, hkv, hkv, max_len, G, page, sign_format=sign, side_bits=4, rope_table=rope_table)
+    if caches is None:
+        bt = synth.shuffled_page_table(seed, batch, max_len // page) if page else None
+        hk = helpers.HostCacheDQ("k", batch, hkv, J, max_len, G, page, bt)
+        hv = helpers.HostCacheDQ("v", batch, hkv, J, max_len, G, page, bt)
+    else:
+        hk, hv = caches
+    dk, dv = hk.to_device(api, shape), hv.to_device(api, shape)
+    api.nsn_encode(shape, torch.from_numpy(cb.astype(np.float16)).cuda(), torch.from_numpy(k).cuda(),
+                   torch.from_numpy(v).cuda(), torch.tensor(starts, dtype=torch.int32).cuda(),
+                   torch.tensor(lens, dtype=torch.int32).cuda(), dk, dv, freeze_means=freeze)
+    torch.cuda.synchronize()
+    hk.from_device(dk)
+    hv.from_device(dv)
+    return k, v, hk, hv
+
+
+def _check_unit(x16, got, cb, G, sign, start=0, frozen=False, rope_inv_freq=None):
+    """got: HostCacheDQ.unit_dict of the first start + L tokens."""
+    L = x16.shape[0]
+    sl = slice(start, start + L)
+    ref = O.encode(x16, cb, G, start=start, sign_format=sign, side_bits=4, rope_inv_freq=rope_inv_freq,
+                   frozen_o=got["o"] if frozen else None)
+    # stage A: the stored side information, bit for bit
+    assert np.array_equal(ref["b_code"], got["b_code"][sl]), "s1 codes"
+    blocks = slice(start // 64, (start + L + 63) // 64)
+    assert np.array_equal(ref["b_par"][blocks].view(np.uint16), got["b_par"][blocks].view(np.uint16)), "s1 levels"
+    if not frozen:
+        g_used = np.unique(O.group_index(L, G, start))
+        assert np.array_equal(ref["o_code"][g_used], got["o_code"][g_used]), "mean codes"
+        assert np.array_equal(ref["o_par"][g_used].view(np.uint16), got["o_par"][g_used].view(np.uint16)), "mean levels"
+    # stage B: conditioned on the device's dequantised means
+    ref = O.encode(x16, cb, G, start=start, sign_format=sign, side_bits=4, given_o=got["o"], return_debug=True,
+                   rope_inv_freq=rope_inv_freq)
+    same = ref["codes"] == got["codes"][sl]
+    near_tie = (ref["second"] - ref["best"]) < 1e-6 * np.maximum(ref["second"], 1e-300)
+    if sign:
+        J = ref["codes"].shape[1] // 2
+        assert np.all(same[:, J:] | (ref["y"].reshape(L, J, 8) == 0).any(axis=2)), "sign bytes"
+        same = same[:, :J]
+    assert np.all(same | near_tie), f"{(~(same | near_tie)).sum()} code mismatches outside the tie window"
+    rows_ok = same.all(axis=1)
+    a_ref = ref["a_stored"].view(np.int16).astype(np.int32)
+    a_got = got["a_stored"][sl].view(np.int16).astype(np.int32)
+    assert np.abs(a_ref - a_got)[rows_ok].max(initial=0) <= 1, "stored scale a'"
+    return int((~same).sum())
+
+
+ENC_CASES = [
+    # name, batch, hkv, lens, sub, G, page, sign
+    ("2bit-groups-ragged", 2, 2, [300, 77], 4, 64, 0, False),
+    ("1bit-onegroup", 1, 1, [515], 8, 0, 0, False),
+    ("sign-groups-paged", 2, 1, [260, 130], 8, 64, 256, True),
+    ("2bit-groups128", 1, 2, [384], 4, 128, 0, False),
+]
+
+
+@pytest.mark.parametrize("name,batch,hkv,lens,sub,G,page,sign", ENC_CASES, ids=[c[0] for c in ENC_CASES])
+def test_double_quant_encode_matches_oracle(gpu_api, codebooks, magnitude_codebook, name, batch, hkv, lens, sub, G, page,
+                                            sign):
+    print(f"case {name} lens={lens} sub={sub} G={G} page={page} sign={sign}", flush=True)
+    cb = magnitude_codebook if sign else codebooks[sub]
+    seed = 1100 + len(name)
+    k, v, hk, hv = _encode_on_gpu(gpu_api, seed, batch, hkv, lens, sub, G, cb, page, sign)
+    flips = 0
+    for b in range(batch):
+        for h in range(hkv):
+            flips += _check_unit(k[b, h, :lens[b]], hk.unit_dict(b, h, lens[b]), cb, G, sign)
+            flips += _check_unit(v[b, h, :lens[b]], hv.unit_dict(b, h, lens[b]), cb, G, sign)
+    print(f"  near-tie code differences: {flips}", flush=True)
+
+
+def test_double_quant_block_append_with_frozen_mean(gpu_api, codebooks):
+    """One group per sequence: a later 64-token block is encoded against the stored (4-bit) mean."""
+    cb = codebooks[4]
+    lens0, more = [192, 64], [64, 37]
+    k0, v0, hk, hv = _encode_on_gpu(gpu_api, 47, 2, 2, lens0, 4, 0, cb, 0, False, max_len=256)
+    means_before = hk.means.copy()
+    k1, v1, hk, hv = _encode_on_gpu(gpu_api, 47, 2, 2, more, 4, 0, cb, 0, False, starts=lens0, freeze=True,
+                                    caches=(hk, hv), max_len=256)
+    assert np.array_equal(means_before, hk.means)
+    for b, (s, n) in enumerate(zip(lens0, more)):
+        for h in range(2):
+            _check_unit(k1[b, h, :n], hk.unit_dict(b, h, s + n), cb, 0, False, start=s, frozen=True)
+            _check_unit(k0[b, h, :s], hk.unit_dict(b, h, s), cb, 0, False)   # the earlier blocks are untouched
+
+
+DEC_CASES = [
+    # name, hq, hkv, lens, sub, G, page, splits, sign, pre_rope
+    ("gqa4-2bit-groups", 8, 2, [777, 130], 4, 64, 0, 4, False, False),
+    ("gqa4-2bit-onegroup", 4, 1, [1030, 1], 4, 0, 0, 0, False, False),
+    ("mha-1bit", 2, 2, [333, 700], 8, 64, 0, 2, False, False),
+    ("gqa2-1bit-paged", 4, 2, [900, 511], 8, 128, 256, 3, False, False),
+    ("empty-and-short", 3, 1, [0, 65], 4, 64, 0, 2, False, False),
+    ("gqa4-sign-groups", 4, 1, [600, 64], 8, 64, 0, 0, True, False),
+    ("gqa8-two-launches", 8, 1, [300, 129], 4, 64, 0, 2, False, False),
+    ("long-six-iterations", 4, 1, [6000], 4, 64, 0, 2, False, False),
+    ("gqa4-2bit-groups-prerope", 8, 2, [777, 130], 4, 64, 0, 4, False, True),
+    ("gqa4-sign-groups-prerope", 4, 1, [3000], 8, 64, 0, 1, True, True),
+    ("gqa2-1bit-onegroup-prerope", 2, 1, [1000, 64], 8, 0, 0, 3, False, True),
+]
+
+
+def _build(seed, hkv, lens, sub, G, cb, page, sign, f):
+    batch = len(lens)
+    J = (2 if sign else 1) * (128 // sub)
+    max_len = ((max(max(lens), 1) + 255) // 256) * 256
+    bt = synth.shuffled_page_table(seed, batch, max_len // page) if page else None
+    kc = helpers.HostCacheDQ("k", batch, hkv, J, max_len, G, page, bt)
+    vc = helpers.HostCacheDQ("v", batch, hkv, J, max_len, G, page, bt)
+    for b in range(batch):
+        for h in range(hkv):
+            if lens[b]:
+                kc.put_unit(b, h, O.encode(synth.make_k(seed, b, h, lens[b]), cb, G, sign_format=sign, side_bits=4,
+                                           rope_inv_freq=f))
+                vc.put_unit(b, h, O.encode(synth.make_v(seed, b, h, lens[b]), cb, G, sign_format=sign, side_bits=4))
+    return kc, vc, max_len
+
+
+@pytest.mark.parametrize("name,hq,hkv,lens,sub,G,page,splits,sign,pre_rope", DEC_CASES, ids=[c[0] for c in DEC_CASES])
+def test_double_quant_decode_matches_oracle(gpu_api, codebooks, magnitude_codebook, rope, name, hq, hkv, lens, sub, G,
+                                            page, splits, sign, pre_rope):
+    import torch
+    api = gpu_api
+    f, table = rope if pre_rope else (None, None)
+    print(f"case {name} lens={lens} sub={sub} G={G} page={page} splits={splits} sign={sign} pre_rope={pre_rope}",
+          flush=True)
+    cb = magnitude_codebook if sign else codebooks[sub]
+    batch, r = len(lens), hq // hkv
+    seed = 1150 + len(name)
+    scale = 1.0 / math.sqrt(128)
+    kc, vc, max_len = _build(seed, hkv, lens, sub, G, cb, page, sign, f)
+    q = synth.make_q(seed, batch, hq)
+    shape = api.make_shape(sub, hq, hkv, max_len, G, page, sign_format=sign, side_bits=4, rope_table=table)
+    cbd = torch.from_numpy(cb.astype(np.float16)).cuda()
+    out = api.nsn_decode_attention(shape, cbd, torch.from_numpy(q).cuda(), kc.to_device(api, shape),
+                                   vc.to_device(api, shape), torch.tensor(lens, dtype=torch.int32).cuda(),
+                                   max(lens), scale, splits)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy().astype(np.float64)
+    worst = 0.0
+    for b in range(batch):
+        if lens[b] == 0:
+            assert np.all(out[b] == 0.0)
+            continue
+        for h in range(hkv):
+            ref = O.decode_attention(q[b, h * r:(h + 1) * r].astype(np.float64), kc.unit_dict(b, h, lens[b]),
+                                     vc.unit_dict(b, h, lens[b]), cb, scale, G, sign_format=sign, rope_inv_freq=f)
+            worst = max(worst, helpers.max_rel_err(out[b, h * r:(h + 1) * r], ref))
+    print(f"  max rel err {worst:.3e}", flush=True)
+    assert worst < TOL, worst
+
+
+def test_double_quant_generation_with_residual_and_flush(gpu_api, codebooks):
+    """The paper's loop with 4-bit side information: 64-token Shift groups, fp16 residual, group flush."""
+    import torch
+    api = gpu_api
+    sub, B, Hq, Hkv, G, seed, steps = 4, 2, 8, 2, 64, 99, 70
+    r, J, CAP = Hq // Hkv, 32, 64
+    cb = codebooks[sub]
+    prefill = [200, 64]
+    max_len = 512
+    shape = api.make_shape(sub, Hq, Hkv, max_len, G, 0, side_bits=4)
+    cbd = torch.from_numpy(cb.astype(np.float16)).cuda()
+    kc, vc = api.alloc_cache(shape, B), api.alloc_cache(shape, B)
+    scale = 1.0 / math.sqrt(128)
+    total = max(prefill) + steps
+    xk = np.zeros((B, Hkv, total, 128), dtype=np.float16)
+    xv = np.zeros_like(xk)
+    for b in range(B):
+        for h in range(Hkv):
+            xk[b, h] = synth.make_k(seed, b, h, total)
+            xv[b, h] = synth.make_v(seed, b, h, total)
+    coded = [(n // G) * G for n in prefill]
+    res_n = [n - c for n, c in zip(prefill, coded)]
+    api.nsn_encode(shape, cbd, torch.from_numpy(xk[:, :, :max(coded)].copy()).cuda(),
+                   torch.from_numpy(xv[:, :, :max(coded)].copy()).cuda(), torch.zeros(B, dtype=torch.int32).cuda(),
+                   torch.tensor(coded, dtype=torch.int32).cuda(), kc, vc)
+    k_res = torch.zeros((B, Hkv, CAP, 128), dtype=torch.float16).cuda()
+    v_res = torch.zeros_like(k_res)
+    for b in range(B):
+        k_res[b, :, :res_n[b]] = torch.from_numpy(xk[b, :, coded[b]:prefill[b]]).cuda()
+        v_res[b, :, :res_n[b]] = torch.from_numpy(xv[b, :, coded[b]:prefill[b]]).cuda()
+    dec_ws = torch.zeros(api.nsn_workspace_bytes(shape, api.NSN_OP_DECODE, B), dtype=torch.uint8).cuda()
+    hk = helpers.HostCacheDQ("k", B, Hkv, J, max_len, G)
+    hv = helpers.HostCacheDQ("v", B, Hkv, J, max_len, G)
+    worst, flushes = 0.0, 0
+    pos = list(prefill)
+    for step in range(steps):
+        for b in range(B):
+            k_res[b, :, res_n[b]] = torch.from_numpy(xk[b, :, pos[b]]).cuda()
+            v_res[b, :, res_n[b]] = torch.from_numpy(xv[b, :, pos[b]]).cuda()
+            res_n[b] += 1
+            pos[b] += 1
+        q = synth.make_q(seed, B, Hq, step=step)
+        out = api.nsn_decode_attention_residual(
+            shape, cbd, torch.from_numpy(q).cuda(), kc, vc, torch.tensor(coded, dtype=torch.int32).cuda(),
+            max(coded), k_res, v_res, torch.tensor(res_n, dtype=torch.int32).cuda(), scale, 0, workspace=dec_ws)
+        torch.cuda.synchronize()
+        if step % 9 == 0 or step == steps - 1 or max(res_n) == CAP:
+            out_h = out.cpu().numpy().astype(np.float64)
+            hk.from_device(kc)
+            hv.from_device(vc)
+            for b in range(B):
+                for h in range(Hkv):
+                    ref = O.decode_attention_residual(
+                        q[b, h * r:(h + 1) * r].astype(np.float64), hk.unit_dict(b, h, coded[b]),
+                        hv.unit_dict(b, h, coded[b]), xk[b, h, coded[b]:pos[b]], xv[b, h, coded[b]:pos[b]], cb, scale, G)
+                    worst = max(worst, helpers.max_rel_err(out_h[b, h * r:(h + 1) * r], ref))
+        full = [n == CAP for n in res_n]
+        if any(full):
+            n_new = [CAP if fl else 0 for fl in full]
+            api.nsn_encode(shape, cbd, k_res, v_res, torch.tensor(coded, dtype=torch.int32).cuda(),
+                           torch.tensor(n_new, dtype=torch.int32).cuda(), kc, vc)
+            torch.cuda.synchronize()
+            hk.from_device(kc)
+            for b in range(B):
+                if not full[b]:
+                    continue
+                flushes += 1
+                for h in range(Hkv):
+                    _check_unit(xk[b, h, coded[b]:coded[b] + CAP], hk.unit_dict(b, h, coded[b] + CAP), cb, G, False,
+                                start=coded[b])
+                coded[b] += CAP
+                res_n[b] = 0
+    print(f"  {flushes} flushes, worst decode max rel err {worst:.3e}", flush=True)
+    assert flushes >= 2
+    assert worst < TOL, worst
