@@ -63,6 +63,11 @@ def parse():
                    help="keys are normalised before the rotary embedding (Sec. 3.2): the encoder turns v_nsn by "
                         "the token position, the attention kernel turns the stored mean (App. B)")
     p.add_argument("--rope-base", type=float, default=500000.0, help="rotary base of --pre-rope (Llama-3: 5e5)")
+    p.add_argument("--side-bits", type=int, default=16, choices=[16, 4],
+                   help="4 = double quantization (Sec. 3.5): s1 as 4-bit codes per 64 tokens, means as 4-bit codes "
+                        "per 32 channels")
+    p.add_argument("--codebook-bits", type=int, default=16, choices=[16, 4],
+                   help="4 = codebook entries snapped to 16 levels (Sec. 3.5)")
     p.add_argument("--finetune-iters", type=int, default=0,
                    help="cosine fine-tuning steps applied to the K-Means codebook (Sec. 3.4); 0 = none")
     p.add_argument("--finetune-lr", type=float, default=2048.0)
@@ -101,15 +106,26 @@ def random_cache_decode(args, cfg) -> int:
     max_len = ((max(lens) + 255) // 256) * 256
     G = args.group_size
     rope_table = api.nsn_build_rope_table(synth.rope_inv_freq(args.rope_base), max_len) if args.pre_rope else None
-    shape = api.make_shape(sub, Hq, Hkv, max_len, G, page, sign_format=args.sign_format, rope_table=rope_table)
+    shape = api.make_shape(sub, Hq, Hkv, max_len, G, page, sign_format=args.sign_format, rope_table=rope_table,
+                           side_bits=args.side_bits)
+    dq = args.side_bits == 4
     bt = torch.from_numpy(synth.shuffled_page_table(seed, B, max_len // page)).to(dev) if page else None
     g = torch.Generator(device=dev).manual_seed(seed)
     caches = []
     for _ in range(2):
         c = api.alloc_cache(shape, B, block_table=bt)
         c.codes.random_(0, 256, generator=g)
-        c.norms.copy_((torch.rand(c.norms.shape, device=dev, generator=g) + 0.5).half())
-        c.means.copy_((0.1 * torch.randn(c.means.shape, device=dev, generator=g)).half())
+        if dq:  # records: fp16 a' in [0.5, 1.5), random 4-bit codes, (min, step) = (0.5, 1/16) resp. (-0.2, 1/32)
+            rec = c.norms.view(-1, 164)
+            rec[:, :128] = (torch.rand((rec.shape[0], 64), device=dev, generator=g) + 0.5).half().view(torch.uint8)
+            rec[:, 128:160].random_(0, 256, generator=g)
+            rec[:, 160:164] = torch.tensor([0.5, 0.0625], dtype=torch.float16, device=dev).view(torch.uint8)
+            mrec = c.means.view(-1, 80)
+            mrec[:, :64].random_(0, 256, generator=g)
+            mrec[:, 64:] = torch.tensor([-0.2, 0.03125] * 4, dtype=torch.float16, device=dev).view(torch.uint8)
+        else:
+            c.norms.copy_((torch.rand(c.norms.shape, device=dev, generator=g) + 0.5).half())
+            c.means.copy_((0.1 * torch.randn(c.means.shape, device=dev, generator=g)).half())
         caches.append(c)
     kc, vc = caches
     codebook = (torch.randn((256, sub), device=dev, generator=g)).half()
@@ -118,7 +134,8 @@ def random_cache_decode(args, cfg) -> int:
     q = torch.from_numpy(synth.make_q(seed, B, Hq)).to(dev)
     lens_d = torch.tensor(lens, dtype=torch.int32, device=dev)
     n_groups = sum((n + G - 1) // G for n in lens) if G else B
-    step_bytes = sum(lens) * Hkv * (2 * J + 8) + n_groups * Hkv * 2 * 256
+    norm_b, mean_b = (2 * 164 / 64, 80) if dq else (8, 256)  # per token (K + V) / per mean vector
+    step_bytes = int(sum(lens) * Hkv * (2 * J + norm_b)) + n_groups * Hkv * 2 * mean_b
     n_copies = max(1, int(math.ceil(args.rotate_bytes / step_bytes)))
     copies = [(kc, vc)] + [tuple(api.CodedCache(c.codes.clone(), c.norms.clone(), c.means.clone(), bt)
                                  for c in (kc, vc)) for _ in range(n_copies - 1)]
@@ -151,7 +168,7 @@ def random_cache_decode(args, cfg) -> int:
         "config": {"workload": f"{args.workload}:{cfg['name']}", "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "cached_tokens": sum(lens), "sub_dim": sub, "sign_format": bool(args.sign_format),
                    "page_size": page, "group_size": G, "pre_rope_keys": bool(args.pre_rope),
-                   "cache_copies_in_rotation": n_copies, "step": "decode attention only"},
+                   "side_bits": args.side_bits, "cache_copies_in_rotation": n_copies, "step": "decode attention only"},
         "decode_us_per_step": round(us, 3), "bytes_per_step": step_bytes,
         "roofline": {"bound": "hbm", "kernel": "nsn::dec_mfma_kernel (one launch per decode step)",
                      "achieved": round(gbps, 2), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
@@ -170,6 +187,11 @@ def main() -> int:
     if args.policy == "append" and args.group_size != 0:
         print("bench.py: --policy append encodes single tokens against a stored mean and needs --group-size 0",
               file=sys.stderr)
+        return 2
+
+    if args.policy == "append" and args.side_bits == 4:
+        print("bench.py: --side-bits 4 stores one set of s1 levels per 64-token block and needs block-wise encodes "
+              "(--policy residual)", file=sys.stderr)
         return 2
 
     import numpy as np
@@ -204,6 +226,8 @@ def main() -> int:
     if args.finetune_iters > 0:
         codebook, cos_before, cos_after = api.nsn_finetune_codebook(samples, codebook, args.finetune_iters,
                                                                     args.finetune_lr)
+    if args.codebook_bits == 4:
+        api.nsn_quantize_codebook(codebook)
     torch.cuda.synchronize()
     codebook_s = time.time() - t0
     del samples
@@ -215,7 +239,9 @@ def main() -> int:
     # room for one flushed residual behind the L cached tokens
     inv_freq = synth.rope_inv_freq(args.rope_base) if args.pre_rope else None
     rope_table = api.nsn_build_rope_table(inv_freq, L + RES) if args.pre_rope else None
-    shape = api.make_shape(sub, Hq, Hkv, L + RES, G, sign_format=sign, rope_table=rope_table)
+    shape = api.make_shape(sub, Hq, Hkv, L + RES, G, sign_format=sign, rope_table=rope_table,
+                           side_bits=args.side_bits)
+    dq = args.side_bits == 4
     kc, vc = api.alloc_cache(shape, B), api.alloc_cache(shape, B)
     zeros = torch.zeros(B, dtype=torch.int32, device=dev)
     full = torch.full((B,), L, dtype=torch.int32, device=dev)
@@ -236,8 +262,9 @@ def main() -> int:
     encode_tokens_per_s = B * L / (enc_ms * 1e-3)
 
     # ---- replicate the coded cache so the timed loop streams from HBM -------------------------
-    coded_bytes = B * Hkv * L * (2 * J + 8)                 # K+V codes + two fp16 pairs per token
-    mean_bytes = B * Hkv * 2 * 128 * 2 * api.nsn_max_groups(shape)
+    # K+V codes + two fp16 pairs per token (4-bit side information: two 164-byte records per 64 tokens)
+    coded_bytes = B * Hkv * L * 2 * J + (B * Hkv * (L // 64) * 2 * 164 if dq else B * Hkv * L * 8)
+    mean_bytes = B * Hkv * 2 * (80 if dq else 256) * api.nsn_max_groups(shape)
     step_bytes = coded_bytes + mean_bytes
     n_copies = max(1, int(math.ceil(args.rotate_bytes / step_bytes)))
     copies = [(kc, vc)]
@@ -346,7 +373,8 @@ def main() -> int:
         "config": {"workload": f"{args.workload}:{cfg['name']}", "batch": B, "n_q_heads": Hq,
                    "n_kv_heads": Hkv, "cached_tokens": L, "sub_dim": sub, "bits": 2 if sign else 8 // sub,
                    "sign_format": sign, "codebook_finetune_iters": args.finetune_iters,
-                   "pre_rope_keys": bool(args.pre_rope),
+                   "pre_rope_keys": bool(args.pre_rope), "side_bits": args.side_bits,
+                   "codebook_bits": args.codebook_bits,
                    "group_size": G, "cache_copies_in_rotation": n_copies,
                    "residual_size": RES if args.policy == "residual" else 0,
                    "residual_encodes_in_timed_region": flushes if args.policy == "residual" else 0,
@@ -383,8 +411,8 @@ def main() -> int:
         worst = 0.0
         for (b, h) in units:
             t0 = time.perf_counter()
-            ek = O.encode(k_host[b, h], cb_host, G, sign_format=sign, rope_inv_freq=inv_freq)
-            ev = O.encode(v_host[b, h], cb_host, G, sign_format=sign)
+            ek = O.encode(k_host[b, h], cb_host, G, sign_format=sign, rope_inv_freq=inv_freq, side_bits=args.side_bits)
+            ev = O.encode(v_host[b, h], cb_host, G, sign_format=sign, side_bits=args.side_bits)
             t_enc += time.perf_counter() - t0
             t0 = time.perf_counter()
             ref = O.decode_attention(q_host[b, h * r:(h + 1) * r].astype(np.float64), ek, ev, cb_host, scale, G,

@@ -220,6 +220,21 @@ int nsn_finetune_codebook(const float* samples_dev, int64_t n_samples, int sub_d
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Codebook entries on 16 levels (Sec. 3.5, "we also apply 4-bit quantization to codebook entries"):
+ * every entry is replaced by fp16(min + step * code), code = the 4-bit round-to-nearest level of
+ * the entry between the smallest and the largest entry of the whole codebook (one fp16 (min, step)
+ * pair per codebook: the paper does not state a grouping).  The kernels keep reading an fp16
+ * codebook; the 4-bit form matters for where a codebook is stored, not for these kernels, whose
+ * LDS table is an expanded, replicated copy anyway.
+ *   codebook_dev  in/out, dev fp16 [n_codes][sub_dim]
+ *   codes_dev     out, dev u8 [n_codes * sub_dim] (one code per byte), may be NULL
+ *   levels_dev    out, dev fp16 [2] = (min, step), may be NULL
+ * One kernel on `stream`, no synchronisation.  Errors: INVALID_ARG, UNSUPPORTED (sub_dim, n_codes), HIP.
+ */
+int nsn_quantize_codebook(void* codebook_dev, int sub_dim, int n_codes, uint8_t* codes_dev,
+                          void* levels_dev, void* stream);
+
+/*
  * Encoder (Sec. 3.2 steps 1-3, Hadamard rotation of Sec. 2, Eq. 1 on contiguous sub-vectors
  * of the rotated token, scale adjustment of Sec. 3.3).  For every sequence b it encodes the
  * n_new[b] tokens found in k_fp16 / v_fp16 and writes them at cache positions

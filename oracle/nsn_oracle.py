@@ -190,6 +190,16 @@ def rtn4_decode(codes, mn, st) -> np.ndarray:
     return float(mn) + float(st) * np.asarray(codes, dtype=F64)
 
 
+def quantize_codebook_4bit(codebook):
+    """Sec. 3.5, last sentence: the codebook entries themselves on 16 levels.  The grouping is not
+    stated; one (minimum, step) pair for the whole codebook is this build's reading.  Returns the
+    codebook as the kernels see it (every entry = fp16(min + step * code)) and the codes."""
+    c = np.asarray(codebook, dtype=F64)
+    code, mn, st = rtn4_encode(c.reshape(-1))
+    vals = fp16_rne(rtn4_decode(code, mn, st)).astype(F64).reshape(c.shape)
+    return vals, code.reshape(c.shape), mn, st
+
+
 def quantize_side_info(b16: np.ndarray, o_mean: np.ndarray, start: int = 0):
     """b16 fp16 [l] (first-Normalize scales of tokens start.., start a multiple of 64),
     o_mean float64 [n_groups][d] (rows that are all zero are groups without tokens).

@@ -65,6 +65,7 @@ def lib() -> C.CDLL:
                                          C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
         L.nsn_finetune_codebook.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_double,
                                             C.c_void_p, C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.nsn_quantize_codebook.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.nsn_rope_table_bytes.restype = C.c_size_t
         L.nsn_rope_table_bytes.argtypes = [C.c_int]
         L.nsn_build_rope_table.argtypes = [C.POINTER(C.c_float), C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -203,6 +204,17 @@ def nsn_finetune_codebook(samples: torch.Tensor, codebook: torch.Tensor, iters: 
     _check(lib().nsn_finetune_codebook(samples.data_ptr(), n, sub, N_CODES, iters, float(lr), codebook.data_ptr(),
                                        cos, workspace.data_ptr(), workspace.numel(), _stream()))
     return codebook, cos[0], cos[1]
+
+
+def nsn_quantize_codebook(codebook: torch.Tensor):
+    """codebook: cuda fp16 [256][sub_dim], snapped in place to 16 levels.
+    Returns (codebook, codes cuda u8 [256][sub_dim], levels cuda fp16 [2] = (min, step))."""
+    assert codebook.is_cuda and codebook.dtype == torch.float16 and codebook.is_contiguous()
+    n, sub = codebook.shape
+    codes = torch.empty((n, sub), dtype=torch.uint8, device=codebook.device)
+    levels = torch.empty(2, dtype=torch.float16, device=codebook.device)
+    _check(lib().nsn_quantize_codebook(codebook.data_ptr(), sub, n, codes.data_ptr(), levels.data_ptr(), _stream()))
+    return codebook, codes, levels
 
 
 def nsn_encode(shape: nsn_shape, codebook: torch.Tensor, k: torch.Tensor, v: torch.Tensor,

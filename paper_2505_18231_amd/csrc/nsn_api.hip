@@ -159,6 +159,21 @@ int nsn_finetune_codebook(const float* samples_dev, int64_t n_samples, int sub_d
   return rc;
 }
 
+int nsn_quantize_codebook(void* codebook_dev, int sub_dim, int n_codes, uint8_t* codes_dev, void* levels_dev,
+                          void* stream) {
+  if (n_codes != kCodes || (sub_dim != 4 && sub_dim != 8)) {
+    set_error("quantize_codebook: unsupported n_codes=%d sub_dim=%d (256 codes of 4 or 8 dims)", n_codes, sub_dim);
+    return NSN_ERR_UNSUPPORTED;
+  }
+  if (!codebook_dev) {
+    set_error("quantize_codebook: codebook is NULL");
+    return NSN_ERR_INVALID_ARG;
+  }
+  const int rc = codebook_quantize(codebook_dev, sub_dim, codes_dev, levels_dev, static_cast<hipStream_t>(stream));
+  if (rc == NSN_ERR_HIP) set_error("quantize_codebook: HIP error: %s", hipGetErrorString(hipGetLastError()));
+  return rc;
+}
+
 int nsn_encode(const nsn_shape* shape, const void* codebook_dev, const void* k_fp16, const void* v_fp16,
                int max_new, const int32_t* seq_start_dev, const int32_t* n_new_dev, int batch, int freeze_means,
                const nsn_cache* k_cache, const nsn_cache* v_cache, void* workspace, size_t workspace_bytes,

@@ -232,4 +232,46 @@ int codebook_run(const float* samples, int64_t n_samples, int sub_dim, int iters
                       : codebook_run_t<4>(samples, n_samples, iters, codebook_out, mse_host, workspace, stream);
 }
 
+// Codebook entries on 16 levels (Sec. 3.5): one workgroup; thread c owns codeword c.
+template <int SUB>
+__global__ __launch_bounds__(256) void cb_quantize_kernel(__half* __restrict__ codebook, uint8_t* __restrict__ codes,
+                                                          __half* __restrict__ levels) {
+  __shared__ float red_lo[4], red_hi[4];
+  const int c = threadIdx.x, lane = c & 63, wave = c >> 6;
+  float x[SUB], lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < SUB; ++i) {
+    x[i] = __half2float(codebook[c * SUB + i]);
+    lo = fminf(lo, x[i]);
+    hi = fmaxf(hi, x[i]);
+  }
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    lo = fminf(lo, __shfl_xor(lo, m, 64));
+    hi = fmaxf(hi, __shfl_xor(hi, m, 64));
+  }
+  if (lane == 0) red_lo[wave] = lo, red_hi[wave] = hi;
+  __syncthreads();
+  lo = fminf(fminf(red_lo[0], red_lo[1]), fminf(red_lo[2], red_lo[3]));
+  hi = fmaxf(fmaxf(red_hi[0], red_hi[1]), fmaxf(red_hi[2], red_hi[3]));
+  const __half mn16 = f64_to_f16((double)lo), st16 = f64_to_f16(((double)hi - (double)lo) / 15.0);
+  const double mn = (double)__half2float(mn16), st = (double)__half2float(st16);
+#pragma unroll
+  for (int i = 0; i < SUB; ++i) {
+    int code = 0;
+    if (st != 0.0) code = (int)fmin(fmax(floor(((double)x[i] - mn) / st + 0.5), 0.0), 15.0);
+    codebook[c * SUB + i] = f64_to_f16(mn + st * (double)code);
+    if (codes) codes[c * SUB + i] = (uint8_t)code;
+  }
+  if (levels && c == 0) levels[0] = mn16, levels[1] = st16;
+}
+
+int codebook_quantize(void* codebook_io, int sub_dim, uint8_t* codes_out, void* levels_out, hipStream_t stream) {
+  if (sub_dim == 4)
+    cb_quantize_kernel<4><<<1, 256, 0, stream>>>(static_cast<__half*>(codebook_io), codes_out, static_cast<__half*>(levels_out));
+  else
+    cb_quantize_kernel<8><<<1, 256, 0, stream>>>(static_cast<__half*>(codebook_io), codes_out, static_cast<__half*>(levels_out));
+  return hipGetLastError() == hipSuccess ? NSN_OK : NSN_ERR_HIP;
+}
+
 }  // namespace nsn

@@ -51,6 +51,7 @@ int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const
                   const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                   int n_splits, const nsn_residual* residual, float* out, void* workspace, hipStream_t stream);
 
+int codebook_quantize(void* codebook_io, int sub_dim, uint8_t* codes_out, void* levels_out, hipStream_t stream);
 size_t rope_table_bytes(int max_len);
 int rope_table_build(const float* inv_freq_host, int max_len, void* table_dev, hipStream_t stream);
 

@@ -44,3 +44,16 @@ def test_finetune_matches_oracle_and_raises_cosine(gpu_api, sub, n, iters, lr):
     # zero steps: the codebook is returned unchanged
     same, c0, c1 = gpu_api.nsn_finetune_codebook(torch.from_numpy(samples).cuda(), cbd.clone(), 0, lr)
     assert torch.equal(same, cbd) and c0 == c1
+
+
+@pytest.mark.parametrize("sub", [4, 8])
+def test_codebook_on_16_levels_matches_oracle(gpu_api, codebooks, sub):
+    import torch
+    cb = codebooks[sub]
+    want, code, mn, st = O.quantize_codebook_4bit(cb)
+    got, codes, levels = gpu_api.nsn_quantize_codebook(torch.from_numpy(cb.astype(np.float16)).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().astype(np.float64), want)
+    assert np.array_equal(codes.cpu().numpy(), code)
+    lv = levels.cpu().numpy()
+    assert lv[0] == mn and lv[1] == st

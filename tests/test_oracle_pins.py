@@ -581,3 +581,15 @@ def test_double_quantized_side_information_round_trip(sub, G):
     # effective per-token scale = dequantised s1 times the stored fp16 s2 alpha
     assert np.array_equal(enc["a"], enc["b"] * enc["a_stored"].astype(np.float64))
     assert np.allclose(enc["a_stored"].astype(np.float64), enc["s2"] * enc["alpha"], rtol=2.0 ** -10)
+
+
+def test_codebook_on_16_levels_keeps_its_quality():
+    x = synth.codebook_samples(12, 1 << 13, 8).astype(np.float64)
+    cb, _, _ = O.build_codebook(x, 256, 5)
+    q, code, mn, st = O.quantize_codebook_4bit(cb)
+    assert len(np.unique(q)) <= 16 and code.max() == 15 and code.min() == 0
+    assert np.abs(q - cb).max() <= 0.5 * float(st) + 2.0 ** -10 * np.abs(cb).max()
+    assert np.array_equal(q, q.astype(np.float16).astype(np.float64))          # what an fp16 table holds
+    # cosine similarity of N(0,1) vectors to their codewords: a small loss only (the paper reports none on perplexity)
+    before, after = 1.0 - O.cosine_loss(x, cb), 1.0 - O.cosine_loss(x, q)
+    assert after > before - 0.01, (before, after)
