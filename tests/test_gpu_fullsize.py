@@ -95,3 +95,71 @@ def test_mha_large_batch_shape_two_sequences(gpu_api, codebooks):
     # Llama-2-7B shape (32 kv heads = 32 query heads, 32768 tokens, 2-bit, per-sequence channel
     # biases); two of the 64 sequences, so that the host-side generation stays small
     _run(gpu_api, "C3", codebooks[4], [(0, 0), (1, 31)], token_sample=4096, batch=2)
+
+
+def test_llama3_8b_shape_in_the_papers_own_configuration(gpu_api):
+    """Everything the paper's pipeline has, at the benchmark's size: sign + index 2-bit codes with a
+    magnitude codebook, 64-token Shift groups, keys normalised before the rotary embedding (the mean is
+    turned inside the attention kernel), 4-bit side information, codebook entries on 16 levels, and a
+    partly filled fp16 residual in the softmax.  The oracle re-computes three (sequence, head) units."""
+    import torch
+    from tests.test_gpu_double_quant import _check_unit
+    api = gpu_api
+    cfg = synth.CONFIGS["C1"]
+    B, Hq, Hkv, L, seed = cfg["batch"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["length"], cfg["seed"]
+    G, J, r, RES = 64, 32, Hq // Hkv, 64
+    scale = 1.0 / math.sqrt(128)
+    sample_units = [(0, 0), (3, 5), (7, 7)]
+    x = np.abs(synth.codebook_samples(4242, 1 << 13, 8).astype(np.float64))
+    cb, _, _ = O.build_codebook(x, 256, 5)
+    cb, _, _, _ = O.quantize_codebook_4bit(cb)
+    f = synth.rope_inv_freq(500000.0)
+    table = api.nsn_build_rope_table(f, L + RES)
+    shape = api.make_shape(8, Hq, Hkv, L + RES, G, sign_format=True, rope_table=table, side_bits=4)
+    kc, vc = api.alloc_cache(shape, B), api.alloc_cache(shape, B)
+    cbd = torch.from_numpy(cb.astype(np.float16)).cuda()
+    zeros = torch.zeros(B, dtype=torch.int32).cuda()
+    full = torch.full((B,), L, dtype=torch.int32).cuda()
+    k_units, v_units = {}, {}
+    res_rows = [37, 64, 1, 0, 12, 63, 5, 20]
+    k_res = np.zeros((B, Hkv, RES, 128), dtype=np.float16)
+    v_res = np.zeros_like(k_res)
+    for b in range(B):
+        k = np.empty((1, Hkv, L, 128), dtype=np.float16)
+        v = np.empty_like(k)
+        for h in range(Hkv):
+            k[0, h] = synth.make_k(seed, b, h, L)
+            v[0, h] = synth.make_v(seed, b, h, L)
+            # residual keys are the embedded ones, as attention uses them
+            k_res[b, h, :res_rows[b]] = O.rope(synth.make_k(seed, b, h, res_rows[b], start=L).astype(np.float64),
+                                               L + np.arange(res_rows[b]), f).astype(np.float16)
+            v_res[b, h, :res_rows[b]] = synth.make_v(seed, b, h, res_rows[b], start=L)
+            if (b, h) in sample_units:
+                k_units[(b, h)], v_units[(b, h)] = k[0, h].copy(), v[0, h].copy()
+        sub_k = api.CodedCache(kc.codes[b:b + 1], kc.norms[b:b + 1], kc.means[b:b + 1], None)
+        sub_v = api.CodedCache(vc.codes[b:b + 1], vc.norms[b:b + 1], vc.means[b:b + 1], None)
+        api.nsn_encode(shape, cbd, torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), zeros[:1], full[:1],
+                       sub_k, sub_v)
+    q = synth.make_q(seed, B, Hq)
+    out = api.nsn_decode_attention_residual(shape, cbd, torch.from_numpy(q).cuda(), kc, vc, full, L,
+                                            torch.from_numpy(k_res).cuda(), torch.from_numpy(v_res).cuda(),
+                                            torch.tensor(res_rows, dtype=torch.int32).cuda(), scale, 0)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy().astype(np.float64)
+    hk = helpers.HostCacheDQ("k", B, Hkv, J, L + RES, G)
+    hv = helpers.HostCacheDQ("v", B, Hkv, J, L + RES, G)
+    hk.from_device(kc)
+    hv.from_device(vc)
+    worst = 0.0
+    for (b, h) in sample_units:
+        kd, vd = hk.unit_dict(b, h, L), hv.unit_dict(b, h, L)
+        flips = (_check_unit(k_units[(b, h)], kd, cb, G, True, rope_inv_freq=f) +
+                 _check_unit(v_units[(b, h)], vd, cb, G, True))
+        ref = O.decode_attention_residual(q[b, h * r:(h + 1) * r].astype(np.float64), kd, vd,
+                                          k_res[b, h, :res_rows[b]], v_res[b, h, :res_rows[b]], cb, scale, G,
+                                          sign_format=True, rope_inv_freq=f)
+        err = helpers.max_rel_err(out[b, h * r:(h + 1) * r], ref)
+        print(f"  unit (b={b}, h={h}): near-tie code differences {flips}, decode max rel err {err:.3e}", flush=True)
+        worst = max(worst, err)
+    assert worst < 2e-3, worst
+    assert np.isfinite(out).all()
