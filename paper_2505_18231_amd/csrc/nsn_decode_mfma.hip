@@ -861,14 +861,17 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       else
         load_group(gi + NW, nxt_full);
     }
-    float a_k = 0.f, b_k = 0.f, a_v = 0.f, b_v = 0.f;
+    // (selects, not a branch on `valid`: a branch would pin the wait for these registers to the top of
+    // the iteration, right behind the next group's loads)
+    float a_k, b_k, a_v, b_v;
     if constexpr (DQ) {  // b = min + step * code, a = b * a'
       const uint32_t sh = (lane & 1) * 4;
       const float bk = lvl(cur.s.kp, (cur.s.kq >> sh) & 15u), bv = lvl(cur.s.vp, (cur.s.vq >> sh) & 15u);
-      if (valid) a_k = bk * half_bits(cur.s.ka), b_k = bk, a_v = bv * half_bits(cur.s.va), b_v = bv;
+      a_k = valid ? bk * half_bits(cur.s.ka) : 0.f, b_k = valid ? bk : 0.f;
+      a_v = valid ? bv * half_bits(cur.s.va) : 0.f, b_v = valid ? bv : 0.f;
     } else {
-      if (valid)
-        a_k = __low2float(cur.s.nk), b_k = __high2float(cur.s.nk), a_v = __low2float(cur.s.nv), b_v = __high2float(cur.s.nv);
+      a_k = valid ? __low2float(cur.s.nk) : 0.f, b_k = valid ? __high2float(cur.s.nk) : 0.f;
+      a_v = valid ? __low2float(cur.s.nv) : 0.f, b_v = valid ? __high2float(cur.s.nv) : 0.f;
     }
 
     // Shift group bookkeeping (wave-uniform): mean term of the old group, q . o^k of the new one
