@@ -170,7 +170,7 @@ __device__ long long g_dec_timing[48];
 //   ROPE only: 32 KiB  fp16 hi and lo parts of (cos, sin)(j * inv_freq[i]), rows of 256 bytes whose
 //                      16-byte chunks are XOR-swizzled by the row number (conflict-free operand reads)
 //              32 KiB  per wave, q . RoPE_t(o^k) of the 64 tokens of its next four groups, four heads each
-// One workgroup of 8 waves per compute unit shares a single table (about 92 of the 160 KiB).
+// One workgroup of 8 (or 11) main waves per compute unit shares a single table (about 92 of the 160 KiB).
 template <int SUB, int NW, bool SGN = false, bool ROPE = false>
 struct DecSmem {
   // sign + index format: a 4 KiB table of sign masks sits in front of the codebook table
@@ -422,7 +422,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   if (spec) load_group(wave, cur);
   // The split's first Shift group is shared by all waves when there is one group per sequence:
   // its q . o^k is formed once per workgroup (waves that do not rotate a query head), not per wave.
-  static_assert(NW == 8, "prologue work split assumes 8 waves: 4 rotate the query, 4 do the rest");
+  static_assert(NW >= 8, "prologue work split: waves 0-3 rotate the query, waves 4.. do the rest");
   const int grp_pre = group_of(g, min(t0, g.page_tokens * g.pages_per_seq - 1));
   Side pre = {};  // only the key-side mean fields are used
   if (!ROPE && wave >= 4 && wave - 4 < R) {
@@ -550,12 +550,14 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     constexpr int NW16 = 16;  // 16-byte slots per 256-byte code row
     typedef uint32_t u4v __attribute__((ext_vector_type(4)));
     typedef uint32_t u2v __attribute__((ext_vector_type(2)));
-    auto fill = [&](auto nc, int first) {
+    auto fill = [&](auto nc, int first, auto stride_c) {
       constexpr int N = decltype(nc)::value;
+      constexpr int STRIDE = decltype(stride_c)::value;
+      constexpr bool GUARD = (STRIDE != 256);  // other wave counts: the last round may run past the table
       u4v tmp[N];
 #pragma unroll
       for (int u = 0; u < N; ++u) {
-        const int code = (first + u * 256) >> 4;
+        const int code = min((first + u * STRIDE) >> 4, kCodes - 1);
         if constexpr (SUB == 4) {
           const u2v c2 = reinterpret_cast<const u2v*>(sm_stage)[code];
           tmp[u] = u4v{c2.x, c2.y, c2.x, c2.y};
@@ -565,15 +567,24 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       }
 #pragma unroll
       for (int u = 0; u < N; ++u) {
-        const int i = first + u * 256;
-        *reinterpret_cast<u4v*>(sm_table + TB + (i >> 4) * 256 + (i & 15) * 16) = tmp[u];
+        const int i = first + u * STRIDE;
+        if (!GUARD || i < kCodes * NW16)
+          *reinterpret_cast<u4v*>(sm_table + TB + (i >> 4) * 256 + (i & 15) * 16) = tmp[u];
       }
     };
-    static_assert(256 * 6 + 256 * 10 == kCodes * NW16, "slot split must cover the table");
-    if (wave < 4)
-      fill(std::integral_constant<int, 6>{}, tid);
-    else if (main_wave)
-      fill(std::integral_constant<int, 10>{}, 256 * 6 + (tid - 256));
+    if constexpr (NW == 8) {
+      static_assert(256 * 6 + 256 * 10 == kCodes * NW16, "slot split must cover the table");
+      if (wave < 4)
+        fill(std::integral_constant<int, 6>{}, tid, std::integral_constant<int, 256>{});
+      else if (main_wave)
+        fill(std::integral_constant<int, 10>{}, 256 * 6 + (tid - 256), std::integral_constant<int, 256>{});
+    } else {  // the four rotating waves take 4 slots per thread, the other NW - 4 waves share the rest
+      constexpr int REST = (NW - 4) * 64, ROUNDS = (kCodes * NW16 - 1024 + REST - 1) / REST;
+      if (wave < 4)
+        fill(std::integral_constant<int, 4>{}, tid, std::integral_constant<int, 256>{});
+      else if (main_wave)
+        fill(std::integral_constant<int, ROUNDS>{}, 1024 + (tid - 256), std::integral_constant<int, REST>{});
+    }
   }
   __syncthreads();
   NSN_TSTAMP(1);
@@ -1275,6 +1286,20 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
                       : launch_one<kSub, 8, 4, kSgn, kRope, kDq>(NSN_ARGS);
     };
     auto with_format = [&](auto rope, auto dq) {
+      if constexpr (!decltype(rope)::value && !decltype(dq)::value) {
+        // Long splits of the 4-dim format run with 11 main waves (12 with the residual wave: three per
+        // SIMD, still 168 registers each): the loop is bound by the compute unit's LDS instruction
+        // rate, and a third wave per SIMD overlaps a little more of the other work with it (-3 % to
+        // -6 % on 16k-32k token splits, +3 % on 2k token splits, whose prologue it lengthens).
+        // NSN_DECODE_NW=8 / 11 overrides the choice.
+        static const int nw_env = [] { const char* e = getenv("NSN_DECODE_NW"); return e ? atoi(e) : 0; }();
+        const int per_tokens = (((max_seq_len + n_splits - 1) / n_splits) + 63) & ~63;
+        const bool nw11 = nw_env == 11 || (nw_env != 8 && per_tokens >= 4096);
+        if (nw11 && !g.sign && s.sub_dim == 4)
+          return r == 1   ? launch_one<4, 11, 1>(NSN_ARGS)
+                 : r == 2 ? launch_one<4, 11, 2>(NSN_ARGS)
+                          : launch_one<4, 11, 4>(NSN_ARGS);
+      }
       if (g.sign) return with_r(std::integral_constant<int, 8>{}, std::true_type{}, rope, dq);
       if (s.sub_dim == 4) return with_r(std::integral_constant<int, 4>{}, std::false_type{}, rope, dq);
       return with_r(std::integral_constant<int, 8>{}, std::false_type{}, rope, dq);

@@ -70,6 +70,8 @@ CASES = [
     ("gqa8-2bit", 1, 8, 1, [300], 4, 64, 0, 2),          # 8 query heads per kv head
     ("long-2bit-many-splits", 1, 4, 1, [5000], 4, 0, 0, 16),
     ("long-1bit-groups", 1, 4, 2, [3000], 8, 64, 0, 3),
+    ("long-2bit-eleven-waves", 2, 4, 1, [9000, 4100], 4, 64, 0, 2),   # splits of >= 4096 tokens: the 11-wave instance
+    ("long-2bit-eleven-waves-mha", 1, 1, 1, [5000], 4, 0, 0, 1),
 ]
 
 

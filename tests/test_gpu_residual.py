@@ -28,6 +28,7 @@ CASES = [
     ("nothing-at-all", 4, 1, [0, 192], [0, 0], 8, 64, 0, 0),
     ("gqa8-two-launches", 16, 2, [384, 64], [33, 64], 4, 64, 0, 0),   # 8 query heads per kv head
     ("gqa5-two-launches", 5, 1, [130], [7], 8, 0, 0, 2),              # 4 + 1
+    ("long-eleven-waves", 4, 1, [4608, 64], [64, 3], 4, 64, 0, 1),    # 4096+ token split: 11 main waves + the residual wave
 ]
 
 
