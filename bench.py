@@ -34,7 +34,7 @@ if ROOT not in sys.path:
 PEAK_HBM_GBPS = 8000.0
 # HBM bytes per decode launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs kept under profiles/
 # (scaled by the same counters on a plain 256 MiB copy); only for the workload they were taken on.
-MEASURED_TRAFFIC_BYTES = {"C1": (38789 + 1322) * 1024}
+MEASURED_TRAFFIC_BYTES = {"C1": (38804 + 1322) * 1024}
 
 
 def parse():
