@@ -192,6 +192,13 @@ struct DecSmem {
   static constexpr int kRopeDotBytes = NW * kRopeBatch * 64 * 16;
   static constexpr int kBytes = ROPE ? kRopeDotOffset + kRopeDotBytes : kPlainBytes;
   static_assert(kBytes <= 160 * 1024, "LDS of one compute unit");
+  // Residual launches of the instances that have the room stage the fp16 residual rows in LDS: key rows
+  // with a padded stride (a lane reads its own token's row), value rows as they are.
+  static constexpr bool kResInLds = !ROPE;
+  static constexpr int kResKStride = SUB == 4 ? 264 : 272;
+  static constexpr int kResOffset = (kBytes + 255) & ~255;
+  static constexpr int kResBytes = kResInLds ? 64 * kResKStride + 64 * 256 : 0;
+  static_assert(kResOffset + kResBytes <= 160 * 1024, "LDS of one compute unit");
   static_assert(kRaccBytes <= kTable, "per-wave accumulators must fit in the table region");
 };
 
@@ -1006,40 +1013,108 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       }
       const int64_t unit_row = (int64_t)(b * g.n_kv_heads + h) * res.capacity;
       f4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
-      const uint4* krow = reinterpret_cast<const uint4*>(res.k + (unit_row + lane) * kHeadDim);
       const uint4 no_mask[MB] = {};
       const uint4 no_vmask[VMB] = {};
       constexpr std::false_type plain{};  // fp16 rows carry their own signs
-      static_for<NSV / CH>([&](auto cc) {
-        constexpr int ch = decltype(cc)::value;
-        cw_t buf[CH];
-        if constexpr (SUB == 4) {
+      if constexpr (SM::kResInLds) {
+        // A lane needs its own token's whole key row, 8 or 16 bytes per MFMA: read straight from global
+        // memory that is 64 different cache lines per load instruction (measured +1.3 us per launch with a
+        // full residual).  Instead the rows come in with coalesced loads (an instruction covers four
+        // consecutive rows), go to LDS, and every lane reads its row from there; rows past the valid
+        // count are stored as zeros.
+        const uint32_t sk = SM::kResOffset, sv = SM::kResOffset + 64 * SM::kResKStride;
+        const int sub_row = lane >> 4, piece = lane & 15;  // 16 lanes x 16 bytes = one 256-byte row
 #pragma unroll
-          for (int u = 0; u < CH / 2; ++u) {
-            const uint4 x = valid ? krow[(CH / 2) * ch + u] : make_uint4(0u, 0u, 0u, 0u);
-            buf[2 * u] = make_uint2(x.x, x.y);
-            buf[2 * u + 1] = make_uint2(x.z, x.w);
+        for (int hf = 0; hf < 2; ++hf) {
+          uint4 kx[8], vx[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int row = 4 * (8 * hf + u) + sub_row;
+            kx[u] = vx[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (row < rl) {
+              kx[u] = *reinterpret_cast<const uint4*>(res.k + (unit_row + row) * kHeadDim + piece * 8);
+              vx[u] = *reinterpret_cast<const uint4*>(res.v + (unit_row + row) * kHeadDim + piece * 8);
+            }
           }
-        } else {
 #pragma unroll
-          for (int u = 0; u < CH; ++u) buf[u] = valid ? krow[CH * ch + u] : make_uint4(0u, 0u, 0u, 0u);
+          for (int u = 0; u < 8; ++u) {
+            const int row = 4 * (8 * hf + u) + sub_row;
+            unsigned char* kd = smem_raw + sk + row * SM::kResKStride + piece * 16;
+            if constexpr (SM::kResKStride % 16 == 0) {
+              *reinterpret_cast<uint4*>(kd) = kx[u];
+            } else {
+              *reinterpret_cast<uint2*>(kd) = make_uint2(kx[u].x, kx[u].y);
+              *reinterpret_cast<uint2*>(kd + 8) = make_uint2(kx[u].z, kx[u].w);
+            }
+            *reinterpret_cast<uint4*>(smem_raw + sv + row * 256 + piece * 16) = vx[u];
+          }
         }
-        k_contract(cc, plain, buf, no_mask, AH, AL, d0, d1);
-      });
-      const h4 wop = softmax_step(d0, d1, valid, 1.f, 0.f, 1.f, 0.f);
+        // written and read by different lanes of this one wave
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint32_t krow = sk + lane * SM::kResKStride;
+        static_for<NSV / CH>([&](auto cc) {
+          constexpr int ch = decltype(cc)::value;
+          cw_t buf[CH];
 #pragma unroll
-      for (int c = 0; c < SUB; ++c) acc_res[c] = f4{0.f, 0.f, 0.f, 0.f};
-      static_for<IW>([&](auto ac) {
-        constexpr int a = decltype(ac)::value;
-        cw_t cw[4];
+          for (int u = 0; u < CH; ++u) {
+            if constexpr (SUB == 4)
+              buf[u] = lds_read64(krow + (CH * ch + u) * 8);
+            else
+              buf[u] = lds_read128(krow + (CH * ch + u) * 16);
+          }
+          k_contract(cc, plain, buf, no_mask, AH, AL, d0, d1);
+        });
+        const h4 wop = softmax_step(d0, d1, valid, 1.f, 0.f, 1.f, 0.f);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const int t = (lane / LV) * NSV + 4 * a + k;  // the same token order as a coded group
-          cw[k] = cw_t{};
-          if (t < rl) cw[k] = *reinterpret_cast<const cw_t*>(res.v + (unit_row + t) * kHeadDim + (lane % LV) * SUB);
-        }
-        v_contract(ac, plain, cw, no_vmask, wop, acc_res);
-      });
+        for (int c = 0; c < SUB; ++c) acc_res[c] = f4{0.f, 0.f, 0.f, 0.f};
+        static_for<IW>([&](auto ac) {
+          constexpr int a = decltype(ac)::value;
+          cw_t cw[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int t = (lane / LV) * NSV + 4 * a + k;  // the same token order as a coded group
+            if constexpr (SUB == 4)
+              cw[k] = lds_read64(sv + t * 256 + (lane % LV) * 8);
+            else
+              cw[k] = lds_read128(sv + t * 256 + (lane % LV) * 16);
+          }
+          v_contract(ac, plain, cw, no_vmask, wop, acc_res);
+        });
+      } else {
+        const uint4* krow = reinterpret_cast<const uint4*>(res.k + (unit_row + lane) * kHeadDim);
+        static_for<NSV / CH>([&](auto cc) {
+          constexpr int ch = decltype(cc)::value;
+          cw_t buf[CH];
+          if constexpr (SUB == 4) {
+#pragma unroll
+            for (int u = 0; u < CH / 2; ++u) {
+              const uint4 x = valid ? krow[(CH / 2) * ch + u] : make_uint4(0u, 0u, 0u, 0u);
+              buf[2 * u] = make_uint2(x.x, x.y);
+              buf[2 * u + 1] = make_uint2(x.z, x.w);
+            }
+          } else {
+#pragma unroll
+            for (int u = 0; u < CH; ++u) buf[u] = valid ? krow[CH * ch + u] : make_uint4(0u, 0u, 0u, 0u);
+          }
+          k_contract(cc, plain, buf, no_mask, AH, AL, d0, d1);
+        });
+        const h4 wop = softmax_step(d0, d1, valid, 1.f, 0.f, 1.f, 0.f);
+#pragma unroll
+        for (int c = 0; c < SUB; ++c) acc_res[c] = f4{0.f, 0.f, 0.f, 0.f};
+        static_for<IW>([&](auto ac) {
+          constexpr int a = decltype(ac)::value;
+          cw_t cw[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int t = (lane / LV) * NSV + 4 * a + k;  // the same token order as a coded group
+            cw[k] = cw_t{};
+            if (t < rl) cw[k] = *reinterpret_cast<const cw_t*>(res.v + (unit_row + t) * kHeadDim + (lane % LV) * SUB);
+          }
+          v_contract(ac, plain, cw, no_vmask, wop, acc_res);
+        });
+      }
     }
   }
   if (cur_group >= 0) flush_group();
@@ -1218,7 +1293,9 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
                       const CacheView& vv, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                       int n_splits, void* workspace, size_t counter_bytes, const ResidualView& res, int head_off,
                       int r_pass, float* out, hipStream_t stream) {
-  const size_t smem = DecSmem<SUB, NW, SGN, ROPE>::kBytes;
+  using SM = DecSmem<SUB, NW, SGN, ROPE>;
+  const size_t smem_max = SM::kResOffset + SM::kResBytes;  // residual launches stage the fp16 rows behind the rest
+  const size_t smem = res.k != nullptr ? smem_max : (size_t)SM::kBytes;
   static bool attr_done = false;
   if (!attr_done) {
     // the gathers address the codebook table by absolute LDS address: it must start at 0,
@@ -1228,7 +1305,7 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
         fa.sharedSizeBytes != 0)
       return NSN_ERR_HIP;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN, ROPE, DQ>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_max) != hipSuccess)
       return NSN_ERR_HIP;
     attr_done = true;
   }
