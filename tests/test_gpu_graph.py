@@ -142,3 +142,79 @@ def test_residual_step_and_flush_replay_bit_identically(gpu_api, codebooks):
         torch.cuda.synchronize()
         for got, want in zip((kc.codes, kc.norms, kc.means, vc.codes, vc.norms, vc.means), flushed):
             assert torch.equal(got, want), f"flush replay {rep} differs from the eager encode"
+
+
+def test_full_configuration_step_replays_bit_identically(gpu_api, codebooks):
+    """Decode step with everything switched on (un-embedded keys with the mean turned in the kernel, 4-bit
+    side information, 64-token groups, residual) and the residual flush, captured and replayed."""
+    import torch
+    api = gpu_api
+    sub, B, Hq, Hkv, L, G = 4, 2, 8, 2, 640, 64
+    cb = torch.from_numpy(codebooks[sub].astype(np.float16)).cuda()
+    table = api.nsn_build_rope_table(synth.rope_inv_freq(10000.0), 768)
+    shape = api.make_shape(sub, Hq, Hkv, 768, G, rope_table=table, side_bits=4)
+    kc, vc = api.alloc_cache(shape, B), api.alloc_cache(shape, B)
+    k, v = synth.make_kv(63, B, Hkv, L + 64)
+    kd, vd = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    coded = torch.full((B,), L, dtype=torch.int32).cuda()
+    api.nsn_encode(shape, cb, kd[:, :, :L].contiguous(), vd[:, :, :L].contiguous(),
+                   torch.zeros(B, dtype=torch.int32).cuda(), coded, kc, vc)
+    scale = 1.0 / math.sqrt(128)
+    k_res, v_res = kd[:, :, L:].contiguous(), vd[:, :, L:].contiguous()
+    res_len = torch.zeros(B, dtype=torch.int32).cuda()
+    full = torch.full((B,), 64, dtype=torch.int32).cuda()
+    q = torch.zeros((B, Hq, 128), dtype=torch.float16).cuda()
+    out = torch.zeros((B, Hq, 128), dtype=torch.float32).cuda()
+    enc_ws = torch.zeros(max(1, api.nsn_workspace_bytes(shape, api.NSN_OP_ENCODE, B, 64)), dtype=torch.uint8).cuda()
+    dec_ws = torch.zeros(max(1, api.nsn_workspace_bytes(shape, api.NSN_OP_DECODE, B)), dtype=torch.uint8).cuda()
+
+    def attend():
+        api.nsn_decode_attention_residual(shape, cb, q, kc, vc, coded, L, k_res, v_res, res_len, scale, 0, out=out,
+                                          workspace=dec_ws)
+
+    def flush():
+        api.nsn_encode(shape, cb, k_res, v_res, coded, full, kc, vc, workspace=enc_ws)
+
+    def set_inputs(i):
+        res_len.fill_(1 + 21 * i)
+        q.copy_(torch.from_numpy(synth.make_q(63, B, Hq, step=i)))
+
+    eager = []
+    for i in range(3):
+        set_inputs(i)
+        attend()
+        torch.cuda.synchronize()
+        eager.append(out.clone())
+    flush()
+    torch.cuda.synchronize()
+    flushed = [t.clone() for t in (kc.codes, kc.norms, kc.means, vc.codes, vc.norms, vc.means)]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        attend()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g_attend, g_flush = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g_attend):
+        attend()
+    with torch.cuda.graph(g_flush):
+        flush()
+    for rep in range(2):
+        for i in range(3):
+            set_inputs(i)
+            g_attend.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager[i]), f"replay {rep}/{i} differs from the eager result"
+            assert np.isfinite((out * 2).sum().item())   # eager work between replays
+        # wipe what the flush writes (block 10 of the sequence: one norms record, one mean record, 64 tokens of codes)
+        kc.codes[:, :, L * 32:] = 0
+        vc.codes[:, :, L * 32:] = 0
+        kc.norms[:, :, L // 64:] = 0
+        vc.norms[:, :, L // 64:] = 0
+        kc.means[:, :, L // 64:] = 0
+        vc.means[:, :, L // 64:] = 0
+        g_flush.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((kc.codes, kc.norms, kc.means, vc.codes, vc.norms, vc.means), flushed):
+            assert torch.equal(got, want), f"flush replay {rep} differs from the eager encode"

@@ -78,6 +78,24 @@ def test_shape_validation_and_error_text(L):
     assert rc == api.NSN_ERR_INVALID_ARG and b"group_size" in L.nsn_last_error()
     rc = L.nsn_build_codebook(None, 1000, 8, 128, 1, None, None, None, 0, None)
     assert rc == api.NSN_ERR_UNSUPPORTED
+    # side information width, rotary table alignment
+    odd_bits = api.make_shape(4, 32, 8, 8192, 64, side_bits=5)
+    assert api.nsn_workspace_bytes(odd_bits, api.NSN_OP_DECODE, 8) == 0
+    rc = L.nsn_decode_attention(C.byref(odd_bits), None, None, C.byref(kc), C.byref(kc), None, 1, 1, 1.0, 0, None,
+                                None, 0, None)
+    assert rc == api.NSN_ERR_UNSUPPORTED and b"side_bits" in L.nsn_last_error()
+    dq = api.make_shape(4, 32, 8, 8192, 64, side_bits=4)
+    # 4-bit side information: the encoder workspace also carries fp16(s1) of every new token
+    assert api.nsn_workspace_bytes(dq, api.NSN_OP_ENCODE, 8, 8192) == 8 * 8 * 2 * 128 * 128 * 8 + 8 * 8 * 2 * 8192 * 2
+    misaligned = api.make_shape(4, 32, 8, 8192, 64)
+    misaligned.rope_table = 0x1008
+    rc = L.nsn_decode_attention(C.byref(misaligned), None, None, C.byref(kc), C.byref(kc), None, 1, 1, 1.0, 0, None,
+                                None, 0, None)
+    assert rc == api.NSN_ERR_INVALID_ARG and b"rope_table" in L.nsn_last_error()
+    rc = L.nsn_quantize_codebook(None, 4, 256, None, None, None)
+    assert rc == api.NSN_ERR_INVALID_ARG
+    rc = L.nsn_quantize_codebook(None, 5, 256, None, None, None)
+    assert rc == api.NSN_ERR_UNSUPPORTED
     # rotary table: three fixed parts (2 x 16 KiB fp16, 64 KiB fp64) + 1536 bytes per 64-token block
     assert L.nsn_rope_table_bytes(8192) == 98304 + 128 * 1536
     assert L.nsn_rope_table_bytes(100) == 0 and L.nsn_rope_table_bytes(0) == 0
