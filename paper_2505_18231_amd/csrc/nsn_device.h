@@ -55,6 +55,10 @@ struct Geometry {
   int page_tokens;  // tokens per placement unit: page_size if paged, else max_len
   int pages_per_seq;  // max_len / page_size if paged, else 1
   int paged;
+  // log2 of group_size / page_tokens when they are powers of two (the usual case), else -1: the
+  // kernels index groups and pages once or more per 64 tokens, and a division by a run-time value
+  // costs about 35 scalar instructions
+  int group_shift, page_shift;
 };
 
 // Byte offset, inside one placement unit, of the code of (token t of the unit, sub-vector j).
@@ -67,14 +71,23 @@ __host__ __device__ inline int64_t v_code_offset(int J, int64_t t, int j) {
 }
 
 // Index (in tokens) of the first token of the placement unit holding token t of sequence b.
+__device__ inline int page_of(const Geometry& g, int t) {
+  return g.page_shift >= 0 ? t >> g.page_shift : t / g.page_tokens;
+}
 __device__ inline int64_t unit_token_base(const Geometry& g, const int32_t* block_table, int b, int h,
                                           int t) {
   int64_t page = b;
-  if (g.paged) page = block_table[(int64_t)b * g.pages_per_seq + t / g.page_tokens];
+  if (g.paged) page = block_table[(int64_t)b * g.pages_per_seq + page_of(g, t)];
   return (page * g.n_kv_heads + h) * (int64_t)g.page_tokens;
 }
-__device__ inline int token_in_unit(const Geometry& g, int t) { return g.paged ? t % g.page_tokens : t; }
-__device__ inline int group_of(const Geometry& g, int t) { return g.group_size > 0 ? t / g.group_size : 0; }
+__device__ inline int token_in_unit(const Geometry& g, int t) {
+  if (!g.paged) return t;
+  return g.page_shift >= 0 ? t & (g.page_tokens - 1) : t % g.page_tokens;
+}
+__device__ inline int group_of(const Geometry& g, int t) {
+  if (g.group_size <= 0) return 0;
+  return g.group_shift >= 0 ? t >> g.group_shift : t / g.group_size;
+}
 
 // Double quantization: record of the 64-token block holding token t of a placement unit that starts at
 // token index `base`; mean record of (unit-relative) group gidx

@@ -18,6 +18,14 @@ inline Geometry make_geometry(const nsn_shape& s) {
   g.paged = s.page_size > 0;
   g.page_tokens = g.paged ? s.page_size : s.max_len;
   g.pages_per_seq = g.paged ? s.max_len / s.page_size : 1;
+  auto log2_or_minus1 = [](int v) {
+    if (v <= 0 || (v & (v - 1)) != 0) return -1;
+    int k = 0;
+    while ((1 << k) < v) ++k;
+    return k;
+  };
+  g.group_shift = log2_or_minus1(s.group_size);
+  g.page_shift = log2_or_minus1(g.page_tokens);
   return g;
 }
 
