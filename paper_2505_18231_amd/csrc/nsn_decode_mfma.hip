@@ -415,10 +415,12 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     qv[u] = (i < 4 * kHeadDim && hh < r) ? __half2float(q[(int64_t)(b * g.n_q_heads + hq0 + hh) * kHeadDim + c]) : 0.f;
   }
   // ROPE: the fp16 cosine / sine rows go to LDS with the codebook (four 16-byte chunks per thread)
-  uint4 trow[ROPE ? 4 : 1];
-  if constexpr (ROPE) {  // (the residual wave loads in-bounds chunks that it never stores)
+  constexpr int TROWS = ROPE ? (2048 + NT - 1) / NT : 1;  // 2048 16-byte chunks of the hi and lo rows
+  uint4 trow[TROWS];
+  if constexpr (ROPE) {  // (the residual wave and the last round's surplus threads load in-bounds chunks that they never store)
 #pragma unroll
-    for (int u = 0; u < 4; ++u) trow[u] = reinterpret_cast<const uint4*>(g.rope + kRopeHiOff)[min(tid, NT - 1) + u * NT];
+    for (int u = 0; u < TROWS; ++u)
+      trow[u] = reinterpret_cast<const uint4*>(g.rope + kRopeHiOff)[min(min(tid, NT - 1) + u * NT, 2047)];
   }
   RopeIn rin = {};
   if constexpr (ROPE) {
@@ -429,7 +431,8 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   if (spec) load_group(wave, cur);
   // The split's first Shift group is shared by all waves when there is one group per sequence:
   // its q . o^k is formed once per workgroup (waves that do not rotate a query head), not per wave.
-  static_assert(NW >= 8, "prologue work split: waves 0-3 rotate the query, waves 4.. do the rest");
+  static_assert(NW >= 8 || (ROPE && NW == 7), "prologue work split: waves 0-3 rotate the query, waves 4.. do the rest "
+                                              "(waves 4..7 take a head's q . o^k unless the mean is turned in the kernel)");
   const int grp_pre = group_of(g, min(t0, g.page_tokens * g.pages_per_seq - 1));
   Side pre = {};  // only the key-side mean fields are used
   if (!ROPE && wave >= 4 && wave - 4 < R) {
@@ -476,10 +479,11 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   if constexpr (ROPE) {
     if (main_wave) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < TROWS; ++u) {
         const int c = tid + u * NT;  // chunk c: part (hi / lo) c >> 10, row (c >> 4) & 63, 16-byte chunk c & 15
         const int row = (c >> 4) & 63;
-        *reinterpret_cast<uint4*>(sm_rope_tab + (c >> 10) * 16384 + row * 256 + (((c & 15) ^ (row & 15)) << 4)) = trow[u];
+        if (NT * TROWS == 2048 || c < 2048)
+          *reinterpret_cast<uint4*>(sm_rope_tab + (c >> 10) * 16384 + row * 256 + (((c & 15) ^ (row & 15)) << 4)) = trow[u];
       }
     }
   }
@@ -505,11 +509,12 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   if constexpr (SGN) {
     // sign-mask table at LDS address 0: row = sign nibble n (256 bytes), 32 copies of the 8-byte entry
     // whose four fp16 sign bits are bits 0..3 of n
-    if (tid < 16 * 32) {
-      const uint32_t n = tid >> 5;
+    for (int e = tid; e < 16 * 32; e += NT) {  // (one round with 8 waves)
+      if (!main_wave) break;
+      const uint32_t n = e >> 5;
       const uint32_t w0 = ((n & 1u) ? 0x8000u : 0u) | ((n & 2u) ? 0x80000000u : 0u);
       const uint32_t w1 = ((n & 4u) ? 0x8000u : 0u) | ((n & 8u) ? 0x80000000u : 0u);
-      *reinterpret_cast<uint2*>(sm_table + n * 256 + (tid & 31) * 8) = make_uint2(w0, w1);
+      *reinterpret_cast<uint2*>(sm_table + n * 256 + (e & 31) * 8) = make_uint2(w0, w1);
     }
   }
   if (!ROPE && wave >= 4 && wave - 4 < R) {
@@ -1358,9 +1363,18 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
     auto with_r = [&](auto sub, auto sgn, auto rope, auto dq) {
       constexpr int kSub = decltype(sub)::value;
       constexpr bool kSgn = decltype(sgn)::value, kRope = decltype(rope)::value, kDq = decltype(dq)::value;
-      return r == 1   ? launch_one<kSub, 8, 1, kSgn, kRope, kDq>(NSN_ARGS)
-             : r == 2 ? launch_one<kSub, 8, 2, kSgn, kRope, kDq>(NSN_ARGS)
-                      : launch_one<kSub, 8, 4, kSgn, kRope, kDq>(NSN_ARGS);
+      if constexpr (kRope && kDq) {
+        // Mean turned in the kernel AND 4-bit side information: with nine waves (168 registers each) these
+        // instances spill 50-210 bytes per lane; with seven main waves the launch has at most eight, each
+        // may use 256 registers, nothing spills, and they run 12-15 % faster in spite of the missing wave
+        // (the instances with only one of the two options lose 2-8 % that way and keep eight).
+        return r == 1   ? launch_one<kSub, 7, 1, kSgn, kRope, kDq>(NSN_ARGS)
+               : r == 2 ? launch_one<kSub, 7, 2, kSgn, kRope, kDq>(NSN_ARGS)
+                        : launch_one<kSub, 7, 4, kSgn, kRope, kDq>(NSN_ARGS);
+      } else
+        return r == 1   ? launch_one<kSub, 8, 1, kSgn, kRope, kDq>(NSN_ARGS)
+               : r == 2 ? launch_one<kSub, 8, 2, kSgn, kRope, kDq>(NSN_ARGS)
+                        : launch_one<kSub, 8, 4, kSgn, kRope, kDq>(NSN_ARGS);
     };
     auto with_format = [&](auto rope, auto dq) {
       if constexpr (!decltype(rope)::value && !decltype(dq)::value) {
