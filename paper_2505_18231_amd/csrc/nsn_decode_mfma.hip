@@ -1379,9 +1379,9 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
     auto with_format = [&](auto rope, auto dq) {
       if constexpr (!decltype(rope)::value && !decltype(dq)::value) {
         // Long splits of the 4-dim format run with 11 main waves (12 with the residual wave: three per
-        // SIMD, still 168 registers each): the loop is bound by the compute unit's LDS instruction
-        // rate, and a third wave per SIMD overlaps a little more of the other work with it (-3 % to
-        // -6 % on 16k-32k token splits, +3 % on 2k token splits, whose prologue it lengthens).
+        // SIMD, still 168 registers each): a third wave per SIMD overlaps a little more of the vector,
+        // matrix and memory work (-3 % to -6 % on 16k-32k token splits, +3 % on 2k token splits, whose
+        // prologue it lengthens).
         // NSN_DECODE_NW=8 / 11 overrides the choice.
         static const int nw_env = [] { const char* e = getenv("NSN_DECODE_NW"); return e ? atoi(e) : 0; }();
         const int per_tokens = (((max_seq_len + n_splits - 1) / n_splits) + 63) & ~63;
