@@ -178,9 +178,12 @@ struct DecSmem {
   static constexpr int kTable = kTableBytes + kSignLutBytes;
   static constexpr int kQoTabGroups = 64;  // q . o^k of up to 64 Shift groups of a split, four heads each
   static constexpr int kStageBytes = ((kCodes * 2 * SUB + 2 * 4 * kHeadDim * 4 + 16 + kQoTabGroups * 16) + 255) & ~255;
-  static constexpr int kAccmOffset = kTable + kStageBytes;
-  static constexpr int kAccmBytes = (NW + 1) * 4 * kHeadDim * 4;  // + the residual wave's slot
   static constexpr int kRaccBytes = NW * (64 / (kHeadDim / SUB)) * 4 * kHeadDim * 4;
+  // (the per-wave accumulators reuse the table and, where they are larger - 11 waves of 8-dim
+  // sub-vectors -, the staging area behind it: both are dead once the main loop is over)
+  static constexpr int kAccmOffset =
+      kTable + kStageBytes > ((kRaccBytes + 255) & ~255) ? kTable + kStageBytes : ((kRaccBytes + 255) & ~255);
+  static constexpr int kAccmBytes = (NW + 1) * 4 * kHeadDim * 4;  // + the residual wave's slot
   static constexpr int kTailBytes = (2 * (NW + 1) * 4 + 4 + 4 * kHeadDim) * 4;
   static constexpr bool kTailInTable = kRaccBytes + kTailBytes <= kTable;
   static constexpr int kTailOffset = kTailInTable ? kRaccBytes : kAccmOffset + kAccmBytes;
@@ -199,7 +202,7 @@ struct DecSmem {
   static constexpr int kResOffset = (kBytes + 255) & ~255;
   static constexpr int kResBytes = kResInLds ? 64 * kResKStride + 64 * 256 : 0;
   static_assert(kResOffset + kResBytes <= 160 * 1024, "LDS of one compute unit");
-  static_assert(kRaccBytes <= kTable, "per-wave accumulators must fit in the table region");
+  static_assert(kRaccBytes <= kAccmOffset, "per-wave accumulators must end below the mean-term accumulators");
 };
 
 // R = query heads per kv head handled by the kernel instance (1, 2 or 4; three heads run as 4).
@@ -1378,7 +1381,7 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
     };
     auto with_format = [&](auto rope, auto dq) {
       if constexpr (!decltype(rope)::value && !decltype(dq)::value) {
-        // Long splits of the 4-dim format run with 11 main waves (12 with the residual wave: three per
+        // Long splits of the index-only formats run with 11 main waves (12 with the residual wave: three per
         // SIMD, still 168 registers each): a third wave per SIMD overlaps a little more of the vector,
         // matrix and memory work (-3 % to -6 % on 16k-32k token splits, +3 % on 2k token splits, whose
         // prologue it lengthens).
@@ -1390,6 +1393,10 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
           return r == 1   ? launch_one<4, 11, 1>(NSN_ARGS)
                  : r == 2 ? launch_one<4, 11, 2>(NSN_ARGS)
                           : launch_one<4, 11, 4>(NSN_ARGS);
+        if (nw11 && !g.sign && s.sub_dim == 8)
+          return r == 1   ? launch_one<8, 11, 1>(NSN_ARGS)
+                 : r == 2 ? launch_one<8, 11, 2>(NSN_ARGS)
+                          : launch_one<8, 11, 4>(NSN_ARGS);
       }
       if (g.sign) return with_r(std::integral_constant<int, 8>{}, std::true_type{}, rope, dq);
       if (s.sub_dim == 4) return with_r(std::integral_constant<int, 4>{}, std::false_type{}, rope, dq);

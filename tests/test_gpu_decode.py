@@ -72,6 +72,7 @@ CASES = [
     ("long-1bit-groups", 1, 4, 2, [3000], 8, 64, 0, 3),
     ("long-2bit-eleven-waves", 2, 4, 1, [9000, 4100], 4, 64, 0, 2),   # splits of >= 4096 tokens: the 11-wave instance
     ("long-2bit-eleven-waves-mha", 1, 1, 1, [5000], 4, 0, 0, 1),
+    ("long-1bit-eleven-waves", 2, 4, 1, [9000, 4100], 8, 64, 0, 2),   # the 8-dim form of the 11-wave instance
 ]
 
 
