@@ -1258,18 +1258,38 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       }
     }
   } else {
+    // many splits: chunks of SFAST with every load of a chunk issued before its first use (one memory round
+    // trip per chunk instead of one per split), running max carried across the chunks
     float M = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ld_agent(Ph + s * kPartialStrideM + 2 * kHeadDim));
-    if (M > -INFINITY) {
-      for (int s = 0; s < n_splits; ++s) {
-        const float* ps = Ph + s * kPartialStrideM;
-        const float2 ml = ld2(ps + 2 * kHeadDim), pr = ld2(ps + 2 * lane), pq = ld2(ps + kHeadDim + 2 * lane);
-        const float e = fast_exp2(ml.x - M);
-        L = fmaf(e, ml.y, L);
-        x0 = fmaf(e, pr.x, x0);
-        x1 = fmaf(e, pr.y, x1);
-        mm0 = fmaf(e, pq.x, mm0);
-        mm1 = fmaf(e, pq.y, mm1);
+    for (int s0 = 0; s0 < n_splits; s0 += SFAST) {
+      float2 pml[SFAST], pr[SFAST], pq[SFAST];
+#pragma unroll
+      for (int s = 0; s < SFAST; ++s) {
+        pml[s] = make_float2(-INFINITY, 0.f);
+        pr[s] = pq[s] = make_float2(0.f, 0.f);
+        if (s0 + s < n_splits) {  // uniform
+          const float* ps = Ph + (s0 + s) * kPartialStrideM;
+          pml[s] = ld2(ps + 2 * kHeadDim);
+          pr[s] = ld2(ps + 2 * lane);
+          pq[s] = ld2(ps + kHeadDim + 2 * lane);
+        }
+      }
+      float Mn = M;
+#pragma unroll
+      for (int s = 0; s < SFAST; ++s) Mn = fmaxf(Mn, pml[s].x);
+      if (Mn > -INFINITY) {
+        const float corr = (M == -INFINITY) ? 0.f : fast_exp2(M - Mn);
+        L *= corr, x0 *= corr, x1 *= corr, mm0 *= corr, mm1 *= corr;
+#pragma unroll
+        for (int s = 0; s < SFAST; ++s) {
+          const float e = (s0 + s < n_splits) ? fast_exp2(pml[s].x - Mn) : 0.f;  // 2^-inf = 0 for empty splits
+          L = fmaf(e, pml[s].y, L);
+          x0 = fmaf(e, pr[s].x, x0);
+          x1 = fmaf(e, pr[s].y, x1);
+          mm0 = fmaf(e, pq[s].x, mm0);
+          mm1 = fmaf(e, pq[s].y, mm1);
+        }
+        M = Mn;
       }
     }
   }
