@@ -152,7 +152,16 @@ __global__ __launch_bounds__(128) void enc_means_kernel(Geometry g, int max_new,
   if (tokens <= 0 || g_abs >= g.n_groups_max) return;
   const double* p = partial + (((int64_t)(b * g.n_kv_heads + h) * 2 + tensor) * n_chunks) * kHeadDim + c;
   double s = 0.0;
-  for (int k = first_chunk; k < last_chunk; ++k) s += p[(int64_t)k * kHeadDim];
+  // added in chunk order, loaded eight at a time (one load per addition would be one memory round
+  // trip per chunk: 512 of them for a 131072-token sequence)
+  for (int k0 = first_chunk; k0 < last_chunk; k0 += 8) {
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = (k0 + u < last_chunk) ? p[(int64_t)(k0 + u) * kHeadDim] : 0.0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (k0 + u < last_chunk) s += v[u];
+  }
   const double mean = s / (double)tokens;
   const int64_t mean_index = (int64_t)(b * g.n_kv_heads + h) * g.n_groups_max + g_abs;
   if (!g.dq) {
