@@ -33,13 +33,21 @@
  * Coded cache record (one tensor kind, K or V), per (sequence b, kv-head h):
  *   codes  J bytes per token: J = head_dim/sub_dim index bytes; in the sign + index format
  *          J = 32: byte rows j = 0..15 are the indices of sub-vectors 0..15, rows 16..31 their
- *          sign bytes.  Inside one placement unit (see below) the
- *          byte of (token t of the unit, byte row j in [0,J)) sits at
+ *          sign bytes.  Inside one placement unit (see below) the byte of (token t of the
+ *          unit, byte row j in [0,J)) sits at the offset that nsn_k_code_offset /
+ *          nsn_v_code_offset return:
+ *          TILED layout - the (sub_dim, 256) formats with fp16 side information and no rope_table.
+ *          Blocks of 64 tokens, 64 * J bytes each; inside a block one run of J bytes per lane
+ *          of the 64-lane wave that reads it; with QS = J / 4 and tb = t % 64:
+ *            K:  (t / 64) * 64*J + (16 * (j / QS) + tb % 16) * J + (tb / 16) * QS + j % QS
+ *            V:  (t / 64) * 64*J + (16 * (tb % 16 / 4) + 4 * (tb % 4) + j % 4) * J + (tb / 16) * QS + j / 4
+ *          K: a lane holds one 32-channel quarter (QS sub-vectors) of tokens tb % 16 = const of
+ *          the block's four 16-token tiles, which is its A operand of the 16x16x32 score
+ *          contraction; V: a lane holds sub-vectors j % 4 = const of four tokens 16 apart, which
+ *          the transposing LDS read turns into "four tokens of one channel" operands.
+ *          LEGACY layout - the sign + index format, rope_table, side_bits = 4:
  *            K:  t * J + j                                  (token-major)
  *            V:  (t / J) * J*J + j * J + t % J              (blocks of J tokens, sub-vector-major)
- *          K keeps a token's codes together for the score contraction over channels; V keeps
- *          J consecutive tokens of one sub-vector together for the contraction over tokens.
- *          nsn_k_code_offset / nsn_v_code_offset below return these offsets.
  *   norms  one (a, b) fp16 pair per token: b = s1 (first Normalize scale), a = s1*s2*alpha
  *          (second Normalize scale times the scale-adjustment factor of Sec. 3.3).
  *   means  fp16 [n_groups][head_dim]: the Shift vector o of every group of group_size
@@ -160,9 +168,10 @@ size_t nsn_rope_table_bytes(int max_len);
 int nsn_build_rope_table(const float* inv_freq_host, int max_len, void* table_dev, size_t table_bytes,
                          void* stream);
 
-/* Byte offset of the code of (token t, sub-vector j) inside a placement unit; J = codes per token. */
-int64_t nsn_k_code_offset(int J, int64_t t, int j);
-int64_t nsn_v_code_offset(int J, int64_t t, int j);
+/* Byte offset of code byte row j of token t inside a placement unit of a cache of this shape
+ * (see "codes" above); -1 for an invalid shape, t < 0 or j outside [0, J). */
+int64_t nsn_k_code_offset(const nsn_shape* shape, int64_t t, int j);
+int64_t nsn_v_code_offset(const nsn_shape* shape, int64_t t, int j);
 /* Number of mean vectors kept per (sequence, kv-head): max_len / group_size rounded up, or 1. */
 int nsn_max_groups(const nsn_shape* shape);
 /* Text of the calling thread's most recent error ("" if none). Never NULL. */

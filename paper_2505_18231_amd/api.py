@@ -60,7 +60,7 @@ def lib() -> C.CDLL:
         L.nsn_max_groups.argtypes = [C.POINTER(nsn_shape)]
         for fn in (L.nsn_k_code_offset, L.nsn_v_code_offset):
             fn.restype = C.c_int64
-            fn.argtypes = [C.c_int, C.c_int64, C.c_int]
+            fn.argtypes = [C.POINTER(nsn_shape), C.c_int64, C.c_int]
         L.nsn_build_codebook.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                          C.POINTER(C.c_double), C.c_void_p, C.c_size_t, C.c_void_p]
         L.nsn_finetune_codebook.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_double,

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libnsn.so")
-SOURCES = ["nsn_api.hip", "nsn_encode.hip", "nsn_decode.hip", "nsn_decode_mfma.hip", "nsn_codebook.hip", "nsn_rope.hip"]
+SOURCES = ["nsn_api.hip", "nsn_encode.hip", "nsn_decode.hip", "nsn_decode_mfma.hip", "nsn_decode_tile.hip", "nsn_codebook.hip", "nsn_rope.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

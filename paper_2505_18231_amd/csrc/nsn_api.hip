@@ -76,8 +76,16 @@ using namespace nsn;
 
 extern "C" {
 
-int64_t nsn_k_code_offset(int J, int64_t t, int j) { return k_code_offset(J, t, j); }
-int64_t nsn_v_code_offset(int J, int64_t t, int j) { return v_code_offset(J, t, j); }
+int64_t nsn_k_code_offset(const nsn_shape* shape, int64_t t, int j) {
+  if (check_shape(shape) != NSN_OK) return -1;
+  const Geometry g = make_geometry(*shape);
+  return (t < 0 || j < 0 || j >= g.J) ? -1 : code_offset(g.tiled, false, g.J, t, j);
+}
+int64_t nsn_v_code_offset(const nsn_shape* shape, int64_t t, int j) {
+  if (check_shape(shape) != NSN_OK) return -1;
+  const Geometry g = make_geometry(*shape);
+  return (t < 0 || j < 0 || j >= g.J) ? -1 : code_offset(g.tiled, true, g.J, t, j);
+}
 
 int nsn_max_groups(const nsn_shape* shape) {
   if (check_shape(shape) != NSN_OK) return 0;

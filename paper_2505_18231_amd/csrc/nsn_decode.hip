@@ -7,6 +7,7 @@
 //                     codeword domain plus the mean-vector term) and emit an fp32 partial
 //   dec_merge_kernel  merge the splits (running max / sum), one inverse Hadamard per head
 #include <cstdlib>
+#include <type_traits>
 
 #include "nsn_host.h"
 
@@ -128,14 +129,30 @@ __global__ __launch_bounds__(256) void dec_lut_kernel(Geometry g, const __half* 
     if (valid) {
       const int64_t base = unit_token_base(g, kc.block_table, b, h, t);
       const int tin = token_in_unit(g, t);
-      const uint4* kp = reinterpret_cast<const uint4*>(kc.codes + (base + tin) * J);
       float sum = 0.f;
+      if (g.tiled) {  // a token's J bytes lie in four runs of J / 4 (one per 32-channel quarter)
+        constexpr int QS = J / 4;
+        typedef typename std::conditional<QS == 8, uint2, uint32_t>::type run_t;
 #pragma unroll
-      for (int w4 = 0; w4 < J / 16; ++w4) {
-        const uint4 cw = kp[w4];
-        const uint32_t wds[4] = {cw.x, cw.y, cw.z, cw.w};
+        for (int c = 0; c < 4; ++c) {
+          const run_t run = *reinterpret_cast<const run_t*>(kc.codes + base * J + k_code_offset_tiled(J, tin, c * QS));
+          uint32_t wds[2] = {0u, 0u};
+          if constexpr (QS == 8)
+            wds[0] = run.x, wds[1] = run.y;
+          else
+            wds[0] = run;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sum += lut[w4 * 16 + e][(wds[e >> 2] >> ((e & 3) * 8)) & 0xff];
+          for (int e = 0; e < QS; ++e) sum += lut[c * QS + e][(wds[e >> 2] >> ((e & 3) * 8)) & 0xff];
+        }
+      } else {
+        const uint4* kp = reinterpret_cast<const uint4*>(kc.codes + (base + tin) * J);
+#pragma unroll
+        for (int w4 = 0; w4 < J / 16; ++w4) {
+          const uint4 cw = kp[w4];
+          const uint32_t wds[4] = {cw.x, cw.y, cw.z, cw.w};
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sum += lut[w4 * 16 + e][(wds[e >> 2] >> ((e & 3) * 8)) & 0xff];
+        }
       }
       const __half2 nk = kc.norms[base + tin];
       score = scale * (__low2float(nk) * sum + __high2float(nk) * qo_s[group_of(g, t) - g_first]);
@@ -164,7 +181,7 @@ __global__ __launch_bounds__(256) void dec_lut_kernel(Geometry g, const __half* 
       if (tv >= t1) break;
       const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tv);
       const int tin = token_in_unit(g, tv);
-      const int code = vc.codes[vbase * J + v_code_offset(J, tin, jv)];
+      const int code = vc.codes[vbase * J + code_offset(g.tiled, true, J, tin, jv)];
       const float w = pa[tt];
 #pragma unroll
       for (int i = 0; i < SUB; ++i) acc[i] = fmaf(w, cb[code][i], acc[i]);

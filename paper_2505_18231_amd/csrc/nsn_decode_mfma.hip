@@ -1348,9 +1348,10 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
   return NSN_OK;
 }
 
-// arrival counters (one int per (sequence, kv head)) sit at the head of the workspace
+// arrival counters sit at the head of the workspace: one int per (sequence, query head) (this kernel
+// uses one per (sequence, kv head) of them, the tiled-layout kernel all)
 static size_t counter_bytes(const nsn_shape& s, int batch) {
-  return (((size_t)batch * s.n_kv_heads * sizeof(int)) + 255) & ~(size_t)255;
+  return (((size_t)batch * s.n_q_heads * sizeof(int)) + 255) & ~(size_t)255;
 }
 
 int decode_mfma_splits(const nsn_shape& s, int batch, int max_seq_len, int requested) {
@@ -1368,6 +1369,9 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
                        const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                        int n_splits, void* workspace, const nsn_residual* residual, float* out,
                        hipStream_t stream) {
+  if (shape_is_tiled(s))
+    return decode_tile_launch(s, codebook, q, kc, vc, seq_lens, batch, max_seq_len, scale, n_splits, workspace,
+                              counter_bytes(s, batch), residual, out, stream);
   const Geometry g = make_geometry(s);
   ResidualView res = {nullptr, nullptr, nullptr, 0};
   if (residual)

@@ -45,6 +45,7 @@ constexpr int kDqNormRec = 164, kDqNormCodes = 128, kDqNormPar = 160;
 constexpr int kDqMeanRec = 80, kDqMeanPar = 64;
 
 struct Geometry {
+  int tiled;                  // 1: codes in the tiled layout (64-token blocks, see k_code_offset_tiled)
   int dq;                     // 1: norms and means are stored in 4 bits (records above)
   const unsigned char* rope;  // table of nsn_build_rope_table, or nullptr (keys coded as given)
   int sign;         // 1: an 8-dim sub-vector is an index byte plus a sign byte (byte rows 0..15 / 16..31)
@@ -68,6 +69,28 @@ struct Geometry {
 __host__ __device__ inline int64_t k_code_offset(int J, int64_t t, int j) { return t * J + j; }
 __host__ __device__ inline int64_t v_code_offset(int J, int64_t t, int j) {
   return (t / J) * (int64_t)(J * J) + (int64_t)j * J + (t % J);
+}
+
+// Tiled layout (the formats read by dec_tile_kernel): 64-token blocks of 64 * NSV bytes (NSV = sub-vectors
+// per token), one run of NSV bytes per lane of the wave that reads the block (lane = 16 hi + lo):
+//   K: lane = 16 * (j / QS) + t % 16, byte (t % 64 / 16) * QS + j % QS           (QS = NSV / 4)
+//      - a lane holds one 32-channel quarter of tokens t % 16 of the block's four 16-token tiles
+//   V: lane = 16 * (t % 16 / 4) + 4 * (t % 4) + j % 4, byte (t % 64 / 16) * QS + j / 4
+//      - a lane holds sub-vectors j % 4 == const of four tokens that are 16 apart
+__host__ __device__ inline int64_t k_code_offset_tiled(int NSV, int64_t t, int j) {
+  const int QS = NSV / 4, tb = (int)(t & 63);
+  const int lane = 16 * (j / QS) + (tb & 15);
+  return (t >> 6) * (int64_t)(64 * NSV) + lane * NSV + (tb >> 4) * QS + j % QS;
+}
+__host__ __device__ inline int64_t v_code_offset_tiled(int NSV, int64_t t, int j) {
+  const int QS = NSV / 4, tb = (int)(t & 63);
+  const int lane = 16 * ((tb & 15) >> 2) + 4 * (tb & 3) + (j & 3);
+  return (t >> 6) * (int64_t)(64 * NSV) + lane * NSV + (tb >> 4) * QS + (j >> 2);
+}
+// the layout a cache of geometry g uses
+__host__ __device__ inline int64_t code_offset(bool tiled, bool value, int J, int64_t t, int j) {
+  if (tiled) return value ? v_code_offset_tiled(J, t, j) : k_code_offset_tiled(J, t, j);
+  return value ? v_code_offset(J, t, j) : k_code_offset(J, t, j);
 }
 
 // Index (in tokens) of the first token of the placement unit holding token t of sequence b.

@@ -412,10 +412,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
     nrm2 = xor_sum_w<J>(nrm2);
     const double alpha = (dot > 1e-12 * kHeadDim) ? nrm2 / dot : 1.0;
     if (valid) {
-      const int64_t off = tensor ? v_code_offset(JB, tin, jj) : k_code_offset(JB, tin, jj);
+      const int64_t off = code_offset(g.tiled, tensor != 0, JB, tin, jj);
       cv.codes[base * JB + off] = (uint8_t)code;
       if constexpr (SIGN) {
-        const int64_t soff = tensor ? v_code_offset(JB, tin, J + jj) : k_code_offset(JB, tin, J + jj);
+        const int64_t soff = code_offset(g.tiled, tensor != 0, JB, tin, J + jj);
         cv.codes[base * JB + soff] = (uint8_t)sign_byte;
       }
       if (jj == 0) {

@@ -5,11 +5,17 @@
 
 namespace nsn {
 
+// which formats keep their codes in the tiled layout (read by dec_tile_kernel)
+inline bool shape_is_tiled(const nsn_shape& s) {
+  return s.n_codes == kCodes && s.side_bits != 4 && s.rope_table == nullptr;
+}
+
 inline Geometry make_geometry(const nsn_shape& s) {
   Geometry g;
   g.dq = s.side_bits == 4;
   g.rope = static_cast<const unsigned char*>(s.rope_table);
   g.sign = s.n_codes == kSignCodes;
+  g.tiled = shape_is_tiled(s);
   g.J = g.sign ? 2 * (s.head_dim / s.sub_dim) : s.head_dim / s.sub_dim;
   g.n_q_heads = s.n_q_heads;
   g.n_kv_heads = s.n_kv_heads;
@@ -50,6 +56,10 @@ int decode_pick_splits(const nsn_shape& s, int batch, int max_seq_len, int reque
 bool decode_use_mfma(const nsn_shape& s);
 int decode_mfma_splits(const nsn_shape& s, int batch, int max_seq_len, int requested);
 size_t decode_mfma_workspace_bytes(const nsn_shape& s, int batch, int n_splits);
+int decode_tile_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
+                       const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
+                       int n_splits, void* workspace, size_t counter_bytes, const nsn_residual* residual, float* out,
+                       hipStream_t stream);
 int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
                        const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                        int n_splits, void* workspace, const nsn_residual* residual, float* out,

@@ -8,29 +8,37 @@ import numpy as np
 D = 128
 
 
-def code_offsets(J: int, kind: str, n_tokens: int) -> np.ndarray:
-    """[n_tokens][J] byte offset inside a placement unit of (token, sub-vector)."""
+def code_offsets(J: int, kind: str, n_tokens: int, layout: str = "tiled") -> np.ndarray:
+    """[n_tokens][J] byte offset inside a placement unit of (token, byte row); the two layouts of include/nsn.h."""
     t, j = np.meshgrid(np.arange(n_tokens), np.arange(J), indexing="ij")
+    if layout == "legacy":
+        if kind == "k":
+            return t * J + j
+        return (t // J) * (J * J) + j * J + t % J
+    assert layout == "tiled"
+    qs, tb = J // 4, t % 64
     if kind == "k":
-        return t * J + j
-    return (t // J) * (J * J) + j * J + t % J
+        lane = 16 * (j // qs) + tb % 16
+        return (t // 64) * (64 * J) + lane * J + (tb // 16) * qs + j % qs
+    lane = 16 * (tb % 16 // 4) + 4 * (tb % 4) + j % 4
+    return (t // 64) * (64 * J) + lane * J + (tb // 16) * qs + j // 4
 
 
-def pack_codes(codes: np.ndarray, kind: str, capacity: int) -> np.ndarray:
+def pack_codes(codes: np.ndarray, kind: str, capacity: int, layout: str = "tiled") -> np.ndarray:
     """codes u8 [L][J] -> layout bytes u8 [capacity * J] (capacity a multiple of 64 tokens)."""
     L, J = codes.shape
     assert capacity % 64 == 0 and capacity >= L
     full = np.zeros((capacity, J), dtype=np.uint8)
     full[:L] = codes
     out = np.zeros(capacity * J, dtype=np.uint8)
-    out[code_offsets(J, kind, capacity).ravel()] = full.ravel()
+    out[code_offsets(J, kind, capacity, layout).ravel()] = full.ravel()
     return out
 
 
-def unpack_codes(raw: np.ndarray, kind: str, J: int) -> np.ndarray:
+def unpack_codes(raw: np.ndarray, kind: str, J: int, layout: str = "tiled") -> np.ndarray:
     """layout bytes u8 [capacity * J] -> codes u8 [capacity][J]."""
     cap = raw.size // J
-    return raw[code_offsets(J, kind, cap).ravel()].reshape(cap, J)
+    return raw[code_offsets(J, kind, cap, layout).ravel()].reshape(cap, J)
 
 
 def n_groups(length: int, G: int) -> int:
@@ -40,8 +48,10 @@ def n_groups(length: int, G: int) -> int:
 class HostCache:
     """Numpy mirror of one tensor kind's cache buffers (contiguous or paged)."""
 
-    def __init__(self, kind, batch, hkv, J, max_len, G, page_size=0, block_table=None, n_pages=None):
+    def __init__(self, kind, batch, hkv, J, max_len, G, page_size=0, block_table=None, n_pages=None,
+                 layout="tiled"):
         self.kind, self.batch, self.hkv, self.J, self.max_len, self.G = kind, batch, hkv, J, max_len, G
+        self.layout = layout  # "tiled": the (sub_dim, 256) formats with fp16 side information and no rope table
         self.page = page_size
         self.bt = block_table
         self.ng = n_groups(max_len, G)
@@ -75,8 +85,8 @@ class HostCache:
     # logical views -------------------------------------------------------------------------
     def get_codes(self, b, h) -> np.ndarray:
         if not self.page:
-            return unpack_codes(self.codes[b, h], self.kind, self.J)
-        parts = [unpack_codes(self.codes[self.bt[b, p], h], self.kind, self.J)
+            return unpack_codes(self.codes[b, h], self.kind, self.J, self.layout)
+        parts = [unpack_codes(self.codes[self.bt[b, p], h], self.kind, self.J, self.layout)
                  for p in range(self.max_len // self.page)]
         return np.concatenate(parts, axis=0)
 
@@ -87,12 +97,12 @@ class HostCache:
 
     def _set_logical(self, b, h, codes, norms):
         if not self.page:
-            self.codes[b, h] = pack_codes(codes, self.kind, self.max_len)
+            self.codes[b, h] = pack_codes(codes, self.kind, self.max_len, self.layout)
             self.norms[b, h] = norms
             return
         for p in range(self.max_len // self.page):
             sl = slice(p * self.page, (p + 1) * self.page)
-            self.codes[self.bt[b, p], h] = pack_codes(codes[sl], self.kind, self.page)
+            self.codes[self.bt[b, p], h] = pack_codes(codes[sl], self.kind, self.page, self.layout)
             self.norms[self.bt[b, p], h] = norms[sl]
 
     def unit_dict(self, b, h, length) -> dict:
@@ -140,7 +150,7 @@ class HostCacheDQ(HostCache):
     ([0,64) codes, [64,80) four (min, step) fp16 pairs)."""
 
     def __init__(self, kind, batch, hkv, J, max_len, G, page_size=0, block_table=None, n_pages=None):
-        super().__init__(kind, batch, hkv, J, max_len, G, page_size, block_table, n_pages)
+        super().__init__(kind, batch, hkv, J, max_len, G, page_size, block_table, n_pages, layout="legacy")
         units = self.codes.shape[0]
         per_unit = (page_size or max_len) // 64
         self.norms = np.zeros((units, hkv, per_unit, 164), dtype=np.uint8)
@@ -182,11 +192,11 @@ class HostCacheDQ(HostCache):
             rec[blk, 160:164] = enc["b_par"][blk].astype(np.float16).view(np.uint8)
         self._set_records(b, h, rec)
         if not self.page:
-            self.codes[b, h] = pack_codes(logical_codes, self.kind, self.max_len)
+            self.codes[b, h] = pack_codes(logical_codes, self.kind, self.max_len, self.layout)
         else:
             for p in range(self.max_len // self.page):
                 self.codes[self.bt[b, p], h] = pack_codes(logical_codes[p * self.page:(p + 1) * self.page], self.kind,
-                                                          self.page)
+                                                          self.page, self.layout)
 
     def unit_dict(self, b, h, length) -> dict:
         """Effective float64 a, b, o (what the decoder reconstructs) plus the stored fields."""

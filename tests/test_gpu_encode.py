@@ -32,8 +32,9 @@ def run_gpu_encode(api, seed, batch, hkv, lens, sub, G, cb, page=0, per_seq=Fals
     shape = api.make_shape(sub, hkv, hkv, max_len, G, page, sign_format=sign, rope_table=rope_table)
     if caches is None:
         bt = synth.shuffled_page_table(seed, batch, max_len // page) if page else None
-        hk = helpers.HostCache("k", batch, hkv, J, max_len, G, page, bt)
-        hv = helpers.HostCache("v", batch, hkv, J, max_len, G, page, bt)
+        layout = "legacy" if (sign or rope_table is not None) else "tiled"
+        hk = helpers.HostCache("k", batch, hkv, J, max_len, G, page, bt, layout=layout)
+        hv = helpers.HostCache("v", batch, hkv, J, max_len, G, page, bt, layout=layout)
     else:
         hk, hv = caches
     dk, dv = hk.to_device(api, shape), hv.to_device(api, shape)

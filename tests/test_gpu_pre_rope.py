@@ -118,8 +118,8 @@ def _build(seed, hkv, lens, sub, G, cb, page, sign, f):
     J = (2 if sign else 1) * (128 // sub)
     max_len = ((max(max(lens), 1) + 255) // 256) * 256
     bt = synth.shuffled_page_table(seed, batch, max_len // page) if page else None
-    kc = helpers.HostCache("k", batch, hkv, J, max_len, G, page, bt)
-    vc = helpers.HostCache("v", batch, hkv, J, max_len, G, page, bt)
+    kc = helpers.HostCache("k", batch, hkv, J, max_len, G, page, bt, layout="legacy")
+    vc = helpers.HostCache("v", batch, hkv, J, max_len, G, page, bt, layout="legacy")
     for b in range(batch):
         for h in range(hkv):
             if lens[b]:
@@ -203,7 +203,7 @@ def test_pre_rope_generation_with_residual_and_flush(gpu_api, codebooks, rope):
     dec_ws = torch.zeros(api.nsn_workspace_bytes(shape, api.NSN_OP_DECODE, B), dtype=torch.uint8).cuda()
 
     def host_unit(dc, kind, b, h, length):
-        codes = helpers.unpack_codes(dc.codes[b, h].cpu().numpy(), kind, J)[:length]
+        codes = helpers.unpack_codes(dc.codes[b, h].cpu().numpy(), kind, J, "legacy")[:length]
         norms = dc.norms[b, h].cpu().numpy()[:length]
         return dict(codes=codes, a=norms[:, 0], b=norms[:, 1], o=dc.means[b, h].cpu().numpy()[:max(1, length // G)])
 

@@ -40,8 +40,8 @@ def _build(seed, hkv, lens, G, cb, page):
     batch = len(lens)
     max_len = ((max(max(lens), 1) + 255) // 256) * 256
     bt = synth.shuffled_page_table(seed, batch, max_len // page) if page else None
-    kc = helpers.HostCache("k", batch, hkv, J, max_len, G, page, bt)
-    vc = helpers.HostCache("v", batch, hkv, J, max_len, G, page, bt)
+    kc = helpers.HostCache("k", batch, hkv, J, max_len, G, page, bt, layout="legacy")
+    vc = helpers.HostCache("v", batch, hkv, J, max_len, G, page, bt, layout="legacy")
     for b in range(batch):
         for h in range(hkv):
             if lens[b]:
@@ -114,8 +114,8 @@ def test_sign_format_encode_then_decode_with_residual(gpu_api, magnitude_codeboo
         torch.tensor(rlens, dtype=torch.int32).cuda(), scale, 0)
     torch.cuda.synchronize()
     out = out.cpu().numpy().astype(np.float64)
-    hk = helpers.HostCache("k", B, Hkv, J, max_len, G)
-    hv = helpers.HostCache("v", B, Hkv, J, max_len, G)
+    hk = helpers.HostCache("k", B, Hkv, J, max_len, G, layout="legacy")
+    hv = helpers.HostCache("v", B, Hkv, J, max_len, G, layout="legacy")
     hk.from_device(kc)
     hv.from_device(vc)
     worst = 0.0

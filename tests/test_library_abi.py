@@ -33,20 +33,33 @@ def test_exports_every_declared_symbol(L):
         assert hasattr(L, n), n
 
 
-@pytest.mark.parametrize("J", [16, 32])
-def test_layout_offsets_match_header_formulas_and_are_bijections(L, J):
+@pytest.mark.parametrize("fmt", ["1bit", "2bit", "sign", "2bit-dq"])
+def test_layout_offsets_match_header_formulas_and_are_bijections(L, fmt):
     import ctypes as C
-    n = 128
+    n = 192
+    shape = {"1bit": api.make_shape(8, 4, 1, 256), "2bit": api.make_shape(4, 4, 1, 256),
+             "sign": api.make_shape(8, 4, 1, 256, sign_format=True),
+             "2bit-dq": api.make_shape(4, 4, 1, 256, side_bits=4)}[fmt]
+    J = api.code_bytes_per_token(shape)
+    layout = "tiled" if fmt in ("1bit", "2bit") else "legacy"
     for kind, fn in (("k", L.nsn_k_code_offset), ("v", L.nsn_v_code_offset)):
-        fn.restype = C.c_int64
-        fn.argtypes = [C.c_int, C.c_int64, C.c_int]
-        ref = helpers.code_offsets(J, kind, n)
-        got = np.array([[fn(J, t, j) for j in range(J)] for t in range(n)])
+        ref = helpers.code_offsets(J, kind, n, layout)
+        got = np.array([[fn(C.byref(shape), t, j) for j in range(J)] for t in range(n)])
         assert np.array_equal(ref, got)
         assert sorted(got.ravel().tolist()) == list(range(n * J))
-        # a V block holds J consecutive tokens of one sub-vector contiguously
-        if kind == "v":
+        assert fn(C.byref(shape), 0, J) == -1 and fn(C.byref(shape), -1, 0) == -1
+        if layout == "legacy" and kind == "v":
+            # a V block holds J consecutive tokens of one sub-vector contiguously
             assert np.array_equal(ref[:J, 3], 3 * J + np.arange(J))
+        if layout == "tiled":
+            # every 64-token block is self-contained, and inside it every lane owns one run of J bytes
+            assert ref[:64].max() == 64 * J - 1 and ref[64:128].min() == 64 * J
+            lane_of = ref[:64] // J
+            if kind == "k":   # lane = 16 * (32-channel quarter) + token % 16
+                assert np.array_equal(lane_of, 16 * (np.arange(J)[None, :] // (J // 4)) + (np.arange(64) % 16)[:, None])
+            else:             # lane = 16 * (token % 16 / 4) + 4 * (token % 4) + sub-vector % 4
+                tb = np.arange(64)[:, None]
+                assert np.array_equal(lane_of, 16 * (tb % 16 // 4) + 4 * (tb % 4) + np.arange(J)[None, :] % 4)
 
 
 def test_pack_unpack_roundtrip():
@@ -54,14 +67,15 @@ def test_pack_unpack_roundtrip():
     for J in (16, 32):
         codes = g.integers(0, 256, size=(200, J), dtype=np.uint8)
         for kind in "kv":
-            raw = helpers.pack_codes(codes, kind, 256)
-            assert np.array_equal(helpers.unpack_codes(raw, kind, J)[:200], codes)
+            for layout in ("tiled", "legacy"):
+                raw = helpers.pack_codes(codes, kind, 256, layout)
+                assert np.array_equal(helpers.unpack_codes(raw, kind, J, layout)[:200], codes)
 
 
 def test_shape_validation_and_error_text(L):
     good = api.make_shape(4, 32, 8, 8192, 64)
-    # 64 arrival counters (rounded up to 256 B) + one fp32 partial of 258 floats per (head, split)
-    assert api.nsn_workspace_bytes(good, api.NSN_OP_DECODE, 8, 0, 4) == 256 + 8 * 32 * 4 * 258 * 4
+    # 256 arrival counters (one per sequence and query head) + one fp32 partial of 258 floats per (head, split)
+    assert api.nsn_workspace_bytes(good, api.NSN_OP_DECODE, 8, 0, 4) == 8 * 32 * 4 + 8 * 32 * 4 * 258 * 4
     assert api.nsn_workspace_bytes(good, api.NSN_OP_ENCODE, 8, 8192) == 8 * 8 * 2 * 128 * 128 * 8
     assert api.nsn_max_groups(good) == 128
     assert api.nsn_max_groups(api.make_shape(8, 1, 1, 1024, 0)) == 1
