@@ -286,9 +286,16 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   // contiguous caches: the wave's first group is in bounds whatever the sequence length is (clamped into the
   // cache when the split lies beyond it: then it is never processed)
   if constexpr (!PAGED) load_group(min(t0 + (wave << 6), cap_tokens - 64), S0);
-  // residual (Sec. 3.2): wave w < 4 of the last split takes rows [16 w, 16 w + 16); a load instruction covers
-  // four consecutive rows (16 lanes x 16 bytes each); rows beyond the capacity are clamped and masked later
-  const bool res_wave = res.k != nullptr && split == n_splits - 1 && wave < 4;
+  const int len = seq_lens[b];
+  NSN_STAMP(1);
+  // Splits that lie wholly beyond this sequence's end have nothing to do and leave at once (a ragged batch
+  // is launched with the split count of its longest sequence); the others know how many of them there
+  // are.  A sequence without coded tokens keeps split 0 (it may still have residual rows).
+  const int n_live = len > 0 ? (len - 1) / per + 1 : 1;
+  if (split >= n_live) return;
+  // residual (Sec. 3.2): wave w < 4 of the last live split takes rows [16 w, 16 w + 16); a load instruction
+  // covers four consecutive rows (16 lanes x 16 bytes each); rows beyond the capacity are clamped and masked later
+  const bool res_wave = res.k != nullptr && split == n_live - 1 && wave < 4;
   uint4 rk[4], rv[4];
   int res_len = 0;
   if (res_wave) {
@@ -301,8 +308,6 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     }
     res_len = res.lens[b];
   }
-  const int len = seq_lens[b];
-  NSN_STAMP(1);
 
   // ---- prologue: codebook table, query operands --------------------------------------------------
   {
@@ -803,7 +808,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
 
   NSN_STAMP(15);
   // ---- d6: merge the splits; the last wave to arrive for this query head finishes it -------------
-  if (n_splits > 1) {
+  if (n_live > 1) {
     float* Ph = partial + ((int64_t)(b * g.n_q_heads + hq0 + hh) * n_splits) * kPartialStride;
     float* P = Ph + (int64_t)split * kPartialStride;
     auto st2 = [](float* p, float lo, float hi) {  // 8-byte device-scope store (p is 8-byte aligned)
@@ -821,7 +826,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     if (lane == 0) st2(P + 2 * kHeadDim, M, L);
     // The partials are written with device-scope stores (they go through to memory: no cache holds them
     // back), the wave waits until every one has been acknowledged, and only then counts itself in; the
-    // wave that reads n_splits - 1 reads the other splits' partials with device-scope loads (they do not hit
+    // wave that reads n_live - 1 reads the other splits' partials with device-scope loads (they do not hit
     // in a cache that could hold older bytes).  The agent-scope release / acquire fences that would say
     // the same in the memory model make the compiler write back and invalidate the whole L2 around
     // the counter update: measured 7 us + 4 us per launch on the 8 x 8192-token shape.
@@ -832,18 +837,18 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     if (lane == 0) old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     old = __builtin_amdgcn_readfirstlane(old);
     NSN_STAMP(16);
-    if (old != n_splits - 1) return;
+    if (old != n_live - 1) return;
     if (lane == 0) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
     // chunks of eight splits, every load of a chunk issued before its first use; running max across chunks
     constexpr int SF = 8;
     M = -INFINITY, L = 0.f, x0 = x1 = mm0 = mm1 = 0.f;
-    for (int s0 = 0; s0 < n_splits; s0 += SF) {
+    for (int s0 = 0; s0 < n_live; s0 += SF) {
       float2 pml[SF], pr[SF], pq[SF];
 #pragma unroll
       for (int s = 0; s < SF; ++s) {
         pml[s] = make_float2(-INFINITY, 0.f);
         pr[s] = pq[s] = make_float2(0.f, 0.f);
-        if (s0 + s < n_splits) {  // uniform
+        if (s0 + s < n_live) {  // uniform
           const float* ps = Ph + (s0 + s) * kPartialStride;
           pml[s] = ld2(ps + 2 * kHeadDim);
           pr[s] = ld2(ps + 2 * lane);
@@ -858,7 +863,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
         L *= corr, x0 *= corr, x1 *= corr, mm0 *= corr, mm1 *= corr;
 #pragma unroll
         for (int s = 0; s < SF; ++s) {
-          const float e = (s0 + s < n_splits) ? fast_exp2(pml[s].x - Mn) : 0.f;  // 2^-inf = 0 for empty splits
+          const float e = (s0 + s < n_live) ? fast_exp2(pml[s].x - Mn) : 0.f;
           L = fmaf(e, pml[s].y, L);
           x0 = fmaf(e, pr[s].x, x0), x1 = fmaf(e, pr[s].y, x1);
           mm0 = fmaf(e, pq[s].x, mm0), mm1 = fmaf(e, pq[s].y, mm1);
