@@ -304,6 +304,23 @@ int nsn_decode_attention_residual(const nsn_shape* shape, const void* codebook_d
                                   float softmax_scale, int n_splits, float* out, void* workspace,
                                   size_t workspace_bytes, void* stream);
 
+/*
+ * nsn_decode_attention for callers that cannot allocate or hand over device memory for scratch
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * operation and arguments, without a workspace.  The arrival counters and split partials live in a
+ * fixed 4 MiB array inside the library's device image (one copy per GPU, held until the process
+ * ends); the call allocates nothing and clears the counters it uses with a small kernel on `stream`.
+ *   - Needs batch * n_q_heads * n_splits * 1032 bytes + 4 bytes per (sequence, query head), rounded up
+ *     to 256: calls that need more than 4 MiB fail with NSN_ERR_WORKSPACE (use nsn_decode_attention).
+ *   - All calls on one GPU share the array: calls that overlap in time on one GPU (different streams,
+ *     different host threads) race; calls on one stream do not.
+ * Errors: as nsn_decode_attention, plus NSN_ERR_HIP if the array's address cannot be obtained.
+ */
+int nsn_decode_attention_noalloc(const nsn_shape* shape, const void* codebook_dev, const void* q_fp16,
+                                 const nsn_cache* k_cache, const nsn_cache* v_cache,
+                                 const int32_t* seq_lens_dev, int batch, int max_seq_len,
+                                 float softmax_scale, int n_splits, float* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

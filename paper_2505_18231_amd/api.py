@@ -80,6 +80,9 @@ def lib() -> C.CDLL:
             C.POINTER(nsn_shape), C.c_void_p, C.c_void_p, C.POINTER(nsn_cache), C.POINTER(nsn_cache), C.c_void_p,
             C.c_int, C.c_int, C.POINTER(nsn_residual), C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t,
             C.c_void_p]
+        L.nsn_decode_attention_noalloc.argtypes = [C.POINTER(nsn_shape), C.c_void_p, C.c_void_p,
+                                                   C.POINTER(nsn_cache), C.POINTER(nsn_cache), C.c_void_p, C.c_int,
+                                                   C.c_int, C.c_float, C.c_int, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -285,4 +288,19 @@ def nsn_decode_attention_residual(shape: nsn_shape, codebook: torch.Tensor, q: t
                                                C.byref(vc), seq_lens.data_ptr(), batch, max_seq_len,
                                                C.byref(res), float(softmax_scale), n_splits, out.data_ptr(),
                                                workspace.data_ptr(), workspace.numel(), _stream()))
+    return out
+
+
+def nsn_decode_attention_noalloc(shape: nsn_shape, codebook: torch.Tensor, q: torch.Tensor, k_cache: CodedCache,
+                                 v_cache: CodedCache, seq_lens: torch.Tensor, max_seq_len: int,
+                                 softmax_scale: float, n_splits: int = 0, out: torch.Tensor | None = None) -> torch.Tensor:
+    """nsn_decode_attention without a workspace: scratch is a fixed array inside the library (4 MiB per GPU)."""
+    assert q.is_cuda and q.dtype == torch.float16 and q.is_contiguous()
+    assert seq_lens.dtype == torch.int32 and codebook.dtype == torch.float16
+    batch, hq, d = q.shape
+    assert hq == shape.n_q_heads and d == HEAD_DIM and out is not None, "pass `out`: this entry point allocates nothing"
+    kc, vc = k_cache.c_struct(), v_cache.c_struct()
+    _check(lib().nsn_decode_attention_noalloc(C.byref(shape), codebook.data_ptr(), q.data_ptr(), C.byref(kc),
+                                              C.byref(vc), seq_lens.data_ptr(), batch, max_seq_len,
+                                              float(softmax_scale), n_splits, out.data_ptr(), _stream()))
     return out

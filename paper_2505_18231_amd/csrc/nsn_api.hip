@@ -1,6 +1,7 @@
 // extern "C" boundary of libnsn: argument validation and dispatch only.
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 
 #include "nsn_host.h"
 
@@ -68,6 +69,42 @@ static int check_cache(const nsn_shape* s, const nsn_cache* c, const char* name)
     return NSN_ERR_INVALID_ARG;
   }
   return NSN_OK;
+}
+
+// ---- scratch of nsn_decode_attention_noalloc ---------------------------------------------------
+// A fixed array in the library's device image takes the place of the caller's workspace (arrival
+// counters + split partials).  Every GPU that loads the library holds its own copy; the array's name is
+// only a host-side handle, its device address comes from hipGetSymbolAddress once per device.
+constexpr size_t kScratchBytes = 4u << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device (nullptr + error text on failure)
+static void* scratch_address() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    set_error("decode (noalloc): no current device, or device index beyond %d", kMaxDevices - 1);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      set_error("decode (noalloc): hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+// the arrival counters must start at zero (a fill kernel, not a memset node: the call may be captured)
+__global__ void scratch_clear_kernel(int* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
 }
 
 }  // namespace nsn
@@ -252,6 +289,37 @@ int nsn_decode_attention(const nsn_shape* shape, const void* codebook_dev, const
                          void* workspace, size_t workspace_bytes, void* stream) {
   return decode_common(shape, codebook_dev, q_fp16, k_cache, v_cache, seq_lens_dev, batch, max_seq_len, nullptr,
                        softmax_scale, n_splits, out, workspace, workspace_bytes, stream);
+}
+
+int nsn_decode_attention_noalloc(const nsn_shape* shape, const void* codebook_dev, const void* q_fp16,
+                                 const nsn_cache* k_cache, const nsn_cache* v_cache, const int32_t* seq_lens_dev,
+                                 int batch, int max_seq_len, float softmax_scale, int n_splits, float* out,
+                                 void* stream) {
+  int rc = check_shape(shape);
+  if (rc != NSN_OK) return rc;
+  if (batch <= 0 || n_splits < 0 || max_seq_len < 0) {
+    if (batch == 0) return NSN_OK;
+    set_error("decode (noalloc): negative size");
+    return NSN_ERR_INVALID_ARG;
+  }
+  const int splits = decode_pick_splits(*shape, batch, max_seq_len, n_splits);
+  const size_t need = decode_workspace_bytes(*shape, batch, splits);
+  if (need > kScratchBytes) {
+    set_error("decode (noalloc): this call needs %zu scratch bytes, the built-in scratch holds %zu "
+              "(batch * n_q_heads * n_splits * 1032 bytes + counters): use nsn_decode_attention with a workspace",
+              need, kScratchBytes);
+    return NSN_ERR_WORKSPACE;
+  }
+  void* ptr = scratch_address();
+  if (!ptr) return NSN_ERR_HIP;
+  const int n_cnt = (int)(decode_counter_bytes(*shape, batch) / sizeof(int));
+  scratch_clear_kernel<<<(n_cnt + 255) / 256, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<int*>(ptr), n_cnt);
+  if (hipGetLastError() != hipSuccess) {
+    set_error("decode (noalloc): launch failed");
+    return NSN_ERR_HIP;
+  }
+  return decode_common(shape, codebook_dev, q_fp16, k_cache, v_cache, seq_lens_dev, batch, max_seq_len, nullptr,
+                       softmax_scale, n_splits, out, ptr, kScratchBytes, stream);
 }
 
 int nsn_decode_attention_residual(const nsn_shape* shape, const void* codebook_dev, const void* q_fp16,

@@ -1353,6 +1353,7 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
 static size_t counter_bytes(const nsn_shape& s, int batch) {
   return (((size_t)batch * s.n_q_heads * sizeof(int)) + 255) & ~(size_t)255;
 }
+size_t decode_counter_bytes(const nsn_shape& s, int batch) { return counter_bytes(s, batch); }
 
 int decode_mfma_splits(const nsn_shape& s, int batch, int max_seq_len, int requested) {
   const int cap = max(1, min(64, (max_seq_len + 255) / 256));

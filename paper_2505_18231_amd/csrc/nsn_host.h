@@ -56,6 +56,7 @@ int decode_pick_splits(const nsn_shape& s, int batch, int max_seq_len, int reque
 bool decode_use_mfma(const nsn_shape& s);
 int decode_mfma_splits(const nsn_shape& s, int batch, int max_seq_len, int requested);
 size_t decode_mfma_workspace_bytes(const nsn_shape& s, int batch, int n_splits);
+size_t decode_counter_bytes(const nsn_shape& s, int batch);  // arrival counters at the head of the decode workspace
 int decode_tile_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
                        const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                        int n_splits, void* workspace, size_t counter_bytes, const nsn_residual* residual, float* out,
