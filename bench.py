@@ -34,16 +34,17 @@ if ROOT not in sys.path:
 PEAK_HBM_GBPS = 8000.0
 # HBM bytes per decode launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs kept under profiles/
 # (scaled by the same counters on a plain 256 MiB copy); only for the workload they were taken on.
-MEASURED_TRAFFIC_BYTES = {"C1": (38804 + 1322) * 1024}
+MEASURED_TRAFFIC = {}
+DECODE_KERNEL_NAME = "nsn::tile::dec_tile_kernel"
 
 
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    # 2000 warm-up steps (about 40 ms): the GPU takes that long under load to settle at its sustained clock;
-    # after 40 steps the same loop still runs 5 % slower
+    # (the GPU takes about 40 ms under load to settle at its sustained clock: --settle-ms of untimed launches
+    # come before the warm-up, so short warm-ups measure the same clock)
     p.add_argument("--steps", type=int, default=2000)
-    p.add_argument("--warmup", type=int, default=2000)
+    p.add_argument("--warmup", type=int, default=200)
     p.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4"])
     p.add_argument("--random-cache", action="store_true",
                    help="time decode attention only, on a cache filled with random codes and norms "
@@ -78,6 +79,10 @@ def parse():
     p.add_argument("--cpu-units", type=int, default=12, help="(sequence, kv-head) units the oracle is timed on")
     p.add_argument("--codebook-samples", type=int, default=1 << 20)
     p.add_argument("--codebook-iters", type=int, default=50)
+    p.add_argument("--eager", action="store_true",
+                   help="time the steps issued one by one from Python instead of one HIP graph of them")
+    p.add_argument("--settle-ms", type=float, default=60.0,
+                   help="untimed attention launches before the warm-up, so that the GPU has reached its sustained clock")
     p.add_argument("--copy-calibration", action="store_true",
                    help="also run three plain 256 MiB device copies (known traffic) for counter calibration")
     return p.parse_args()
@@ -172,7 +177,7 @@ def random_cache_decode(args, cfg) -> int:
                    "page_size": page, "group_size": G, "pre_rope_keys": bool(args.pre_rope),
                    "side_bits": args.side_bits, "cache_copies_in_rotation": n_copies, "step": "decode attention only"},
         "decode_us_per_step": round(us, 3), "bytes_per_step": step_bytes,
-        "roofline": {"bound": "hbm", "kernel": "nsn::dec_mfma_kernel (one launch per decode step)",
+        "roofline": {"bound": "hbm", "kernel": DECODE_KERNEL_NAME + " (one launch per decode step)",
                      "achieved": round(gbps, 2), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": None, "algorithmic_bytes": step_bytes},
     }), flush=True)
@@ -314,43 +319,91 @@ def main() -> int:
                 api.nsn_encode(shape, codebook, k_res_enc, v_res, full, res_lens[RES - 1], ck, cv,
                                freeze_means=(G == 0), workspace=enc_ws)
 
-    for i in range(args.warmup):
+    def attention_only(i: int):  # the step's attention launch alone (residual rows included, no encode)
+        ck, cv = copies[i % n_copies]
+        if args.policy == "append":
+            api.nsn_decode_attention(shape, codebook, q_dev, ck, cv, full1, L + 1, scale, args.n_splits, out=out,
+                                     workspace=dec_ws)
+        else:
+            api.nsn_decode_attention_residual(shape, codebook, q_dev, ck, cv, full, L, k_res, v_res,
+                                              res_lens[i % RES], scale, args.n_splits, out=out, workspace=dec_ws)
+
+    # ---- untimed: bring the GPU to its sustained clock (it takes ~40 ms under load), first calls of every
+    # kernel (their one-time attribute queries must not fall into a graph capture) -----------------------
+    for i in range(2 * RES):
         step(i)
+    t_settle = time.perf_counter()
+    settle_launches = 0
+    while time.perf_counter() - t_settle < args.settle_ms * 1e-3:
+        for i in range(256):
+            attention_only(i)
+        torch.cuda.synchronize()
+        settle_launches += 256
+
+    def capture(fn, first: int, count: int):
+        """`count` consecutive steps as ONE HIP graph: a replay issues them back to back with no host in between."""
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            for i in range(first, first + count):
+                fn(i)
+        return gr
+
+    use_graph = not args.eager
+    W, K = args.warmup, args.steps
+    if use_graph:
+        g_warm = capture(step, 0, W) if W > 0 else None
+        g_timed = capture(step, W, K)   # the step counter runs on from the warm-up
+        g_attn = capture(attention_only, W, K)
     torch.cuda.synchronize()
     setup_s = time.time() - t_setup
 
-    # ---- timed region: exactly K steps --------------------------------------------------------
+    # ---- timed region: W warm-up steps, then exactly K steps between two events -------------------
+    def run(gr, fn, first, count):
+        if use_graph:
+            gr.replay()
+        else:
+            for i in range(first, first + count):
+                fn(i)
+
+    if W > 0:
+        run(g_warm if use_graph else None, step, 0, W)
+    torch.cuda.synchronize()
+    ev0.record()
+    run(g_timed if use_graph else None, step, W, K)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_per_step = ev0.elapsed_time(ev1) / K
+    flushes = sum(1 for i in range(W, W + K) if i % RES == RES - 1) if args.policy == "residual" else 0
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # the same K steps issued one by one from Python (what a host loop without graphs pays)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev0.record()
-    for i in range(args.warmup, args.warmup + args.steps):  # the step counter runs on from the warm-up
+    for i in range(W, W + K):
         step(i)
     ev1.record()
     torch.cuda.synchronize()
-    flushes = sum(1 for i in range(args.warmup, args.warmup + args.steps) if i % RES == RES - 1)
-    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    ms_per_step = ev0.elapsed_time(ev1) / args.steps
-    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    wall_ms = (time.perf_counter() - t0) * 1e3 / K
+    eager_ms_per_step = ev0.elapsed_time(ev1) / K
 
-    # ---- decode attention alone (the dominant kernel), HIP events on the launch stream --------
-    for i in range(args.warmup):
-        step(i, with_encode=False)
+    # ---- the dominant kernel alone: the step's attention launch, K of them, HIP events on its stream ----
+    run(g_attn if use_graph else None, attention_only, W, K)   # once untimed
     torch.cuda.synchronize()
     ev0.record()
-    for i in range(args.steps):
-        step(i, with_encode=False)
+    run(g_attn if use_graph else None, attention_only, W, K)
     ev1.record()
     torch.cuda.synchronize()
-    dec_us = ev0.elapsed_time(ev1) / args.steps * 1e3
+    dec_us = ev0.elapsed_time(ev1) / K * 1e3
     achieved = step_bytes / (dec_us * 1e-6) / 1e9
-    # same loop on a single cache copy: working set resident in the last-level cache
+    # same kernel on a single cache copy: working set resident in the last-level cache
     ev0.record()
-    for i in range(args.steps):
+    for i in range(K):
         api.nsn_decode_attention(shape, codebook, q_dev, kc, vc, full, L, scale, args.n_splits, out=out,
                                  workspace=dec_ws)
     ev1.record()
     torch.cuda.synchronize()
-    dec_us_hot = ev0.elapsed_time(ev1) / args.steps * 1e3
+    dec_us_hot = ev0.elapsed_time(ev1) / K * 1e3
 
     if args.copy_calibration:  # known traffic: read 256 MiB + write 256 MiB per copy
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -359,13 +412,24 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    # HBM traffic per attention launch: rocprofv3 counters cannot be read from inside the process, so the
+    # figure is the one under profiles/ and is only attached to the option set it was measured on
+    default_options = (args.workload in MEASURED_TRAFFIC and args.n_splits == 0 and not sign and G == 0
+                       and not args.pre_rope and args.side_bits == 16 and args.policy == "residual")
+    traffic = MEASURED_TRAFFIC[args.workload] if default_options else None
+    # encoder (prefill): bound by the vector ALUs.  Peak = 256 CUs x 64 lanes x 2.4 GHz lane-operations per
+    # second (packed fp32 is disabled in this build); the best-two selection over 256 distances alone needs
+    # 3 lane-operations per distance, i.e. 3 x 8192 per token, kv head and tensor: counted as the algorithmic work
+    enc_lane_ops = encode_tokens_per_s * Hkv * 2 * (3 * (128 // sub) * 256)
+    peak_lane_ops = 256 * 64 * 2.4e9
+
     result = {
         "metric": "coded-KV decode attention: achieved HBM GB/s (coded bytes read per step / step time)",
         "value": round(value, 2),
         "unit": "GB/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": K,
+        "warmup": W,
         "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True,
         "scaling": "weak",
@@ -379,12 +443,16 @@ def main() -> int:
                    "codebook_bits": args.codebook_bits,
                    "group_size": G, "cache_copies_in_rotation": n_copies,
                    "residual_size": RES if args.policy == "residual" else 0,
-                   "residual_encodes_in_timed_region": flushes if args.policy == "residual" else 0,
+                   "residual_encodes_in_timed_region": flushes,
+                   "timed_region": ("one HIP graph of the K steps, replayed once between two events"
+                                    if use_graph else "K steps issued from Python between two events"),
+                   "untimed_clock_settle_launches": settle_launches,
                    "step": ("decode attention over the coded cache + fp16 residual; every 64th step encodes the "
                             "full residual (64 tokens per sequence)") if args.policy == "residual"
                    else "append-encode 1 token/sequence + decode attention"},
         "decode_us_per_step": round(dec_us, 3),
         "decode_us_per_step_cache_resident": round(dec_us_hot, 3),
+        "eager_ms_per_step": round(eager_ms_per_step, 6),
         "host_wall_ms_per_step": round(wall_ms, 6),
         "encode_tokens_per_s": round(encode_tokens_per_s, 1),
         "encode_ms_prefill": round(enc_ms, 4),
@@ -393,12 +461,21 @@ def main() -> int:
         "codebook_cosine_before_after_finetune": [cos_before, cos_after],
         "bytes_per_step": step_bytes,
         "setup_s": round(setup_s, 1),
-        "roofline": {"bound": "hbm", "kernel": "nsn::dec_mfma_kernel (one launch per decode step)",
+        "roofline": {"bound": "hbm", "kernel": DECODE_KERNEL_NAME + " (one launch per decode step)",
                      "achieved": round(achieved, 2), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": round(achieved / PEAK_HBM_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if args.n_splits == 0 else None,
+                     "traffic": traffic["bytes"] if traffic else None,
+                     "traffic_source": traffic["source"] if traffic else None,
                      "algorithmic_bytes": step_bytes},
+        "roofline_encode": {"bound": "alu", "kernel": "nsn::enc_quant_kernel (+ enc_stats_kernel, enc_means_kernel)",
+                            "achieved": round(enc_lane_ops / 1e12, 3), "peak": round(peak_lane_ops / 1e12, 2),
+                            "unit": "Tlane-op/s", "frac": round(enc_lane_ops / peak_lane_ops, 4),
+                            "algorithmic_lane_ops_per_token": Hkv * 2 * 3 * (128 // sub) * 256,
+                            "peak_derivation": "256 CUs x 64 lanes x 2.4 GHz, one fp32 operation per lane and clock"},
     }
+    if flushes == 0 and args.policy == "residual":
+        result["config"]["note"] = (f"the {K} timed steps contain no residual flush (one falls on every {RES}th "
+                                    "step): this line times attention steps only; run >= 64 steps to include the encoder")
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ------
     if not args.no_cpu_baseline:
@@ -422,11 +499,13 @@ def main() -> int:
             t_dec += time.perf_counter() - t0
             got = out_host[b, h * r:(h + 1) * r]
             worst = max(worst, float((np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)).max()))
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
         unit_bytes = step_bytes / (B * Hkv)
         result["cpu_baseline"] = {
-            "value": round(len(units) * unit_bytes / t_dec / 1e9, 5), "unit": "GB/s", "cores": threads,
-            "kind": "oracle",
+            "value": round(len(units) * unit_bytes / t_dec / 1e9, 5), "unit": "GB/s", "cores": cores,
+            "blas_threads": blas_threads, "kind": "oracle",
+            "note": "numpy oracle: most of its loops are single-threaded; `cores` = host cores available to it",
             "sample": f"{len(units)} of {B * Hkv} (sequence, kv-head) units of the same workload, "
                       f"decode {t_dec:.2f} s, encode {t_enc:.2f} s",
             "decode_us_per_step_extrapolated": round(t_dec / len(units) * B * Hkv * 1e6, 1),
