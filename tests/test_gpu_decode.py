@@ -112,3 +112,94 @@ def test_split_count_does_not_change_the_result(gpu_api, codebooks, monkeypatch,
         err = helpers.max_rel_err(o, outs[0])
         print(f"  split-count difference {err:.3e}", flush=True)
         assert err < tol
+
+
+def _encoded_case(seed, hq, hkv, L, sub, G, cb, k_fn, v_fn):
+    """One sequence whose keys / values come from k_fn(h), v_fn(h) (fp16 [L][128]), oracle-encoded."""
+    J = 128 // sub
+    max_len = ((L + 255) // 256) * 256
+    kc = helpers.HostCache("k", 1, hkv, J, max_len, G)
+    vc = helpers.HostCache("v", 1, hkv, J, max_len, G)
+    for h in range(hkv):
+        kc.put_unit(0, h, O.encode(k_fn(h), cb, G))
+        vc.put_unit(0, h, O.encode(v_fn(h), cb, G))
+    return kc, vc, synth.make_q(seed, 1, hq), max_len
+
+
+@pytest.mark.parametrize("impl", ["mfma", "lut"])
+@pytest.mark.parametrize("sub", [4, 8])
+@pytest.mark.parametrize("log2_mul", [-12, 0, 9])
+def test_value_scale_does_not_change_the_accuracy(gpu_api, codebooks, monkeypatch, impl, sub, log2_mul):
+    """The first Normalize stores every token norm on its own (Sec. 3.2), so attention over the coded
+    cache (App. B) is as accurate for values of size 2^-12 or 2^9 as for values of size 1."""
+    monkeypatch.setenv("NSN_DECODE_IMPL", impl)
+    cb, scale, L, seed = codebooks[sub], 1.0 / math.sqrt(128), 1500, 60 + sub
+    mul = np.float32(2.0 ** log2_mul)
+    kc, vc, q, max_len = _encoded_case(
+        seed, 8, 2, L, sub, 64, cb, lambda h: synth.make_k(seed, 0, h, L),
+        lambda h: (synth.make_v(seed, 0, h, L).astype(np.float32) * mul).astype(np.float16))
+    ref = oracle_out(kc, vc, q, [L], 8, 2, cb, 64, scale)
+    out = gpu_out(gpu_api, kc, vc, q, [L], 8, 2, sub, 64, cb, max_len, scale, 0, 3)
+    err = helpers.max_rel_err(out, ref)
+    print(f"  impl={impl} sub={sub} V x 2^{log2_mul}: max rel err {err:.3e}, |ref| max {np.abs(ref).max():.3e}",
+          flush=True)
+    assert np.isfinite(out).all()
+    assert err < TOL, err
+
+
+@pytest.mark.parametrize("impl", ["mfma", "lut"])
+@pytest.mark.parametrize("sub", [4, 8])
+def test_sink_token_with_twice_the_norm(gpu_api, codebooks, monkeypatch, impl, sub):
+    """Token 0 of the sequence is an outlier-norm ("sink") token: its key and its value are twice as
+    long as they were drawn (Sec. 3.2 keeps such tokens apart through the stored norm)."""
+    monkeypatch.setenv("NSN_DECODE_IMPL", impl)
+    cb, scale, L, seed = codebooks[sub], 1.0 / math.sqrt(128), 1100, 80 + sub
+
+    def doubled(x):
+        x = x.copy()
+        x[0] = (x[0].astype(np.float32) * 2).astype(np.float16)
+        return x
+    for G in (0, 64):
+        kc, vc, q, max_len = _encoded_case(seed, 4, 1, L, sub, G, cb,
+                                           lambda h: doubled(synth.make_k(seed, 0, h, L)),
+                                           lambda h: doubled(synth.make_v(seed, 0, h, L)))
+        ref = oracle_out(kc, vc, q, [L], 4, 1, cb, G, scale)
+        out = gpu_out(gpu_api, kc, vc, q, [L], 4, 1, sub, G, cb, max_len, scale, 0, 2)
+        err = helpers.max_rel_err(out, ref)
+        print(f"  impl={impl} sub={sub} G={G}: max rel err {err:.3e}", flush=True)
+        assert err < TOL, err
+
+
+@pytest.mark.parametrize("impl", ["mfma", "lut"])
+@pytest.mark.parametrize("where", [0, 70001, 102399])
+def test_one_dominant_token_among_many_low_score_tokens(gpu_api, codebooks, monkeypatch, impl, where):
+    """102400 tokens whose scores are all near zero, and one token whose key points along the first
+    query head (score about +17 after scaling): that head's softmax is almost one-hot, the running
+    maximum jumps once, and the result must still be within the bar.  The cache is 2048 oracle-encoded
+    tokens repeated 50 times (one Shift group, so repeated tokens encode identically)."""
+    monkeypatch.setenv("NSN_DECODE_IMPL", impl)
+    sub, hq, L0, reps, seed = 4, 4, 2048, 50, 97
+    cb, scale, J = codebooks[sub], 1.0 / math.sqrt(128), 32
+    L = L0 * reps
+    q = synth.make_q(seed, 1, hq)
+    k = (synth.make_k(seed, 0, 0, L0).astype(np.float32) * np.float32(0.05)).astype(np.float16)
+    v = synth.make_v(seed, 0, 0, L0)
+    ek, ev = O.encode(k, cb, 0), O.encode(v, cb, 0)
+    tiled_k = dict(codes=np.tile(ek["codes"], (reps, 1)), a=np.tile(ek["a"], reps), b=np.tile(ek["b"], reps), o=ek["o"])
+    tiled_v = dict(codes=np.tile(ev["codes"], (reps, 1)), a=np.tile(ev["a"], reps), b=np.tile(ev["b"], reps), o=ev["o"])
+    star = (q[0, 0].astype(np.float32) * np.float32(1.5)).astype(np.float16)[None, :]
+    es = O.encode(star, cb, 0, start=where, frozen_o=ek["o"])
+    for key in ("codes", "a", "b"):
+        tiled_k[key][where] = es[key][0]
+    kc = helpers.HostCache("k", 1, 1, J, L, 0)
+    vc = helpers.HostCache("v", 1, 1, J, L, 0)
+    kc.put_unit(0, 0, tiled_k)
+    vc.put_unit(0, 0, tiled_v)
+    ref = oracle_out(kc, vc, q, [L], hq, 1, cb, 0, scale)
+    sc = O.lut_scores(q[0].astype(np.float64), kc.unit_dict(0, 0, L), cb, scale, 0)[0]
+    weight = 1.0 / np.exp(sc - sc[where]).sum()
+    assert weight > 0.9, weight
+    out = gpu_out(gpu_api, kc, vc, q, [L], hq, 1, sub, 0, cb, L, scale, 0, 0)
+    err = helpers.max_rel_err(out, ref)
+    print(f"  impl={impl} dominant token at {where} (weight {weight:.4f}): max rel err {err:.3e}", flush=True)
+    assert err < TOL, err

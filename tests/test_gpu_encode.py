@@ -157,6 +157,10 @@ def test_duplicate_codewords_take_the_lowest_index(gpu_api, codebooks, monkeypat
     hits = 0
     for x, hc in ((k, hk), (v, hv)):
         got = hc.unit_dict(0, 0, lens[0])
+        # stage A: the stored first-Normalize scale and the group means are the oracle's own, bit for bit
+        b_ref, o_ref = O.shift_stats(x[0, 0, :lens[0]], 64)
+        assert np.array_equal(b_ref.view(np.uint16), got["b"].view(np.uint16)), "first-Normalize scale"
+        assert np.array_equal(o_ref.view(np.uint16), got["o"].view(np.uint16)), "means"
         ref = O.encode(x[0, 0, :lens[0]], cb, 64, given_b=got["b"], given_o=got["o"], return_debug=True)
         same = ref["codes"] == got["codes"]
         exact_tie = ref["second"] == ref["best"]

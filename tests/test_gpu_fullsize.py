@@ -1,6 +1,7 @@
 """Full-size GPU parity in the launch configuration bench.py times (Llama-3-8B shape, 2-bit,
 batch 8 x 8192 tokens, 32 query heads over 8 kv heads, one Shift group per sequence, automatic
-split count), plus the long-context 1-bit shape (131072 tokens, batch 1).
+split count), plus the long-context 1-bit shape (131072 tokens, batch 1) and the large-batch
+multi-head shape (64 sequences x 32768 tokens, 32 heads).
 
 The GPU encodes and decodes the whole batch; the oracle re-computes a sample of (sequence, kv-head)
 units: the encoder's two-stage check on those units, and decode attention on the very cache bytes
@@ -29,7 +30,7 @@ def check_unit_sampled(x16, got, cb, n_tokens, seed):
     return check_unit(x16[idx], part, cb, 0, frozen=got["o"][:1])
 
 
-def _run(api, cfg_name, cb, sample_units, G=0, token_sample=None, batch=None):
+def _run(api, cfg_name, cb, sample_units, G=0, token_sample=None, batch=None, device_fill=False):
     import torch
     cfg = synth.CONFIGS[cfg_name]
     B, Hq, Hkv, L, sub, seed = (batch or cfg["batch"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["length"],
@@ -43,20 +44,39 @@ def _run(api, cfg_name, cb, sample_units, G=0, token_sample=None, batch=None):
     cbd = torch.from_numpy(cb.astype(np.float16)).cuda()
     zeros = torch.zeros(B, dtype=torch.int32).cuda()
     full = torch.full((B,), L, dtype=torch.int32).cuda()
-    # encode unit by unit batches of heads to bound host memory: one sequence at a time
+    # encode one sequence at a time (bounds host and device staging memory)
     k_units, v_units = {}, {}
+    gen = torch.Generator(device="cuda").manual_seed(seed)
     for b in range(B):
-        k = np.empty((1, Hkv, L, 128), dtype=np.float16)
-        v = np.empty_like(k)
-        for h in range(Hkv):
-            k[0, h] = synth.make_k(seed, b, h, L, per_seq=cfg.get("per_seq", False))
-            v[0, h] = synth.make_v(seed, b, h, L)
-            if (b, h) in sample_units:
-                k_units[(b, h)], v_units[(b, h)] = k[0, h].copy(), v[0, h].copy()
+        if device_fill:
+            # units the oracle does not re-compute are drawn on the device (same recipe: per-channel scale
+            # and bias for keys, N(0,1) values); the sampled units below come from the host generator
+            st = [synth.channel_stats(seed, b, h, per_seq=cfg.get("per_seq", False)) for h in range(Hkv)]
+            sc = torch.tensor(np.stack([s_[0] for s_ in st]), dtype=torch.float32, device="cuda")[:, None, :]
+            bi = torch.tensor(np.stack([s_[1] for s_ in st]), dtype=torch.float32, device="cuda")[:, None, :]
+            kd_ = (torch.randn((Hkv, L, 128), generator=gen, device="cuda") * sc + bi).half()[None]
+            vd_ = torch.randn((Hkv, L, 128), generator=gen, device="cuda").half()[None]
+            for h in range(Hkv):
+                if (b, h) in sample_units:
+                    k_units[(b, h)] = synth.make_k(seed, b, h, L, per_seq=cfg.get("per_seq", False))
+                    v_units[(b, h)] = synth.make_v(seed, b, h, L)
+                    kd_[0, h] = torch.from_numpy(k_units[(b, h)]).cuda()
+                    vd_[0, h] = torch.from_numpy(v_units[(b, h)]).cuda()
+        else:
+            k = np.empty((1, Hkv, L, 128), dtype=np.float16)
+            v = np.empty_like(k)
+            for h in range(Hkv):
+                k[0, h] = synth.make_k(seed, b, h, L, per_seq=cfg.get("per_seq", False))
+                v[0, h] = synth.make_v(seed, b, h, L)
+                if (b, h) in sample_units:
+                    k_units[(b, h)], v_units[(b, h)] = k[0, h].copy(), v[0, h].copy()
+            kd_, vd_ = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
         sub_k = api.CodedCache(kc.codes[b:b + 1], kc.norms[b:b + 1], kc.means[b:b + 1], None)
         sub_v = api.CodedCache(vc.codes[b:b + 1], vc.norms[b:b + 1], vc.means[b:b + 1], None)
-        api.nsn_encode(shape, cbd, torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), zeros[:1], full[:1],
-                       sub_k, sub_v)
+        api.nsn_encode(shape, cbd, kd_, vd_, zeros[:1], full[:1], sub_k, sub_v)
+        if b % 8 == 7:
+            torch.cuda.synchronize()
+            print(f"  encoded sequences 0..{b}", flush=True)
     q = synth.make_q(seed, B, Hq)
     out = api.nsn_decode_attention(shape, cbd, torch.from_numpy(q).cuda(), kc, vc, full, L, scale, 0)
     torch.cuda.synchronize()
@@ -91,10 +111,12 @@ def test_long_context_1bit_full_shape(gpu_api, codebooks):
     _run(gpu_api, "C2", codebooks[8], [(0, 2)], token_sample=4096)
 
 
-def test_mha_large_batch_shape_two_sequences(gpu_api, codebooks):
-    # Llama-2-7B shape (32 kv heads = 32 query heads, 32768 tokens, 2-bit, per-sequence channel
-    # biases); two of the 64 sequences, so that the host-side generation stays small
-    _run(gpu_api, "C3", codebooks[4], [(0, 0), (1, 31)], token_sample=4096, batch=2)
+def test_mha_large_batch_full_shape(gpu_api, codebooks):
+    # Llama-2-7B shape (32 kv heads = 32 query heads, 32768 tokens, 2-bit, per-sequence channel biases),
+    # all 64 sequences in one decode launch; the oracle re-computes five (sequence, head) units, the
+    # last sequence's last head among them
+    _run(gpu_api, "C3", codebooks[4], [(0, 0), (1, 31), (31, 7), (40, 16), (63, 31)], token_sample=2048,
+         device_fill=True)
 
 
 def test_llama3_8b_shape_in_the_papers_own_configuration(gpu_api):

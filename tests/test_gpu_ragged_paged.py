@@ -1,8 +1,8 @@
 """Ragged prefill + paged layout + decode steps that append one token per sequence per step
 (Mistral-7B shape: 32 query heads over 8 kv heads; lengths uniform in [512, 16384]; 256-token pages
 in shuffled physical order; Shift mean over each sequence's prefill, frozen for appended tokens).
-Runs at 1-bit and 2-bit.  The batch is the first 8 sequences of the seeded 32-sequence length draw
-(the oracle re-computes sampled (sequence, head) units)."""
+Runs at 1-bit and 2-bit over the whole seeded 32-sequence batch; the oracle re-computes sampled
+(sequence, head) units: the longest sequence, the shortest one and the last one."""
 import math
 
 import numpy as np
@@ -22,7 +22,7 @@ def test_ragged_paged_prefill_then_append_steps(gpu_api, codebooks, sub):
     api = gpu_api
     cfg = synth.CONFIGS["C4"]
     cb = codebooks[sub]
-    B, Hq, Hkv, page, steps, seed = 8, cfg["n_q_heads"], cfg["n_kv_heads"], cfg["page_size"], cfg["append_steps"], cfg["seed"]
+    B, Hq, Hkv, page, steps, seed = cfg["batch"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["page_size"], cfg["append_steps"], cfg["seed"]
     r = Hq // Hkv
     J = 128 // sub
     lens = synth.ragged_lengths(seed, cfg["batch"], cfg["len_lo"], cfg["len_hi"])[:B].tolist()
@@ -36,7 +36,7 @@ def test_ragged_paged_prefill_then_append_steps(gpu_api, codebooks, sub):
     vc = api.alloc_cache(shape, B, block_table=btd)
     cbd = torch.from_numpy(cb.astype(np.float16)).cuda()
     scale = 1.0 / math.sqrt(128)
-    sample = [(0, 0), (B - 1, Hkv - 1)]
+    sample = sorted({(int(np.argmax(lens)), 0), (int(np.argmin(lens)), Hkv - 1), (B - 1, Hkv - 1)})
 
     # ragged prefill
     max_new = max(lens)
