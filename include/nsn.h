@@ -177,6 +177,21 @@ int nsn_max_groups(const nsn_shape* shape);
 /* Text of the calling thread's most recent error ("" if none). Never NULL. */
 const char* nsn_last_error(void);
 
+/* Kernel variants.  Each operation has a default kernel and one alternative that computes the same
+ * result another way; the alternative exists for cross-checks and measurements.
+ *   NSN_OP_ENCODE  NSN_VARIANT_DEFAULT  nearest-codeword distances (Eq. 1) contracted on the matrix cores
+ *                  NSN_VARIANT_ALT      the same distances by an fp32 vector scan (index-only and
+ *                                       sign + index formats without rope_table)
+ *   NSN_OP_DECODE  NSN_VARIANT_DEFAULT  matrix-core attention kernels (every format)
+ *                  NSN_VARIANT_ALT      App. B as written: a query x codebook score table, fp32 throughout
+ *                                       (index-only formats with fp16 side information, no rope_table, no
+ *                                       residual; other calls fail with NSN_ERR_UNSUPPORTED)
+ * The choice is process-wide and applies to calls made after this one returns.  Its initial value is
+ * taken from the environment, once, at the library's first use: NSN_ENCODE_IMPL=valu and
+ * NSN_DECODE_IMPL=lut select the alternatives.  Returns the previous variant, or NSN_ERR_INVALID_ARG. */
+enum { NSN_VARIANT_DEFAULT = 0, NSN_VARIANT_ALT = 1 };
+int nsn_select_variant(int op, int variant);
+
 /*
  * Workspace (device bytes) an operation needs.
  *   NSN_OP_ENCODE   : n = max_new (token stride of the inputs), n_splits ignored

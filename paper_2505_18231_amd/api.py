@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libnsn.so")
 NSN_OK = 0
 NSN_ERR_INVALID_ARG, NSN_ERR_UNSUPPORTED, NSN_ERR_WORKSPACE, NSN_ERR_HIP = -1, -2, -3, -4
 NSN_OP_ENCODE, NSN_OP_DECODE, NSN_OP_CODEBOOK = 0, 1, 2
+NSN_VARIANT_DEFAULT, NSN_VARIANT_ALT = 0, 1
 HEAD_DIM, N_CODES = 128, 256
 
 
@@ -58,6 +59,7 @@ def lib() -> C.CDLL:
         L.nsn_workspace_bytes.restype = C.c_size_t
         L.nsn_workspace_bytes.argtypes = [C.POINTER(nsn_shape), C.c_int, C.c_int, C.c_int64, C.c_int]
         L.nsn_max_groups.argtypes = [C.POINTER(nsn_shape)]
+        L.nsn_select_variant.argtypes = [C.c_int, C.c_int]
         for fn in (L.nsn_k_code_offset, L.nsn_v_code_offset):
             fn.restype = C.c_int64
             fn.argtypes = [C.POINTER(nsn_shape), C.c_int64, C.c_int]
@@ -135,6 +137,13 @@ def code_bytes_per_token(shape: nsn_shape) -> int:
 
 def nsn_max_groups(shape: nsn_shape) -> int:
     return lib().nsn_max_groups(C.byref(shape))
+
+
+def nsn_select_variant(op: int, variant: int) -> int:
+    """Process-wide kernel variant of NSN_OP_ENCODE / NSN_OP_DECODE; returns the previous one."""
+    prev = lib().nsn_select_variant(op, variant)
+    _check(min(prev, 0))
+    return prev
 
 
 def nsn_workspace_bytes(shape: nsn_shape, op: int, batch: int, n: int = 0, n_splits: int = 0) -> int:

@@ -1,6 +1,8 @@
 // extern "C" boundary of libnsn: argument validation and dispatch only.
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <mutex>
 
 #include "nsn_host.h"
@@ -15,6 +17,22 @@ void set_error(const char* fmt, ...) {
   vsnprintf(g_err, sizeof(g_err), fmt, ap);
   va_end(ap);
 }
+
+// kernel variant per operation (encode, decode); the environment gives the initial value, once
+static std::atomic<int>* variants() {
+  static std::atomic<int> v[2];
+  static const bool init = [] {
+    const char* e = getenv("NSN_ENCODE_IMPL");
+    const char* d = getenv("NSN_DECODE_IMPL");
+    v[NSN_OP_ENCODE].store(e && e[0] == 'v' ? NSN_VARIANT_ALT : NSN_VARIANT_DEFAULT);
+    v[NSN_OP_DECODE].store(d && d[0] == 'l' ? NSN_VARIANT_ALT : NSN_VARIANT_DEFAULT);
+    return true;
+  }();
+  (void)init;
+  return v;
+}
+
+int selected_variant(int op) { return variants()[op].load(std::memory_order_relaxed); }
 
 static int check_shape(const nsn_shape* s) {
   if (!s) {
@@ -130,6 +148,14 @@ int nsn_max_groups(const nsn_shape* shape) {
 }
 
 const char* nsn_last_error(void) { return g_err; }
+
+int nsn_select_variant(int op, int variant) {
+  if ((op != NSN_OP_ENCODE && op != NSN_OP_DECODE) || (variant != NSN_VARIANT_DEFAULT && variant != NSN_VARIANT_ALT)) {
+    set_error("select_variant: op must be NSN_OP_ENCODE or NSN_OP_DECODE, variant NSN_VARIANT_DEFAULT or NSN_VARIANT_ALT");
+    return NSN_ERR_INVALID_ARG;
+  }
+  return variants()[op].exchange(variant);
+}
 
 size_t nsn_rope_table_bytes(int max_len) {
   return (max_len > 0 && max_len % 64 == 0) ? rope_table_bytes(max_len) : 0;
@@ -263,12 +289,12 @@ static int decode_common(const nsn_shape* shape, const void* codebook_dev, const
       return NSN_ERR_INVALID_ARG;
     }
     if (!decode_use_mfma(*shape)) {
-      set_error("decode: the lookup-table kernel (NSN_DECODE_IMPL=lut) has no residual form");
+      set_error("decode: the lookup-table kernel (NSN_VARIANT_ALT) has no residual form");
       return NSN_ERR_UNSUPPORTED;
     }
   }
   if ((shape->rope_table || shape->side_bits == 4) && !decode_use_mfma(*shape)) {
-    set_error("decode: the lookup-table kernel (NSN_DECODE_IMPL=lut) handles neither rope_table nor side_bits = 4");
+    set_error("decode: the lookup-table kernel (NSN_VARIANT_ALT) handles neither rope_table nor side_bits = 4");
     return NSN_ERR_UNSUPPORTED;
   }
   if (batch == 0) return NSN_OK;

@@ -256,9 +256,8 @@ __global__ __launch_bounds__(128) void dec_merge_kernel(int n_q_heads, int n_spl
 // ---------------------------------------------------------------------------------------
 bool decode_use_mfma(const nsn_shape& s) {
   if (s.n_codes == kSignCodes) return true;   // the sign + index format exists in the matrix-core kernel only
-  const char* e = getenv("NSN_DECODE_IMPL");  // "lut" forces the lookup-table kernel
-  if (e && e[0] == 'l') return false;
-  return true;  // up to 8 query heads per kv head (checked with the shape): one launch per four heads
+  // up to 8 query heads per kv head (checked with the shape): one launch per four heads
+  return selected_variant(NSN_OP_DECODE) != NSN_VARIANT_ALT;  // the alternative is the lookup-table kernel
 }
 
 int decode_pick_splits(const nsn_shape& s, int batch, int max_seq_len, int requested) {
@@ -277,12 +276,12 @@ size_t decode_workspace_bytes(const nsn_shape& s, int batch, int n_splits) {
 int decode_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,
                   const nsn_cache& vc, const int32_t* seq_lens, int batch, int max_seq_len, float scale,
                   int n_splits, const nsn_residual* residual, float* out, void* workspace, hipStream_t stream) {
-  if (decode_use_mfma(s))
-    return decode_mfma_launch(s, codebook, q, kc, vc, seq_lens, batch, max_seq_len, scale, n_splits, workspace,
-                              residual, out, stream) == NSN_OK && hipGetLastError() == hipSuccess
-               ? NSN_OK
-               : NSN_ERR_HIP;
-  if (residual) return NSN_ERR_UNSUPPORTED;  // the lookup-table kernel (forced by NSN_DECODE_IMPL) reads coded tokens only
+  if (decode_use_mfma(s)) {
+    const int rc = decode_mfma_launch(s, codebook, q, kc, vc, seq_lens, batch, max_seq_len, scale, n_splits,
+                                      workspace, residual, out, stream);
+    return rc != NSN_OK ? rc : hipGetLastError() == hipSuccess ? NSN_OK : NSN_ERR_HIP;
+  }
+  if (residual) return NSN_ERR_UNSUPPORTED;  // the lookup-table kernel reads coded tokens only
   const Geometry g = make_geometry(s);
   const CacheView kv = make_view(kc), vv = make_view(vc);
   float* partial = static_cast<float*>(workspace);

@@ -145,19 +145,6 @@ __device__ __forceinline__ void quad_transpose(float (&x)[4], int lane) {
   }
 }
 
-#ifdef NSN_DECODE_TIMING
-__device__ long long g_dec_timing[48];
-#define NSN_TSTAMP(slot)                                                                        \
-  do {                                                                                          \
-    if (blockIdx.x == 1 && blockIdx.y == 3 && blockIdx.z == 2 && (threadIdx.x & 63) == 0)       \
-      g_dec_timing[(threadIdx.x >> 6) == 0 ? (slot) : (threadIdx.x >> 6) == 7 ? 16 + (slot) : 47] = clock64(); \
-  } while (0)
-#else
-#define NSN_TSTAMP(slot) \
-  do {                   \
-  } while (0)
-#endif
-
 // LDS plan (dynamic, starts at LDS address 0):
 //   [0, 64 KiB)        codebook table: entry (code c, copy p) at c * 256 + p * (2 * SUB) bytes,
 //                      32 copies of 8 B (SUB = 4) or 16 copies of 16 B (SUB = 8);
@@ -405,7 +392,6 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     in.c23 = reinterpret_cast<const float4*>(rec)[(i0 >> 1) + 1];
   };
 
-  NSN_TSTAMP(0);
   // ---- loads that do not depend on the sequence length go out first ------------------------
   typedef typename std::conditional<SUB == 4, uint2, uint4>::type cw_t;
   cw_t cw_reg = {};
@@ -467,10 +453,6 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     for (int u = 0; u < 16; ++u) orow[u] = (lane < n_tab) ? rp[u] : make_uint4(0u, 0u, 0u, 0u);
   }
   const int len = seq_lens[b];  // scalar load in flight; first used after the prologue
-#ifdef NSN_DECODE_TIMING
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  NSN_TSTAMP(13);
-#endif
 
   // ---- prologue: codebook table, rotated query (independent of the sequence length) ----------
   if (tid < kCodes) reinterpret_cast<cw_t*>(sm_stage)[tid] = cw_reg;
@@ -491,7 +473,6 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     }
   }
   __syncthreads();
-  NSN_TSTAMP(12);
   const float qscale = (float)kInvSqrtD * scale_log2e;
   for (int hh = wave; hh < 4; hh += NW) {  // d1: one wave rotates one head, butterflies across lanes
     float x0 = sm_q_orig[hh][2 * lane], x1 = sm_q_orig[hh][2 * lane + 1];
@@ -602,7 +583,6 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     }
   }
   __syncthreads();
-  NSN_TSTAMP(1);
   const int t1 = min(len, t0 + per);
   const int n_grp = (main_wave && t1 > t0) ? (t1 - t0 + 63) >> 6 : 0;  // the residual wave owns no coded group
   if (!spec && wave < n_grp) load_group(wave, cur);
@@ -863,11 +843,9 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     if (n_grp > wave) rope_compute(rin);
   }
 
-  NSN_TSTAMP(2);
   // ---- main loop: this wave's 64-token groups, next group's loads in flight ------------------
   int it = 0;  // this wave's iteration count
   for (int gi = wave; gi < n_grp; gi += NW, ++it) {
-    NSN_TSTAMP(3 + (gi / NW < 6 ? gi / NW : 6));
     const int tg = t0 + (gi << 6);  // first token of the group (multiple of 64)
     const bool valid = (tg + lane) < t1;
     const bool has_next = gi + NW < n_grp;  // wave-uniform
@@ -986,7 +964,6 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       }
     }
   }
-  NSN_TSTAMP(10);
 
   // ---- residual (Sec. 3.2): the most recent tokens are still fp16 and join the same softmax ---
   // The extra wave of the last split treats them as one more 64-token group: the fp16 key row of
@@ -1142,9 +1119,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   // ---- epilogue: wave results -> LDS (reusing the table), merge the waves -------------------
 #pragma unroll
   for (int i = 0; i < R; ++i) l_run[i] = wave_sum_u(l_run[i]);
-  NSN_TSTAMP(7);
   __syncthreads();  // every wave is done gathering from the table
-  NSN_TSTAMP(8);
   float* racc = reinterpret_cast<float*>(sm_table);  // [NW][NPART][4][128]; the tail follows it
   if (main_wave) {  // the residual wave has no rotated-domain sum
 #pragma unroll
@@ -1160,9 +1135,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       sm_wave_m[wave][i] = m_run[i];
       sm_wave_l[wave][i] = l_run[i];
     }
-  NSN_TSTAMP(9);
   __syncthreads();
-  NSN_TSTAMP(14);
   float* P = partial + ((int64_t)(b * g.n_q_heads + hq0) * n_splits + split) * kPartialStrideM;
   for (int i = tid; i < r * kHeadDim; i += NT) {
     const int hh = i >> 7, c = i & 127;
@@ -1200,7 +1173,6 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       st_agent(Ph + 2 * kHeadDim + 1, L);
     }
   }
-  NSN_TSTAMP(11);
 
   // ---- d6: the last workgroup of this (sequence, kv head) merges the splits -----------------
   // The partials are published with device-scope (write-through) stores and read back with
@@ -1309,12 +1281,6 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   *reinterpret_cast<float2*>(out + (int64_t)(b * g.n_q_heads + hq0 + hh) * kHeadDim + 2 * lane) = o2;
 }
 
-#ifdef NSN_DECODE_TIMING
-extern "C" int nsn_debug_decode_timing(long long* host48) {
-  return hipMemcpyFromSymbol(host48, HIP_SYMBOL(g_dec_timing), sizeof(long long) * 48) == hipSuccess ? 0 : -1;
-}
-#endif
-
 // ---------------------------------------------------------------------------------------
 template <int SUB, int NW, int R, bool SGN = false, bool ROPE = false, bool DQ = false>
 static int launch_one(const Geometry& g, const void* codebook, const void* q, const CacheView& kv,
@@ -1324,19 +1290,16 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
   using SM = DecSmem<SUB, NW, SGN, ROPE>;
   const size_t smem_max = SM::kResOffset + SM::kResBytes;  // residual launches stage the fp16 rows behind the rest
   const size_t smem = res.k != nullptr ? smem_max : (size_t)SM::kBytes;
-  static bool attr_done = false;
-  if (!attr_done) {
-    // the gathers address the codebook table by absolute LDS address: it must start at 0,
-    // i.e. the kernel may not own any static LDS in front of its dynamic block
+  // once per instance (thread-safe static initialisation): the gathers address the codebook table by
+  // absolute LDS address, so it must start at 0, i.e. the kernel may not own any static LDS in front of
+  // its dynamic block; and the dynamic block is raised to the residual launch's size
+  static const bool attr_ok = [&] {
     hipFuncAttributes fa;
-    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN, ROPE, DQ>)) != hipSuccess ||
-        fa.sharedSizeBytes != 0)
-      return NSN_ERR_HIP;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN, ROPE, DQ>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_max) != hipSuccess)
-      return NSN_ERR_HIP;
-    attr_done = true;
-  }
+    const void* fn = reinterpret_cast<const void*>(dec_mfma_kernel<SUB, NW, R, SGN, ROPE, DQ>);
+    return hipFuncGetAttributes(&fa, fn) == hipSuccess && fa.sharedSizeBytes == 0 &&
+           hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_max) == hipSuccess;
+  }();
+  if (!attr_ok) return NSN_ERR_HIP;
   const int per = (((max_seq_len + n_splits - 1) / n_splits) + 63) & ~63;
   int* counters = static_cast<int*>(workspace);
   float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + counter_bytes);
@@ -1345,7 +1308,7 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
   dec_mfma_kernel<SUB, NW, R, SGN, ROPE, DQ><<<grid, waves * 64, smem, stream>>>(
       g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens, scale * 1.44269504088896340736f, n_splits,
       per, partial, counters, res, head_off, r_pass, out);
-  return NSN_OK;
+  return hipGetLastError() == hipSuccess ? NSN_OK : NSN_ERR_HIP;
 }
 
 // arrival counters sit at the head of the workspace: one int per (sequence, query head) (this kernel
@@ -1406,22 +1369,9 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
     };
     auto with_format = [&](auto rope, auto dq) {
       if constexpr (!decltype(rope)::value && !decltype(dq)::value) {
-        // Long splits of the index-only formats run with 11 main waves (12 with the residual wave: three per
-        // SIMD, still 168 registers each): a third wave per SIMD overlaps a little more of the vector,
-        // matrix and memory work (-3 % to -6 % on 16k-32k token splits, +3 % on 2k token splits, whose
-        // prologue it lengthens).
-        // NSN_DECODE_NW=8 / 11 overrides the choice.
-        static const int nw_env = [] { const char* e = getenv("NSN_DECODE_NW"); return e ? atoi(e) : 0; }();
-        const int per_tokens = (((max_seq_len + n_splits - 1) / n_splits) + 63) & ~63;
-        const bool nw11 = nw_env == 11 || (nw_env != 8 && per_tokens >= 4096);
-        if (nw11 && !g.sign && s.sub_dim == 4)
-          return r == 1   ? launch_one<4, 11, 1>(NSN_ARGS)
-                 : r == 2 ? launch_one<4, 11, 2>(NSN_ARGS)
-                          : launch_one<4, 11, 4>(NSN_ARGS);
-        if (nw11 && !g.sign && s.sub_dim == 8)
-          return r == 1   ? launch_one<8, 11, 1>(NSN_ARGS)
-                 : r == 2 ? launch_one<8, 11, 2>(NSN_ARGS)
-                          : launch_one<8, 11, 4>(NSN_ARGS);
+        // index-only codes with fp16 side information and no rotary table run in the tiled-layout kernel
+        // (dispatched above); what is left here without either option is the sign + index format
+        return g.sign ? with_r(std::integral_constant<int, 8>{}, std::true_type{}, rope, dq) : (int)NSN_ERR_UNSUPPORTED;
       }
       if (g.sign) return with_r(std::integral_constant<int, 8>{}, std::true_type{}, rope, dq);
       if (s.sub_dim == 4) return with_r(std::integral_constant<int, 4>{}, std::false_type{}, rope, dq);

@@ -188,24 +188,6 @@ __global__ __launch_bounds__(128) void enc_means_kernel(Geometry g, int max_new,
 // grid (64- or 16-token chunk, kv_head * 2 + tensor, sequence), block 256.  A lane owns one
 // sub-vector (SUB channels) of one token; a wave covers 64 / J tokens at a time.
 // ---------------------------------------------------------------------------------------
-#ifdef NSN_DECODE_TIMING
-__device__ long long g_enc_timing[16];
-#define NSN_ETSTAMP(slot)                                                             \
-  do {                                                                                \
-    if (blockIdx.x == 0 && blockIdx.y == 3 && blockIdx.z == 2 && threadIdx.x == 0) {  \
-      g_enc_timing[slot] = clock64();                                                 \
-      g_enc_timing[8 + (slot)] = wall_clock64();                                      \
-    }                                                                                 \
-  } while (0)
-extern "C" int nsn_debug_encode_timing(long long* host16) {
-  return hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_enc_timing), sizeof(long long) * 16) == hipSuccess ? 0 : -1;
-}
-#else
-#define NSN_ETSTAMP(slot) \
-  do {                    \
-  } while (0)
-#endif
-
 // MFMA:  distance contraction on the matrix cores (else the fp32 vector-ALU scan)
 // FUSED: append mode - the first-Normalize scale is computed here instead of by the stats kernel
 // The register budget is pinned to the main path's needs (4 waves per SIMD at sub-vector length 4,
@@ -284,15 +266,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
     }
     return k;
   };
-  NSN_ETSTAMP(0);
   Tok nxt = fetch(0);
 
   vq_tables_fill<SUB>(T, [&](int c, int i) { return (double)__half2float(codebook[c * SUB + i]); });
   MfmaCodebook<SUB> MC;
-  NSN_ETSTAMP(1);
   if constexpr (MFMA) mfma_codebook_load<SUB>(MC, T, lane);
   if (blockIdx.x * (4 * wave_tokens) >= count) return;
-  NSN_ETSTAMP(2);
 
   const int n_it = wave_tokens / TPW;
   for (int it = 0; it < n_it; ++it) {
@@ -304,7 +283,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
     const int tin = cur.tin;
     const vec_t xraw = cur.xraw, oraw = cur.oraw;
     __half b16f = cur.b16;
-    NSN_ETSTAMP(3);
     double xs[SUB], os[SUB];
     {
       const __half* xh = reinterpret_cast<const __half*>(&xraw);
@@ -384,7 +362,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
 #pragma unroll
     for (int i = 0; i < SUB; ++i) y[i] = v[i] * kInvSqrtD;
 
-    NSN_ETSTAMP(4);
     // sign + index format: the nearest signed codeword has the signs of y and the magnitude
     // codeword nearest to |y| (the magnitudes are non-negative), and y . y_Q = |y| . C[code]
     double ys[SUB];
@@ -400,7 +377,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
     else
       code = vq_search<SUB>(T, ys);
 
-    NSN_ETSTAMP(5);
     // scale adjustment: alpha = ||y||^2 / (y . y_Q)
     double dot = 0.0, nrm2 = 0.0;
 #pragma unroll
@@ -425,7 +401,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
           reinterpret_cast<__half*>(cv.norms)[2 * (base + tin)] = f64_to_f16(bb * s2 * alpha);
       }
     }
-    NSN_ETSTAMP(6);
   }
 }
 
@@ -455,8 +430,7 @@ int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, co
   const int n_chunks = (max_new + ct - 1) / ct;
   double* partial = static_cast<double*>(workspace);
   __half* ws_b = reinterpret_cast<__half*>(static_cast<unsigned char*>(workspace) + encode_partial_bytes(s, batch, max_new));
-  const char* impl = getenv("NSN_ENCODE_IMPL");  // "valu" forces the vector-ALU distance scan
-  const bool use_mfma = !(impl && impl[0] == 'v');
+  const bool use_mfma = selected_variant(NSN_OP_ENCODE) != NSN_VARIANT_ALT;  // the alternative is the vector-ALU scan
   if (!freeze_means || g.dq) {  // side_bits = 4: the s1 codes of a block need all its tokens first
     const dim3 grid_a(n_chunks, s.n_kv_heads * 2, batch);
     enc_stats_kernel<<<grid_a, 256, 0, stream>>>(g, (const __half*)k_in, (const __half*)v_in, max_new, s.max_len,

@@ -45,6 +45,7 @@ inline CacheView make_view(const nsn_cache& c) {
 }
 
 void set_error(const char* fmt, ...);
+int selected_variant(int op);  // NSN_VARIANT_* of NSN_OP_ENCODE / NSN_OP_DECODE (see nsn_select_variant)
 
 // per-operation entry points implemented in the .hip files
 size_t encode_workspace_bytes(const nsn_shape& s, int batch, int64_t max_new);

@@ -32,3 +32,19 @@ def gpu_api():
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     api.lib()  # fails loudly if libnsn.so is not built
     return api
+
+
+@pytest.fixture
+def select_variant(gpu_api):
+    """select_variant("decode", "lut") / ("encode", "valu") picks the alternative kernel for this test;
+    the library's variants are back to what they were when the test ends."""
+    api, saved = gpu_api, {}
+
+    def pick(op_name, impl):
+        op = {"encode": api.NSN_OP_ENCODE, "decode": api.NSN_OP_DECODE}[op_name]
+        variant = api.NSN_VARIANT_ALT if impl in ("lut", "valu") else api.NSN_VARIANT_DEFAULT
+        prev = api.nsn_select_variant(op, variant)
+        saved.setdefault(op, prev)
+    yield pick
+    for op, prev in saved.items():
+        api.nsn_select_variant(op, prev)

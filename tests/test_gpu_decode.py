@@ -78,10 +78,10 @@ CASES = [
 
 @pytest.mark.parametrize("impl", ["mfma", "lut"])
 @pytest.mark.parametrize("name,batch,hq,hkv,lens,sub,G,page,splits", CASES, ids=[c[0] for c in CASES])
-def test_decode_matches_oracle(gpu_api, codebooks, monkeypatch, impl, name, batch, hq, hkv, lens, sub, G, page,
+def test_decode_matches_oracle(gpu_api, codebooks, select_variant, impl, name, batch, hq, hkv, lens, sub, G, page,
                                splits):
     # "mfma": matrix-core kernel (default for <= 4 query heads per kv head); "lut": lookup-table kernel
-    monkeypatch.setenv("NSN_DECODE_IMPL", impl)
+    select_variant("decode", impl)
     print(f"case {name} impl={impl} lens={lens} sub={sub} G={G} page={page} splits={splits}", flush=True)
     cb = codebooks[sub]
     scale = 1.0 / math.sqrt(128)
@@ -98,8 +98,8 @@ def test_decode_matches_oracle(gpu_api, codebooks, monkeypatch, impl, name, batc
 
 
 @pytest.mark.parametrize("impl", ["mfma", "lut"])
-def test_split_count_does_not_change_the_result(gpu_api, codebooks, monkeypatch, impl):
-    monkeypatch.setenv("NSN_DECODE_IMPL", impl)
+def test_split_count_does_not_change_the_result(gpu_api, codebooks, select_variant, impl):
+    select_variant("decode", impl)
     cb = codebooks[4]
     scale = 1.0 / math.sqrt(128)
     lens = [1500, 640]
@@ -129,10 +129,10 @@ def _encoded_case(seed, hq, hkv, L, sub, G, cb, k_fn, v_fn):
 @pytest.mark.parametrize("impl", ["mfma", "lut"])
 @pytest.mark.parametrize("sub", [4, 8])
 @pytest.mark.parametrize("log2_mul", [-12, 0, 9])
-def test_value_scale_does_not_change_the_accuracy(gpu_api, codebooks, monkeypatch, impl, sub, log2_mul):
+def test_value_scale_does_not_change_the_accuracy(gpu_api, codebooks, select_variant, impl, sub, log2_mul):
     """The first Normalize stores every token norm on its own (Sec. 3.2), so attention over the coded
     cache (App. B) is as accurate for values of size 2^-12 or 2^9 as for values of size 1."""
-    monkeypatch.setenv("NSN_DECODE_IMPL", impl)
+    select_variant("decode", impl)
     cb, scale, L, seed = codebooks[sub], 1.0 / math.sqrt(128), 1500, 60 + sub
     mul = np.float32(2.0 ** log2_mul)
     kc, vc, q, max_len = _encoded_case(
@@ -149,10 +149,10 @@ def test_value_scale_does_not_change_the_accuracy(gpu_api, codebooks, monkeypatc
 
 @pytest.mark.parametrize("impl", ["mfma", "lut"])
 @pytest.mark.parametrize("sub", [4, 8])
-def test_sink_token_with_twice_the_norm(gpu_api, codebooks, monkeypatch, impl, sub):
+def test_sink_token_with_twice_the_norm(gpu_api, codebooks, select_variant, impl, sub):
     """Token 0 of the sequence is an outlier-norm ("sink") token: its key and its value are twice as
     long as they were drawn (Sec. 3.2 keeps such tokens apart through the stored norm)."""
-    monkeypatch.setenv("NSN_DECODE_IMPL", impl)
+    select_variant("decode", impl)
     cb, scale, L, seed = codebooks[sub], 1.0 / math.sqrt(128), 1100, 80 + sub
 
     def doubled(x):
@@ -172,12 +172,12 @@ def test_sink_token_with_twice_the_norm(gpu_api, codebooks, monkeypatch, impl, s
 
 @pytest.mark.parametrize("impl", ["mfma", "lut"])
 @pytest.mark.parametrize("where", [0, 70001, 102399])
-def test_one_dominant_token_among_many_low_score_tokens(gpu_api, codebooks, monkeypatch, impl, where):
+def test_one_dominant_token_among_many_low_score_tokens(gpu_api, codebooks, select_variant, impl, where):
     """102400 tokens whose scores are all near zero, and one token whose key points along the first
     query head (score about +17 after scaling): that head's softmax is almost one-hot, the running
     maximum jumps once, and the result must still be within the bar.  The cache is 2048 oracle-encoded
     tokens repeated 50 times (one Shift group, so repeated tokens encode identically)."""
-    monkeypatch.setenv("NSN_DECODE_IMPL", impl)
+    select_variant("decode", impl)
     sub, hq, L0, reps, seed = 4, 4, 2048, 50, 97
     cb, scale, J = codebooks[sub], 1.0 / math.sqrt(128), 32
     L = L0 * reps

@@ -84,9 +84,9 @@ CASES = [
 
 @pytest.mark.parametrize("impl", ["mfma", "valu"])
 @pytest.mark.parametrize("name,batch,hkv,lens,sub,G,page", CASES, ids=[c[0] for c in CASES])
-def test_encode_matches_oracle(gpu_api, codebooks, monkeypatch, impl, name, batch, hkv, lens, sub, G, page):
+def test_encode_matches_oracle(gpu_api, codebooks, select_variant, impl, name, batch, hkv, lens, sub, G, page):
     # "mfma": distance contraction on the matrix cores (default); "valu": fp32 vector-ALU scan
-    monkeypatch.setenv("NSN_ENCODE_IMPL", impl)
+    select_variant("encode", impl)
     print(f"case {name} impl={impl} lens={lens} sub={sub} G={G} page={page}", flush=True)
     cb = codebooks[sub]
     seed = 300 + len(name)
@@ -100,8 +100,8 @@ def test_encode_matches_oracle(gpu_api, codebooks, monkeypatch, impl, name, batc
 
 
 @pytest.mark.parametrize("impl", ["mfma", "valu"])
-def test_append_with_frozen_means(gpu_api, codebooks, monkeypatch, impl):
-    monkeypatch.setenv("NSN_ENCODE_IMPL", impl)
+def test_append_with_frozen_means(gpu_api, codebooks, select_variant, impl):
+    select_variant("encode", impl)
     cb = codebooks[8]
     lens0 = [200, 64]
     k0, v0, hk, hv = run_gpu_encode(gpu_api, 41, 2, 2, lens0, 8, 0, cb, max_len=256)
@@ -142,11 +142,11 @@ def test_zero_tokens_and_constant_tokens(gpu_api, codebooks):
 
 @pytest.mark.parametrize("impl", ["mfma", "valu"])
 @pytest.mark.parametrize("sub", [4, 8])
-def test_duplicate_codewords_take_the_lowest_index(gpu_api, codebooks, monkeypatch, impl, sub):
+def test_duplicate_codewords_take_the_lowest_index(gpu_api, codebooks, select_variant, impl, sub):
     """Equal codewords give exactly equal distances: the argmin must be the lowest index (the rule
     the oracle states), also when three or more entries coincide; all other sub-vectors keep the
     usual bar (bit-exact outside the 1e-6 tie window)."""
-    monkeypatch.setenv("NSN_ENCODE_IMPL", impl)
+    select_variant("encode", impl)
     cb = codebooks[sub].copy()
     cb[77] = cb[5]
     cb[200] = cb[5]          # a triple
@@ -188,10 +188,10 @@ SIGN_CASES = [
 
 @pytest.mark.parametrize("impl", ["mfma", "valu"])
 @pytest.mark.parametrize("name,batch,hkv,lens,G,page", SIGN_CASES, ids=[c[0] for c in SIGN_CASES])
-def test_sign_format_encode_matches_oracle(gpu_api, magnitude_codebook, monkeypatch, impl, name, batch, hkv, lens,
+def test_sign_format_encode_matches_oracle(gpu_api, magnitude_codebook, select_variant, impl, name, batch, hkv, lens,
                                            G, page):
     """The paper's 2-bit format: 8 sign bits + 8-bit index of a magnitude codeword per 8-dim sub-vector."""
-    monkeypatch.setenv("NSN_ENCODE_IMPL", impl)
+    select_variant("encode", impl)
     print(f"case {name} impl={impl} lens={lens} G={G} page={page}", flush=True)
     cb = magnitude_codebook
     k, v, hk, hv = run_gpu_encode(gpu_api, 500 + len(name), batch, hkv, lens, 8, G, cb, page, sign=True)

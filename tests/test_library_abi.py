@@ -117,6 +117,20 @@ def test_shape_validation_and_error_text(L):
     assert rc == api.NSN_ERR_INVALID_ARG and b"rope" in L.nsn_last_error()
 
 
+def test_variant_selection_returns_the_previous_choice(L):
+    first = api.nsn_select_variant(api.NSN_OP_DECODE, api.NSN_VARIANT_ALT)
+    assert first in (api.NSN_VARIANT_DEFAULT, api.NSN_VARIANT_ALT)
+    # the lookup-table decode kernel takes index-only formats without a residual only: the shape check says so
+    dq = api.make_shape(4, 32, 8, 8192, 64, side_bits=4)
+    kc = api.nsn_cache(1, 1, 1, None)
+    rc = L.nsn_decode_attention(C.byref(dq), 1, 1, C.byref(kc), C.byref(kc), 1, 1, 64, 1.0, 0, 1, None, 0, None)
+    assert rc == api.NSN_ERR_UNSUPPORTED and b"lookup-table" in L.nsn_last_error()
+    assert api.nsn_select_variant(api.NSN_OP_DECODE, first) == api.NSN_VARIANT_ALT
+    assert api.nsn_select_variant(api.NSN_OP_ENCODE, api.NSN_VARIANT_DEFAULT) in (0, 1)
+    assert L.nsn_select_variant(api.NSN_OP_CODEBOOK, 0) == api.NSN_ERR_INVALID_ARG
+    assert L.nsn_select_variant(api.NSN_OP_DECODE, 2) == api.NSN_ERR_INVALID_ARG
+
+
 def test_product_package_does_not_import_oracle():
     pkg = os.path.join(ROOT, "paper_2505_18231_amd")
     for dirpath, _, files in os.walk(pkg):
