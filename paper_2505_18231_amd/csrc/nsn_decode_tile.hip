@@ -53,17 +53,37 @@ constexpr float kWeightScale = 1024.0f;           // fp16 weights carry 2^10 / A
 constexpr int kTableBytes = 65536;
 
 #ifdef NSN_TILE_TIMING
-__device__ long long g_tile_timing[2 * 32 * 2];
-#define NSN_STAMP(slot)                                                                              \
+// stamps stay in scalar registers until the wave leaves (a store at the stamp itself would queue behind
+// the wave's outstanding loads and shift everything after it)
+__device__ long long g_tile_timing[2 * 32];
+#define NSN_STAMP_DECL long long ts_[32] = {}
+#define NSN_STAMP(slot) ts_[slot] = clock64()
+#define NSN_STAMP_IT(it)                                  \
+  do {                                                    \
+    if ((it) == 0) ts_[5] = clock64();                    \
+    else if ((it) == 1) ts_[6] = clock64();               \
+    else if ((it) == 2) ts_[7] = clock64();               \
+    else if ((it) == 3) ts_[8] = clock64();               \
+    else ts_[9] = clock64();                              \
+  } while (0)
+#define NSN_STAMP_FLUSH                                                                              \
   do {                                                                                               \
     if (blockIdx.x == 1 && blockIdx.y == 3 && blockIdx.z == 2 && (threadIdx.x & 63) == 0 &&          \
         ((threadIdx.x >> 6) == 0 || (threadIdx.x >> 6) == 5)) {                                      \
-      g_tile_timing[((threadIdx.x >> 6) == 0 ? 0 : 64) + (slot)] = clock64();                        \
-      g_tile_timing[((threadIdx.x >> 6) == 0 ? 0 : 64) + 32 + (slot)] = wall_clock64();              \
+      for (int i_ = 0; i_ < 32; ++i_) g_tile_timing[((threadIdx.x >> 6) == 0 ? 0 : 32) + i_] = ts_[i_]; \
     }                                                                                                \
   } while (0)
 #else
+#define NSN_STAMP_DECL \
+  do {                 \
+  } while (0)
 #define NSN_STAMP(slot) \
+  do {                  \
+  } while (0)
+#define NSN_STAMP_IT(it) \
+  do {                   \
+  } while (0)
+#define NSN_STAMP_FLUSH \
   do {                  \
   } while (0)
 #endif
@@ -130,6 +150,16 @@ __device__ __forceinline__ float xor32(float v) {
   float a = v, b = v;
   lane_swap32(a, b);  // a: the lower half twice, b: the upper half twice
   return ((threadIdx.x >> 5) & 1) ? a : b;
+}
+// value of lane (lane ^ M): DPP inside a 16-lane row, register swaps across rows
+template <int M>
+__device__ __forceinline__ float xor_reg(float v) {
+  if constexpr (M == 16)
+    return xor16(v);
+  else if constexpr (M == 32)
+    return xor32(v);
+  else
+    return xor_lane<M>(v);
 }
 // max of finite or infinite values (never NaN here): the plain instruction, without the operand
 // canonicalisation that fmaxf() adds under IEEE rules (one extra instruction per operand)
@@ -237,6 +267,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   const int t0 = split * per;
   const int64_t mean_base = (int64_t)(b * g.n_kv_heads + h) * g.n_groups_max;
   const int cap_tokens = g.page_tokens * g.pages_per_seq;
+  NSN_STAMP_DECL;
   NSN_STAMP(0);
 
   // ---- loads of one group (all unconditional: callers clamp the group index into the cache) ----
@@ -282,7 +313,9 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   const int grp_first = shift_group(min(t0, cap_tokens - 64));
   const uint32_t ok_first = *reinterpret_cast<const uint32_t*>(
       reinterpret_cast<const unsigned char*>(kc.means + (mean_base + grp_first) * kHeadDim) + lane_x4);
-  Regs S0, S1, S2;
+  // (the three small loads stay ahead of the bulk ones: the waits for them then leave every later load in flight)
+  __builtin_amdgcn_sched_barrier(0);
+  Regs S0{}, S1{}, S2{};
   // contiguous caches: the wave's first group is in bounds whatever the sequence length is (clamped into the
   // cache when the split lies beyond it: then it is never processed)
   if constexpr (!PAGED) load_group(min(t0 + (wave << 6), cap_tokens - 64), S0);
@@ -293,23 +326,13 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   // are.  A sequence without coded tokens keeps split 0 (it may still have residual rows).
   const int n_live = len > 0 ? (len - 1) / per + 1 : 1;
   if (split >= n_live) return;
-  // residual (Sec. 3.2): wave w < 4 of the last live split takes rows [16 w, 16 w + 16); a load instruction
-  // covers four consecutive rows (16 lanes x 16 bytes each); rows beyond the capacity are clamped and masked later
-  const bool res_wave = res.k != nullptr && split == n_live - 1 && wave < 4;
-  uint4 rk[4], rv[4];
-  int res_len = 0;
-  if (res_wave) {
-    const int64_t unit_row = (int64_t)(b * g.n_kv_heads + h) * res.capacity;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int row = min(16 * wave + 4 * u + (lane >> 4), res.capacity - 1);
-      rk[u] = *reinterpret_cast<const uint4*>(res.k + (unit_row + row) * kHeadDim + (lane & 15) * 8);
-      rv[u] = *reinterpret_cast<const uint4*>(res.v + (unit_row + row) * kHeadDim + (lane & 15) * 8);
-    }
-    res_len = res.lens[b];
+  const int t1 = min(len, t0 + per);
+  const int n_grp = (t1 > t0) ? (t1 - t0 + 63) >> 6 : 0;  // 64-token groups of this split
+  if constexpr (PAGED) {
+    if (wave < n_grp) load_group(t0 + (wave << 6), S0);
   }
-
   // ---- prologue: codebook table, query operands --------------------------------------------------
+  NSN_STAMP(25);
   {
     // thread (code = tid / 2, half = tid % 2) fills eight 16-byte slots of its half row, starting at a
     // slot that depends on the code so that the 64 stores of a wave spread over all banks
@@ -323,6 +346,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
 #pragma unroll
     for (int u = 0; u < 8; ++u) lds_write128(row + (((u + code) & 7) << 4), v);
   }
+  NSN_STAMP(26);
   if (wave < 4) {  // d1: wave w rotates head w (zeros for a head that this launch does not have)
     const bool has_head = wave < r;
     const float x0 = has_head ? __low2float(q2_raw) : 0.f, x1 = has_head ? __high2float(q2_raw) : 0.f;
@@ -338,7 +362,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     float y0 = x0 + x1, y1 = x0 - x1;
     static_for<6>([&](auto kc_) {  // lane bit k <-> element bit k + 1
       constexpr int m = 1 << decltype(kc_)::value;
-      const float p0 = xor_lane<m>(y0), p1 = xor_lane<m>(y1);
+      const float p0 = xor_reg<m>(y0), p1 = xor_reg<m>(y1);
       const bool upper = (lane & m) != 0;
       y0 = upper ? p0 - y0 : y0 + p0;
       y1 = upper ? p1 - y1 : y1 + p1;
@@ -357,21 +381,30 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     if (lane == 0) lds_write32(SM::kQoFirst + hh * 4, __float_as_uint(d * scale_log2e));
   }
   NSN_STAMP(2);
+  __builtin_amdgcn_sched_barrier(0);
+  // residual (Sec. 3.2): wave w < 4 of the last live split takes rows [16 w, 16 w + 16); a load instruction
+  // covers four consecutive rows (16 lanes x 16 bytes each); rows beyond the capacity are clamped and masked later
+  const bool res_wave = res.k != nullptr && split == n_live - 1 && wave < 4;
+  uint4 rk[4], rv[4];
+  int res_len = 0;
+  if (res_wave) {
+    const int64_t unit_row = (int64_t)(b * g.n_kv_heads + h) * res.capacity;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int row = min(16 * wave + 4 * u + (lane >> 4), res.capacity - 1);
+      rk[u] = *reinterpret_cast<const uint4*>(res.k + (unit_row + row) * kHeadDim + (lane & 15) * 8);
+      rv[u] = *reinterpret_cast<const uint4*>(res.v + (unit_row + row) * kHeadDim + (lane & 15) * 8);
+    }
+    res_len = res.lens[b];
+  }
+  // the wave's second group goes out behind the first ones of all waves; every later group is requested
+  // when the one before it is about to be needed (see process_group), so that a wave never has more than
+  // two groups in flight.  The compute unit's address pipeline takes about 28 cycles per 1 KiB load
+  // instruction and a wave blocks at a load that cannot be accepted yet: a wave that asks for three groups
+  // at once sits at its load instructions while the data of its first group is already in its registers.
+  if (wave + NW < n_grp) load_group(t0 + ((wave + NW) << 6), S1);
   __syncthreads();
   NSN_STAMP(3);
-  // the wave's second and third groups: three groups per wave are in flight while the operands are set up
-  if constexpr (!PAGED) load_group(min(t0 + ((wave + NW) << 6), cap_tokens - 64), S1);
-
-  const int t1 = min(len, t0 + per);
-  const int n_grp = (t1 > t0) ? (t1 - t0 + 63) >> 6 : 0;
-  const int tg_last = t0 + ((max(n_grp, 1) - 1) << 6);  // first token of the split's last group
-  if constexpr (PAGED) {
-    if (wave < n_grp) {
-      load_group(t0 + (wave << 6), S0);
-      load_group(min(t0 + ((wave + NW) << 6), tg_last), S1);
-      load_group(min(t0 + ((wave + 2 * NW) << 6), tg_last), S2);
-    }
-  }
 
   // B operands of the score contraction (see the header): for tile parity p and k-step s the lane's eight
   // k-slots are channels [32 c + 8 s, +8) of head n % 4: hi part if n / 4 == p, lo part if n / 4 == p + 2,
@@ -637,7 +670,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   // every one of the 48 matrix instructions of a group.
   h8 KA[4], KB[4];
   int stamp_it = 0;
-  auto process_group = [&](int gi, const Regs& G, const Regs& Gn) {
+  auto process_group = [&](int gi, const Regs& G, const Regs& Gn, Regs& Gnn) {
     const int tg = t0 + (gi << 6);
     // Shift group bookkeeping (wave-uniform)
     const int grp = shift_group(tg);
@@ -712,6 +745,9 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     v_contract(c1, VB, wop);
     v_gather(c3, G, VD);
     __builtin_amdgcn_sched_barrier(0);
+    // the group after the next one: requested just before the next one's bytes are first needed (below)
+    if (gi + 2 * NW < n_grp) load_group(t0 + ((gi + 2 * NW) << 6), Gnn);  // wave-uniform
+    __builtin_amdgcn_sched_barrier(0);
     v_contract(c2, VC, wop);
     k_gather(c0, Gn, KA);  // (any bytes are valid table indices: harmless when there is no next group)
     __builtin_amdgcn_sched_barrier(0);
@@ -721,32 +757,24 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   };
 
   NSN_STAMP(4);
-  // ---- main loop: this wave's groups wave, wave + NW, ...; three groups are in flight or in registers ----
+  // ---- main loop: this wave's groups wave, wave + NW, ...; three register sets rotate (in use, next, in flight) ----
   if (wave < n_grp) {
     int gi = wave;
     k_gather(c0, S0, KA);
     k_gather(c1, S0, KB);
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (!PAGED) load_group(min(t0 + ((wave + 2 * NW) << 6), tg_last), S2);
-    __builtin_amdgcn_sched_barrier(0);
-    while (true) {  // the set that has just been consumed is refilled with the group three rounds ahead
-      process_group(gi, S0, S1);
-      load_group(min(t0 + ((gi + 3 * NW) << 6), tg_last), S0);
-      NSN_STAMP(5 + min(stamp_it, 6));
+    while (true) {
+      process_group(gi, S0, S1, S2);
+      NSN_STAMP_IT(stamp_it);
       ++stamp_it;
       gi += NW;
       if (gi >= n_grp) break;
-      process_group(gi, S1, S2);
-      NSN_STAMP(20);
-      load_group(min(t0 + ((gi + 3 * NW) << 6), tg_last), S1);
-      NSN_STAMP(21);
-      NSN_STAMP(5 + min(stamp_it, 6));
+      process_group(gi, S1, S2, S0);
+      NSN_STAMP_IT(stamp_it);
       ++stamp_it;
       gi += NW;
       if (gi >= n_grp) break;
-      process_group(gi, S2, S0);
-      load_group(min(t0 + ((gi + 3 * NW) << 6), tg_last), S2);
-      NSN_STAMP(5 + min(stamp_it, 6));
+      process_group(gi, S2, S0, S1);
+      NSN_STAMP_IT(stamp_it);
       ++stamp_it;
       gi += NW;
       if (gi >= n_grp) break;
@@ -781,7 +809,10 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   NSN_STAMP(14);
 
   // ---- merge the waves: wave i takes head i, a lane channels 2 lane, 2 lane + 1 ------------------
-  if (wave >= r) return;
+  if (wave >= r) {
+    NSN_STAMP_FLUSH;
+    return;
+  }
   const int hh = wave;
   float M = -INFINITY, L = 0.f, x0 = 0.f, x1 = 0.f, mm0 = 0.f, mm1 = 0.f;
   {
@@ -837,7 +868,10 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     if (lane == 0) old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     old = __builtin_amdgcn_readfirstlane(old);
     NSN_STAMP(16);
-    if (old != n_live - 1) return;
+    if (old != n_live - 1) {
+      NSN_STAMP_FLUSH;
+      return;
+    }
     if (lane == 0) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
     // chunks of eight splits, every load of a chunk issued before its first use; running max across chunks
     constexpr int SF = 8;
@@ -880,7 +914,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   }
   static_for<6>([&](auto kc_) {
     constexpr int m = 1 << decltype(kc_)::value;
-    const float p0 = xor_lane<m>(x0), p1 = xor_lane<m>(x1);
+    const float p0 = xor_reg<m>(x0), p1 = xor_reg<m>(x1);
     const bool upper = (lane & m) != 0;
     x0 = upper ? p0 - x0 : x0 + p0;
     x1 = upper ? p1 - x1 : x1 + p1;
@@ -889,11 +923,12 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   if (L > 0.f) o2 = make_float2((x0 * (float)kInvSqrtD + mm0) / L, (x1 * (float)kInvSqrtD + mm1) / L);
   *reinterpret_cast<float2*>(out + (int64_t)(b * g.n_q_heads + hq0 + hh) * kHeadDim + 2 * lane) = o2;
   NSN_STAMP(18);
+  NSN_STAMP_FLUSH;
 }
 
 #ifdef NSN_TILE_TIMING
-extern "C" int nsn_debug_tile_timing(long long* host128) {
-  return hipMemcpyFromSymbol(host128, HIP_SYMBOL(g_tile_timing), sizeof(long long) * 128) == hipSuccess ? 0 : -1;
+extern "C" int nsn_debug_tile_timing(long long* host64) {
+  return hipMemcpyFromSymbol(host64, HIP_SYMBOL(g_tile_timing), sizeof(long long) * 64) == hipSuccess ? 0 : -1;
 }
 #endif
 
