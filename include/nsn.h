@@ -325,7 +325,7 @@ int nsn_decode_attention_residual(const nsn_shape* shape, const void* codebook_d
  * operation and arguments, without a workspace.  The arrival counters and split partials live in a
  * fixed 4 MiB array inside the library's device image (one copy per GPU, held until the process
  * ends); the call allocates nothing and clears the counters it uses with a small kernel on `stream`.
- *   - Needs batch * n_q_heads * n_splits * 1032 bytes + 4 bytes per (sequence, query head), rounded up
+ *   - Needs batch * n_q_heads * n_splits * 1032 bytes + 256 bytes per (sequence, query head), rounded up
  *     to 256: calls that need more than 4 MiB fail with NSN_ERR_WORKSPACE (use nsn_decode_attention).
  *   - All calls on one GPU share the array: calls that overlap in time on one GPU (different streams,
  *     different host threads) race; calls on one stream do not.

@@ -1180,7 +1180,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   __builtin_amdgcn_s_waitcnt(0);  // this wave's partial stores have completed
   __syncthreads();
   if (tid == 0) {
-    int* cnt = counters + (b * g.n_kv_heads + h);
+    int* cnt = counters + (b * g.n_kv_heads + h) * kCounterStrideInts;
     const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int last = (old == n_splits - 1);
     if (last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
@@ -1311,10 +1311,11 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
   return hipGetLastError() == hipSuccess ? NSN_OK : NSN_ERR_HIP;
 }
 
-// arrival counters sit at the head of the workspace: one int per (sequence, query head) (this kernel
-// uses one per (sequence, kv head) of them, the tiled-layout kernel all)
+// arrival counters sit at the head of the workspace: one per (sequence, query head), each on a 256-byte
+// line of its own (atomic updates of one line are served one after the other, wherever in the line they
+// fall); this kernel uses one per (sequence, kv head) of them, the tiled-layout kernel all
 static size_t counter_bytes(const nsn_shape& s, int batch) {
-  return (((size_t)batch * s.n_q_heads * sizeof(int)) + 255) & ~(size_t)255;
+  return (size_t)batch * s.n_q_heads * kCounterStrideInts * sizeof(int);
 }
 size_t decode_counter_bytes(const nsn_shape& s, int batch) { return counter_bytes(s, batch); }
 
@@ -1322,11 +1323,17 @@ int decode_mfma_splits(const nsn_shape& s, int batch, int max_seq_len, int reque
   const int cap = max(1, min(64, (max_seq_len + 255) / 256));
   if (requested > 0) return min(requested, 64);
   const int units = max(1, batch * s.n_kv_heads);
+  // Half a chip's worth of units or more: splitting cannot even out a ragged batch any further (a split is a
+  // workgroup with its own table and epilogue), the persistent instance can
+  if (shape_is_tiled(s) && units >= 128) return kSplitsFlat;
   return max(1, min(cap, (256 + units - 1) / units));  // one 8-wave workgroup per compute unit
 }
 
 size_t decode_mfma_workspace_bytes(const nsn_shape& s, int batch, int n_splits) {
-  return counter_bytes(s, batch) + (size_t)batch * s.n_q_heads * n_splits * kPartialStrideM * sizeof(float);
+  // kSplitsFlat: two partials per run and query head of a kv head
+  const size_t partials = n_splits == kSplitsFlat ? (size_t)kFlatRunsMax * 2 * (s.n_q_heads / s.n_kv_heads)
+                                                  : (size_t)batch * s.n_q_heads * n_splits;
+  return counter_bytes(s, batch) + partials * kPartialStrideM * sizeof(float);
 }
 
 int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, const nsn_cache& kc,

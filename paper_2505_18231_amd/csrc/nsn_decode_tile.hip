@@ -31,6 +31,11 @@
 // wave would lengthen a four-group loop by a quarter).  Waves merge through LDS once; splits
 // merge through fp32 partials in the workspace, the last wave to arrive (integer counter per query
 // head) finishing the head: merge, one inverse Hadamard in registers, mean-vector term, output.
+#include <algorithm>
+#define NSN_PAGE_VMEM
+#ifndef NSN_SF
+#define NSN_SF 32
+#endif
 #include <type_traits>
 
 #include "nsn_host.h"
@@ -56,10 +61,27 @@ constexpr int kTableBytes = 65536;
 // stamps stay in scalar registers until the wave leaves (a store at the stamp itself would queue behind
 // the wave's outstanding loads and shift everything after it)
 __device__ long long g_tile_timing[2 * 32];
-#define NSN_STAMP_DECL long long ts_[32] = {}
-#define NSN_STAMP(slot) ts_[slot] = clock64()
+#ifndef NSN_STAMP_RUN
+#define NSN_STAMP_RUN 100
+#endif
+#define NSN_STAMP_SPLIT \
+  (gridDim.y == 1 ? blockIdx.x == NSN_STAMP_RUN : (blockIdx.x == 1 && blockIdx.y == 3 && blockIdx.z == (gridDim.z > 2 ? 2 : 0)))
+#define NSN_STAMP_DECL   \
+  long long ts_[32] = {}; \
+  bool stamp_on_ = true
+#ifdef NSN_STAMP_FIRST
+#define NSN_STAMP_NEXT_SEGMENT stamp_on_ = false
+#else
+#define NSN_STAMP_NEXT_SEGMENT \
+  do {                         \
+  } while (0)
+#endif
+#define NSN_STAMP(slot) \
+  if (stamp_on_) ts_[slot] = clock64()
+#define NSN_STAMP_WALL(slot) ts_[slot] = wall_clock64()
 #define NSN_STAMP_IT(it)                                  \
   do {                                                    \
+    if (!stamp_on_) break;                                \
     if ((it) == 0) ts_[5] = clock64();                    \
     else if ((it) == 1) ts_[6] = clock64();               \
     else if ((it) == 2) ts_[7] = clock64();               \
@@ -68,7 +90,7 @@ __device__ long long g_tile_timing[2 * 32];
   } while (0)
 #define NSN_STAMP_FLUSH                                                                              \
   do {                                                                                               \
-    if (blockIdx.x == 1 && blockIdx.y == 3 && blockIdx.z == 2 && (threadIdx.x & 63) == 0 &&          \
+    if (NSN_STAMP_SPLIT && (threadIdx.x & 63) == 0 && \
         ((threadIdx.x >> 6) == 0 || (threadIdx.x >> 6) == 5)) {                                      \
       for (int i_ = 0; i_ < 32; ++i_) g_tile_timing[((threadIdx.x >> 6) == 0 ? 0 : 32) + i_] = ts_[i_]; \
     }                                                                                                \
@@ -85,6 +107,12 @@ __device__ long long g_tile_timing[2 * 32];
   } while (0)
 #define NSN_STAMP_FLUSH \
   do {                  \
+  } while (0)
+#define NSN_STAMP_WALL(slot) \
+  do {                       \
+  } while (0)
+#define NSN_STAMP_NEXT_SEGMENT \
+  do {                         \
   } while (0)
 #endif
 
@@ -244,12 +272,22 @@ struct GroupRegs {
 // shifts (the other instance divides: about 35 scalar instructions per index)
 // PAGED: the caches are paged (block tables); the other instance never reads a block table and can
 // fetch its first group before the sequence length is known
-template <int SUB, int NW, bool POW2, bool PAGED>
+// FLAT: the launch is one persistent workgroup per compute unit.  All 64-token groups of all (sequence,
+// kv head) units form one list (unit by unit, a unit without coded tokens counts as one group); workgroup c
+// takes the c-th of n_splits equal runs of that list, which is a sequence of segments: (unit, first group,
+// number of groups).  A unit that is cut by a run boundary is merged through partial results exactly as a
+// split one is in the other instance.  Ragged batches and batches with more units than compute units keep
+// every compute unit busy this way, and the codebook table is built once per workgroup.
+// Every unit takes kSegCost list slots in front of its groups: a segment costs about as much as that many
+// groups (query rotation, two barriers, the merge of the waves, a cold start of the loads), so that runs with
+// many short units get fewer groups.  A run that ends inside those slots leaves the unit to the next run.
+constexpr int kSegCost = 24;
+template <int SUB, int NW, bool POW2, bool PAGED, bool FLAT>
 __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __half* __restrict__ codebook,
                                                            const __half* __restrict__ q, CacheView kc, CacheView vc,
-                                                           const int32_t* __restrict__ seq_lens, float scale_log2e,
-                                                           int n_splits, int per, float* partial, int* counters,
-                                                           ResidualView res, int head_off, int r_pass,
+                                                           const int32_t* __restrict__ seq_lens, int batch,
+                                                           float scale_log2e, int n_splits, int per, float* partial,
+                                                           int* counters, ResidualView res, int head_off, int r_pass,
                                                            float* __restrict__ out) {
   static_assert(NW == 8, "prologue work split: 512 threads fill the table, waves 0..3 rotate the query");
   constexpr int NSV = kHeadDim / SUB;  // sub-vectors (= code bytes) per token
@@ -258,19 +296,102 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   using Regs = GroupRegs<CW>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
-  const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int r = r_pass;
-  const int hq0 = h * (g.n_q_heads / g.n_kv_heads) + head_off;
-  const int tid = threadIdx.x, lane = tid & 63;
+  const int tid = threadIdx.x, lane0 = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int rho = lane >> 4, n16 = lane & 15, head = lane & 3, tile_of_lane = n16 >> 2;
-  const int t0 = split * per;
-  const int64_t mean_base = (int64_t)(b * g.n_kv_heads + h) * g.n_groups_max;
   const int cap_tokens = g.page_tokens * g.pages_per_seq;
+  // the segment at hand (!FLAT: the launch's one (split, kv head, sequence))
+  int split = FLAT ? 0 : blockIdx.x, h = FLAT ? 0 : blockIdx.y, b = FLAT ? 0 : blockIdx.z;
+  int t0 = split * per;
+  int64_t mean_base = (int64_t)(b * g.n_kv_heads + h) * g.n_groups_max;
   NSN_STAMP_DECL;
   NSN_STAMP(0);
+  NSN_STAMP_WALL(30);
 
+  // ---- loads that do not depend on the sequence length go out first ------------------------------
+  // (all unconditional, so that the wait for the codebook can leave the later ones in flight)
+  typedef typename std::conditional<SUB == 4, uint2, uint4>::type cw_t;
+  const cw_t cw_reg = reinterpret_cast<const cw_t*>(codebook)[tid >> 1];  // two threads per code row
+
+  // ---- FLAT: this workgroup's run of the group list (every wave computes the same numbers) --------
+  const int hkv = g.n_kv_heads;
+  int run_q = 0, run_pos = 0, run_end = 0, seg_g = 0;  // run length, list position, end of the run, slot inside the unit
+  // codebook table: thread (code = tid / 2, half = tid % 2) fills eight 16-byte slots of its half row, starting
+  // at a slot that depends on the code so that the 64 stores of a wave spread over all banks
+  auto fill_table = [&]() {
+    const int code = tid >> 1, half = tid & 1;
+    u4v v;
+    if constexpr (SUB == 4)
+      v = u4v{cw_reg.x, cw_reg.y, cw_reg.x, cw_reg.y};
+    else
+      v = u4v{cw_reg.x, cw_reg.y, cw_reg.z, cw_reg.w};
+    const uint32_t row = code * 256 + half * 128;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) lds_write128(row + (((u + code) & 7) << 4), v);
+  };
+  if constexpr (FLAT) {
+    auto groups_of = [](int len) { return max(1, (len + 63) >> 6); };
+    // list positions taken by the sequences of one 64-sequence block: this lane's sequence, and the inclusive
+    // prefix sums over the lanes
+    auto block_sizes = [&](int b0, int& n, int& incl) {
+      n = (b0 + lane0 < batch) ? (groups_of(seq_lens[b0 + lane0]) + kSegCost) * hkv : 0;
+      incl = n;
+      static_for<6>([&](auto kc_) {
+        constexpr int d = 1 << decltype(kc_)::value;
+        const int up = __shfl_up(incl, d);
+        incl += (lane0 >= d) ? up : 0;
+      });
+    };
+    int n0, incl0;
+    block_sizes(0, n0, incl0);  // (the table is filled while these lengths are on their way)
+    fill_table();
+    int total = __builtin_amdgcn_readlane(incl0, 63);
+    for (int b0 = 64; b0 < batch; b0 += 64) {
+      int n, incl;
+      block_sizes(b0, n, incl);
+      total += __builtin_amdgcn_readlane(incl, 63);
+    }
+    run_q = (total + n_splits - 1) / n_splits;
+    run_pos = (int)blockIdx.x * run_q;
+    if (run_pos >= total) return;  // (all waves alike, before any barrier)
+    run_end = min(total, run_pos + run_q);
+    // the sequence that holds list position run_pos: sequences are laid out one after the other, each as
+    // n_kv_heads units of its group count
+    int before = 0;  // list positions in front of the 64-sequence block at hand
+    for (int b0 = 0; b0 < batch; b0 += 64) {
+      int n = n0, incl = incl0;
+      if (b0 > 0) block_sizes(b0, n, incl);
+      const int n_before = __popcll(__ballot(b0 + lane0 < batch && before + incl <= run_pos));  // sequences that end at or before it
+      const int n_here = min(64, batch - b0);
+      if (n_before < n_here) {
+        b = b0 + n_before;
+        const int incl_b = __builtin_amdgcn_readlane(incl, n_before), n_b = __builtin_amdgcn_readlane(n, n_before);
+        const int off = run_pos - (before + incl_b - n_b);  // position inside the sequence's n_kv_heads units
+        const int slots = n_b / hkv;
+        h = off / slots;
+        seg_g = off - h * slots;  // (position among the unit's slots)
+        break;
+      }
+      before += __builtin_amdgcn_readlane(incl, 63);
+    }
+  }
+
+  bool first_segment = true;
+  // FLAT: the next segment's sequence length, query row and first mean row are fetched a segment ahead
+  int len_cur = 0, nb = 0, nh = 0;
+  __half2 q2_next = __half2{};
+  uint32_t okf_next = 0u;
+  if constexpr (FLAT) len_cur = seq_lens[b];
+  for (;;) {  // FLAT: one pass per segment of the run; otherwise a single pass
+  // Everything a pass derives from the lane number is derived anew in each pass: values that the compiler
+  // could compute once in front of the segment loop would stay in registers through all of it, and this
+  // kernel has none to spare.
+  int lane = lane0;
+  if constexpr (FLAT) asm volatile("" : "+v"(lane));
+  const int rho = lane >> 4, n16 = lane & 15, head = lane & 3, tile_of_lane = n16 >> 2;
   // ---- loads of one group (all unconditional: callers clamp the group index into the cache) ----
+  int lane_zero = 0;
+  asm volatile("" : "+v"(lane_zero));  // (a zero the compiler takes for a per-lane value)
   const uint32_t lane_code_off = lane * NSV;
   const uint32_t norm_off = (16 * tile_of_lane + 4 * rho) * 4;  // bytes: the lane's first token of the group
   const uint32_t lane_x4 = lane * 4;
@@ -279,7 +400,14 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     if constexpr (!PAGED) return (int64_t)(b * g.n_kv_heads + h) * g.page_tokens + tg;
     const int page = POW2 ? tg >> g.page_shift : tg / g.page_tokens;
     const int tin = POW2 ? tg & (g.page_tokens - 1) : tg % g.page_tokens;
-    return ((int64_t)block_table[(int64_t)b * g.pages_per_seq + page] * g.n_kv_heads + h) * g.page_tokens + tin;
+#ifdef NSN_PAGE_VMEM
+    // the table entry comes through the vector memory path: a scalar load would share its counter with the
+    // LDS gathers in flight, and the wait for it would drain them
+    const int phys = __builtin_amdgcn_readfirstlane(block_table[(int64_t)b * g.pages_per_seq + page + lane_zero]);
+#else
+    const int phys = block_table[(int64_t)b * g.pages_per_seq + page];
+#endif
+    return ((int64_t)phys * g.n_kv_heads + h) * g.page_tokens + tin;
   };
   auto shift_group = [&](int tg) -> int {
     return g.group_size <= 0 ? 0 : POW2 ? tg >> g.group_shift : tg / g.group_size;
@@ -302,50 +430,85 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     G.ov = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lane_x4);
   };
 
-  // ---- loads that do not depend on the sequence length go out first ------------------------------
-  // (all unconditional, so that the wait for the codebook can leave the later ones in flight)
-  typedef typename std::conditional<SUB == 4, uint2, uint4>::type cw_t;
-  const cw_t cw_reg = reinterpret_cast<const cw_t*>(codebook)[tid >> 1];  // two threads per code row
+  int len, n_live, t1, n_grp, first_run = 0;
+  bool res_here;  // this segment holds the unit's last group: it takes the residual rows
+  if constexpr (FLAT) {
+    len = len_cur;
+    const int ng = max(1, (len + 63) >> 6);
+    const int take_slots = min(ng + kSegCost - seg_g, run_end - run_pos);
+    const int g0 = max(seg_g - kSegCost, 0), g1 = max(seg_g + take_slots - kSegCost, 0);  // the segment's groups
+    if (g1 == g0) break;  // the run ends inside the unit's cost slots (all waves alike, no barrier pending)
+    const int unit_pos = run_pos - seg_g + kSegCost;  // list position of the unit's first group
+    first_run = unit_pos / run_q;
+    n_live = (unit_pos + ng - 1) / run_q - first_run + 1;  // runs that hold groups of this unit
+    split = (int)blockIdx.x - first_run;
+    t0 = g0 << 6;
+    t1 = min(len, g1 << 6);
+    res_here = g1 == ng;
+    mean_base = (int64_t)(b * hkv + h) * g.n_groups_max;
+    // advance to the next segment's start (used at the end of the pass)
+    run_pos += take_slots;
+    seg_g = 0;  // (a run that goes on goes on with the next unit)
+  }
+  const int hq0 = h * (g.n_q_heads / hkv) + head_off;
   // waves 0..3 rotate one query head each (the others load a valid row that they do not use)
-  const __half2 q2_raw = *reinterpret_cast<const __half2*>(
-      q + (int64_t)(b * g.n_q_heads + hq0 + min(wave & 3, r - 1)) * kHeadDim + 2 * lane);
+  auto q_row = [&](int bb, int hh0) {
+    return *reinterpret_cast<const __half2*>(q + (int64_t)(bb * g.n_q_heads + hh0 + min(wave & 3, r - 1)) * kHeadDim +
+                                             2 * lane);
+  };
+  auto mean_row_k = [&](int64_t base, int grp) {
+    return *reinterpret_cast<const uint32_t*>(
+        reinterpret_cast<const unsigned char*>(kc.means + (base + grp) * kHeadDim) + lane_x4);
+  };
   // the split's first Shift group: its q . o^k is formed once per workgroup (waves 4..7, one head each)
   const int grp_first = shift_group(min(t0, cap_tokens - 64));
-  const uint32_t ok_first = *reinterpret_cast<const uint32_t*>(
-      reinterpret_cast<const unsigned char*>(kc.means + (mean_base + grp_first) * kHeadDim) + lane_x4);
+  __half2 q2_raw = q2_next;
+  uint32_t ok_first = okf_next;
+  if (!FLAT || first_segment) {
+    q2_raw = q_row(b, hq0);
+    ok_first = mean_row_k(mean_base, grp_first);
+  }
+  if constexpr (FLAT) {
+    // the unit after this one (if the run goes on, this segment ends its unit and the next begins one)
+    nb = b, nh = h;
+    if (run_pos < run_end && ++nh == hkv) {
+      nh = 0;
+      ++nb;
+    }
+    len_cur = seq_lens[nb];
+    q2_next = q_row(nb, nh * (g.n_q_heads / hkv) + head_off);
+    okf_next = mean_row_k((int64_t)(nb * hkv + nh) * g.n_groups_max, 0);
+  }
   // (the three small loads stay ahead of the bulk ones: the waits for them then leave every later load in flight)
   __builtin_amdgcn_sched_barrier(0);
-  Regs S0{}, S1{}, S2{};
-  // contiguous caches: the wave's first group is in bounds whatever the sequence length is (clamped into the
-  // cache when the split lies beyond it: then it is never processed)
-  if constexpr (!PAGED) load_group(min(t0 + (wave << 6), cap_tokens - 64), S0);
-  const int len = seq_lens[b];
-  NSN_STAMP(1);
-  // Splits that lie wholly beyond this sequence's end have nothing to do and leave at once (a ragged batch
-  // is launched with the split count of its longest sequence); the others know how many of them there
-  // are.  A sequence without coded tokens keeps split 0 (it may still have residual rows).
-  const int n_live = len > 0 ? (len - 1) / per + 1 : 1;
-  if (split >= n_live) return;
-  const int t1 = min(len, t0 + per);
-  const int n_grp = (t1 > t0) ? (t1 - t0 + 63) >> 6 : 0;  // 64-token groups of this split
-  if constexpr (PAGED) {
-    if (wave < n_grp) load_group(t0 + (wave << 6), S0);
+  Regs S0, S1, S2;  // each is either loaded or zeroed before it is read (zeros are valid table indices)
+  if constexpr (!FLAT) {
+    // contiguous caches: the wave's first group is in bounds whatever the sequence length is (clamped into
+    // the cache when the split lies beyond it: then it is never processed)
+    if constexpr (!PAGED) load_group(min(t0 + (wave << 6), cap_tokens - 64), S0);  // (wslot == wave here)
+    len = seq_lens[b];
+    NSN_STAMP(1);
+    // Splits that lie wholly beyond this sequence's end have nothing to do and leave at once (a ragged batch
+    // is launched with the split count of its longest sequence); the others know how many of them there
+    // are.  A sequence without coded tokens keeps split 0 (it may still have residual rows).
+    n_live = len > 0 ? (len - 1) / per + 1 : 1;
+    if (split >= n_live) return;
+    t1 = min(len, t0 + per);
+    res_here = split == n_live - 1;
+  }
+  n_grp = (t1 > t0) ? (t1 - t0 + 63) >> 6 : 0;  // 64-token groups of this segment
+  // FLAT: waves 4..7 take the segment's first groups: they are the ones that come out of the previous
+  // segment early (waves 0..3 merge it), and a short segment then does not wait for the late ones
+  const int wslot = FLAT ? (wave + 4) & 7 : wave;
+  if constexpr (PAGED || FLAT) {
+    if (wslot < n_grp)
+      load_group(t0 + (wslot << 6), S0);
+    else
+      S0 = Regs{};
   }
   // ---- prologue: codebook table, query operands --------------------------------------------------
   NSN_STAMP(25);
-  {
-    // thread (code = tid / 2, half = tid % 2) fills eight 16-byte slots of its half row, starting at a
-    // slot that depends on the code so that the 64 stores of a wave spread over all banks
-    const int code = tid >> 1, half = tid & 1;
-    u4v v;
-    if constexpr (SUB == 4)
-      v = u4v{cw_reg.x, cw_reg.y, cw_reg.x, cw_reg.y};
-    else
-      v = u4v{cw_reg.x, cw_reg.y, cw_reg.z, cw_reg.w};
-    const uint32_t row = code * 256 + half * 128;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) lds_write128(row + (((u + code) & 7) << 4), v);
-  }
+  if constexpr (!FLAT) fill_table();
   NSN_STAMP(26);
   if (wave < 4) {  // d1: wave w rotates head w (zeros for a head that this launch does not have)
     const bool has_head = wave < r;
@@ -374,7 +537,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     lds_write32(SM::kQlo + e2 * 2,
                 __builtin_bit_cast(uint32_t, h2v{(_Float16)(y0 - (float)h0), (_Float16)(y1 - (float)h1)}));
   } else {
-    if (wave == 4 && lane < 32) lds_write32(SM::kZero + lane * 4, 0u);
+    if (first_segment && wave == 4 && lane < 32) lds_write32(SM::kZero + lane * 4, 0u);
     const int hh = wave - 4;  // this wave loaded the query of head wave & 3 = hh
     const float x0 = hh < r ? __low2float(q2_raw) : 0.f, x1 = hh < r ? __high2float(q2_raw) : 0.f;
     const float d = wave_sum_all(x0 * half_lo_f(ok_first) + x1 * half_hi_f(ok_first));
@@ -384,10 +547,10 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   __builtin_amdgcn_sched_barrier(0);
   // residual (Sec. 3.2): wave w < 4 of the last live split takes rows [16 w, 16 w + 16); a load instruction
   // covers four consecutive rows (16 lanes x 16 bytes each); rows beyond the capacity are clamped and masked later
-  const bool res_wave = res.k != nullptr && split == n_live - 1 && wave < 4;
+  const bool res_wave = res.k != nullptr && res_here && wave < 4;
   uint4 rk[4], rv[4];
   int res_len = 0;
-  if (res_wave) {
+  auto load_residual_rows = [&]() {
     const int64_t unit_row = (int64_t)(b * g.n_kv_heads + h) * res.capacity;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -395,6 +558,11 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
       rk[u] = *reinterpret_cast<const uint4*>(res.k + (unit_row + row) * kHeadDim + (lane & 15) * 8);
       rv[u] = *reinterpret_cast<const uint4*>(res.v + (unit_row + row) * kHeadDim + (lane & 15) * 8);
     }
+  };
+  if (res_wave) {
+    // (the persistent instance fetches the rows where it stages them: thirty-two registers held from here
+    // to there do not fit beside its other state)
+    if constexpr (!FLAT) load_residual_rows();
     res_len = res.lens[b];
   }
   // the wave's second group goes out behind the first ones of all waves; every later group is requested
@@ -402,9 +570,20 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   // two groups in flight.  The compute unit's address pipeline takes about 28 cycles per 1 KiB load
   // instruction and a wave blocks at a load that cannot be accepted yet: a wave that asks for three groups
   // at once sits at its load instructions while the data of its first group is already in its registers.
-  if (wave + NW < n_grp) load_group(t0 + ((wave + NW) << 6), S1);
+  if (wslot + NW < n_grp)
+    load_group(t0 + ((wslot + NW) << 6), S1);
+  else
+    S1 = Regs{};
   __syncthreads();
   NSN_STAMP(3);
+  if constexpr (FLAT) {
+    // segments are short and start cold: three groups per wave go out before the first is used, and the set
+    // that a group leaves takes the group three rounds on (see process_group)
+    if (wslot + 2 * NW < n_grp)
+      load_group(t0 + ((wslot + 2 * NW) << 6), S2);
+    else
+      S2 = Regs{};
+  }
 
   // B operands of the score contraction (see the header): for tile parity p and k-step s the lane's eight
   // k-slots are channels [32 c + 8 s, +8) of head n % 4: hi part if n / 4 == p, lo part if n / 4 == p + 2,
@@ -538,6 +717,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     const int rl = min(res_len, res.capacity);
     if (rl > 16 * wave) {  // wave-uniform
       const uint32_t sk = SM::kRes + wave * SM::kResWave, sv = sk + 16 * SM::kResKStride;
+      if constexpr (FLAT) load_residual_rows();
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int row = 4 * u + (lane >> 4);  // row of the tile; rows past the valid count are stored as zeros
@@ -668,9 +848,16 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   // A gather batch is always issued two batches ahead of its matrix instructions; scheduling barriers keep
   // the compiler from sinking the gathers next to their uses, which would expose the LDS latency at
   // every one of the 48 matrix instructions of a group.
+  // (inside a stage the matrix instructions go first: the operands they consume are dead before the next
+  // gathers land, so a later batch can take over an earlier one's registers)
+#ifdef NSN_NO_STAGE_SPLIT
+#define STAGE_SPLIT
+#else
+#define STAGE_SPLIT __builtin_amdgcn_sched_barrier(0)
+#endif
   h8 KA[4], KB[4];
   int stamp_it = 0;
-  auto process_group = [&](int gi, const Regs& G, const Regs& Gn, Regs& Gnn) {
+  auto process_group = [&](int gi, Regs& G, const Regs& Gn, Regs& Gnn) {
     const int tg = t0 + (gi << 6);
     // Shift group bookkeeping (wave-uniform)
     const int grp = shift_group(tg);
@@ -698,15 +885,19 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     h4 VA[8], VB[8], VC[8], VD[8];
     __builtin_amdgcn_sched_barrier(0);
     k_contract(c0, KA, D0, D1);
+    STAGE_SPLIT;
     k_gather(c2, G, KC);
     __builtin_amdgcn_sched_barrier(0);
     k_contract(c1, KB, D0, D1);
+    STAGE_SPLIT;
     k_gather(c3, G, KD);
     __builtin_amdgcn_sched_barrier(0);
     k_contract(c2, KC, D0, D1);
+    STAGE_SPLIT;
     v_gather(c0, G, VA);  // the first value-side gathers fly during the softmax arithmetic
     __builtin_amdgcn_sched_barrier(0);
     k_contract(c3, KD, D0, D1);
+    STAGE_SPLIT;
     v_gather(c1, G, VB);
     __builtin_amdgcn_sched_barrier(0);
     // hi + lo columns: lanes n < 8 take tiles 0, 1 from D0, lanes n >= 8 tiles 2, 3 from D1
@@ -740,26 +931,37 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     // d5: out_rot[head][channel] += sum over tokens of weight * codeword channel
     __builtin_amdgcn_sched_barrier(0);
     v_contract(c0, VA, wop);
+    STAGE_SPLIT;
     v_gather(c2, G, VC);
     __builtin_amdgcn_sched_barrier(0);
     v_contract(c1, VB, wop);
+    STAGE_SPLIT;
     v_gather(c3, G, VD);
     __builtin_amdgcn_sched_barrier(0);
     // the group after the next one: requested just before the next one's bytes are first needed (below)
-    if (gi + 2 * NW < n_grp) load_group(t0 + ((gi + 2 * NW) << 6), Gnn);  // wave-uniform
+    if constexpr (FLAT) {  // (this group's bytes have all been used by now)
+      if (gi + 3 * NW < n_grp) load_group(t0 + ((gi + 3 * NW) << 6), G);
+    } else {
+      if (gi + 2 * NW < n_grp)  // wave-uniform
+        load_group(t0 + ((gi + 2 * NW) << 6), Gnn);
+      else
+        Gnn = Regs{};
+    }
     __builtin_amdgcn_sched_barrier(0);
     v_contract(c2, VC, wop);
+    STAGE_SPLIT;
     k_gather(c0, Gn, KA);  // (any bytes are valid table indices: harmless when there is no next group)
     __builtin_amdgcn_sched_barrier(0);
     v_contract(c3, VD, wop);
+    STAGE_SPLIT;
     k_gather(c1, Gn, KB);
     __builtin_amdgcn_sched_barrier(0);
   };
 
   NSN_STAMP(4);
   // ---- main loop: this wave's groups wave, wave + NW, ...; three register sets rotate (in use, next, in flight) ----
-  if (wave < n_grp) {
-    int gi = wave;
+  if (wslot < n_grp) {
+    int gi = wslot;
     k_gather(c0, S0, KA);
     k_gather(c1, S0, KB);
     while (true) {
@@ -809,10 +1011,8 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   NSN_STAMP(14);
 
   // ---- merge the waves: wave i takes head i, a lane channels 2 lane, 2 lane + 1 ------------------
-  if (wave >= r) {
-    NSN_STAMP_FLUSH;
-    return;
-  }
+  [&]() {
+  if (wave >= r) return;
   const int hh = wave;
   float M = -INFINITY, L = 0.f, x0 = 0.f, x1 = 0.f, mm0 = 0.f, mm1 = 0.f;
   {
@@ -840,8 +1040,17 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   NSN_STAMP(15);
   // ---- d6: merge the splits; the last wave to arrive for this query head finishes it -------------
   if (n_live > 1) {
-    float* Ph = partial + ((int64_t)(b * g.n_q_heads + hq0 + hh) * n_splits) * kPartialStride;
-    float* P = Ph + (int64_t)split * kPartialStride;
+    // !FLAT: partial [sequence][query head][split].  FLAT: [run][slot][query head of the kv head]: slot 0 for
+    // the segment that continues a unit begun in an earlier run, slot 1 for the one that begins a unit and
+    // leaves its end to the next run (a run has at most one of each); run c of the unit's runs
+    // first_run .. first_run + n_live - 1 therefore wrote slot 1 if c == first_run, else slot 0.
+    auto partial_of = [&](int s) -> float* {
+      if constexpr (FLAT)
+        return partial + ((int64_t)((first_run + s) * 2 + (s == 0 ? 1 : 0)) * (g.n_q_heads / hkv) + head_off + hh) * kPartialStride;
+      else
+        return partial + ((int64_t)(b * g.n_q_heads + hq0 + hh) * n_splits + s) * kPartialStride;
+    };
+    float* P = partial_of(split);
     auto st2 = [](float* p, float lo, float hi) {  // 8-byte device-scope store (p is 8-byte aligned)
       __hip_atomic_store(reinterpret_cast<unsigned long long*>(p),
                          ((unsigned long long)__float_as_uint(hi) << 32) | __float_as_uint(lo), __ATOMIC_RELAXED,
@@ -863,48 +1072,53 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     // the counter update: measured 7 us + 4 us per launch on the 8 x 8192-token shape.
     __builtin_amdgcn_s_waitcnt(0);
     __builtin_amdgcn_wave_barrier();
-    int* cnt = counters + (b * g.n_q_heads + hq0 + hh);
+    int* cnt = counters + (b * g.n_q_heads + hq0 + hh) * kCounterStrideInts;
     int old = 0;
     if (lane == 0) old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     old = __builtin_amdgcn_readfirstlane(old);
     NSN_STAMP(16);
-    if (old != n_live - 1) {
-      NSN_STAMP_FLUSH;
-      return;
-    }
+    if (old != n_live - 1) return;
     if (lane == 0) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
-    // chunks of eight splits, every load of a chunk issued before its first use; running max across chunks
-    constexpr int SF = 8;
+    // chunks of SF splits, every load of a chunk issued before its first use (a chunk costs one trip to
+    // memory); running max across chunks.  Up to eight live splits take one chunk of eight, more take chunks
+    // of thirty-two (the loop's registers are free by now).
     M = -INFINITY, L = 0.f, x0 = x1 = mm0 = mm1 = 0.f;
-    for (int s0 = 0; s0 < n_live; s0 += SF) {
-      float2 pml[SF], pr[SF], pq[SF];
-#pragma unroll
-      for (int s = 0; s < SF; ++s) {
-        pml[s] = make_float2(-INFINITY, 0.f);
-        pr[s] = pq[s] = make_float2(0.f, 0.f);
-        if (s0 + s < n_live) {  // uniform
-          const float* ps = Ph + (s0 + s) * kPartialStride;
-          pml[s] = ld2(ps + 2 * kHeadDim);
-          pr[s] = ld2(ps + 2 * lane);
-          pq[s] = ld2(ps + kHeadDim + 2 * lane);
-        }
-      }
-      float Mn = M;
-#pragma unroll
-      for (int s = 0; s < SF; ++s) Mn = fmaxf(Mn, pml[s].x);
-      if (Mn > -INFINITY) {
-        const float corr = (M == -INFINITY) ? 0.f : fast_exp2(M - Mn);
-        L *= corr, x0 *= corr, x1 *= corr, mm0 *= corr, mm1 *= corr;
+    auto merge_chunks = [&](auto sfc) {
+      constexpr int SF = decltype(sfc)::value;
+      for (int s0 = 0; s0 < n_live; s0 += SF) {
+        float2 pml[SF], pr[SF], pq[SF];
 #pragma unroll
         for (int s = 0; s < SF; ++s) {
-          const float e = (s0 + s < n_live) ? fast_exp2(pml[s].x - Mn) : 0.f;
-          L = fmaf(e, pml[s].y, L);
-          x0 = fmaf(e, pr[s].x, x0), x1 = fmaf(e, pr[s].y, x1);
-          mm0 = fmaf(e, pq[s].x, mm0), mm1 = fmaf(e, pq[s].y, mm1);
+          pml[s] = make_float2(-INFINITY, 0.f);
+          pr[s] = pq[s] = make_float2(0.f, 0.f);
+          if (s0 + s < n_live) {  // uniform
+            const float* ps = partial_of(s0 + s);
+            pml[s] = ld2(ps + 2 * kHeadDim);
+            pr[s] = ld2(ps + 2 * lane);
+            pq[s] = ld2(ps + kHeadDim + 2 * lane);
+          }
         }
-        M = Mn;
+        float Mn = M;
+#pragma unroll
+        for (int s = 0; s < SF; ++s) Mn = fmaxf(Mn, pml[s].x);
+        if (Mn > -INFINITY) {
+          const float corr = (M == -INFINITY) ? 0.f : fast_exp2(M - Mn);
+          L *= corr, x0 *= corr, x1 *= corr, mm0 *= corr, mm1 *= corr;
+#pragma unroll
+          for (int s = 0; s < SF; ++s) {
+            const float e = (s0 + s < n_live) ? fast_exp2(pml[s].x - Mn) : 0.f;
+            L = fmaf(e, pml[s].y, L);
+            x0 = fmaf(e, pr[s].x, x0), x1 = fmaf(e, pr[s].y, x1);
+            mm0 = fmaf(e, pq[s].x, mm0), mm1 = fmaf(e, pq[s].y, mm1);
+          }
+          M = Mn;
+        }
       }
-    }
+    };
+    if (n_live <= 8)
+      merge_chunks(std::integral_constant<int, 8>{});
+    else
+      merge_chunks(std::integral_constant<int, NSN_SF>{});
   }
   NSN_STAMP(17);
   // one inverse Hadamard per head (H is its own inverse), across the wave's lanes in registers
@@ -923,8 +1137,17 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   if (L > 0.f) o2 = make_float2((x0 * (float)kInvSqrtD + mm0) / L, (x1 * (float)kInvSqrtD + mm1) / L);
   *reinterpret_cast<float2*>(out + (int64_t)(b * g.n_q_heads + hq0 + hh) * kHeadDim + 2 * lane) = o2;
   NSN_STAMP(18);
+  }();
+  if constexpr (!FLAT) break;
+  if (run_pos >= run_end) break;
+  b = nb, h = nh;  // the next unit (its first row and length are on their way or here)
+  first_segment = false;
+  NSN_STAMP_NEXT_SEGMENT;
+  }  // segments
+  NSN_STAMP_WALL(31);
   NSN_STAMP_FLUSH;
 }
+
 
 #ifdef NSN_TILE_TIMING
 extern "C" int nsn_debug_tile_timing(long long* host64) {
@@ -932,7 +1155,7 @@ extern "C" int nsn_debug_tile_timing(long long* host64) {
 }
 #endif
 
-template <int SUB, int NW, bool POW2, bool PAGED>
+template <int SUB, int NW, bool POW2, bool PAGED, bool FLAT>
 static int launch_one(const Geometry& g, const void* codebook, const void* q, const CacheView& kv, const CacheView& vv,
                       const int32_t* seq_lens, int batch, int max_seq_len, float scale, int n_splits, void* workspace,
                       size_t counter_bytes, const ResidualView& res, int head_off, int r_pass, float* out,
@@ -943,22 +1166,33 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
     // the gathers address the codebook table by absolute LDS address: it must start at 0, i.e. the
     // kernel may not own any static LDS in front of its dynamic block
     hipFuncAttributes fa;
-    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(dec_tile_kernel<SUB, NW, POW2, PAGED>)) != hipSuccess ||
-        fa.sharedSizeBytes != 0)
-      return (int)NSN_ERR_HIP;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(dec_tile_kernel<SUB, NW, POW2, PAGED>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)SM::kBytesRes) != hipSuccess)
+    const void* fn = reinterpret_cast<const void*>(dec_tile_kernel<SUB, NW, POW2, PAGED, FLAT>);
+    if (hipFuncGetAttributes(&fa, fn) != hipSuccess || fa.sharedSizeBytes != 0) return (int)NSN_ERR_HIP;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SM::kBytesRes) != hipSuccess)
       return (int)NSN_ERR_HIP;
     return (int)NSN_OK;
   }();  // initialised once, thread-safe
   if (attr_rc != NSN_OK) return attr_rc;
-  const int per = (((max_seq_len + n_splits - 1) / n_splits) + 63) & ~63;
   int* counters = static_cast<int*>(workspace);
   float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + counter_bytes);
-  const dim3 grid(n_splits, g.n_kv_heads, batch);
-  dec_tile_kernel<SUB, NW, POW2, PAGED><<<grid, NW * 64, smem, stream>>>(g, (const __half*)codebook, (const __half*)q, kv, vv,
-                                                            seq_lens, scale * 1.44269504088896340736f, n_splits, per,
-                                                            partial, counters, res, head_off, r_pass, out);
+  int per = 0;
+  dim3 grid;
+  if constexpr (FLAT) {
+    // one workgroup per compute unit, never more runs than the workspace has partial slots for
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+      return NSN_ERR_HIP;
+    const int64_t groups_max = (int64_t)batch * g.n_kv_heads * max(1, (max_seq_len + 63) / 64);
+    n_splits = (int)std::min<int64_t>(std::min(n_cu, kFlatRunsMax), groups_max);
+    grid = dim3(n_splits, 1, 1);
+  } else {
+    per = (((max_seq_len + n_splits - 1) / n_splits) + 63) & ~63;
+    grid = dim3(n_splits, g.n_kv_heads, batch);
+  }
+  dec_tile_kernel<SUB, NW, POW2, PAGED, FLAT><<<grid, NW * 64, smem, stream>>>(
+      g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens, batch, scale * 1.44269504088896340736f, n_splits,
+      per, partial, counters, res, head_off, r_pass, out);
   return hipGetLastError() == hipSuccess ? NSN_OK : NSN_ERR_HIP;
 }
 
@@ -981,13 +1215,21 @@ int decode_tile_launch(const nsn_shape& s, const void* codebook, const void* q, 
 #define NSN_TILE_ARGS \
   g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, counter_bytes, res, head_off, r, out, stream
     const bool pow2 = (g.group_size <= 0 || g.group_shift >= 0) && (!g.paged || g.page_shift >= 0);
-    auto with_flags = [&](auto sub) {
+    auto with_flags = [&](auto sub, auto flat) {
       constexpr int kSub = decltype(sub)::value;
+      constexpr bool kFlat = decltype(flat)::value;
       if (g.paged)
-        return pow2 ? tile::launch_one<kSub, 8, true, true>(NSN_TILE_ARGS) : tile::launch_one<kSub, 8, false, true>(NSN_TILE_ARGS);
-      return pow2 ? tile::launch_one<kSub, 8, true, false>(NSN_TILE_ARGS) : tile::launch_one<kSub, 8, false, false>(NSN_TILE_ARGS);
+        return pow2 ? tile::launch_one<kSub, 8, true, true, kFlat>(NSN_TILE_ARGS)
+                    : tile::launch_one<kSub, 8, false, true, kFlat>(NSN_TILE_ARGS);
+      return pow2 ? tile::launch_one<kSub, 8, true, false, kFlat>(NSN_TILE_ARGS)
+                  : tile::launch_one<kSub, 8, false, false, kFlat>(NSN_TILE_ARGS);
     };
-    const int rc = s.sub_dim == 4 ? with_flags(std::integral_constant<int, 4>{}) : with_flags(std::integral_constant<int, 8>{});
+    auto with_sub = [&](auto flat) {
+      return s.sub_dim == 4 ? with_flags(std::integral_constant<int, 4>{}, flat)
+                            : with_flags(std::integral_constant<int, 8>{}, flat);
+    };
+    // n_splits == kSplitsFlat: the persistent instance that cuts the list of all groups into equal runs
+    const int rc = n_splits == kSplitsFlat ? with_sub(std::true_type{}) : with_sub(std::false_type{});
 #undef NSN_TILE_ARGS
     if (rc != NSN_OK) return rc;
   }

@@ -32,6 +32,7 @@ struct ResidualView {
 };
 
 constexpr int kSignCodes = 65536;  // n_codes value that selects the sign + index format
+constexpr int kCounterStrideInts = 64;  // decode arrival counters: one per 256-byte line
 
 // Table of nsn_build_rope_table (byte offsets): fp16 hi / lo of (cos, sin)(j * inv_freq[i]) as
 // rows [j][128] (64 cosines, then 64 sines), the same angles in fp64 as (cos, sin) pairs [j][i],

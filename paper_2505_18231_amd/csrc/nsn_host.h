@@ -53,6 +53,10 @@ int encode_launch(const nsn_shape& s, const void* codebook, const void* k_in, co
                   const int32_t* seq_start, const int32_t* n_new, int batch, int freeze_means,
                   const nsn_cache& kc, const nsn_cache& vc, void* workspace, hipStream_t stream);
 
+// A resolved split count of kSplitsFlat selects the tiled-layout kernel's persistent instance: one workgroup
+// per compute unit (at most kFlatRunsMax), each taking an equal run of the list of all 64-token groups.
+constexpr int kSplitsFlat = 0;
+constexpr int kFlatRunsMax = 256;
 int decode_pick_splits(const nsn_shape& s, int batch, int max_seq_len, int requested);
 bool decode_use_mfma(const nsn_shape& s);
 int decode_mfma_splits(const nsn_shape& s, int batch, int max_seq_len, int requested);

@@ -56,6 +56,7 @@ def gpu_out(api, kc, vc, q, lens, hq, hkv, sub, G, cb, max_len, scale, page=0, n
     return out.cpu().numpy().astype(np.float64)
 
 
+FLAT_LENS = [0, 1, 64, 65, 130, 300, 17, 256, 511, 77, 128, 5, 200, 333, 90, 400]
 CASES = [
     # name, batch, hq, hkv, lens, sub, G, page, splits
     ("tiny-1bit", 1, 1, 1, [1024], 8, 0, 0, 0),
@@ -73,6 +74,12 @@ CASES = [
     ("long-2bit-eleven-waves", 2, 4, 1, [9000, 4100], 4, 64, 0, 2),   # splits of >= 4096 tokens: the 11-wave instance
     ("long-2bit-eleven-waves-mha", 1, 1, 1, [5000], 4, 0, 0, 1),
     ("long-1bit-eleven-waves", 2, 4, 1, [9000, 4100], 8, 64, 0, 2),   # the 8-dim form of the 11-wave instance
+    # 128 (sequence, kv head) units and automatic splitting: the persistent instance (equal runs of the list of
+    # all 64-token groups; short units share a run, long ones are cut by run boundaries; empty sequences)
+    ("flat-ragged-2bit", 16, 16, 8, FLAT_LENS, 4, 64, 0, 0),
+    ("flat-paged-1bit", 16, 8, 8, FLAT_LENS[5:] + FLAT_LENS[:5], 8, 0, 256, 0),
+    ("flat-gqa8-2bit-onegroup", 16, 64, 8, FLAT_LENS[::-1], 4, 0, 0, 0),
+    ("flat-long-units-1bit", 16, 32, 8, [2100, 0, 70, 1500] + [40] * 12, 8, 128, 0, 0),
 ]
 
 

@@ -29,6 +29,12 @@ CASES = [
     ("gqa8-two-launches", 16, 2, [384, 64], [33, 64], 4, 64, 0, 0),   # 8 query heads per kv head
     ("gqa5-two-launches", 5, 1, [130], [7], 8, 0, 0, 2),              # 4 + 1
     ("long-eleven-waves", 4, 1, [4608, 64], [64, 3], 4, 64, 0, 1),    # 4096+ token split: 11 main waves + the residual wave
+    # 128 units, automatic splitting: the persistent instance; the segment with a unit's last group takes the
+    # residual, also for units without coded tokens
+    ("flat-ragged-2bit", 32, 8, [0, 1, 64, 65, 130, 300, 17, 256, 511, 77, 128, 5, 200, 333, 90, 400],
+     [3, 64, 0, 17, 33, 64, 1, 0, 20, 5, 64, 63, 2, 48, 0, 9], 4, 64, 0, 0),
+    ("flat-paged-1bit-gqa8", 64, 8, [700, 0, 64, 65, 130, 900, 17, 256, 511, 77, 128, 5, 200, 333, 90, 0],
+     [64, 0, 0, 17, 33, 64, 1, 0, 20, 5, 64, 63, 2, 48, 0, 9], 8, 0, 256, 0),
 ]
 
 

@@ -74,8 +74,8 @@ def test_pack_unpack_roundtrip():
 
 def test_shape_validation_and_error_text(L):
     good = api.make_shape(4, 32, 8, 8192, 64)
-    # 256 arrival counters (one per sequence and query head) + one fp32 partial of 258 floats per (head, split)
-    assert api.nsn_workspace_bytes(good, api.NSN_OP_DECODE, 8, 0, 4) == 8 * 32 * 4 + 8 * 32 * 4 * 258 * 4
+    # 256 arrival counters (one 256-byte line per sequence and query head) + one fp32 partial of 258 floats per (head, split)
+    assert api.nsn_workspace_bytes(good, api.NSN_OP_DECODE, 8, 0, 4) == 8 * 32 * 256 + 8 * 32 * 4 * 258 * 4
     assert api.nsn_workspace_bytes(good, api.NSN_OP_ENCODE, 8, 8192) == 8 * 8 * 2 * 128 * 128 * 8
     assert api.nsn_max_groups(good) == 128
     assert api.nsn_max_groups(api.make_shape(8, 1, 1, 1024, 0)) == 1
