@@ -30,8 +30,8 @@ __device__ __forceinline__ void static_for_pow2(F&& f) {
 
 // ---------------------------------------------------------------------------------------
 // Stage A: first Normalize scale per token, partial channel sums of the normalised tokens.
-// grid (chunk, kv_head * 2 + tensor, sequence), block 256 = 4 waves; a wave owns one token
-// at a time, a lane owns two channels.
+// grid (chunk, kv_head * 2 + tensor, sequence), block 256 = 4 waves; a wave takes four tokens at a
+// time (sixteen lanes per token, a lane owns eight consecutive channels: one 16-byte load).
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void enc_stats_kernel(Geometry g, const __half* __restrict__ k_in,
                                                         const __half* __restrict__ v_in, int max_new,
@@ -41,39 +41,78 @@ __global__ __launch_bounds__(256) void enc_stats_kernel(Geometry g, const __half
                                                         int chunk_tokens, int n_chunks, __half* __restrict__ ws_b) {
   const int chunk = blockIdx.x, h = blockIdx.y >> 1, tensor = blockIdx.y & 1, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = lane >> 4, col = lane & 15;  // token of the wave's four, channels [8 col, 8 col + 8)
   const CacheView& cv = tensor ? vc : kc;
   const __half* in = (tensor ? v_in : k_in) + ((int64_t)(b * g.n_kv_heads + h) * max_new) * kHeadDim;
   __half* wsb = ws_b + ((int64_t)(b * g.n_kv_heads + h) * 2 + tensor) * max_new;  // side_bits = 4 only
   const int start = seq_start[b];
-  const int count = min(n_new[b], max_new);
+  const int count = min(min(n_new[b], max_new), max_len - start);  // tokens that have a place in the cache
   const int t_end = min((chunk + 1) * chunk_tokens, count);
 
-  double acc0 = 0.0, acc1 = 0.0;
-  for (int t = chunk * chunk_tokens + wave; t < t_end; t += 4) {
-    const int pos = start + t;
-    if (pos >= max_len) break;
-    const __half2 xv = *reinterpret_cast<const __half2*>(in + (int64_t)t * kHeadDim + 2 * lane);
-    const double x0 = (double)__low2float(xv), x1 = (double)__high2float(xv);
-    const double ss = xor_sum_w<64>(x0 * x0 + x1 * x1);
-    const double s1 = sqrt(ss) / kSqrtD;
+  double acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.0;
+  // four steps of loads in flight
+  auto fetch = [&](int t) -> uint4 {
+    return t < t_end ? *reinterpret_cast<const uint4*>(in + (int64_t)t * kHeadDim + 8 * col) : make_uint4(0u, 0u, 0u, 0u);
+  };
+  int t = chunk * chunk_tokens + 4 * wave + row;
+  uint4 cur = fetch(t), nx1 = fetch(t + 16), nx2 = fetch(t + 32), nx3 = fetch(t + 48);
+  for (; t - row < t_end; t += 16) {  // (t - row: the same bound for the wave's four tokens)
+    const uint4 raw = cur;
+    cur = nx1, nx1 = nx2, nx2 = nx3;
+    nx3 = fetch(t + 64);
+    const __half* xh = reinterpret_cast<const __half*>(&raw);
+    double x[8], ss = 0.0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      x[i] = (double)__half2float(xh[i]);
+      ss = fma(x[i], x[i], ss);
+    }
+    ss = xor_sum_w<16>(ss);
+    // s1 = sqrt(ss / d) and 1 / fp16(s1) by the hardware estimates and Newton steps (ss is a sum of squares
+    // of fp16 values: zero or far inside the fp64 range, so no scaling is needed).  Both are within an fp64
+    // unit or two of the correctly rounded values; what is stored is rounded to fp16.
+    const double sd = ss * (1.0 / kHeadDim);
+    double s1 = 0.0;
+    if (sd != 0.0) {
+      const double y = __builtin_amdgcn_rsq(sd);
+      double gq = sd * y, hq = 0.5 * y;
+      const double r0 = fma(-hq, gq, 0.5);
+      gq = fma(gq, r0, gq), hq = fma(hq, r0, hq);
+      s1 = fma(fma(-gq, gq, sd), hq, gq);
+    }
     const __half b16 = f64_to_f16(s1);
     const double bb = (double)__half2float(b16);
+    double rb = 0.0;  // (tokens past the end arrive as zeros and add nothing)
     if (bb != 0.0) {
-      acc0 += x0 / bb;
-      acc1 += x1 / bb;
+      rb = __builtin_amdgcn_rcp(bb);
+      rb = fma(fma(-bb, rb, 1.0), rb, rb);
+      rb = fma(fma(-bb, rb, 1.0), rb, rb);
     }
-    if (lane == 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = fma(x[i], rb, acc[i]);
+    if (col == 0 && t < t_end) {
       if (g.dq) {
         wsb[t] = b16;
       } else {
+        const int pos = start + t;
         const int64_t base = unit_token_base(g, cv.block_table, b, h, pos);
         reinterpret_cast<__half*>(cv.norms)[2 * (base + token_in_unit(g, pos)) + 1] = b16;
       }
     }
   }
+  // the wave's four token rows, then the four waves
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    acc[i] += xor_lane<16>(acc[i]);
+    acc[i] += xor_lane<32>(acc[i]);
+  }
   __shared__ double red[4][kHeadDim];
-  red[wave][2 * lane] = acc0;
-  red[wave][2 * lane + 1] = acc1;
+  if (row == 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) red[wave][8 * col + i] = acc[i];
+  }
   __syncthreads();
   if (threadIdx.x < kHeadDim) {
     const int c = threadIdx.x;
@@ -307,17 +346,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(SUB == 4 ? 
       if (valid && jj == 0 && !g.dq) reinterpret_cast<__half*>(cv.norms)[2 * (base + tin) + 1] = b16f;
     }
     const double bb = (double)__half2float(b16f);
+    // one division per token instead of one per channel: x * (1 / b) is within one fp64 unit of x / b, eight
+    // decimal orders below anything the fp16 results and the code decisions can see
+    const double rb = bb != 0.0 ? 1.0 / bb : 0.0;
     double v[SUB];
 #pragma unroll
-    for (int i = 0; i < SUB; ++i) v[i] = valid ? (bb != 0.0 ? xs[i] / bb : 0.0) - os[i] : 0.0;
+    for (int i = 0; i < SUB; ++i) v[i] = valid ? xs[i] * rb - os[i] : 0.0;
     // second Normalize
     double ss = 0.0;
 #pragma unroll
     for (int i = 0; i < SUB; ++i) ss += v[i] * v[i];
     ss = xor_sum_w<J>(ss);
-    const double s2 = sqrt(ss) / kSqrtD;
+    const double s2 = sqrt(ss) * kInvSqrtD;  // (feeds the stored scale a, compared to one fp16 unit)
+    const double r2 = (s2 != 0.0) ? 1.0 / s2 : 0.0;
 #pragma unroll
-    for (int i = 0; i < SUB; ++i) v[i] = (s2 != 0.0) ? v[i] / s2 : 0.0;
+    for (int i = 0; i < SUB; ++i) v[i] *= r2;
     if constexpr (ROPE) {
       if (tensor == 0) {  // keys only; the partner channel c ^ 64 lives in lane jj ^ (J / 2)
         // cos / sin of position * inv_freq[pair] from the fp64 table: block part and in-block part

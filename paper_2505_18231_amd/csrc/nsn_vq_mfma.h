@@ -7,7 +7,7 @@
 // [y_hi | y_lo | 1 1 yn_hi yn_lo 0..].  Codewords are fp16 values, so -2c is exact; y, ||c||^2 and
 // ||y||^2 are split into fp16 hi + lo parts (about 22 bits).  D > 0, so its bit pattern orders
 // like an integer: the low 4 bits are replaced by the row slot and the best two keys are kept
-// with one min and one med3 per value.  If the runner-up is within the error window of the best
+// with a min3, a med3 and a min per pair of values.  If the runner-up is within the error window of the best
 // (key granularity + fp32 rounding of the contraction), the decision is retaken in fp64 among the
 // codewords inside that window, so the result equals the fp64 exhaustive search of the
 // vector-ALU form.
@@ -147,11 +147,17 @@ __device__ inline int vq_search_mfma(const VqTables<SUB>& T, const MfmaCodebook<
       uint32_t& m2r = (m & 1) ? mb2 : ma2;
       int& blkr = (m & 1) ? blkb : blka;
       const uint32_t prev = m1r;
+      // two keys at a time: the smallest of {best, a, b} is the new best, and the runner-up of everything
+      // seen so far is the smaller of the old runner-up and the median of {best, a, b} (five instructions
+      // per pair: two index insertions, min3, med3, min)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const uint32_t u = (__float_as_uint(d[r]) & 0xFFFFFFF0u) | (uint32_t)r;
-        m2r = __float_as_uint(__builtin_amdgcn_fmed3f(__uint_as_float(m1r), __uint_as_float(m2r), __uint_as_float(u)));
-        m1r = min(m1r, u);
+      for (int r = 0; r < 16; r += 2) {
+        const uint32_t ua = (__float_as_uint(d[r]) & 0xFFFFFFF0u) | (uint32_t)r;
+        const uint32_t ub = (__float_as_uint(d[r + 1]) & 0xFFFFFFF0u) | (uint32_t)(r + 1);
+        const uint32_t mid = __float_as_uint(
+            __builtin_amdgcn_fmed3f(__uint_as_float(m1r), __uint_as_float(ua), __uint_as_float(ub)));
+        m2r = min(m2r, mid);
+        m1r = min(m1r, min(ua, ub));
       }
       blkr = (m1r < prev) ? m : blkr;
     }
