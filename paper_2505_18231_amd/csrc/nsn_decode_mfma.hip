@@ -30,6 +30,10 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int kPartialStrideM = 2 * kHeadDim + 2;  // rotated acc, mean-term acc, m (log2 units), l
 constexpr float kLazyMaxLog2 = 5.0f;               // rescale only when a score beats the running max by 2^5
+// The fp16 softmax weights are p a^v 2^10 / A with A a running power of two >= every a^v seen so far: they
+// lie in [0, 2^15] whatever the scale of the values is (the first Normalize of Sec. 3.2 keeps every token
+// norm apart, so attention must not depend on it either); the accumulators are in units of A / 2^10.
+constexpr float kWeightScaleM = 1024.0f;
 constexpr int kTableBytes = 65536;
 
 template <int N, typename F>
@@ -738,9 +742,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
 
   // d3/d4: scores in log2 units, lazy running max, weights.  Returns the fp16 weights as the
   // value-side A operand: lane i of a quad holds head i, the quad's four tokens.
+  float a_run = 0.f, w_scale = 0.f;  // A (0 = no token yet) and 2^10 / A, the same in every lane
   auto softmax_step = [&](const f4& d0, const f4& d1, bool valid, float a_k, float b_k, float a_v, float b_v) -> h4 {
     float s[4], w[4];
-    bool need = false;
+    bool need = a_v > a_run;
 #pragma unroll
     for (int i = 0; i < R; ++i) {
       const float dot = PACK ? (d0[i] + d0[R + i]) + (d1[i] + d1[R + i]) : d0[i] + d1[i];
@@ -748,6 +753,14 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       need = need || (s[i] - m_run[i] > kLazyMaxLog2);
     }
     if (__any(need)) {
+      // A: the next power of two >= the largest a^v of the wave (kept once it is large enough)
+      const float amax_w = wave_max_u(a_v);
+      float a_new = a_run;
+      if (amax_w > a_run) a_new = __uint_as_float((__float_as_uint(amax_w) + 0x007fffffu) & 0x7f800000u);
+      const float a_inv = (a_new > 0.f) ? __builtin_amdgcn_rcpf(a_new) : 0.f;  // exact: a power of two
+      const float a_ratio = a_run * a_inv;
+      a_run = a_new;
+      w_scale = kWeightScaleM * a_inv;
 #pragma unroll
       for (int i = 0; i < R; ++i) {
         const float m_new = fmaxf(m_run[i], wave_max_u(s[i]));
@@ -755,8 +768,9 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
         l_run[i] *= corr;
         beta[i] *= corr;
         cf[i] *= corr;
+        const float corr_a = corr * a_ratio;
 #pragma unroll
-        for (int c = 0; c < SUB; ++c) acc[c][i] *= corr;
+        for (int c = 0; c < SUB; ++c) acc[c][i] *= corr_a;
         m_run[i] = m_new;
       }
     }
@@ -767,7 +781,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       const float p = fast_exp2(s[i] - m_run[i]);  // 0 for masked lanes
       l_run[i] += p;
       beta[i] = fmaf(p, b_v, beta[i]);
-      w[i] = p * a_v;
+      w[i] = p * (a_v * w_scale);
     }
     quad_transpose(w, lane);
     h4 wop;
@@ -1109,7 +1123,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     for (int i = 0; i < R; ++i)
 #pragma unroll
       for (int c = 0; c < SUB; ++c) {
-        float v = acc_res[c][i];
+        float v = acc_res[c][i] * (a_run * (1.0f / kWeightScaleM));
         v += xor_lane<32>(v);
         if constexpr (NPART == 4) v += xor_lane<16>(v);
         if (lane < LV) sm_accm[wave][i][lane * SUB + c] += v;
@@ -1122,12 +1136,14 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   __syncthreads();  // every wave is done gathering from the table
   float* racc = reinterpret_cast<float*>(sm_table);  // [NW][NPART][4][128]; the tail follows it
   if (main_wave) {  // the residual wave has no rotated-domain sum
+    const float acc_unit = a_run * (1.0f / kWeightScaleM);
 #pragma unroll
     for (int i = 0; i < R; ++i)
 #pragma unroll
       for (int c4 = 0; c4 < SUB / 4; ++c4)
         *reinterpret_cast<float4*>(&racc[((wave * NPART + lane / LV) * 4 + i) * kHeadDim + (lane % LV) * SUB + 4 * c4]) =
-            make_float4(acc[4 * c4][i], acc[4 * c4 + 1][i], acc[4 * c4 + 2][i], acc[4 * c4 + 3][i]);
+            make_float4(acc[4 * c4][i] * acc_unit, acc[4 * c4 + 1][i] * acc_unit, acc[4 * c4 + 2][i] * acc_unit,
+                        acc[4 * c4 + 3][i] * acc_unit);
   }
 #pragma unroll
   for (int i = 0; i < R; ++i)

@@ -36,7 +36,7 @@ CASES = [
 ]
 
 
-def _build(seed, hkv, lens, G, cb, page):
+def _build(seed, hkv, lens, G, cb, page, v_mul=1.0):
     batch = len(lens)
     max_len = ((max(max(lens), 1) + 255) // 256) * 256
     bt = synth.shuffled_page_table(seed, batch, max_len // page) if page else None
@@ -46,7 +46,8 @@ def _build(seed, hkv, lens, G, cb, page):
         for h in range(hkv):
             if lens[b]:
                 kc.put_unit(b, h, O.encode(synth.make_k(seed, b, h, lens[b]), cb, G, sign_format=True))
-                vc.put_unit(b, h, O.encode(synth.make_v(seed, b, h, lens[b]), cb, G, sign_format=True))
+                v = (synth.make_v(seed, b, h, lens[b]).astype(np.float32) * np.float32(v_mul)).astype(np.float16)
+                vc.put_unit(b, h, O.encode(v, cb, G, sign_format=True))
     return kc, vc, max_len
 
 
@@ -78,6 +79,34 @@ def test_sign_format_decode_matches_oracle(gpu_api, magnitude_codebook, name, hq
                                      vc.unit_dict(b, h, lens[b]), cb, scale, G, sign_format=True)
             worst = max(worst, helpers.max_rel_err(out[b, h * r:(h + 1) * r], ref))
     print(f"  max rel err {worst:.3e}", flush=True)
+    assert worst < TOL, worst
+
+
+@pytest.mark.parametrize("log2_mul", [-12, 9])
+def test_sign_format_value_scale_does_not_change_the_accuracy(gpu_api, magnitude_codebook, log2_mul):
+    """Values of size 2^-12 or 2^9 (the first Normalize of Sec. 3.2 stores every token norm on its own):
+    the kernel that serves this format keeps its fp16 softmax weights free of the value scale too."""
+    import torch
+    api, cb = gpu_api, magnitude_codebook
+    hq, hkv, lens, G = 8, 2, [900, 130], 64
+    batch, r, seed, scale = len(lens), hq // hkv, 733, 1.0 / math.sqrt(128)
+    kc, vc, max_len = _build(seed, hkv, lens, G, cb, 0, v_mul=2.0 ** log2_mul)
+    q = synth.make_q(seed, batch, hq)
+    shape = api.make_shape(8, hq, hkv, max_len, G, 0, sign_format=True)
+    cbd = torch.from_numpy(cb.astype(np.float16)).cuda()
+    out = api.nsn_decode_attention(shape, cbd, torch.from_numpy(q).cuda(), kc.to_device(api, shape),
+                                   vc.to_device(api, shape), torch.tensor(lens, dtype=torch.int32).cuda(),
+                                   max(lens), scale, 3)
+    torch.cuda.synchronize()
+    out = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(out).all()
+    worst = 0.0
+    for b in range(batch):
+        for h in range(hkv):
+            ref = O.decode_attention(q[b, h * r:(h + 1) * r].astype(np.float64), kc.unit_dict(b, h, lens[b]),
+                                     vc.unit_dict(b, h, lens[b]), cb, scale, G, sign_format=True)
+            worst = max(worst, helpers.max_rel_err(out[b, h * r:(h + 1) * r], ref))
+    print(f"  V x 2^{log2_mul}: max rel err {worst:.3e}", flush=True)
     assert worst < TOL, worst
 
 
