@@ -23,19 +23,16 @@
 //     the accumulators are out_rot[head][channel] partial sums per 16-lane group.
 //   * the fp16 weights are p a^v / A with A a power of two >= every a^v seen so far (rescaled lazily like
 //     the running max), so the value contraction does not depend on the scale of V.
-// One workgroup per (split, kv head, sequence), 8 waves, one 64 KiB codebook table replicated per LDS
-// bank group (conflict-free gathers: one v_perm_b32 forms the address from a code byte).  Cache bytes
-// are fetched two groups ahead into rotating register sets.  The fp16 residual (Sec. 3.2) is one more
+// One workgroup per (split, kv head, sequence) - or, for batches of 128 units and more, one persistent
+// workgroup per compute unit that takes an equal run of all groups (see the kernel's FLAT flag) - 8 waves,
+// one 64 KiB codebook table replicated per LDS bank group (conflict-free gathers: one v_perm_b32 forms the
+// address from a code byte).  Cache bytes are fetched two groups ahead into rotating register sets.  The fp16 residual (Sec. 3.2) is one more
 // group whose four 16-token tiles are taken by waves 0..3 of the last split before their own groups (a
 // quarter group each: a ninth wave would cap every wave at 168 registers, and a whole extra group on one
 // wave would lengthen a four-group loop by a quarter).  Waves merge through LDS once; splits
 // merge through fp32 partials in the workspace, the last wave to arrive (integer counter per query
 // head) finishing the head: merge, one inverse Hadamard in registers, mean-vector term, output.
 #include <algorithm>
-#define NSN_PAGE_VMEM
-#ifndef NSN_SF
-#define NSN_SF 32
-#endif
 #include <type_traits>
 
 #include "nsn_host.h"
@@ -56,65 +53,6 @@ constexpr int kPartialStride = 2 * kHeadDim + 2;  // rotated acc, mean-term acc,
 constexpr float kLazyMaxLog2 = 5.0f;              // rescale only when a score beats the running max by 2^5
 constexpr float kWeightScale = 1024.0f;           // fp16 weights carry 2^10 / A: small weights stay normal numbers
 constexpr int kTableBytes = 65536;
-
-#ifdef NSN_TILE_TIMING
-// stamps stay in scalar registers until the wave leaves (a store at the stamp itself would queue behind
-// the wave's outstanding loads and shift everything after it)
-__device__ long long g_tile_timing[2 * 32];
-#ifndef NSN_STAMP_RUN
-#define NSN_STAMP_RUN 100
-#endif
-#define NSN_STAMP_SPLIT \
-  (gridDim.y == 1 ? blockIdx.x == NSN_STAMP_RUN : (blockIdx.x == 1 && blockIdx.y == 3 && blockIdx.z == (gridDim.z > 2 ? 2 : 0)))
-#define NSN_STAMP_DECL   \
-  long long ts_[32] = {}; \
-  bool stamp_on_ = true
-#ifdef NSN_STAMP_FIRST
-#define NSN_STAMP_NEXT_SEGMENT stamp_on_ = false
-#else
-#define NSN_STAMP_NEXT_SEGMENT \
-  do {                         \
-  } while (0)
-#endif
-#define NSN_STAMP(slot) \
-  if (stamp_on_) ts_[slot] = clock64()
-#define NSN_STAMP_WALL(slot) ts_[slot] = wall_clock64()
-#define NSN_STAMP_IT(it)                                  \
-  do {                                                    \
-    if (!stamp_on_) break;                                \
-    if ((it) == 0) ts_[5] = clock64();                    \
-    else if ((it) == 1) ts_[6] = clock64();               \
-    else if ((it) == 2) ts_[7] = clock64();               \
-    else if ((it) == 3) ts_[8] = clock64();               \
-    else ts_[9] = clock64();                              \
-  } while (0)
-#define NSN_STAMP_FLUSH                                                                              \
-  do {                                                                                               \
-    if (NSN_STAMP_SPLIT && (threadIdx.x & 63) == 0 && \
-        ((threadIdx.x >> 6) == 0 || (threadIdx.x >> 6) == 5)) {                                      \
-      for (int i_ = 0; i_ < 32; ++i_) g_tile_timing[((threadIdx.x >> 6) == 0 ? 0 : 32) + i_] = ts_[i_]; \
-    }                                                                                                \
-  } while (0)
-#else
-#define NSN_STAMP_DECL \
-  do {                 \
-  } while (0)
-#define NSN_STAMP(slot) \
-  do {                  \
-  } while (0)
-#define NSN_STAMP_IT(it) \
-  do {                   \
-  } while (0)
-#define NSN_STAMP_FLUSH \
-  do {                  \
-  } while (0)
-#define NSN_STAMP_WALL(slot) \
-  do {                       \
-  } while (0)
-#define NSN_STAMP_NEXT_SEGMENT \
-  do {                         \
-  } while (0)
-#endif
 
 template <int N, typename F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -304,9 +242,6 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   int split = FLAT ? 0 : blockIdx.x, h = FLAT ? 0 : blockIdx.y, b = FLAT ? 0 : blockIdx.z;
   int t0 = split * per;
   int64_t mean_base = (int64_t)(b * g.n_kv_heads + h) * g.n_groups_max;
-  NSN_STAMP_DECL;
-  NSN_STAMP(0);
-  NSN_STAMP_WALL(30);
 
   // ---- loads that do not depend on the sequence length go out first ------------------------------
   // (all unconditional, so that the wait for the codebook can leave the later ones in flight)
@@ -400,13 +335,9 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     if constexpr (!PAGED) return (int64_t)(b * g.n_kv_heads + h) * g.page_tokens + tg;
     const int page = POW2 ? tg >> g.page_shift : tg / g.page_tokens;
     const int tin = POW2 ? tg & (g.page_tokens - 1) : tg % g.page_tokens;
-#ifdef NSN_PAGE_VMEM
     // the table entry comes through the vector memory path: a scalar load would share its counter with the
     // LDS gathers in flight, and the wait for it would drain them
     const int phys = __builtin_amdgcn_readfirstlane(block_table[(int64_t)b * g.pages_per_seq + page + lane_zero]);
-#else
-    const int phys = block_table[(int64_t)b * g.pages_per_seq + page];
-#endif
     return ((int64_t)phys * g.n_kv_heads + h) * g.page_tokens + tin;
   };
   auto shift_group = [&](int tg) -> int {
@@ -487,7 +418,6 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     // the cache when the split lies beyond it: then it is never processed)
     if constexpr (!PAGED) load_group(min(t0 + (wave << 6), cap_tokens - 64), S0);  // (wslot == wave here)
     len = seq_lens[b];
-    NSN_STAMP(1);
     // Splits that lie wholly beyond this sequence's end have nothing to do and leave at once (a ragged batch
     // is launched with the split count of its longest sequence); the others know how many of them there
     // are.  A sequence without coded tokens keeps split 0 (it may still have residual rows).
@@ -507,9 +437,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
       S0 = Regs{};
   }
   // ---- prologue: codebook table, query operands --------------------------------------------------
-  NSN_STAMP(25);
   if constexpr (!FLAT) fill_table();
-  NSN_STAMP(26);
   if (wave < 4) {  // d1: wave w rotates head w (zeros for a head that this launch does not have)
     const bool has_head = wave < r;
     const float x0 = has_head ? __low2float(q2_raw) : 0.f, x1 = has_head ? __high2float(q2_raw) : 0.f;
@@ -543,7 +471,6 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     const float d = wave_sum_all(x0 * half_lo_f(ok_first) + x1 * half_hi_f(ok_first));
     if (lane == 0) lds_write32(SM::kQoFirst + hh * 4, __float_as_uint(d * scale_log2e));
   }
-  NSN_STAMP(2);
   __builtin_amdgcn_sched_barrier(0);
   // residual (Sec. 3.2): wave w < 4 of the last live split takes rows [16 w, 16 w + 16); a load instruction
   // covers four consecutive rows (16 lanes x 16 bytes each); rows beyond the capacity are clamped and masked later
@@ -575,7 +502,6 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   else
     S1 = Regs{};
   __syncthreads();
-  NSN_STAMP(3);
   if constexpr (FLAT) {
     // segments are short and start cold: three groups per wave go out before the first is used, and the set
     // that a group leaves takes the group three rounds on (see process_group)
@@ -850,13 +776,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   // every one of the 48 matrix instructions of a group.
   // (inside a stage the matrix instructions go first: the operands they consume are dead before the next
   // gathers land, so a later batch can take over an earlier one's registers)
-#ifdef NSN_NO_STAGE_SPLIT
-#define STAGE_SPLIT
-#else
-#define STAGE_SPLIT __builtin_amdgcn_sched_barrier(0)
-#endif
   h8 KA[4], KB[4];
-  int stamp_it = 0;
   auto process_group = [&](int gi, Regs& G, const Regs& Gn, Regs& Gnn) {
     const int tg = t0 + (gi << 6);
     // Shift group bookkeeping (wave-uniform)
@@ -885,19 +805,19 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     h4 VA[8], VB[8], VC[8], VD[8];
     __builtin_amdgcn_sched_barrier(0);
     k_contract(c0, KA, D0, D1);
-    STAGE_SPLIT;
+    __builtin_amdgcn_sched_barrier(0);
     k_gather(c2, G, KC);
     __builtin_amdgcn_sched_barrier(0);
     k_contract(c1, KB, D0, D1);
-    STAGE_SPLIT;
+    __builtin_amdgcn_sched_barrier(0);
     k_gather(c3, G, KD);
     __builtin_amdgcn_sched_barrier(0);
     k_contract(c2, KC, D0, D1);
-    STAGE_SPLIT;
+    __builtin_amdgcn_sched_barrier(0);
     v_gather(c0, G, VA);  // the first value-side gathers fly during the softmax arithmetic
     __builtin_amdgcn_sched_barrier(0);
     k_contract(c3, KD, D0, D1);
-    STAGE_SPLIT;
+    __builtin_amdgcn_sched_barrier(0);
     v_gather(c1, G, VB);
     __builtin_amdgcn_sched_barrier(0);
     // hi + lo columns: lanes n < 8 take tiles 0, 1 from D0, lanes n >= 8 tiles 2, 3 from D1
@@ -931,11 +851,11 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     // d5: out_rot[head][channel] += sum over tokens of weight * codeword channel
     __builtin_amdgcn_sched_barrier(0);
     v_contract(c0, VA, wop);
-    STAGE_SPLIT;
+    __builtin_amdgcn_sched_barrier(0);
     v_gather(c2, G, VC);
     __builtin_amdgcn_sched_barrier(0);
     v_contract(c1, VB, wop);
-    STAGE_SPLIT;
+    __builtin_amdgcn_sched_barrier(0);
     v_gather(c3, G, VD);
     __builtin_amdgcn_sched_barrier(0);
     // the group after the next one: requested just before the next one's bytes are first needed (below)
@@ -949,16 +869,15 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     }
     __builtin_amdgcn_sched_barrier(0);
     v_contract(c2, VC, wop);
-    STAGE_SPLIT;
+    __builtin_amdgcn_sched_barrier(0);
     k_gather(c0, Gn, KA);  // (any bytes are valid table indices: harmless when there is no next group)
     __builtin_amdgcn_sched_barrier(0);
     v_contract(c3, VD, wop);
-    STAGE_SPLIT;
+    __builtin_amdgcn_sched_barrier(0);
     k_gather(c1, Gn, KB);
     __builtin_amdgcn_sched_barrier(0);
   };
 
-  NSN_STAMP(4);
   // ---- main loop: this wave's groups wave, wave + NW, ...; three register sets rotate (in use, next, in flight) ----
   if (wslot < n_grp) {
     int gi = wslot;
@@ -966,24 +885,17 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     k_gather(c1, S0, KB);
     while (true) {
       process_group(gi, S0, S1, S2);
-      NSN_STAMP_IT(stamp_it);
-      ++stamp_it;
       gi += NW;
       if (gi >= n_grp) break;
       process_group(gi, S1, S2, S0);
-      NSN_STAMP_IT(stamp_it);
-      ++stamp_it;
       gi += NW;
       if (gi >= n_grp) break;
       process_group(gi, S2, S0, S1);
-      NSN_STAMP_IT(stamp_it);
-      ++stamp_it;
       gi += NW;
       if (gi >= n_grp) break;
     }
   }
   if (cur_group >= 0) flush_group();
-  NSN_STAMP(12);
 
   // ---- epilogue: this wave's sums -> its merge slot ------------------------------------------------
   {
@@ -1006,9 +918,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     const float l_tot = head_sum(l_run);
     if (lane < 4) lds_write64(mbase + 4096 + lane * 8, u2v{__float_as_uint(m_run), __float_as_uint(l_tot)});
   }
-  NSN_STAMP(13);
   __syncthreads();
-  NSN_STAMP(14);
 
   // ---- merge the waves: wave i takes head i, a lane channels 2 lane, 2 lane + 1 ------------------
   [&]() {
@@ -1037,7 +947,6 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     }
   }
 
-  NSN_STAMP(15);
   // ---- d6: merge the splits; the last wave to arrive for this query head finishes it -------------
   if (n_live > 1) {
     // !FLAT: partial [sequence][query head][split].  FLAT: [run][slot][query head of the kv head]: slot 0 for
@@ -1076,7 +985,6 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     int old = 0;
     if (lane == 0) old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     old = __builtin_amdgcn_readfirstlane(old);
-    NSN_STAMP(16);
     if (old != n_live - 1) return;
     if (lane == 0) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
     // chunks of SF splits, every load of a chunk issued before its first use (a chunk costs one trip to
@@ -1118,9 +1026,8 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     if (n_live <= 8)
       merge_chunks(std::integral_constant<int, 8>{});
     else
-      merge_chunks(std::integral_constant<int, NSN_SF>{});
+      merge_chunks(std::integral_constant<int, 32>{});
   }
-  NSN_STAMP(17);
   // one inverse Hadamard per head (H is its own inverse), across the wave's lanes in registers
   {
     const float a0 = x0 + x1, a1 = x0 - x1;
@@ -1136,24 +1043,14 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   float2 o2 = make_float2(0.f, 0.f);
   if (L > 0.f) o2 = make_float2((x0 * (float)kInvSqrtD + mm0) / L, (x1 * (float)kInvSqrtD + mm1) / L);
   *reinterpret_cast<float2*>(out + (int64_t)(b * g.n_q_heads + hq0 + hh) * kHeadDim + 2 * lane) = o2;
-  NSN_STAMP(18);
   }();
   if constexpr (!FLAT) break;
   if (run_pos >= run_end) break;
   b = nb, h = nh;  // the next unit (its first row and length are on their way or here)
   first_segment = false;
-  NSN_STAMP_NEXT_SEGMENT;
   }  // segments
-  NSN_STAMP_WALL(31);
-  NSN_STAMP_FLUSH;
 }
 
-
-#ifdef NSN_TILE_TIMING
-extern "C" int nsn_debug_tile_timing(long long* host64) {
-  return hipMemcpyFromSymbol(host64, HIP_SYMBOL(g_tile_timing), sizeof(long long) * 64) == hipSuccess ? 0 : -1;
-}
-#endif
 
 template <int SUB, int NW, bool POW2, bool PAGED, bool FLAT>
 static int launch_one(const Geometry& g, const void* codebook, const void* q, const CacheView& kv, const CacheView& vv,
