@@ -34,7 +34,11 @@ if ROOT not in sys.path:
 PEAK_HBM_GBPS = 8000.0
 # HBM bytes per decode launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs kept under profiles/
 # (scaled by the same counters on a plain 256 MiB copy); only for the workload they were taken on.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    "C1": {"bytes": (20308.0 * 2.000 + 1272.0 * 1.000) * 1024,
+           "source": "profiles/decode_C1_hbm_traffic.txt: rocprofv3 FETCH_SIZE 20308.0 x 2.000 + WRITE_SIZE 1272.0 x 1.000 "
+                     "KiB per launch (factors from a 256 MiB copy in the same runs), residual rows included"},
+}
 DECODE_KERNEL_NAME = "nsn::tile::dec_tile_kernel"
 
 
@@ -419,8 +423,9 @@ def main() -> int:
     traffic = MEASURED_TRAFFIC[args.workload] if default_options else None
     # encoder (prefill): bound by the vector ALUs.  Peak = 256 CUs x 64 lanes x 2.4 GHz lane-operations per
     # second (packed fp32 is disabled in this build); the best-two selection over 256 distances alone needs
-    # 3 lane-operations per distance, i.e. 3 x 8192 per token, kv head and tensor: counted as the algorithmic work
-    enc_lane_ops = encode_tokens_per_s * Hkv * 2 * (3 * (128 // sub) * 256)
+    # 2.5 lane-operations per distance (index insertion, and min3 + med3 + min per pair), i.e. 2.5 x 8192 per token,
+    # kv head and tensor: counted as the algorithmic work
+    enc_lane_ops = encode_tokens_per_s * Hkv * 2 * (2.5 * (128 // sub) * 256)
     peak_lane_ops = 256 * 64 * 2.4e9
 
     result = {
@@ -470,7 +475,7 @@ def main() -> int:
         "roofline_encode": {"bound": "alu", "kernel": "nsn::enc_quant_kernel (+ enc_stats_kernel, enc_means_kernel)",
                             "achieved": round(enc_lane_ops / 1e12, 3), "peak": round(peak_lane_ops / 1e12, 2),
                             "unit": "Tlane-op/s", "frac": round(enc_lane_ops / peak_lane_ops, 4),
-                            "algorithmic_lane_ops_per_token": Hkv * 2 * 3 * (128 // sub) * 256,
+                            "algorithmic_lane_ops_per_token": int(Hkv * 2 * 2.5 * (128 // sub) * 256),
                             "peak_derivation": "256 CUs x 64 lanes x 2.4 GHz, one fp32 operation per lane and clock"},
     }
     if flushes == 0 and args.policy == "residual":
