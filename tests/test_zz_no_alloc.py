@@ -38,6 +38,16 @@ def test_noalloc_matches_workspace_entry_point_twice(gpu_api, codebooks):
     assert np.array_equal(out, ref)
 
 
+def test_noalloc_persistent_instance_matches_workspace_entry_point(gpu_api, codebooks):
+    # 16 sequences x 8 kv heads = 128 units with automatic splitting: the persistent instance, whose partials
+    # (two per run) and counters live in the same scratch array
+    lens = [0, 1, 64, 65, 130, 300, 17, 256, 511, 77, 128, 5, 200, 333, 90, 400]
+    out, ref = _both(gpu_api, codebooks[4], 33, 16, 16, 8, lens, 4, 64, 0)
+    assert np.array_equal(out, ref)
+    out, ref = _both(gpu_api, codebooks[4], 34, 2, 8, 2, [700, 100], 4, 64, 3)   # then a small split call again
+    assert np.array_equal(out, ref)
+
+
 def test_noalloc_rejects_calls_beyond_its_scratch(gpu_api, codebooks):
     import torch
     api = gpu_api
