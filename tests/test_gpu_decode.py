@@ -80,6 +80,9 @@ CASES = [
     ("flat-paged-1bit", 16, 8, 8, FLAT_LENS[5:] + FLAT_LENS[:5], 8, 0, 256, 0),
     ("flat-gqa8-2bit-onegroup", 16, 64, 8, FLAT_LENS[::-1], 4, 0, 0, 0),
     ("flat-long-units-1bit", 16, 32, 8, [2100, 0, 70, 1500] + [40] * 12, 8, 128, 0, 0),
+    # more than 64 sequences: the run boundaries are found across several 64-sequence blocks of lengths
+    ("flat-130-sequences-1bit", 130, 2, 1, [(i * 37) % 200 for i in range(130)], 8, 0, 0, 0),
+    ("flat-200-sequences-2bit-paged", 200, 4, 1, [(i * 53) % 300 for i in range(200)], 4, 64, 256, 0),
 ]
 
 
