@@ -36,7 +36,7 @@
  *          sign bytes.  Inside one placement unit (see below) the byte of (token t of the
  *          unit, byte row j in [0,J)) sits at the offset that nsn_k_code_offset /
  *          nsn_v_code_offset return:
- *          TILED layout - the (sub_dim, 256) formats with fp16 side information and no rope_table.
+ *          TILED layout - the (sub_dim, 256) formats without rope_table (either width of side information).
  *          Blocks of 64 tokens, 64 * J bytes each; inside a block one run of J bytes per lane
  *          of the 64-lane wave that reads it; with QS = J / 4 and tb = t % 64:
  *            K:  (t / 64) * 64*J + (16 * (j / QS) + tb % 16) * J + (tb / 16) * QS + j % QS
@@ -45,7 +45,7 @@
  *          the block's four 16-token tiles, which is its A operand of the 16x16x32 score
  *          contraction; V: a lane holds sub-vectors j % 4 = const of four tokens 16 apart, which
  *          the transposing LDS read turns into "four tokens of one channel" operands.
- *          LEGACY layout - the sign + index format, rope_table, side_bits = 4:
+ *          LEGACY layout - the sign + index format, and every format with rope_table:
  *            K:  t * J + j                                  (token-major)
  *            V:  (t / J) * J*J + j * J + t % J              (blocks of J tokens, sub-vector-major)
  *   norms  one (a, b) fp16 pair per token: b = s1 (first Normalize scale), a = s1*s2*alpha

@@ -1396,9 +1396,9 @@ int decode_mfma_launch(const nsn_shape& s, const void* codebook, const void* q, 
                         : launch_one<kSub, 8, 4, kSgn, kRope, kDq>(NSN_ARGS);
     };
     auto with_format = [&](auto rope, auto dq) {
-      if constexpr (!decltype(rope)::value && !decltype(dq)::value) {
-        // index-only codes with fp16 side information and no rotary table run in the tiled-layout kernel
-        // (dispatched above); what is left here without either option is the sign + index format
+      if constexpr (!decltype(rope)::value) {
+        // index-only codes without a rotary table run in the tiled-layout kernel (dispatched above), with
+        // either width of side information; what is left here without the table is the sign + index format
         return g.sign ? with_r(std::integral_constant<int, 8>{}, std::true_type{}, rope, dq) : (int)NSN_ERR_UNSUPPORTED;
       }
       if (g.sign) return with_r(std::integral_constant<int, 8>{}, std::true_type{}, rope, dq);

@@ -204,7 +204,15 @@ struct GroupRegs {
   uint32_t kc[CW], vc[CW];  // the lane's code bytes of the group (tiled layout: CW dwords per tensor)
   uint4 nk, nv;             // (a, b) fp16 pairs of the lane's four tokens 16 tile + 4 rho + {0..3}
   uint32_t ok, ov;          // channels 2 lane, 2 lane + 1 of the group's Shift vectors (fp16 pairs)
+  // 4-bit side information (DQ): nk / nv = {a' of the four tokens (two words), their four s1 nibbles, the
+  // block's (min, step)}; ok / ov = the byte with the two channels' nibbles, okp / ovp = (min, step) of the
+  // lane's 32-channel group
+  uint32_t okp, ovp;
 };
+// min + step * code of a 4-bit level (par = fp16 pair (min, step))
+__device__ __forceinline__ float dq_level(uint32_t par, uint32_t code) {
+  return fmaf(half_hi_f(par), (float)code, half_lo_f(par));
+}
 
 // POW2: group_size (if any) and, for paged caches, page_size are powers of two: group and page indices are
 // shifts (the other instance divides: about 35 scalar instructions per index)
@@ -220,7 +228,8 @@ struct GroupRegs {
 // groups (query rotation, two barriers, the merge of the waves, a cold start of the loads), so that runs with
 // many short units get fewer groups.  A run that ends inside those slots leaves the unit to the next run.
 constexpr int kSegCost = 24;
-template <int SUB, int NW, bool POW2, bool PAGED, bool FLAT>
+// DQ: norms and means are stored in 4 bits (Sec. 3.5): 164-byte norm records per 64-token block, 80-byte mean records
+template <int SUB, int NW, bool POW2, bool PAGED, bool FLAT, bool DQ>
 __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __half* __restrict__ codebook,
                                                            const __half* __restrict__ q, CacheView kc, CacheView vc,
                                                            const int32_t* __restrict__ seq_lens, int batch,
@@ -315,7 +324,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   // FLAT: the next segment's sequence length, query row and first mean row are fetched a segment ahead
   int len_cur = 0, nb = 0, nh = 0;
   __half2 q2_next = __half2{};
-  uint32_t okf_next = 0u;
+  uint32_t okf_next = 0u, okfp_next = 0u;
   if constexpr (FLAT) len_cur = seq_lens[b];
   for (;;) {  // FLAT: one pass per segment of the run; otherwise a single pass
   // Everything a pass derives from the lane number is derived anew in each pass: values that the compiler
@@ -354,11 +363,37 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
       G.kc[4 * w4] = kv4.x, G.kc[4 * w4 + 1] = kv4.y, G.kc[4 * w4 + 2] = kv4.z, G.kc[4 * w4 + 3] = kv4.w;
       G.vc[4 * w4] = vv4.x, G.vc[4 * w4 + 1] = vv4.y, G.vc[4 * w4 + 2] = vv4.z, G.vc[4 * w4 + 3] = vv4.w;
     }
-    G.nk = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(kc.norms + kbase) + norm_off);
-    G.nv = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(vc.norms + vbase) + norm_off);
-    const int64_t mo = (mean_base + shift_group(tg)) * kHeadDim;
-    G.ok = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(kc.means + mo) + lane_x4);
-    G.ov = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lane_x4);
+    if constexpr (DQ) {
+      // (kbase, vbase are multiples of 64: one norm record per 64-token block of the buffer)
+      const unsigned char* kr = reinterpret_cast<const unsigned char*>(kc.norms) + (kbase >> 6) * kDqNormRec;
+      const unsigned char* vr = reinterpret_cast<const unsigned char*>(vc.norms) + (vbase >> 6) * kDqNormRec;
+      const uint32_t tok0 = norm_off >> 2;  // the lane's first token of the group (a multiple of 4)
+      const uint2 ka = *reinterpret_cast<const uint2*>(kr + 2 * tok0), va = *reinterpret_cast<const uint2*>(vr + 2 * tok0);
+      G.nk = make_uint4(ka.x, ka.y, *reinterpret_cast<const uint16_t*>(kr + kDqNormCodes + (tok0 >> 1)),
+                        *reinterpret_cast<const uint32_t*>(kr + kDqNormPar));
+      G.nv = make_uint4(va.x, va.y, *reinterpret_cast<const uint16_t*>(vr + kDqNormCodes + (tok0 >> 1)),
+                        *reinterpret_cast<const uint32_t*>(vr + kDqNormPar));
+      const int64_t mo = (mean_base + shift_group(tg)) * kDqMeanRec;
+      const unsigned char* km = reinterpret_cast<const unsigned char*>(kc.means) + mo;
+      const unsigned char* vm = reinterpret_cast<const unsigned char*>(vc.means) + mo;
+      G.ok = km[lane], G.ov = vm[lane];
+      G.okp = *reinterpret_cast<const uint32_t*>(km + kDqMeanPar + 4 * (lane >> 4));
+      G.ovp = *reinterpret_cast<const uint32_t*>(vm + kDqMeanPar + 4 * (lane >> 4));
+    } else {
+      G.nk = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(kc.norms + kbase) + norm_off);
+      G.nv = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(vc.norms + vbase) + norm_off);
+      const int64_t mo = (mean_base + shift_group(tg)) * kHeadDim;
+      G.ok = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(kc.means + mo) + lane_x4);
+      G.ov = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lane_x4);
+    }
+  };
+  // the lane's two channels of a Shift vector from its stored words
+  auto mean_pair = [&](uint32_t w, uint32_t par, float& o0, float& o1) {
+    if constexpr (DQ) {
+      o0 = dq_level(par, w & 15u), o1 = dq_level(par, (w >> 4) & 15u);
+    } else {
+      o0 = half_lo_f(w), o1 = half_hi_f(w);
+    }
   };
 
   int len, n_live, t1, n_grp, first_run = 0;
@@ -387,17 +422,24 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     return *reinterpret_cast<const __half2*>(q + (int64_t)(bb * g.n_q_heads + hh0 + min(wave & 3, r - 1)) * kHeadDim +
                                              2 * lane);
   };
-  auto mean_row_k = [&](int64_t base, int grp) {
-    return *reinterpret_cast<const uint32_t*>(
-        reinterpret_cast<const unsigned char*>(kc.means + (base + grp) * kHeadDim) + lane_x4);
+  auto mean_row_k = [&](int64_t base, int grp, uint32_t& w, uint32_t& par) {
+    if constexpr (DQ) {
+      const unsigned char* km = reinterpret_cast<const unsigned char*>(kc.means) + (base + grp) * kDqMeanRec;
+      w = km[lane];
+      par = *reinterpret_cast<const uint32_t*>(km + kDqMeanPar + 4 * (lane >> 4));
+    } else {
+      w = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(kc.means + (base + grp) * kHeadDim) +
+                                             lane_x4);
+      par = 0u;
+    }
   };
   // the split's first Shift group: its q . o^k is formed once per workgroup (waves 4..7, one head each)
   const int grp_first = shift_group(min(t0, cap_tokens - 64));
   __half2 q2_raw = q2_next;
-  uint32_t ok_first = okf_next;
+  uint32_t ok_first = okf_next, okp_first = okfp_next;
   if (!FLAT || first_segment) {
     q2_raw = q_row(b, hq0);
-    ok_first = mean_row_k(mean_base, grp_first);
+    mean_row_k(mean_base, grp_first, ok_first, okp_first);
   }
   if constexpr (FLAT) {
     // the unit after this one (if the run goes on, this segment ends its unit and the next begins one)
@@ -408,7 +450,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     }
     len_cur = seq_lens[nb];
     q2_next = q_row(nb, nh * (g.n_q_heads / hkv) + head_off);
-    okf_next = mean_row_k((int64_t)(nb * hkv + nh) * g.n_groups_max, 0);
+    mean_row_k((int64_t)(nb * hkv + nh) * g.n_groups_max, 0, okf_next, okfp_next);
   }
   // (the three small loads stay ahead of the bulk ones: the waits for them then leave every later load in flight)
   __builtin_amdgcn_sched_barrier(0);
@@ -468,7 +510,9 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     if (first_segment && wave == 4 && lane < 32) lds_write32(SM::kZero + lane * 4, 0u);
     const int hh = wave - 4;  // this wave loaded the query of head wave & 3 = hh
     const float x0 = hh < r ? __low2float(q2_raw) : 0.f, x1 = hh < r ? __high2float(q2_raw) : 0.f;
-    const float d = wave_sum_all(x0 * half_lo_f(ok_first) + x1 * half_hi_f(ok_first));
+    float of0, of1;
+    mean_pair(ok_first, okp_first, of0, of1);
+    const float d = wave_sum_all(x0 * of0 + x1 * of1);
     if (lane == 0) lds_write32(SM::kQoFirst + hh * 4, __float_as_uint(d * scale_log2e));
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -786,7 +830,8 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
       if (grp == grp_first) {
         qo = lds_read32f(SM::kQoFirst + head * 4);
       } else {
-        const float o0 = half_lo(G.ok), o1 = half_hi(G.ok);
+        float o0, o1;
+        mean_pair(G.ok, G.okp, o0, o1);
         float qd[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -796,7 +841,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
         const float lo01 = (head & 1) ? qd[1] : qd[0], hi23 = (head & 1) ? qd[3] : qd[2];
         qo = ((head & 2) ? hi23 : lo01) * scale_log2e;
       }
-      ov0 = half_lo(G.ov), ov1 = half_hi(G.ov);
+      mean_pair(G.ov, G.ovp, ov0, ov1);
       cur_group = grp;
     }
     // d2/d3: HT(q) . C[codes] of the group's 64 tokens, four heads
@@ -830,21 +875,35 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     }
     const bool all_valid = (tg + 64 <= t1);
     bool valid[4] = {true, true, true, true};
-    uint32_t nkw[4] = {G.nk.x, G.nk.y, G.nk.z, G.nk.w}, nvw[4] = {G.nv.x, G.nv.y, G.nv.z, G.nv.w};
     if (!all_valid) {  // wave-uniform: only a sequence's last group has masked tokens (their bytes may be anything)
       const int tb0 = tg + 16 * tile_of_lane + 4 * rho;  // the lane's first token
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        valid[k] = (tb0 + k) < t1;
-        nkw[k] = valid[k] ? nkw[k] : 0u;
-        nvw[k] = valid[k] ? nvw[k] : 0u;
-      }
+      for (int k = 0; k < 4; ++k) valid[k] = (tb0 + k) < t1;
     }
     float ak[4], bk[4], av[4], bv[4];
+    if constexpr (DQ) {  // b = min + step * code, a = b * a'
+      const float apk[4] = {half_lo(G.nk.x), half_hi(G.nk.x), half_lo(G.nk.y), half_hi(G.nk.y)};
+      const float apv[4] = {half_lo(G.nv.x), half_hi(G.nv.x), half_lo(G.nv.y), half_hi(G.nv.y)};
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      ak[k] = half_lo(nkw[k]), bk[k] = half_hi(nkw[k]);
-      av[k] = half_lo(nvw[k]), bv[k] = half_hi(nvw[k]);
+      for (int k = 0; k < 4; ++k) {
+        const float b_k = dq_level(G.nk.w, (G.nk.z >> (4 * k)) & 15u), b_v = dq_level(G.nv.w, (G.nv.z >> (4 * k)) & 15u);
+        bk[k] = valid[k] ? b_k : 0.f, ak[k] = valid[k] ? b_k * apk[k] : 0.f;
+        bv[k] = valid[k] ? b_v : 0.f, av[k] = valid[k] ? b_v * apv[k] : 0.f;
+      }
+    } else {
+      uint32_t nkw[4] = {G.nk.x, G.nk.y, G.nk.z, G.nk.w}, nvw[4] = {G.nv.x, G.nv.y, G.nv.z, G.nv.w};
+      if (!all_valid) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          nkw[k] = valid[k] ? nkw[k] : 0u;
+          nvw[k] = valid[k] ? nvw[k] : 0u;
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        ak[k] = half_lo(nkw[k]), bk[k] = half_hi(nkw[k]);
+        av[k] = half_lo(nvw[k]), bv[k] = half_hi(nvw[k]);
+      }
     }
     const h4 wop = softmax_step(sc, valid, all_valid, ak, bk, av, bv);
 
@@ -1052,7 +1111,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
 }
 
 
-template <int SUB, int NW, bool POW2, bool PAGED, bool FLAT>
+template <int SUB, int NW, bool POW2, bool PAGED, bool FLAT, bool DQ>
 static int launch_one(const Geometry& g, const void* codebook, const void* q, const CacheView& kv, const CacheView& vv,
                       const int32_t* seq_lens, int batch, int max_seq_len, float scale, int n_splits, void* workspace,
                       size_t counter_bytes, const ResidualView& res, int head_off, int r_pass, float* out,
@@ -1063,7 +1122,7 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
     // the gathers address the codebook table by absolute LDS address: it must start at 0, i.e. the
     // kernel may not own any static LDS in front of its dynamic block
     hipFuncAttributes fa;
-    const void* fn = reinterpret_cast<const void*>(dec_tile_kernel<SUB, NW, POW2, PAGED, FLAT>);
+    const void* fn = reinterpret_cast<const void*>(dec_tile_kernel<SUB, NW, POW2, PAGED, FLAT, DQ>);
     if (hipFuncGetAttributes(&fa, fn) != hipSuccess || fa.sharedSizeBytes != 0) return (int)NSN_ERR_HIP;
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SM::kBytesRes) != hipSuccess)
       return (int)NSN_ERR_HIP;
@@ -1087,7 +1146,7 @@ static int launch_one(const Geometry& g, const void* codebook, const void* q, co
     per = (((max_seq_len + n_splits - 1) / n_splits) + 63) & ~63;
     grid = dim3(n_splits, g.n_kv_heads, batch);
   }
-  dec_tile_kernel<SUB, NW, POW2, PAGED, FLAT><<<grid, NW * 64, smem, stream>>>(
+  dec_tile_kernel<SUB, NW, POW2, PAGED, FLAT, DQ><<<grid, NW * 64, smem, stream>>>(
       g, (const __half*)codebook, (const __half*)q, kv, vv, seq_lens, batch, scale * 1.44269504088896340736f, n_splits,
       per, partial, counters, res, head_off, r_pass, out);
   return hipGetLastError() == hipSuccess ? NSN_OK : NSN_ERR_HIP;
@@ -1112,18 +1171,21 @@ int decode_tile_launch(const nsn_shape& s, const void* codebook, const void* q, 
 #define NSN_TILE_ARGS \
   g, codebook, q, kv, vv, seq_lens, batch, max_seq_len, scale, n_splits, workspace, counter_bytes, res, head_off, r, out, stream
     const bool pow2 = (g.group_size <= 0 || g.group_shift >= 0) && (!g.paged || g.page_shift >= 0);
-    auto with_flags = [&](auto sub, auto flat) {
+    auto with_flags = [&](auto sub, auto flat, auto dq) {
       constexpr int kSub = decltype(sub)::value;
-      constexpr bool kFlat = decltype(flat)::value;
+      constexpr bool kFlat = decltype(flat)::value, kDq = decltype(dq)::value;
       if (g.paged)
-        return pow2 ? tile::launch_one<kSub, 8, true, true, kFlat>(NSN_TILE_ARGS)
-                    : tile::launch_one<kSub, 8, false, true, kFlat>(NSN_TILE_ARGS);
-      return pow2 ? tile::launch_one<kSub, 8, true, false, kFlat>(NSN_TILE_ARGS)
-                  : tile::launch_one<kSub, 8, false, false, kFlat>(NSN_TILE_ARGS);
+        return pow2 ? tile::launch_one<kSub, 8, true, true, kFlat, kDq>(NSN_TILE_ARGS)
+                    : tile::launch_one<kSub, 8, false, true, kFlat, kDq>(NSN_TILE_ARGS);
+      return pow2 ? tile::launch_one<kSub, 8, true, false, kFlat, kDq>(NSN_TILE_ARGS)
+                  : tile::launch_one<kSub, 8, false, false, kFlat, kDq>(NSN_TILE_ARGS);
     };
     auto with_sub = [&](auto flat) {
-      return s.sub_dim == 4 ? with_flags(std::integral_constant<int, 4>{}, flat)
-                            : with_flags(std::integral_constant<int, 8>{}, flat);
+      if (g.dq)
+        return s.sub_dim == 4 ? with_flags(std::integral_constant<int, 4>{}, flat, std::true_type{})
+                              : with_flags(std::integral_constant<int, 8>{}, flat, std::true_type{});
+      return s.sub_dim == 4 ? with_flags(std::integral_constant<int, 4>{}, flat, std::false_type{})
+                            : with_flags(std::integral_constant<int, 8>{}, flat, std::false_type{});
     };
     // n_splits == kSplitsFlat: the persistent instance that cuts the list of all groups into equal runs
     const int rc = n_splits == kSplitsFlat ? with_sub(std::true_type{}) : with_sub(std::false_type{});

@@ -6,9 +6,7 @@
 namespace nsn {
 
 // which formats keep their codes in the tiled layout (read by dec_tile_kernel)
-inline bool shape_is_tiled(const nsn_shape& s) {
-  return s.n_codes == kCodes && s.side_bits != 4 && s.rope_table == nullptr;
-}
+inline bool shape_is_tiled(const nsn_shape& s) { return s.n_codes == kCodes && s.rope_table == nullptr; }
 
 inline Geometry make_geometry(const nsn_shape& s) {
   Geometry g;

@@ -51,7 +51,7 @@ class HostCache:
     def __init__(self, kind, batch, hkv, J, max_len, G, page_size=0, block_table=None, n_pages=None,
                  layout="tiled"):
         self.kind, self.batch, self.hkv, self.J, self.max_len, self.G = kind, batch, hkv, J, max_len, G
-        self.layout = layout  # "tiled": the (sub_dim, 256) formats with fp16 side information and no rope table
+        self.layout = layout  # "tiled": the (sub_dim, 256) formats without a rope table
         self.page = page_size
         self.bt = block_table
         self.ng = n_groups(max_len, G)
@@ -149,8 +149,10 @@ class HostCacheDQ(HostCache):
     ([0,128) a' fp16, [128,160) s1 codes, [160,164) (min, step) fp16), means = 80-byte records per group
     ([0,64) codes, [64,80) four (min, step) fp16 pairs)."""
 
-    def __init__(self, kind, batch, hkv, J, max_len, G, page_size=0, block_table=None, n_pages=None):
-        super().__init__(kind, batch, hkv, J, max_len, G, page_size, block_table, n_pages, layout="legacy")
+    def __init__(self, kind, batch, hkv, J, max_len, G, page_size=0, block_table=None, n_pages=None,
+                 layout="tiled"):
+        # layout: "tiled" for index-only codes of keys taken as given, "legacy" with sign bytes or a rotary table
+        super().__init__(kind, batch, hkv, J, max_len, G, page_size, block_table, n_pages, layout=layout)
         units = self.codes.shape[0]
         per_unit = (page_size or max_len) // 64
         self.norms = np.zeros((units, hkv, per_unit, 164), dtype=np.uint8)

@@ -45,8 +45,9 @@ def _encode_on_gpu(api, seed, batch, hkv, lens, sub, G, cb, page, sign, starts=N
     shape = api.make_shape(sub, hkv, hkv, max_len, G, page, sign_format=sign, side_bits=4, rope_table=rope_table)
     if caches is None:
         bt = synth.shuffled_page_table(seed, batch, max_len // page) if page else None
-        hk = helpers.HostCacheDQ("k", batch, hkv, J, max_len, G, page, bt)
-        hv = helpers.HostCacheDQ("v", batch, hkv, J, max_len, G, page, bt)
+        layout = "legacy" if (sign or rope_table is not None) else "tiled"
+        hk = helpers.HostCacheDQ("k", batch, hkv, J, max_len, G, page, bt, layout=layout)
+        hv = helpers.HostCacheDQ("v", batch, hkv, J, max_len, G, page, bt, layout=layout)
     else:
         hk, hv = caches
     dk, dv = hk.to_device(api, shape), hv.to_device(api, shape)
@@ -142,6 +143,9 @@ DEC_CASES = [
     ("gqa4-2bit-groups-prerope", 8, 2, [777, 130], 4, 64, 0, 4, False, True),
     ("gqa4-sign-groups-prerope", 4, 1, [3000], 8, 64, 0, 1, True, True),
     ("gqa2-1bit-onegroup-prerope", 2, 1, [1000, 64], 8, 0, 0, 3, False, True),
+    # 128 units, automatic splitting: the persistent instance of the tiled-layout kernel with 4-bit side information
+    ("flat-ragged-2bit", 16, 8, [0, 64, 65, 130, 300, 17, 256, 511, 77, 128, 5, 200, 333, 90, 400, 1], 4, 64, 0, 0, False, False),
+    ("flat-paged-1bit", 8, 8, [300, 17, 256, 511, 77, 128, 5, 200, 333, 90, 400, 0, 1, 64, 65, 130], 8, 128, 256, 0, False, False),
 ]
 
 
@@ -150,8 +154,9 @@ def _build(seed, hkv, lens, sub, G, cb, page, sign, f):
     J = (2 if sign else 1) * (128 // sub)
     max_len = ((max(max(lens), 1) + 255) // 256) * 256
     bt = synth.shuffled_page_table(seed, batch, max_len // page) if page else None
-    kc = helpers.HostCacheDQ("k", batch, hkv, J, max_len, G, page, bt)
-    vc = helpers.HostCacheDQ("v", batch, hkv, J, max_len, G, page, bt)
+    layout = "legacy" if (sign or f is not None) else "tiled"
+    kc = helpers.HostCacheDQ("k", batch, hkv, J, max_len, G, page, bt, layout=layout)
+    vc = helpers.HostCacheDQ("v", batch, hkv, J, max_len, G, page, bt, layout=layout)
     for b in range(batch):
         for h in range(hkv):
             if lens[b]:

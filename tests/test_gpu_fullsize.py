@@ -168,8 +168,8 @@ def test_llama3_8b_shape_in_the_papers_own_configuration(gpu_api):
                                             torch.tensor(res_rows, dtype=torch.int32).cuda(), scale, 0)
     torch.cuda.synchronize()
     out = out.cpu().numpy().astype(np.float64)
-    hk = helpers.HostCacheDQ("k", B, Hkv, J, L + RES, G)
-    hv = helpers.HostCacheDQ("v", B, Hkv, J, L + RES, G)
+    hk = helpers.HostCacheDQ("k", B, Hkv, J, L + RES, G, layout="legacy")
+    hv = helpers.HostCacheDQ("v", B, Hkv, J, L + RES, G, layout="legacy")
     hk.from_device(kc)
     hv.from_device(vc)
     worst = 0.0

@@ -41,7 +41,7 @@ def test_layout_offsets_match_header_formulas_and_are_bijections(L, fmt):
              "sign": api.make_shape(8, 4, 1, 256, sign_format=True),
              "2bit-dq": api.make_shape(4, 4, 1, 256, side_bits=4)}[fmt]
     J = api.code_bytes_per_token(shape)
-    layout = "tiled" if fmt in ("1bit", "2bit") else "legacy"
+    layout = "tiled" if fmt in ("1bit", "2bit", "2bit-dq") else "legacy"
     for kind, fn in (("k", L.nsn_k_code_offset), ("v", L.nsn_v_code_offset)):
         ref = helpers.code_offsets(J, kind, n, layout)
         got = np.array([[fn(C.byref(shape), t, j) for j in range(J)] for t in range(n)])
