@@ -81,6 +81,7 @@ CASES = [
     ("flat-gqa8-2bit-onegroup", 16, 64, 8, FLAT_LENS[::-1], 4, 0, 0, 0),
     ("flat-long-units-1bit", 16, 32, 8, [2100, 0, 70, 1500] + [40] * 12, 8, 128, 0, 0),
     # more than 64 sequences: the run boundaries are found across several 64-sequence blocks of lengths
+    ("flat-all-empty", 16, 8, 8, [0] * 16, 4, 64, 0, 0),
     ("flat-130-sequences-1bit", 130, 2, 1, [(i * 37) % 200 for i in range(130)], 8, 0, 0, 0),
     ("flat-200-sequences-2bit-paged", 200, 4, 1, [(i * 53) % 300 for i in range(200)], 4, 64, 256, 0),
 ]
@@ -102,6 +103,8 @@ def test_decode_matches_oracle(gpu_api, codebooks, select_variant, impl, name, b
         if lens[b] == 0:
             assert np.all(out[b] == 0.0)
     live = [b for b in range(batch) if lens[b] > 0]
+    if not live:
+        return
     err = helpers.max_rel_err(out[live], ref[live])
     print(f"  max rel err {err:.3e}", flush=True)
     assert err < TOL, err
