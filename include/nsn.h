@@ -199,7 +199,8 @@ int nsn_select_variant(int op, int variant);
  *                     The decode workspace starts with arrival counters: fill it with zeros
  *                     ONCE after allocating it; every call leaves it ready for the next one.
  *                     Calls that share one workspace must not overlap in time.
- *   NSN_OP_CODEBOOK : n = n_samples, batch and n_splits ignored
+ *   NSN_OP_CODEBOOK : n = n_samples, batch and n_splits ignored; the workspace starts on a
+ *                     16-byte boundary (INVALID_ARG otherwise)
  * Returns 0 for an invalid shape.
  */
 size_t nsn_workspace_bytes(const nsn_shape* shape, int op, int batch, int64_t n, int n_splits);

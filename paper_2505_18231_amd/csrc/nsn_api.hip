@@ -202,6 +202,10 @@ int nsn_build_codebook(const float* samples_dev, int64_t n_samples, int sub_dim,
     set_error("build_codebook: workspace of %zu bytes needed", codebook_workspace_bytes(sub_dim, n_samples));
     return NSN_ERR_WORKSPACE;
   }
+  if (reinterpret_cast<uintptr_t>(workspace) & 15) {
+    set_error("build_codebook: the workspace must start on a 16-byte boundary");
+    return NSN_ERR_INVALID_ARG;
+  }
   const int rc = codebook_run(samples_dev, n_samples, sub_dim, iters, codebook_dev, mse_host, workspace,
                               static_cast<hipStream_t>(stream));
   if (rc == NSN_ERR_HIP) set_error("build_codebook: HIP error: %s", hipGetErrorString(hipGetLastError()));
@@ -223,6 +227,10 @@ int nsn_finetune_codebook(const float* samples_dev, int64_t n_samples, int sub_d
   if (!workspace || workspace_bytes < codebook_workspace_bytes(sub_dim, n_samples)) {
     set_error("finetune_codebook: workspace of %zu bytes needed", codebook_workspace_bytes(sub_dim, n_samples));
     return NSN_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(workspace) & 15) {
+    set_error("finetune_codebook: the workspace must start on a 16-byte boundary");
+    return NSN_ERR_INVALID_ARG;
   }
   const int rc = finetune_run(samples_dev, n_samples, sub_dim, iters, lr, codebook_dev, cos_host, workspace,
                               static_cast<hipStream_t>(stream));

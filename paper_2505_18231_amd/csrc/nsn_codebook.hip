@@ -50,23 +50,57 @@ __global__ __launch_bounds__(256) void km_assign_kernel(const float* __restrict_
   if (threadIdx.x == 0) block_err[blockIdx.x] = ((red[0] + red[1]) + red[2]) + red[3];
 }
 
+constexpr int kUpdateThreads = 1024;
+constexpr int kUpdateWaves = kUpdateThreads / 64;
+
+// Calls fn(idx) for every sample assigned to cluster k, in an order that depends only on n and
+// the workgroup size (by thread, then ascending index), so the fp64 sums that follow are
+// reproducible.  The assignments are scanned 16 to a load, four loads in flight; a word is taken
+// apart only if one of its four bytes matches.
+template <class F>
+__device__ __forceinline__ void for_each_member(const uint8_t* __restrict__ assign, int64_t n, int k, F&& fn) {
+  constexpr int64_t kStep = (int64_t)kUpdateThreads * 16;
+  const int64_t n16 = n & ~(int64_t)15;
+  const uint32_t kk = (uint32_t)k * 0x01010101u;
+  for (int64_t base = (int64_t)threadIdx.x * 16; base < n16; base += 4 * kStep) {
+    uint4 w[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      w[u] = base + u * kStep < n16 ? *reinterpret_cast<const uint4*>(assign + base + u * kStep)
+                                    : make_uint4(~kk, ~kk, ~kk, ~kk);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t ws[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t x = ws[j] ^ kk;  // a zero byte marks a member
+        if (((x - 0x01010101u) & ~x & 0x80808080u) != 0u) {
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            if (((x >> (8 * b)) & 0xffu) == 0u) fn(base + u * kStep + 4 * j + b);
+        }
+      }
+    }
+  }
+  for (int64_t idx = n16 + threadIdx.x; idx < n; idx += kUpdateThreads)
+    if (assign[idx] == k) fn(idx);
+}
+
 template <int SUB>
-__global__ __launch_bounds__(256) void km_update_kernel(const float* __restrict__ samples, int64_t n,
+__global__ __launch_bounds__(kUpdateThreads) void km_update_kernel(const float* __restrict__ samples, int64_t n,
                                                         const uint8_t* __restrict__ assign,
                                                         double* __restrict__ centroids) {
-  __shared__ double red[4][SUB + 1];
+  __shared__ double red[kUpdateWaves][SUB + 1];
   const int k = blockIdx.x;
   double sum[SUB];
 #pragma unroll
   for (int i = 0; i < SUB; ++i) sum[i] = 0.0;
   double cnt = 0.0;
-  for (int64_t idx = threadIdx.x; idx < n; idx += 256) {
-    if (assign[idx] == k) {
+  for_each_member(assign, n, k, [&](int64_t idx) {
 #pragma unroll
-      for (int i = 0; i < SUB; ++i) sum[i] += (double)samples[idx * SUB + i];
-      cnt += 1.0;
-    }
-  }
+    for (int i = 0; i < SUB; ++i) sum[i] += (double)samples[idx * SUB + i];
+    cnt += 1.0;
+  });
 #pragma unroll
   for (int i = 0; i < SUB; ++i) sum[i] = xor_sum(sum[i], 64);
   cnt = xor_sum(cnt, 64);
@@ -79,8 +113,12 @@ __global__ __launch_bounds__(256) void km_update_kernel(const float* __restrict_
   __syncthreads();
   if (threadIdx.x <= SUB) {
     const int i = threadIdx.x;
-    const double tot_cnt = ((red[0][SUB] + red[1][SUB]) + red[2][SUB]) + red[3][SUB];
-    if (i < SUB && tot_cnt > 0.0) centroids[k * SUB + i] = (((red[0][i] + red[1][i]) + red[2][i]) + red[3][i]) / tot_cnt;
+    double tot_cnt = 0.0, tot = 0.0;
+    for (int w = 0; w < kUpdateWaves; ++w) {
+      tot_cnt += red[w][SUB];
+      tot += red[w][i];  // for i == SUB the count again: unused
+    }
+    if (i < SUB && tot_cnt > 0.0) centroids[k * SUB + i] = tot / tot_cnt;
   }
 }
 
@@ -89,30 +127,28 @@ __global__ __launch_bounds__(256) void km_update_kernel(const float* __restrict_
 // orthogonal to it:  c += lr / (N |c|) * (S - (S . c^) c^).   cos_sum[k] = S . c^ is the cluster's
 // share of the summed cosine similarity BEFORE the move.
 template <int SUB>
-__global__ __launch_bounds__(256) void ft_update_kernel(const float* __restrict__ samples, int64_t n,
+__global__ __launch_bounds__(kUpdateThreads) void ft_update_kernel(const float* __restrict__ samples, int64_t n,
                                                         const uint8_t* __restrict__ assign,
                                                         double* __restrict__ centroids, double lr,
                                                         double* __restrict__ cos_sum) {
-  __shared__ double red[4][SUB];
+  __shared__ double red[kUpdateWaves][SUB];
   const int k = blockIdx.x;
   double sum[SUB];
 #pragma unroll
   for (int i = 0; i < SUB; ++i) sum[i] = 0.0;
-  for (int64_t idx = threadIdx.x; idx < n; idx += 256) {
-    if (assign[idx] == k) {
-      double x[SUB], n2 = 0.0;
+  for_each_member(assign, n, k, [&](int64_t idx) {
+    double x[SUB], n2 = 0.0;
 #pragma unroll
-      for (int i = 0; i < SUB; ++i) {
-        x[i] = (double)samples[idx * SUB + i];
-        n2 += x[i] * x[i];
-      }
-      if (n2 > 0.0) {
-        const double nx = sqrt(n2);
-#pragma unroll
-        for (int i = 0; i < SUB; ++i) sum[i] += x[i] / nx;
-      }
+    for (int i = 0; i < SUB; ++i) {
+      x[i] = (double)samples[idx * SUB + i];
+      n2 += x[i] * x[i];
     }
-  }
+    if (n2 > 0.0) {
+      const double nx = sqrt(n2);
+#pragma unroll
+      for (int i = 0; i < SUB; ++i) sum[i] += x[i] / nx;
+    }
+  });
 #pragma unroll
   for (int i = 0; i < SUB; ++i) sum[i] = xor_sum(sum[i], 64);
   const int wave = threadIdx.x >> 6;
@@ -125,7 +161,8 @@ __global__ __launch_bounds__(256) void ft_update_kernel(const float* __restrict_
     double S[SUB], c[SUB], cn2 = 0.0;
 #pragma unroll
     for (int i = 0; i < SUB; ++i) {
-      S[i] = ((red[0][i] + red[1][i]) + red[2][i]) + red[3][i];
+      S[i] = 0.0;
+      for (int w = 0; w < kUpdateWaves; ++w) S[i] += red[w][i];
       c[i] = centroids[k * SUB + i];
       cn2 += c[i] * c[i];
     }
@@ -162,7 +199,7 @@ static int codebook_run_t(const float* samples, int64_t n, int iters, void* code
   km_init_kernel<<<(n_elems + 255) / 256, 256, 0, stream>>>(samples, centroids, n_elems);
   for (int it = 0; it < iters; ++it) {
     km_assign_kernel<SUB><<<kAssignBlocks, 256, 0, stream>>>(samples, n, centroids, assign, block_err);
-    km_update_kernel<SUB><<<kCodes, 256, 0, stream>>>(samples, n, assign, centroids);
+    km_update_kernel<SUB><<<kCodes, kUpdateThreads, 0, stream>>>(samples, n, assign, centroids);
   }
   km_round_kernel<<<(n_elems + 255) / 256, 256, 0, stream>>>(centroids, static_cast<__half*>(codebook_out), n_elems);
   km_assign_kernel<SUB><<<kAssignBlocks, 256, 0, stream>>>(samples, n, centroids, assign, block_err);
@@ -190,7 +227,7 @@ static int finetune_run_t(const float* samples, int64_t n, int iters, double lr,
   double host_cos[kCodes];
   auto mean_cos = [&](double* out) -> int {  // assignment + cosine sums of the current centroids (no move: lr = 0)
     km_assign_kernel<SUB><<<kAssignBlocks, 256, 0, stream>>>(samples, n, centroids, assign, block_err);
-    ft_update_kernel<SUB><<<kCodes, 256, 0, stream>>>(samples, n, assign, centroids, 0.0, cos_sum);
+    ft_update_kernel<SUB><<<kCodes, kUpdateThreads, 0, stream>>>(samples, n, assign, centroids, 0.0, cos_sum);
     if (hipGetLastError() != hipSuccess) return NSN_ERR_HIP;
     if (hipMemcpyAsync(host_cos, cos_sum, sizeof(host_cos), hipMemcpyDeviceToHost, stream) != hipSuccess)
       return NSN_ERR_HIP;
@@ -206,7 +243,7 @@ static int finetune_run_t(const float* samples, int64_t n, int iters, double lr,
   if (cos_host && (rc = mean_cos(&before)) != NSN_OK) return rc;
   for (int it = 0; it < iters; ++it) {
     km_assign_kernel<SUB><<<kAssignBlocks, 256, 0, stream>>>(samples, n, centroids, assign, block_err);
-    ft_update_kernel<SUB><<<kCodes, 256, 0, stream>>>(samples, n, assign, centroids, lr, cos_sum);
+    ft_update_kernel<SUB><<<kCodes, kUpdateThreads, 0, stream>>>(samples, n, assign, centroids, lr, cos_sum);
   }
   km_round_kernel<<<(n_elems + 255) / 256, 256, 0, stream>>>(centroids, static_cast<__half*>(codebook_io), n_elems);
   if (hipGetLastError() != hipSuccess) return NSN_ERR_HIP;
