@@ -325,6 +325,8 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   int len_cur = 0, nb = 0, nh = 0;
   __half2 q2_next = __half2{};
   uint32_t okf_next = 0u, okfp_next = 0u;
+  // PAGED: the wave's window of block-table entries (see load_window); the first group of a pass loads it
+  int win0 = -(1 << 30), win_k = 0, win_v = 0, nwin_k = 0, nwin_v = 0;
   if constexpr (FLAT) len_cur = seq_lens[b];
   for (;;) {  // FLAT: one pass per segment of the run; otherwise a single pass
   // Everything a pass derives from the lane number is derived anew in each pass: values that the compiler
@@ -334,26 +336,40 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   if constexpr (FLAT) asm volatile("" : "+v"(lane));
   const int rho = lane >> 4, n16 = lane & 15, head = lane & 3, tile_of_lane = n16 >> 2;
   // ---- loads of one group (all unconditional: callers clamp the group index into the cache) ----
-  int lane_zero = 0;
-  asm volatile("" : "+v"(lane_zero));  // (a zero the compiler takes for a per-lane value)
   const uint32_t lane_code_off = lane * NSV;
   const uint32_t norm_off = (16 * tile_of_lane + 4 * rho) * 4;  // bytes: the lane's first token of the group
   const uint32_t lane_x4 = lane * 4;
+  // Paged caches: the wave keeps 64 consecutive block-table entries of its sequence in two registers (lane i:
+  // page win0 + i, clamped into the sequence's table row) and picks a group's entries with lane reads.  An
+  // entry loaded right before its use would make the wave wait for every load it has in flight (loads return
+  // in order); the window is loaded once per segment (the persistent instance asks for the next segment's
+  // window when it leaves its main loop) and again only when a group lies beyond it.
+  auto load_window = [&](int bb, int w0, int& wk, int& wv) {
+    const int64_t e = (int64_t)bb * g.pages_per_seq + min(w0 + lane, g.pages_per_seq - 1);
+    wk = kc.block_table[e], wv = vc.block_table[e];
+  };
   // token index (counted over the whole buffer) of the first token of the group that starts at token tg
-  auto group_base = [&](const int32_t* block_table, int tg) -> int64_t {
-    if constexpr (!PAGED) return (int64_t)(b * g.n_kv_heads + h) * g.page_tokens + tg;
-    const int page = POW2 ? tg >> g.page_shift : tg / g.page_tokens;
-    const int tin = POW2 ? tg & (g.page_tokens - 1) : tg % g.page_tokens;
-    // the table entry comes through the vector memory path: a scalar load would share its counter with the
-    // LDS gathers in flight, and the wait for it would drain them
-    const int phys = __builtin_amdgcn_readfirstlane(block_table[(int64_t)b * g.pages_per_seq + page + lane_zero]);
-    return ((int64_t)phys * g.n_kv_heads + h) * g.page_tokens + tin;
+  auto group_bases = [&](int tg, int64_t& kbase, int64_t& vbase) {
+    if constexpr (!PAGED) {
+      kbase = vbase = (int64_t)(b * g.n_kv_heads + h) * g.page_tokens + tg;
+    } else {
+      const int page = POW2 ? tg >> g.page_shift : tg / g.page_tokens;
+      const int tin = POW2 ? tg & (g.page_tokens - 1) : tg % g.page_tokens;
+      if ((unsigned)(page - win0) >= 64u) {  // wave-uniform
+        win0 = page & ~63;
+        load_window(b, win0, win_k, win_v);
+      }
+      const int pk = __builtin_amdgcn_readlane(win_k, page - win0), pv = __builtin_amdgcn_readlane(win_v, page - win0);
+      kbase = ((int64_t)pk * g.n_kv_heads + h) * g.page_tokens + tin;
+      vbase = ((int64_t)pv * g.n_kv_heads + h) * g.page_tokens + tin;
+    }
   };
   auto shift_group = [&](int tg) -> int {
     return g.group_size <= 0 ? 0 : POW2 ? tg >> g.group_shift : tg / g.group_size;
   };
   auto load_group = [&](int tg, Regs& G) {  // tg: first token of the group (a multiple of 64 inside the cache)
-    const int64_t kbase = group_base(kc.block_table, tg), vbase = group_base(vc.block_table, tg);  // wave-uniform
+    int64_t kbase, vbase;  // wave-uniform
+    group_bases(tg, kbase, vbase);
     const unsigned char* kp = kc.codes + kbase * NSV + lane_code_off;
     const unsigned char* vp = vc.codes + vbase * NSV + lane_code_off;
 #pragma unroll
@@ -532,7 +548,8 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   };
   if (res_wave) {
     // (the persistent instance fetches the rows where it stages them: thirty-two registers held from here
-    // to there do not fit beside its other state)
+    // to there do not fit beside its other state; fetching and staging them at the segment's start through
+    // waves 4..7, which reach a segment first, was measured and is no faster)
     if constexpr (!FLAT) load_residual_rows();
     res_len = res.lens[b];
   }
@@ -955,6 +972,8 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     }
   }
   if (cur_group >= 0) flush_group();
+  // the window of the unit that the next segment begins (pages 0..63), back before that segment asks for it
+  if constexpr (FLAT && PAGED) load_window(nb, 0, nwin_k, nwin_v);
 
   // ---- epilogue: this wave's sums -> its merge slot ------------------------------------------------
   {
@@ -1107,6 +1126,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   if (run_pos >= run_end) break;
   b = nb, h = nh;  // the next unit (its first row and length are on their way or here)
   first_segment = false;
+  if constexpr (PAGED) win0 = 0, win_k = nwin_k, win_v = nwin_v;
   }  // segments
 }
 

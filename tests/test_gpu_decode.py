@@ -67,6 +67,9 @@ CASES = [
     ("mha-2bit", 2, 4, 4, [333, 700], 4, 64, 0, 2),
     ("paged-1bit", 3, 4, 2, [1000, 256, 37], 8, 0, 256, 0),
     ("paged-2bit-groups", 2, 8, 2, [900, 511], 4, 128, 256, 5),
+    # more than 64 pages per sequence: a wave's window of block-table entries is reloaded on the way
+    ("paged64-long-2bit", 2, 4, 2, [5000, 4200], 4, 64, 64, 3),
+    ("paged192-long-1bit", 1, 4, 1, [13000], 8, 0, 192, 2),
     ("empty-and-short", 3, 2, 1, [0, 1, 65], 8, 64, 0, 2),
     ("gqa8-2bit", 1, 8, 1, [300], 4, 64, 0, 2),          # 8 query heads per kv head
     ("long-2bit-many-splits", 1, 4, 1, [5000], 4, 0, 0, 16),
@@ -81,6 +84,7 @@ CASES = [
     ("flat-gqa8-2bit-onegroup", 16, 64, 8, FLAT_LENS[::-1], 4, 0, 0, 0),
     ("flat-long-units-1bit", 16, 32, 8, [2100, 0, 70, 1500] + [40] * 12, 8, 128, 0, 0),
     # more than 64 sequences: the run boundaries are found across several 64-sequence blocks of lengths
+    ("flat-paged64-long-1bit", 16, 8, 8, [4500, 0, 70, 5000] + [40] * 12, 8, 128, 64, 0),
     ("flat-all-empty", 16, 8, 8, [0] * 16, 4, 64, 0, 0),
     ("flat-130-sequences-1bit", 130, 2, 1, [(i * 37) % 200 for i in range(130)], 8, 0, 0, 0),
     ("flat-200-sequences-2bit-paged", 200, 4, 1, [(i * 53) % 300 for i in range(200)], 4, 64, 256, 0),
