@@ -220,3 +220,57 @@ def test_one_dominant_token_among_many_low_score_tokens(gpu_api, codebooks, sele
     err = helpers.max_rel_err(out, ref)
     print(f"  impl={impl} dominant token at {where} (weight {weight:.4f}): max rel err {err:.3e}", flush=True)
     assert err < TOL, err
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_persistent_instance_agrees_with_forced_splits_on_random_shapes(gpu_api, seed):
+    """The persistent instance (automatic split choice, 128 or more units) against the one-workgroup-per-split
+    instance (forced split count), which the oracle cases above cover, on random batch shapes: ragged lengths
+    with empty sequences, several kv-head counts, paged and contiguous caches, Shift groups, both code widths.
+    Cache contents are random bytes (every byte is a valid code); the two launches differ in how the softmax
+    partials are cut, so they agree to the rounding of the fp16 value weights, not bit for bit."""
+    import torch
+    api = gpu_api
+    rng = np.random.default_rng(9000 + seed)
+    hkv = int(rng.choice([1, 2, 4, 8]))
+    r = int(rng.choice([1, 2, 4]))
+    batch = int(rng.integers((128 + hkv - 1) // hkv, (128 + hkv - 1) // hkv + 40))
+    sub = int(rng.choice([4, 8]))
+    # (page size, Shift group size): powers of two and the general instances (192)
+    page, G = [(0, 0), (0, 64), (0, 128), (0, 192), (64, 0), (64, 64), (256, 64), (256, 128), (256, 0),
+               (192, 0)][int(rng.integers(0, 10))]
+    top = int(rng.choice([90, 700, 3000]))
+    lens = rng.integers(0, top, size=batch)
+    lens[rng.integers(0, batch, size=3)] = 0
+    lens[rng.integers(0, batch)] = top + 2000  # one long unit, cut by several run boundaries
+    lens = [int(n) for n in lens]
+    max_len = ((max(lens) + 767) // 768) * 768
+    print(f"seed {seed}: batch={batch} hkv={hkv} r={r} sub={sub} page={page} G={G} top={top}", flush=True)
+    shape = api.make_shape(sub, hkv * r, hkv, max_len, G, page)
+    dev = torch.device("cuda")
+    g = torch.Generator(device=dev).manual_seed(seed)
+    bt = torch.from_numpy(synth.shuffled_page_table(seed, batch, max_len // page)).to(dev) if page else None
+    caches = []
+    for _ in range(2):
+        c = api.alloc_cache(shape, batch, block_table=bt)
+        c.codes.random_(0, 256, generator=g)
+        c.norms.copy_((torch.rand(c.norms.shape, device=dev, generator=g) + 0.5).half())
+        c.means.copy_((0.2 * torch.randn(c.means.shape, device=dev, generator=g)).half())
+        caches.append(c)
+    cb = torch.randn((256, sub), device=dev, generator=g).half()
+    q = torch.randn((batch, hkv * r, 128), device=dev, generator=g).half()
+    lens_d = torch.tensor(lens, dtype=torch.int32, device=dev)
+    scale = 1.0 / math.sqrt(128)
+    outs = []
+    for n_splits in (0, 1, 3):
+        o = api.nsn_decode_attention(shape, cb, q, caches[0], caches[1], lens_d, max(lens), scale, n_splits)
+        torch.cuda.synchronize()
+        outs.append(o.cpu().numpy().astype(np.float64))
+    for b in range(batch):
+        if lens[b] == 0:
+            assert np.all(outs[0][b] == 0.0)
+    assert np.all(np.isfinite(outs[0]))
+    for o in outs[1:]:
+        err = helpers.max_rel_err(outs[0], o)
+        print(f"  difference to a forced split count {err:.3e}", flush=True)
+        assert err < 1e-3, err
