@@ -144,17 +144,23 @@ template <int CTRL, int BANK>
 __device__ __forceinline__ int dpp_i32(int old, int v) {
   return __builtin_amdgcn_update_dpp(old, v, CTRL, 0xf, BANK, false);
 }
+// (every lane has a valid source in these patterns and the callers run with all lanes active, so the
+// destination needs no defined previous value: the form without one saves the move that would set it)
+template <int CTRL, int BANK>
+__device__ __forceinline__ int dpp_mov_i32(int v) {
+  return __builtin_amdgcn_mov_dpp(v, CTRL, 0xf, BANK, true);
+}
 template <int M>
 __device__ __forceinline__ int xor_lane_i32(int v) {
   if constexpr (M == 1) {
-    return dpp_i32<0xB1, 0xf>(0, v);  // quad_perm [1,0,3,2]
+    return dpp_mov_i32<0xB1, 0xf>(v);  // quad_perm [1,0,3,2]
   } else if constexpr (M == 2) {
-    return dpp_i32<0x4E, 0xf>(0, v);  // quad_perm [2,3,0,1]
+    return dpp_mov_i32<0x4E, 0xf>(v);  // quad_perm [2,3,0,1]
   } else if constexpr (M == 4) {
-    const int t = dpp_i32<0x104, 0x5>(0, v);  // row_shl:4 into lanes whose bit 2 is clear
-    return dpp_i32<0x114, 0xa>(t, v);         // row_shr:4 into lanes whose bit 2 is set
+    const int t = dpp_mov_i32<0x104, 0x5>(v);  // row_shl:4 into lanes whose bit 2 is clear
+    return dpp_i32<0x114, 0xa>(t, v);          // row_shr:4 into lanes whose bit 2 is set
   } else if constexpr (M == 8) {
-    return dpp_i32<0x128, 0xf>(0, v);  // row_ror:8
+    return dpp_mov_i32<0x128, 0xf>(v);  // row_ror:8
   } else {
     return __shfl_xor(v, M, 64);
   }

@@ -52,16 +52,18 @@ __global__ __launch_bounds__(256) void enc_stats_kernel(Geometry g, const __half
   double acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.0;
-  // four steps of loads in flight
+  // four steps of loads in flight; a token past the end is read from the last valid row (the chunk has at
+  // least one: t_end > chunk start, or the loop below does not run) and its weight is set to zero
   auto fetch = [&](int t) -> uint4 {
-    return t < t_end ? *reinterpret_cast<const uint4*>(in + (int64_t)t * kHeadDim + 8 * col) : make_uint4(0u, 0u, 0u, 0u);
+    return *reinterpret_cast<const uint4*>(in + (int64_t)min(t, max(t_end - 1, 0)) * kHeadDim + 8 * col);
   };
-  int t = chunk * chunk_tokens + 4 * wave + row;
-  uint4 cur = fetch(t), nx1 = fetch(t + 16), nx2 = fetch(t + 32), nx3 = fetch(t + 48);
-  for (; t - row < t_end; t += 16) {  // (t - row: the same bound for the wave's four tokens)
-    const uint4 raw = cur;
-    cur = nx1, nx1 = nx2, nx2 = nx3;
-    nx3 = fetch(t + 64);
+  // where fp16(s1) of token t goes: one address that is linear in t, except for paged caches
+  const bool linear = g.dq || !g.paged;  // uniform
+  __half* const b_out = g.dq ? wsb
+                             : reinterpret_cast<__half*>(cv.norms) +
+                                   2 * ((int64_t)(b * g.n_kv_heads + h) * g.page_tokens + start) + 1;
+  const int b_stride = g.dq ? 1 : 2;
+  auto step = [&](const uint4 raw, int t) {
     const __half* xh = reinterpret_cast<const __half*>(&raw);
     double x[8], ss = 0.0;
 #pragma unroll
@@ -84,8 +86,8 @@ __global__ __launch_bounds__(256) void enc_stats_kernel(Geometry g, const __half
     }
     const __half b16 = f64_to_f16(s1);
     const double bb = (double)__half2float(b16);
-    double rb = 0.0;  // (tokens past the end arrive as zeros and add nothing)
-    if (bb != 0.0) {
+    double rb = 0.0;  // (tokens past the end add nothing)
+    if (bb != 0.0 && t < t_end) {
       rb = __builtin_amdgcn_rcp(bb);
       rb = fma(fma(-bb, rb, 1.0), rb, rb);
       rb = fma(fma(-bb, rb, 1.0), rb, rb);
@@ -93,12 +95,25 @@ __global__ __launch_bounds__(256) void enc_stats_kernel(Geometry g, const __half
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = fma(x[i], rb, acc[i]);
     if (col == 0 && t < t_end) {
-      if (g.dq) {
-        wsb[t] = b16;
+      if (linear) {
+        b_out[(int64_t)t * b_stride] = b16;
       } else {
         const int pos = start + t;
         const int64_t base = unit_token_base(g, cv.block_table, b, h, pos);
         reinterpret_cast<__half*>(cv.norms)[2 * (base + token_in_unit(g, pos)) + 1] = b16;
+      }
+    }
+  };
+  // the four buffers are refilled in place, four steps to a round (no register moves between steps)
+  const int tw = chunk * chunk_tokens + 4 * wave;  // the wave's first token of a step (uniform)
+  uint4 buf[4] = {fetch(tw + row), fetch(tw + row + 16), fetch(tw + row + 32), fetch(tw + row + 48)};
+  for (int t0 = tw; t0 < t_end; t0 += 64) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (t0 + 16 * u < t_end) {  // wave-uniform
+        const uint4 raw = buf[u];
+        buf[u] = fetch(t0 + 16 * u + row + 64);
+        step(raw, t0 + 16 * u + row);
       }
     }
   }
