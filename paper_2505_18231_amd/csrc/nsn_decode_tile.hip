@@ -367,11 +367,22 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   auto shift_group = [&](int tg) -> int {
     return g.group_size <= 0 ? 0 : POW2 ? tg >> g.group_shift : tg / g.group_size;
   };
-  auto load_group = [&](int tg, Regs& G) {  // tg: first token of the group (a multiple of 64 inside the cache)
-    int64_t kbase, vbase;  // wave-uniform
-    group_bases(tg, kbase, vbase);
-    const unsigned char* kp = kc.codes + kbase * NSV + lane_code_off;
-    const unsigned char* vp = vc.codes + vbase * NSV + lane_code_off;
+  // tg: first token of the group (a multiple of 64 inside the cache).  A group that does not exist (`real` false:
+  // the wave's list of groups has ended) is loaded all the same, from the first bytes of every array (one cache line
+  // per instruction, nothing of it is used: any bytes are valid table indices).  With loads that are only issued
+  // under a condition, the number of loads behind a given one depends on the path, the compiler's wait counts
+  // take the smallest, and every wait for a group's bytes becomes a wait for all loads in flight, the groups
+  // requested ahead included.
+  auto load_group = [&](int tg, bool real, Regs& G) {
+    int64_t kbase = 0, vbase = 0, mgrp = 0;  // wave-uniform
+    if (real) {
+      group_bases(tg, kbase, vbase);
+      mgrp = mean_base + shift_group(tg);
+    }
+    const uint32_t lco = real ? lane_code_off : 0u, noff = real ? norm_off : 0u, lx4 = real ? lane_x4 : 0u;
+    const uint32_t ln = real ? (uint32_t)lane : 0u;
+    const unsigned char* kp = kc.codes + kbase * NSV + lco;
+    const unsigned char* vp = vc.codes + vbase * NSV + lco;
 #pragma unroll
     for (int w4 = 0; w4 < CW / 4; ++w4) {
       const uint4 kv4 = reinterpret_cast<const uint4*>(kp)[w4];
@@ -383,24 +394,24 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
       // (kbase, vbase are multiples of 64: one norm record per 64-token block of the buffer)
       const unsigned char* kr = reinterpret_cast<const unsigned char*>(kc.norms) + (kbase >> 6) * kDqNormRec;
       const unsigned char* vr = reinterpret_cast<const unsigned char*>(vc.norms) + (vbase >> 6) * kDqNormRec;
-      const uint32_t tok0 = norm_off >> 2;  // the lane's first token of the group (a multiple of 4)
+      const uint32_t tok0 = noff >> 2;  // the lane's first token of the group (a multiple of 4)
       const uint2 ka = *reinterpret_cast<const uint2*>(kr + 2 * tok0), va = *reinterpret_cast<const uint2*>(vr + 2 * tok0);
       G.nk = make_uint4(ka.x, ka.y, *reinterpret_cast<const uint16_t*>(kr + kDqNormCodes + (tok0 >> 1)),
                         *reinterpret_cast<const uint32_t*>(kr + kDqNormPar));
       G.nv = make_uint4(va.x, va.y, *reinterpret_cast<const uint16_t*>(vr + kDqNormCodes + (tok0 >> 1)),
                         *reinterpret_cast<const uint32_t*>(vr + kDqNormPar));
-      const int64_t mo = (mean_base + shift_group(tg)) * kDqMeanRec;
+      const int64_t mo = mgrp * kDqMeanRec;
       const unsigned char* km = reinterpret_cast<const unsigned char*>(kc.means) + mo;
       const unsigned char* vm = reinterpret_cast<const unsigned char*>(vc.means) + mo;
-      G.ok = km[lane], G.ov = vm[lane];
-      G.okp = *reinterpret_cast<const uint32_t*>(km + kDqMeanPar + 4 * (lane >> 4));
-      G.ovp = *reinterpret_cast<const uint32_t*>(vm + kDqMeanPar + 4 * (lane >> 4));
+      G.ok = km[ln], G.ov = vm[ln];
+      G.okp = *reinterpret_cast<const uint32_t*>(km + kDqMeanPar + 4 * (ln >> 4));
+      G.ovp = *reinterpret_cast<const uint32_t*>(vm + kDqMeanPar + 4 * (ln >> 4));
     } else {
-      G.nk = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(kc.norms + kbase) + norm_off);
-      G.nv = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(vc.norms + vbase) + norm_off);
-      const int64_t mo = (mean_base + shift_group(tg)) * kHeadDim;
-      G.ok = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(kc.means + mo) + lane_x4);
-      G.ov = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lane_x4);
+      G.nk = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(kc.norms + kbase) + noff);
+      G.nv = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(vc.norms + vbase) + noff);
+      const int64_t mo = mgrp * kHeadDim;
+      G.ok = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(kc.means + mo) + lx4);
+      G.ov = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lx4);
     }
   };
   // the lane's two channels of a Shift vector from its stored words
@@ -470,11 +481,11 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   }
   // (the three small loads stay ahead of the bulk ones: the waits for them then leave every later load in flight)
   __builtin_amdgcn_sched_barrier(0);
-  Regs S0, S1, S2;  // each is either loaded or zeroed before it is read (zeros are valid table indices)
+  Regs S0, S1, S2;  // each is loaded before it is read (with the bytes of a group that exists, or with any bytes)
   if constexpr (!FLAT) {
     // contiguous caches: the wave's first group is in bounds whatever the sequence length is (clamped into
     // the cache when the split lies beyond it: then it is never processed)
-    if constexpr (!PAGED) load_group(min(t0 + (wave << 6), cap_tokens - 64), S0);  // (wslot == wave here)
+    if constexpr (!PAGED) load_group(min(t0 + (wave << 6), cap_tokens - 64), true, S0);  // (wslot == wave here)
     len = seq_lens[b];
     // Splits that lie wholly beyond this sequence's end have nothing to do and leave at once (a ragged batch
     // is launched with the split count of its longest sequence); the others know how many of them there
@@ -488,12 +499,7 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   // FLAT: waves 4..7 take the segment's first groups: they are the ones that come out of the previous
   // segment early (waves 0..3 merge it), and a short segment then does not wait for the late ones
   const int wslot = FLAT ? (wave + 4) & 7 : wave;
-  if constexpr (PAGED || FLAT) {
-    if (wslot < n_grp)
-      load_group(t0 + (wslot << 6), S0);
-    else
-      S0 = Regs{};
-  }
+  if constexpr (PAGED || FLAT) load_group(t0 + (wslot << 6), wslot < n_grp, S0);
   // ---- prologue: codebook table, query operands --------------------------------------------------
   if constexpr (!FLAT) fill_table();
   if (wave < 4) {  // d1: wave w rotates head w (zeros for a head that this launch does not have)
@@ -558,18 +564,12 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   // two groups in flight.  The compute unit's address pipeline takes about 28 cycles per 1 KiB load
   // instruction and a wave blocks at a load that cannot be accepted yet: a wave that asks for three groups
   // at once sits at its load instructions while the data of its first group is already in its registers.
-  if (wslot + NW < n_grp)
-    load_group(t0 + ((wslot + NW) << 6), S1);
-  else
-    S1 = Regs{};
+  load_group(t0 + ((wslot + NW) << 6), wslot + NW < n_grp, S1);
   __syncthreads();
   if constexpr (FLAT) {
     // segments are short and start cold: three groups per wave go out before the first is used, and the set
     // that a group leaves takes the group three rounds on (see process_group)
-    if (wslot + 2 * NW < n_grp)
-      load_group(t0 + ((wslot + 2 * NW) << 6), S2);
-    else
-      S2 = Regs{};
+    load_group(t0 + ((wslot + 2 * NW) << 6), wslot + 2 * NW < n_grp, S2);
   }
 
   // B operands of the score contraction (see the header): for tile parity p and k-step s the lane's eight
@@ -935,14 +935,10 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
     v_gather(c3, G, VD);
     __builtin_amdgcn_sched_barrier(0);
     // the group after the next one: requested just before the next one's bytes are first needed (below)
-    if constexpr (FLAT) {  // (this group's bytes have all been used by now)
-      if (gi + 3 * NW < n_grp) load_group(t0 + ((gi + 3 * NW) << 6), G);
-    } else {
-      if (gi + 2 * NW < n_grp)  // wave-uniform
-        load_group(t0 + ((gi + 2 * NW) << 6), Gnn);
-      else
-        Gnn = Regs{};
-    }
+    if constexpr (FLAT)  // (this group's bytes have all been used by now)
+      load_group(t0 + ((gi + 3 * NW) << 6), gi + 3 * NW < n_grp, G);
+    else
+      load_group(t0 + ((gi + 2 * NW) << 6), gi + 2 * NW < n_grp, Gnn);
     __builtin_amdgcn_sched_barrier(0);
     v_contract(c2, VC, wop);
     __builtin_amdgcn_sched_barrier(0);
