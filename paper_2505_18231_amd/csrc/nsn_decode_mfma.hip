@@ -296,20 +296,27 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   // are short of registers, refill the code registers in place as soon as their phase is over; the
   // others fetch the whole next group one iteration ahead into a second set (longer prefetch
   // distance: measured 0.7 us faster on the 38 MB shape).
-  auto load_k_codes = [&](int gi, Grp& G) {
+  // A group that does not exist (`real` false: the wave's list has ended) is loaded all the same, from the first
+  // bytes of every array (one cache line per instruction; nothing of it is used).  Loads that are only issued
+  // under a condition make the number of loads behind a given one depend on the path; the compiler's wait
+  // counts then take the smallest, and a wait for this group's bytes also waits for the next group's.
+  auto group_base = [&](const int32_t* block_table, int tg, bool real) -> int64_t {  // wave-uniform
+    return real ? unit_token_base(g, block_table, b, h, tg) + token_in_unit(g, tg) : 0;
+  };
+  auto load_k_codes = [&](int gi, bool real, Grp& G) {
     const int tg = t0 + (gi << 6);
-    const int64_t kbase = unit_token_base(g, kc.block_table, b, h, tg) + token_in_unit(g, tg);  // wave-uniform
-    const uint4* kp = reinterpret_cast<const uint4*>(kc.codes + kbase * J + k_lane_off);
+    const int64_t kbase = group_base(kc.block_table, tg, real);
+    const uint4* kp = reinterpret_cast<const uint4*>(kc.codes + kbase * J + (real ? k_lane_off : 0u));
 #pragma unroll
     for (int w4 = 0; w4 < KW / 4; ++w4) {
       const uint4 kv4 = kp[w4];
       G.kcode[4 * w4] = kv4.x, G.kcode[4 * w4 + 1] = kv4.y, G.kcode[4 * w4 + 2] = kv4.z, G.kcode[4 * w4 + 3] = kv4.w;
     }
   };
-  auto load_v_codes = [&](int gi, Grp& G) {
+  auto load_v_codes = [&](int gi, bool real, Grp& G) {
     const int tg = t0 + (gi << 6);
-    const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tg) + token_in_unit(g, tg);
-    const uint4* vp = reinterpret_cast<const uint4*>(vc.codes + vbase * J + v_lane_off);
+    const int64_t vbase = group_base(vc.block_table, tg, real);
+    const uint4* vp = reinterpret_cast<const uint4*>(vc.codes + vbase * J + (real ? v_lane_off : 0u));
 #pragma unroll
     for (int w4 = 0; w4 < KW / 4; ++w4) {
       // sign format: the value side's second 16 bytes are the sign row, NSV rows of J bytes further on
@@ -317,33 +324,33 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       G.vcode[4 * w4] = vv4.x, G.vcode[4 * w4 + 1] = vv4.y, G.vcode[4 * w4 + 2] = vv4.z, G.vcode[4 * w4 + 3] = vv4.w;
     }
   };
-  auto load_side = [&](int gi, Side& S) {
+  auto load_side = [&](int gi, bool real, Side& S) {
     const int tg = t0 + (gi << 6);
-    const int tin = token_in_unit(g, tg);
-    const int64_t kbase = unit_token_base(g, kc.block_table, b, h, tg) + tin;
-    const int64_t vbase = unit_token_base(g, vc.block_table, b, h, tg) + tin;
+    const int64_t kbase = group_base(kc.block_table, tg, real), vbase = group_base(vc.block_table, tg, real);
+    const int64_t mgrp = real ? mean_base + group_of(g, tg) : 0;  // wave-uniform
+    const uint32_t ln = real ? (uint32_t)lane : 0u, lx4 = 4 * ln;  // (a missing group: every lane reads the same bytes)
     if constexpr (DQ) {
       const unsigned char* kr = reinterpret_cast<const unsigned char*>(kc.norms) + (kbase >> 6) * kDqNormRec;
       const unsigned char* vr = reinterpret_cast<const unsigned char*>(vc.norms) + (vbase >> 6) * kDqNormRec;
-      S.ka = *reinterpret_cast<const uint16_t*>(kr + 2 * lane);
-      S.va = *reinterpret_cast<const uint16_t*>(vr + 2 * lane);
-      S.kq = kr[kDqNormCodes + (lane >> 1)];
-      S.vq = vr[kDqNormCodes + (lane >> 1)];
+      S.ka = *reinterpret_cast<const uint16_t*>(kr + 2 * ln);
+      S.va = *reinterpret_cast<const uint16_t*>(vr + 2 * ln);
+      S.kq = kr[kDqNormCodes + (ln >> 1)];
+      S.vq = vr[kDqNormCodes + (ln >> 1)];
       S.kp = *reinterpret_cast<const __half2*>(kr + kDqNormPar);
       S.vp = *reinterpret_cast<const __half2*>(vr + kDqNormPar);
-      const int64_t mo = (mean_base + group_of(g, tg)) * kDqMeanRec;  // wave-uniform
+      const int64_t mo = mgrp * kDqMeanRec;
       const unsigned char* km = reinterpret_cast<const unsigned char*>(kc.means) + mo;
       const unsigned char* vm = reinterpret_cast<const unsigned char*>(vc.means) + mo;
-      S.okq = km[lane];
-      S.ovq = vm[lane];
-      S.okp = *reinterpret_cast<const __half2*>(km + kDqMeanPar + 4 * (lane >> 4));
-      S.ovp = *reinterpret_cast<const __half2*>(vm + kDqMeanPar + 4 * (lane >> 4));
+      S.okq = km[ln];
+      S.ovq = vm[ln];
+      S.okp = *reinterpret_cast<const __half2*>(km + kDqMeanPar + 4 * (ln >> 4));
+      S.ovp = *reinterpret_cast<const __half2*>(vm + kDqMeanPar + 4 * (ln >> 4));
     } else {
-      S.nk = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.norms + kbase) + lane_x4);
-      S.nv = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.norms + vbase) + lane_x4);
-      const int64_t mo = (mean_base + group_of(g, tg)) * kHeadDim;  // wave-uniform
-      S.ok2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.means + mo) + lane_x4);
-      S.ov2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lane_x4);
+      S.nk = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.norms + kbase) + lx4);
+      S.nv = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.norms + vbase) + lx4);
+      const int64_t mo = mgrp * kHeadDim;
+      S.ok2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(kc.means + mo) + lx4);
+      S.ov2 = *reinterpret_cast<const __half2*>(reinterpret_cast<const unsigned char*>(vc.means + mo) + lx4);
     }
   };
   // the lane's two channels of a Shift vector as floats
@@ -359,10 +366,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       o1 = __high2float(o2);
     }
   };
-  auto load_group = [&](int gi, Grp& G) {
-    load_k_codes(gi, G);
-    load_v_codes(gi, G);
-    load_side(gi, G.s);
+  auto load_group = [&](int gi, bool real, Grp& G) {
+    load_k_codes(gi, real, G);
+    load_v_codes(gi, real, G);
+    load_side(gi, real, G.s);
   };
 
   // ROPE: global operands of one batch of the mean term (four groups gi0, gi0 + NW, ...).  The four
@@ -421,7 +428,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   }
   Grp cur;
   const bool spec = main_wave && !g.paged && (t0 + (wave << 6) + 64 <= g.page_tokens);  // in bounds whatever the length
-  if (spec) load_group(wave, cur);
+  if (spec) load_group(wave, true, cur);
   // The split's first Shift group is shared by all waves when there is one group per sequence:
   // its q . o^k is formed once per workgroup (waves that do not rotate a query head), not per wave.
   static_assert(NW >= 8 || (ROPE && NW == 7), "prologue work split: waves 0-3 rotate the query, waves 4.. do the rest "
@@ -589,7 +596,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
   __syncthreads();
   const int t1 = min(len, t0 + per);
   const int n_grp = (main_wave && t1 > t0) ? (t1 - t0 + 63) >> 6 : 0;  // the residual wave owns no coded group
-  if (!spec && wave < n_grp) load_group(wave, cur);
+  if (!spec && wave < n_grp) load_group(wave, true, cur);
 
   // A operands of the score contraction: slot s = channels [4s, 4s+4); block (lane / 4) of
   // register pair p holds slot 16 p + block for head (lane % 4); fp16 hi and lo parts.
@@ -873,12 +880,10 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
     }
     Side nxt;
     Grp nxt_full;
-    if (has_next) {
-      if constexpr (kInPlace)
-        load_side(gi + NW, nxt);
-      else
-        load_group(gi + NW, nxt_full);
-    }
+    if constexpr (kInPlace)
+      load_side(gi + NW, has_next, nxt);
+    else
+      load_group(gi + NW, has_next, nxt_full);
     // (selects, not a branch on `valid`: a branch would pin the wait for these registers to the top of
     // the iteration, right behind the next group's loads)
     float a_k, b_k, a_v, b_v;
@@ -945,7 +950,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
       });
     }
     if constexpr (kInPlace)
-      if (has_next) load_k_codes(gi + NW, cur);  // the key codes are consumed: refill them in place
+      load_k_codes(gi + NW, has_next, cur);  // the key codes are consumed: refill them in place
     constexpr std::integral_constant<bool, SGN> vsgn{};
     cw_t vbufA[4], vbufB[4];
     uint4 vmskA[VMB], vmskB[VMB];
@@ -969,13 +974,11 @@ __global__ __launch_bounds__((NW + 1) * 64) void dec_mfma_kernel(Geometry g, con
         v_contract(ac, vsgn, vbufB, vmskB, wop, acc);
       }
     });
-    if (has_next) {
-      if constexpr (kInPlace) {
-        load_v_codes(gi + NW, cur);  // likewise the value codes
-        cur.s = nxt;
-      } else {
-        cur = nxt_full;
-      }
+    if constexpr (kInPlace) {
+      load_v_codes(gi + NW, has_next, cur);  // likewise the value codes
+      cur.s = nxt;
+    } else {
+      cur = nxt_full;
     }
   }
 
