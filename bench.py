@@ -35,8 +35,8 @@ PEAK_HBM_GBPS = 8000.0
 # HBM bytes per decode launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs kept under profiles/
 # (scaled by the same counters on a plain 256 MiB copy); only for the workload they were taken on.
 MEASURED_TRAFFIC = {
-    "C1": {"bytes": (20308.0 * 2.000 + 1272.0 * 1.000) * 1024,
-           "source": "profiles/decode_C1_hbm_traffic.txt: rocprofv3 FETCH_SIZE 20308.0 x 2.000 + WRITE_SIZE 1272.0 x 1.000 "
+    "C1": {"bytes": (20310.9 * 2.000 + 1272.0 * 1.000) * 1024,
+           "source": "profiles/decode_C1_hbm_traffic.txt: rocprofv3 FETCH_SIZE 20310.9 x 2.000 + WRITE_SIZE 1272.0 x 1.000 "
                      "KiB per launch (factors from a 256 MiB copy in the same runs), residual rows included"},
 }
 DECODE_KERNEL_NAME = "nsn::tile::dec_tile_kernel"
