@@ -274,3 +274,19 @@ def test_persistent_instance_agrees_with_forced_splits_on_random_shapes(gpu_api,
         err = helpers.max_rel_err(outs[0], o)
         print(f"  difference to a forced split count {err:.3e}", flush=True)
         assert err < 1e-3, err
+
+
+@pytest.mark.parametrize("sub,page", [(4, 0), (8, 0), (4, 64)])
+def test_smallest_cache_one_group(gpu_api, codebooks, sub, page):
+    """A cache of a single 64-token group per array (the smallest the layout allows): the loads that the kernel
+    issues for groups past the end of a wave's list read the first bytes of each array and must stay inside it."""
+    cb = codebooks[sub]
+    scale = 1.0 / math.sqrt(128)
+    lens = [37]
+    kc, vc, q, max_len = build_case(4242, 1, 1, 1, lens, sub, 0, cb, page, max_len=64)
+    assert max_len == 64
+    ref = oracle_out(kc, vc, q, lens, 1, 1, cb, 0, scale)
+    out = gpu_out(gpu_api, kc, vc, q, lens, 1, 1, sub, 0, cb, max_len, scale, page)
+    err = helpers.max_rel_err(out, ref)
+    print(f"  sub={sub} page={page}: max rel err {err:.3e}", flush=True)
+    assert err < TOL, err
