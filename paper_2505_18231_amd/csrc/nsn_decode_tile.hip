@@ -227,7 +227,7 @@ __device__ __forceinline__ float dq_level(uint32_t par, uint32_t code) {
 // Every unit takes kSegCost list slots in front of its groups: a segment costs about as much as that many
 // groups (query rotation, two barriers, the merge of the waves, a cold start of the loads), so that runs with
 // many short units get fewer groups.  A run that ends inside those slots leaves the unit to the next run.
-constexpr int kSegCost = 24;
+constexpr int kSegCost = 32;
 // DQ: norms and means are stored in 4 bits (Sec. 3.5): 164-byte norm records per 64-token block, 80-byte mean records
 template <int SUB, int NW, bool POW2, bool PAGED, bool FLAT, bool DQ>
 __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __half* __restrict__ codebook,
