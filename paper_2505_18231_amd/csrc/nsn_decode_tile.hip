@@ -563,12 +563,12 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
   // the one before it is about to be needed (see process_group).  The compute unit's address pipeline takes
   // about 28 cycles per 1 KiB load instruction and a wave blocks at a load that cannot be accepted yet: a wave
   // that asks for more at once sits at its load instructions while the data of its first group is already in
-  // its registers.  The per-split instance asks for the second group behind the first barrier (the barrier
-  // then does not wait for eight waves' worth of load issue: 15.55 -> 15.17 us on the 8 x 8192-token shape);
-  // the persistent instance, whose segments start cold, in front of it.
+  // its registers.  The per-split instance asks for the second group behind the first barrier and the residual
+  // tile (the barrier then does not wait for eight waves' worth of load issue: 15.55 -> 15.17 us on the
+  // 8 x 8192-token shape; behind the tile: 14.66 -> 14.38 us); the persistent instance, whose segments start
+  // cold, in front of the barrier.
   if constexpr (FLAT) load_group(t0 + ((wslot + NW) << 6), wslot + NW < n_grp, S1);
   __syncthreads();
-  if constexpr (!FLAT) load_group(t0 + ((wslot + NW) << 6), wslot + NW < n_grp, S1);
   if constexpr (FLAT) {
     // segments are short and start cold: three groups per wave go out before the first is used, and the set
     // that a group leaves takes the group three rounds on (see process_group)
@@ -779,6 +779,9 @@ __global__ __launch_bounds__(NW * 64) void dec_tile_kernel(Geometry g, const __h
       cf = 1.f;
     }
   }
+  // (per-split instance: the wave's second group, see above; behind the residual tile, which needs no loads, so
+  // that a wave with a tile asks out of the way of the other waves' load issue)
+  if constexpr (!FLAT) load_group(t0 + ((wslot + NW) << 6), wslot + NW < n_grp, S1);
 
   // Gathers and contractions of one group, in batches.  Key side: sixteen matrix instructions in four
   // batches of four (tiles (0, 2) or (1, 3) x two k-steps, so that consecutive instructions alternate
