@@ -290,3 +290,53 @@ def test_smallest_cache_one_group(gpu_api, codebooks, sub, page):
     err = helpers.max_rel_err(out, ref)
     print(f"  sub={sub} page={page}: max rel err {err:.3e}", flush=True)
     assert err < TOL, err
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_matrix_core_and_lookup_table_kernels_agree_on_random_shapes(gpu_api, select_variant, seed):
+    """The default (matrix-core) decode kernel against the lookup-table kernel, which computes the same sums in
+    fp32 with scalar arithmetic and shares no code with it, on random small batch shapes: 1 to 8 query heads per
+    kv head, forced and automatic split counts, paged and contiguous caches, Shift groups, both code widths.
+    Cache contents are random bytes (every byte is a valid code)."""
+    import torch
+    api = gpu_api
+    rng = np.random.default_rng(7000 + seed)
+    hkv = int(rng.choice([1, 2, 4]))
+    r = int(rng.choice([1, 2, 3, 4, 8]))
+    batch = int(rng.integers(1, 7))
+    sub = int(rng.choice([4, 8]))
+    page, G = [(0, 0), (0, 64), (0, 128), (0, 192), (64, 0), (64, 64), (256, 64), (256, 128), (256, 0),
+               (192, 0)][int(rng.integers(0, 10))]
+    n_splits = int(rng.choice([0, 0, 1, 2, 3, 5, 9]))
+    lens = [int(n) for n in rng.integers(0, 3000, size=batch)]
+    lens[int(rng.integers(0, batch))] = int(rng.integers(1, 6000))  # at least one sequence with tokens
+    max_len = ((max(lens) + 767) // 768) * 768
+    print(f"seed {seed}: batch={batch} hkv={hkv} r={r} sub={sub} page={page} G={G} splits={n_splits} lens={lens}", flush=True)
+    shape = api.make_shape(sub, hkv * r, hkv, max_len, G, page)
+    dev = torch.device("cuda")
+    g = torch.Generator(device=dev).manual_seed(seed)
+    bt = torch.from_numpy(synth.shuffled_page_table(seed, batch, max_len // page)).to(dev) if page else None
+    caches = []
+    for _ in range(2):
+        c = api.alloc_cache(shape, batch, block_table=bt)
+        c.codes.random_(0, 256, generator=g)
+        c.norms.copy_((torch.rand(c.norms.shape, device=dev, generator=g) + 0.5).half())
+        c.means.copy_((0.2 * torch.randn(c.means.shape, device=dev, generator=g)).half())
+        caches.append(c)
+    cb = torch.randn((256, sub), device=dev, generator=g).half()
+    q = torch.randn((batch, hkv * r, 128), device=dev, generator=g).half()
+    lens_d = torch.tensor(lens, dtype=torch.int32, device=dev)
+    scale = 1.0 / math.sqrt(128)
+    outs = {}
+    for impl in ("mfma", "lut"):
+        select_variant("decode", impl)
+        o = api.nsn_decode_attention(shape, cb, q, caches[0], caches[1], lens_d, max(lens), scale, n_splits)
+        torch.cuda.synchronize()
+        outs[impl] = o.cpu().numpy().astype(np.float64)
+    for b in range(batch):
+        if lens[b] == 0:
+            assert np.all(outs["mfma"][b] == 0.0)
+    assert np.all(np.isfinite(outs["mfma"]))
+    err = helpers.max_rel_err(outs["mfma"], outs["lut"])
+    print(f"  difference between the two kernels {err:.3e}", flush=True)
+    assert err < TOL, err
