@@ -201,3 +201,39 @@ def test_sign_format_encode_matches_oracle(gpu_api, magnitude_codebook, select_v
             flips += check_unit(k[b, h, :lens[b]], hk.unit_dict(b, h, lens[b]), cb, G, sign=True)
             flips += check_unit(v[b, h, :lens[b]], hv.unit_dict(b, h, lens[b]), cb, G, sign=True)
     print(f"  near-tie code differences: {flips}", flush=True)
+
+
+@pytest.mark.parametrize("sub,G,page,sign,side_bits", [(4, 0, 0, False, 16), (8, 64, 256, False, 16), (8, 0, 0, True, 16),
+                                                       (4, 128, 0, False, 4)])
+def test_matrix_core_and_vector_searches_store_the_same_bytes(gpu_api, select_variant, sub, G, page, sign, side_bits):
+    """The two encoder variants (distance contraction on the matrix cores with an fp64 recheck inside its error
+    window; plain vector-ALU scan) on 2.6 million sub-vector searches of random tokens with channel structure:
+    every stored byte (codes, scales, means) must be the same, ties and near ties included."""
+    import torch
+    api = gpu_api
+    dev = torch.device("cuda")
+    g = torch.Generator(device=dev).manual_seed(1234 + sub + G)
+    batch, hkv, lens = 3, 2, [4096, 2500, 77]
+    max_new, max_len = max(lens), 4096
+    chan = torch.exp(torch.randn((1, hkv, 1, 128), device=dev, generator=g))
+    bias = 2.0 * torch.randn((batch, hkv, 1, 128), device=dev, generator=g)
+    k = (torch.randn((batch, hkv, max_new, 128), device=dev, generator=g) * chan + bias).half()
+    v = torch.randn((batch, hkv, max_new, 128), device=dev, generator=g).half()
+    cb = torch.randn((256, sub), device=dev, generator=g)
+    if sign:
+        cb = cb.abs()
+    cb = cb.half()
+    shape = api.make_shape(sub, hkv, hkv, max_len, G, page, sign_format=sign, side_bits=side_bits)
+    bt = torch.from_numpy(synth.shuffled_page_table(5, batch, max_len // page)).to(dev) if page else None
+    starts = torch.zeros(batch, dtype=torch.int32, device=dev)
+    n_new = torch.tensor(lens, dtype=torch.int32, device=dev)
+    stored = {}
+    for impl in ("mfma", "valu"):
+        select_variant("encode", impl)
+        kc, vc = api.alloc_cache(shape, batch, block_table=bt), api.alloc_cache(shape, batch, block_table=bt)
+        api.nsn_encode(shape, cb, k, v, starts, n_new, kc, vc)
+        torch.cuda.synchronize()
+        stored[impl] = [t.clone() for c in (kc, vc) for t in (c.codes, c.norms, c.means)]
+    for a, b in zip(stored["mfma"], stored["valu"]):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+    assert int(stored["mfma"][0].count_nonzero()) > 0
